@@ -1,0 +1,191 @@
+"""Semantic pins: what key switching, HRot, HMult+relin and BSGS PCMM must mean after decryption.
+
+Encode/decode is pinned to the slot definition (Sec. 2.1: S = N/2 slots, SIMD semantics; Rot shifts
+slots cyclically). Error bounds are stated as numbers.
+"""
+import numpy as np
+import pytest
+
+from ckks_inputs import config_params, galois_element, make_params, uniform_slots, normal_slots, uniform_residues
+from oracle import ref
+from harness import Keys, encode_plain_eval
+
+
+def test_encode_decode_against_slot_definition():
+    N = 64
+    z = uniform_slots(1, N // 2) + 1j * uniform_slots(2, N // 2)
+    m = ref.encode(z, N, 2.0**30)
+    back = ref.decode(m, N, 2.0**30)
+    assert np.max(np.abs(back - z)) < 2.0**-20
+    sl = [0, 1, 7, N // 2 - 1]
+    assert np.max(np.abs(ref.decode_definition(m.tolist(), N, 2.0**30, sl) - back[sl])) < 1e-9
+    # slot-wise product <-> negacyclic polynomial product (the SIMD property)
+    z2 = uniform_slots(3, N // 2)
+    m2 = ref.encode(z2, N, 2.0**30)
+    prod = ref.negacyclic_signed(m, m2)
+    got = ref.decode([int(x) for x in prod], N, 2.0**60)
+    assert np.max(np.abs(got - z * z2)) < 2.0**-20
+    # the Galois map 5^k rotates slots left by k
+    for k in (1, 5):
+        rot = ref.automorph_signed(m, galois_element(k, 6))
+        assert np.max(np.abs(ref.decode(rot, N, 2.0**30) - np.roll(z, -k))) < 2.0**-20
+
+
+def test_encrypt_decrypt_roundtrip():
+    p = make_params(8, 3, 40, 1, 50, 3)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 11)
+    z = uniform_slots(4, p.N // 2)
+    ct = keys.encrypt_slots(z, 2.0**30, 3)
+    assert np.max(np.abs(keys.decrypt_slots(ct, 2.0**30) - z)) < 2.0**-18
+
+
+def ks_noise(params, c, keys, nlimbs, s_from, evk, seed):
+    d = uniform_residues(seed, params.q[:nlimbs], (1,), params.N)
+    ks = c.keyswitch(d, evk)[0]
+    ids = list(range(nlimbs))
+    sf = c.ntt(c.signed_to_rns(s_from, ids)[None], ids)
+    want = c.pointwise(d, sf, ids, "mul")                       # d * s_from
+    got = c.ntt(c.decrypt_rns(ks, keys.s)[None], ids)           # ks.b + ks.a * s
+    diff = c.intt(c.pointwise(got, want, ids, "sub"), ids)[0]
+    return max(abs(v) for v in ref.crt_centred(diff, params.q[:nlimbs]))
+
+
+@pytest.mark.parametrize("shape", [
+    # logN nq qbits K pbits dnum nlimbs
+    (8, 4, 40, 2, 50, 2, 4),
+    (8, 4, 40, 2, 50, 2, 3),      # lower level, ragged last digit
+    (8, 4, 40, 1, 50, 4, 4),      # alpha = 1
+    (8, 6, 50, 3, 60, 2, 6),
+    (8, 6, 50, 3, 60, 2, 2),      # single digit present
+    (8, 5, 50, 5, 60, 1, 5),      # dnum = 1
+])
+def test_keyswitch_identity(shape):
+    """ks.b + ks.a*s = d*s_from + small: the textbook correctness of hybrid key switching.
+    Bound: ModDown rounding (K/2+1)(1+h) plus key noise beta*alpha*q_max*N*6sigma/P."""
+    logN, nq, qb, K, pb, dnum, nlimbs = shape
+    p = make_params(logN, nq, qb, K, pb, dnum)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 5, hamming_weight=32)
+    s_from = ref.automorph_signed(keys.s, 5)
+    evk = keys.evk_for(s_from)
+    noise = ks_noise(p, c, keys, nlimbs, s_from, evk, 77)
+    P = 1
+    for x in p.p:
+        P *= x
+    Qj = 1
+    for x in p.q[:p.alpha]:
+        Qj *= x
+    bound = (K / 2 + 1) * (1 + 32) + p.beta(nlimbs) * Qj * p.N * 20 / P
+    assert noise <= bound, (noise, bound)
+    assert noise < min(p.q) / 4
+
+
+def test_keyswitch_with_wrong_key_is_garbage():
+    p = make_params(8, 4, 40, 2, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 5, hamming_weight=32)
+    s_from = ref.automorph_signed(keys.s, 5)
+    evk = keys.evk_for(ref.automorph_signed(keys.s, 25))
+    assert ks_noise(p, c, keys, 4, s_from, evk, 77) > 2**100
+
+
+@pytest.mark.parametrize("name", ["tiny_hrot_k2", "tiny_hrot_d4"])
+def test_hrot_rotates_slots_tiny(name):
+    """decrypt(HRot_k(ct)) = slots rotated left by k, max |err| < 2^-16 at Delta = 2^30, N = 2^12."""
+    p = config_params(name)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 21)
+    z = uniform_slots(8, p.N // 2)
+    ct = keys.encrypt_slots(z, 2.0**30, len(p.q))
+    for k in (1, 1234):
+        g = galois_element(k, p.logN)
+        out = c.hrot(ct[None], g, keys.rotation_key(g))[0]
+        err = np.max(np.abs(keys.decrypt_slots(out, 2.0**30) - np.roll(z, -k)))
+        assert err < 2.0**-16, err
+
+
+def test_hrot_literal_tiny_config_is_noise_unsound():
+    """One 50-bit special prime for 80-bit digits: the integer identities hold but the slots drown in
+    key-switch noise. Recorded so nobody mistakes the literal config for a decrypt test."""
+    p = config_params("tiny_hrot")
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 21)
+    z = uniform_slots(8, p.N // 2)
+    ct = keys.encrypt_slots(z, 2.0**30, len(p.q))
+    g = galois_element(3, p.logN)
+    out = c.hrot(ct[None], g, keys.rotation_key(g))[0]
+    err = np.max(np.abs(keys.decrypt_slots(out, 2.0**30) - np.roll(z, -3)))
+    assert err > 1.0
+
+
+def test_hmult_relin_multiplies_slots():
+    p = make_params(10, 4, 40, 2, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 31)
+    z1 = normal_slots(1, p.N // 2, 0.1)
+    z2 = normal_slots(2, p.N // 2, 0.1)
+    a = keys.encrypt_slots(z1, 2.0**30, 4)
+    b = keys.encrypt_slots(z2, 2.0**30, 4)
+    out = c.hmult_relin(a[None], b[None], keys.relin_key())[0]
+    err = np.max(np.abs(keys.decrypt_slots(out, 2.0**60) - z1 * z2))
+    assert err < 2.0**-16, err
+    # without relinearisation the 3-component product decrypts to the same thing (pins d0,d1,d2 ordering)
+    ids = [0, 1, 2, 3]
+    d0 = c.pointwise(a[0:1], b[0:1], ids, "mul")
+    d1 = c.pointwise(c.pointwise(a[0:1], b[1:2], ids, "mul"), c.pointwise(a[1:2], b[0:1], ids, "mul"), ids, "add")
+    d2 = c.pointwise(a[1:2], b[1:2], ids, "mul")
+    three = np.concatenate([d0, d1, d2])
+    err3 = np.max(np.abs(ref.decode(c.decrypt_centred(three, keys.s), p.N, 2.0**60) - z1 * z2))
+    assert err3 < 2.0**-16
+
+
+def test_pcmm_bsgs_is_a_matrix_product():
+    """Diagonal BSGS with n1*n2 = d diagonals on vectors x||x packed in d2-slot segments: y = x W."""
+    p = make_params(8, 4, 40, 2, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 41)
+    S = p.N // 2
+    dim, seg, n1, n2 = 6, 16, 3, 2
+    ntok = S // seg
+    rng = np.random.default_rng(0)
+    X = rng.uniform(-1, 1, (ntok, dim))
+    W = rng.normal(0, 0.5, (dim, dim))
+    z = np.zeros(S)
+    for t in range(ntok):
+        z[t * seg:t * seg + dim] = X[t]
+        z[t * seg + dim:t * seg + 2 * dim] = X[t]
+    ct = keys.encrypt_slots(z, 2.0**30, 4)
+    # diagonal (g,b): at segment offset j' in [g*n1, g*n1+dim): W[(j'+b) % dim][j' - g*n1]
+    pts = np.empty((n2, n1, 4, p.N), dtype=np.uint64)
+    for g in range(n2):
+        for b in range(n1):
+            dvec = np.zeros(S)
+            for t in range(ntok):
+                for j in range(dim):
+                    jp = j + g * n1
+                    dvec[t * seg + jp] = W[(jp + b) % dim][j]
+            pts[g, b] = encode_plain_eval(c, dvec, 2.0**30, 4)
+    baby = [keys.rotation_key(galois_element(b, p.logN)) for b in range(1, n1)]
+    # giant step rotates RIGHT-aligned partial sums back by g*n1: slot j' = j + g*n1 -> j
+    giant = [keys.rotation_key(galois_element(g * n1, p.logN)) for g in range(1, n2)]
+    out = c.pcmm_bsgs(ct[None], pts, n1, n2, 1, baby, giant)[0]
+    y = keys.decrypt_slots(out, 2.0**60).real
+    Y = X @ W
+    for t in range(ntok):
+        assert np.max(np.abs(y[t * seg:t * seg + dim] - Y[t])) < 2.0**-14
+
+
+def test_hrot_rotates_slots_at_full_size():
+    """N = 2^16, 24 limbs of 50 bits, 8 special 60-bit primes, dnum = 3, Delta = 2^40:
+    decrypt(HRot_k(ct)) equals the slot vector rotated left by k with max |err| < 2^-20."""
+    p = config_params("keyswitch_micro")
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 51)
+    z = uniform_slots(9, p.N // 2)
+    ct = keys.encrypt_slots(z, 2.0**40, len(p.q))
+    k = 12345
+    g = galois_element(k, p.logN)
+    out = c.hrot(ct[None], g, keys.rotation_key(g))[0]
+    err = np.max(np.abs(keys.decrypt_slots(out, 2.0**40) - np.roll(z, -k)))
+    assert err < 2.0**-20, err
