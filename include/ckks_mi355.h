@@ -1,0 +1,157 @@
+/*
+ * ckks_mi355 - batched RNS-CKKS polynomial arithmetic on one AMD Instinct MI355X (gfx950).
+ *
+ * C ABI of the hot path under encrypted Transformer inference: per-limb negacyclic
+ * NTT/INTT, Galois automorphism, hybrid key switching (ModUp to the P-extended basis,
+ * inner product with the evaluation key, ModDown), and on top of those HRot,
+ * HMult+relinearize and the diagonal BSGS ciphertext-plaintext matmul.
+ *
+ * Conventions common to all calls
+ * -------------------------------
+ * Ring: Z_q[x]/(x^N+1), N = 2^logN (paper Sec. 2.1). Coefficients are held in RNS form
+ * over the main primes q_0..q_L and, during key switching only, the special primes
+ * p_0..p_{K-1} (paper Sec. 2.1, last paragraph; Sec. 2.2). A "modulus id" indexes the
+ * list q_0..q_L, p_0..p_{K-1} given at context creation.
+ *
+ * Layout: RNS-major (paper Sec. 2.2): uint64 tensors with the N residues of one modulus
+ * contiguous. Polynomial batches are [npoly][nlimbs][N]; ciphertext batches are
+ * [B][2][nlimbs][N] holding (c0, c1) with Dec = c0 + c1*s; a ciphertext at nlimbs limbs
+ * uses moduli q_0..q_{nlimbs-1}. Evaluation keys are [dnum][2][L+1+K][N] with row 0 = b,
+ * row 1 = a, over ALL moduli of the context (q rows first, then p rows).
+ *
+ * Domain: the "evaluation domain" is the output order of ckks_ntt: index k holds the
+ * polynomial's value at psi^(2*bitrev_logN(k)+1). Ciphertexts, keys and pre-encoded
+ * plaintexts cross this ABI in the evaluation domain. Every residue crossing the ABI
+ * must be canonical (in [0, modulus)) and every output is canonical.
+ *
+ * Pointers: arguments documented "device" are device addresses on the context's GPU and
+ * are owned by the caller (the library never frees or reallocates them); arguments
+ * documented "host" are ordinary host pointers read before the call returns. The
+ * library owns only the context and its constant tables.
+ *
+ * Streams: every call enqueues its kernels on `stream` (a hipStream_t passed as void*;
+ * NULL = the default stream) and returns without synchronising. Workspace passed to a
+ * call must stay untouched until that stream has drained the call.
+ *
+ * Errors: calls return CKKS_OK or a negative code; they never throw or abort. After a
+ * failure ckks_last_error() returns a thread-local message. Nothing is enqueued when an
+ * argument check fails.
+ */
+#ifndef CKKS_MI355_H
+#define CKKS_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CKKS_OK 0
+#define CKKS_EINVAL (-1)     /* null pointer, bad modulus, even Galois element, ... */
+#define CKKS_ESHAPE (-2)     /* limb count / batch / digit count outside what the context supports */
+#define CKKS_EWORKSPACE (-3) /* workspace pointer null, misaligned or smaller than ckks_workspace_bytes() */
+#define CKKS_EHIP (-4)       /* a HIP runtime call failed; message holds hipGetErrorString */
+
+#define CKKS_OP_KEYSWITCH 1
+#define CKKS_OP_HROT 2
+#define CKKS_OP_HMULT_RELIN 3
+#define CKKS_OP_PCMM_BSGS 4
+
+typedef struct ckks_ctx ckks_ctx;
+
+/* Thread-local description of the last failure on this thread ("" if none). */
+const char* ckks_last_error(void);
+
+/*
+ * Create a context on GPU `device` for ring degree 2^logN (10 <= logN <= 17), main primes
+ * q[0..nq) (the top level, L+1 = nq), special primes p[0..np), and digit count dnum
+ * (digit width alpha = ceil(nq/dnum) limbs; paper Sec. 2.1: special primes "used for digit
+ * decomposition"). psi[i] is a primitive 2N-th root of unity modulo the i-th modulus
+ * (q first, then p). All three arrays are host pointers. Every modulus must be a distinct
+ * prime < 2^61 congruent to 1 mod 2N, and psi[i]^N must be -1; otherwise CKKS_EINVAL.
+ * Builds twiddle tables and base-conversion constants in device memory owned by the context.
+ */
+int ckks_ctx_create(ckks_ctx** ctx, uint32_t logN, const uint64_t* q, uint32_t nq, const uint64_t* p, uint32_t np,
+                    uint32_t dnum, const uint64_t* psi, int device);
+int ckks_ctx_destroy(ckks_ctx* ctx);
+
+/*
+ * Bytes of device workspace that `op` (CKKS_OP_*) needs for a batch of `batch`
+ * ciphertexts at `nlimbs` limbs; n1 is the baby-step count for CKKS_OP_PCMM_BSGS and is
+ * ignored otherwise. Returns 0 on a bad argument. Workspace must be 256-byte aligned.
+ */
+size_t ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch, uint32_t nlimbs, uint32_t n1);
+
+/*
+ * Forward / inverse negacyclic NTT of every limb-vector of data[npoly][nlimbs][N]
+ * (device, in place). Limb slot l uses modulus id limb_ids[l] (host array of nlimbs ids).
+ * Forward: coefficient order in, evaluation order (see above) out. Inverse is its exact
+ * inverse, including the 1/N factor (paper Sec. 3.2.1: NTT/INTT couple all coefficients
+ * within one modulus).
+ */
+int ckks_ntt(ckks_ctx* ctx, uint64_t* data, uint32_t npoly, const uint32_t* limb_ids, uint32_t nlimbs, void* stream);
+int ckks_intt(ckks_ctx* ctx, uint64_t* data, uint32_t npoly, const uint32_t* limb_ids, uint32_t nlimbs, void* stream);
+
+/*
+ * Galois automorphism a(X) -> a(X^galois_elt) on in[npoly][nlimbs][N] -> out (device, out
+ * must not overlap in). galois_elt must be odd and < 2N. eval_domain != 0: operands are
+ * in the evaluation domain (a pure index permutation); eval_domain == 0: coefficient
+ * domain (permutation with sign flips). Paper Sec. 3.2.1 (automorphisms, intra-prime
+ * coupling); Sec. 2.1 (Rot).
+ */
+int ckks_automorph(ckks_ctx* ctx, uint64_t* out, const uint64_t* in, uint32_t npoly, const uint32_t* limb_ids,
+                   uint32_t nlimbs, uint32_t galois_elt, int eval_domain, void* stream);
+
+/*
+ * Hybrid key switch (paper Sec. 2.1: extend to Z_{Q*P}, multiply by the key, reduce back
+ * to Z_Q; Sec. 3.2.1: ModUp computes new residues from all residues of a digit).
+ *   d      device [B][nlimbs][N], evaluation domain, moduli q_0..q_{nlimbs-1}
+ *   evk    device [dnum][2][L+1+K][N]
+ *   ks_out device [B][2][nlimbs][N]: ks_out[.,0] + ks_out[.,1]*s = d*s_from + small error
+ * The digits are groups of alpha consecutive limbs; at nlimbs < L+1 only the first
+ * ceil(nlimbs/alpha) digits exist and the last may be short. Base conversion uses the
+ * centred representative. galois_elt is informational (the permutation is NOT applied
+ * here); dnum must equal the context's. ks_out must not overlap d.
+ */
+int ckks_keyswitch(ckks_ctx* ctx, uint64_t* ks_out, const uint64_t* d, uint32_t B, uint32_t nlimbs,
+                   const uint64_t* evk, uint32_t galois_elt, uint32_t dnum, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * HRot: ct_out = (sigma_g(c0) + ks.b, ks.a) with ks = keyswitch(sigma_g(c1), evk_rot),
+ * g = galois_elt; one (g, key) pair for the whole batch (paper Sec. 2.1: Rot shifts the
+ * slots cyclically; g = 5^k mod 2N rotates left by k). ct_in, ct_out: device
+ * [B][2][nlimbs][N], must not overlap.
+ */
+int ckks_hrot(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+              uint32_t galois_elt, const uint64_t* evk_rot, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * HMult + relinearize (paper Sec. 2.1: CMult, Relin): with ct_a = (a0,a1), ct_b = (b0,b1):
+ * d0 = a0*b0, d1 = a0*b1 + a1*b0, d2 = a1*b1 (pointwise per limb), ks = keyswitch(d2,
+ * evk_mult), ct_out = (d0 + ks.b, d1 + ks.a). No rescale: the output scale is the product
+ * of the input scales. ct_out may alias neither input.
+ */
+int ckks_hmult_relin(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_a, const uint64_t* ct_b, uint32_t B,
+                     uint32_t nlimbs, const uint64_t* evk_mult, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Diagonal baby-step/giant-step ciphertext-plaintext matmul, one rotation at a time, no
+ * hoisting (paper Sec. 5.1 "Implementation"; Sec. 3.2.2 BSGS matmul):
+ *   ct_out = sum_{g<n2} rot_{g*n1*stride}( sum_{b<n1} pt_diag[g][b] (.) rot_{b*stride}(ct_in) )
+ * where rot_r is HRot with Galois element 5^r mod 2N and rot_0 is the identity.
+ *   pt_diag   device [n2][n1][nlimbs][N], evaluation domain, shared by the whole batch
+ *   evk_baby  host array of n1-1 device pointers; evk_baby[b-1] switches 5^(b*stride)
+ *   evk_giant host array of n2-1 device pointers; evk_giant[g-1] switches 5^(g*n1*stride)
+ * ct_in, ct_out: device [B][2][nlimbs][N], must not overlap. Output scale = input scale
+ * times the plaintext scale (no rescale).
+ */
+int ckks_pcmm_bsgs(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                   const uint64_t* pt_diag, uint32_t n1, uint32_t n2, uint32_t stride,
+                   const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws, size_t ws_bytes,
+                   void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKKS_MI355_H */

@@ -1,0 +1,157 @@
+"""ctypes binding of include/ckks_mi355.h. Argument marshalling only; every step runs in the HIP kernels.
+
+Tensors are torch CUDA tensors with 8-byte elements (torch.int64 or torch.uint64 storage of the
+uint64 residues), contiguous, on the context's device. Calls are enqueued on torch's current stream.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libckks_mi355.so")
+
+OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS = 1, 2, 3, 4
+
+_SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
+            "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs"]
+
+
+class CkksError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("ckks_mi355 error %d: %s" % (code, msg))
+        self.code = code
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def exported_symbols():
+    return list(_SYMBOLS)
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libckks_mi355.so is not built: run `python -m paper_2604_03425_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(_LIB_PATH)
+    u64p, u32p, vp = C.c_void_p, C.POINTER(C.c_uint32), C.c_void_p
+    lib.ckks_last_error.restype = C.c_char_p
+    lib.ckks_ctx_create.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_uint64), C.c_uint32,
+                                    C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64), C.c_int]
+    lib.ckks_ctx_destroy.argtypes = [vp]
+    lib.ckks_workspace_bytes.restype = C.c_size_t
+    lib.ckks_workspace_bytes.argtypes = [vp, C.c_int, C.c_uint32, C.c_uint32, C.c_uint32]
+    lib.ckks_ntt.argtypes = [vp, u64p, C.c_uint32, u32p, C.c_uint32, vp]
+    lib.ckks_intt.argtypes = [vp, u64p, C.c_uint32, u32p, C.c_uint32, vp]
+    lib.ckks_automorph.argtypes = [vp, u64p, u64p, C.c_uint32, u32p, C.c_uint32, C.c_uint32, C.c_int, vp]
+    lib.ckks_keyswitch.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, vp,
+                                   C.c_size_t, vp]
+    lib.ckks_hrot.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
+    lib.ckks_hmult_relin.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
+    lib.ckks_pcmm_bsgs.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, C.c_uint32,
+                                   C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
+    for name in _SYMBOLS:
+        getattr(lib, name)
+    return lib
+
+
+_lib = _load()
+
+
+def _check(rc):
+    if rc != 0:
+        raise CkksError(rc, _lib.ckks_last_error().decode())
+
+
+def _ptr(t, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.element_size() != 8 or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous CUDA tensor with 8-byte elements" % name)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ids(ids):
+    arr = (C.c_uint32 * len(ids))(*[int(i) for i in ids])
+    return arr, C.c_uint32(len(ids))
+
+
+class Context:
+    """Owns a ckks_ctx. `params` needs logN, q, p, dnum, psi (see ckks_inputs.CkksParams)."""
+
+    def __init__(self, params, device=0):
+        self.params = params
+        self.N = 1 << params.logN
+        self.nq, self.np_ = len(params.q), len(params.p)
+        q = (C.c_uint64 * self.nq)(*params.q)
+        p = (C.c_uint64 * max(1, self.np_))(*(params.p or [0]))
+        psi = (C.c_uint64 * (self.nq + self.np_))(*params.psi)
+        self.handle = C.c_void_p()
+        self.device = device
+        _check(_lib.ckks_ctx_create(C.byref(self.handle), params.logN, q, self.nq, p, self.np_, params.dnum, psi, device))
+
+    def close(self):
+        if self.handle:
+            _lib.ckks_ctx_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace(self, op, batch, nlimbs, n1=0):
+        n = ckks_workspace_bytes(self, op, batch, nlimbs, n1)
+        if n == 0:
+            raise CkksError(-2, "bad shape for workspace query")
+        return torch.empty(n // 8, dtype=torch.int64, device="cuda:%d" % self.device)
+
+
+def ckks_workspace_bytes(ctx, op, batch, nlimbs, n1=0):
+    return int(_lib.ckks_workspace_bytes(ctx.handle, op, batch, nlimbs, n1))
+
+
+def ckks_ntt(ctx, data, npoly, limb_ids):
+    ids, n = _ids(limb_ids)
+    _check(_lib.ckks_ntt(ctx.handle, _ptr(data, "data"), npoly, ids, n, _stream()))
+
+
+def ckks_intt(ctx, data, npoly, limb_ids):
+    ids, n = _ids(limb_ids)
+    _check(_lib.ckks_intt(ctx.handle, _ptr(data, "data"), npoly, ids, n, _stream()))
+
+
+def ckks_automorph(ctx, out, inp, npoly, limb_ids, galois_elt, eval_domain):
+    ids, n = _ids(limb_ids)
+    _check(_lib.ckks_automorph(ctx.handle, _ptr(out, "out"), _ptr(inp, "in"), npoly, ids, n, galois_elt,
+                               1 if eval_domain else 0, _stream()))
+
+
+def ckks_keyswitch(ctx, ks_out, d, B, nlimbs, evk, galois_elt, dnum, ws):
+    _check(_lib.ckks_keyswitch(ctx.handle, _ptr(ks_out, "ks_out"), _ptr(d, "d"), B, nlimbs, _ptr(evk, "evk"),
+                               galois_elt, dnum, _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_hrot(ctx, ct_out, ct_in, B, nlimbs, galois_elt, evk_rot, ws):
+    _check(_lib.ckks_hrot(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, galois_elt,
+                          _ptr(evk_rot, "evk_rot"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_hmult_relin(ctx, ct_out, ct_a, ct_b, B, nlimbs, evk_mult, ws):
+    _check(_lib.ckks_hmult_relin(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_a, "ct_a"), _ptr(ct_b, "ct_b"), B, nlimbs,
+                                 _ptr(evk_mult, "evk_mult"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws):
+    baby = (C.c_void_p * max(1, n1 - 1))(*[_ptr(k, "evk_baby").value for k in evk_baby])
+    giant = (C.c_void_p * max(1, n2 - 1))(*[_ptr(k, "evk_giant").value for k in evk_giant])
+    if len(evk_baby) != n1 - 1 or len(evk_giant) != n2 - 1:
+        raise ValueError("need n1-1 baby-step keys and n2-1 giant-step keys")
+    _check(_lib.ckks_pcmm_bsgs(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs,
+                               _ptr(pt_diag, "pt_diag"), n1, n2, stride, baby, giant, _ptr(ws, "ws"), ws.numel() * 8,
+                               _stream()))

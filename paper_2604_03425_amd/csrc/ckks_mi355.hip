@@ -1,0 +1,634 @@
+// Host side of libckks_mi355: context tables, argument checks, launch sequences.
+#include "../../include/ckks_mi355.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "kernels.cuh"
+
+typedef unsigned __int128 u128;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+#define HIP_TRY(expr)                                                                            \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess) return fail(CKKS_EHIP, std::string(#expr ": ") + hipGetErrorString(e_)); \
+  } while (0)
+
+// ---- host modular arithmetic (table generation only) ----
+inline u64 h_mul(u64 a, u64 b, u64 m) { return (u64)((u128)a * b % m); }
+u64 h_pow(u64 a, u64 e, u64 m) {
+  u64 r = 1;
+  a %= m;
+  for (; e; e >>= 1) {
+    if (e & 1) r = h_mul(r, a, m);
+    a = h_mul(a, a, m);
+  }
+  return r;
+}
+inline u64 h_inv(u64 a, u64 m) { return h_pow(a, m - 2, m); }
+inline u64 h_shoup(u64 w, u64 m) { return (u64)(((u128)w << 64) / m); }
+bool h_is_prime(u64 n) {
+  if (n < 2) return false;
+  const u64 bases[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+  for (u64 b : bases)
+    if (n % b == 0) return n == b;
+  u64 d = n - 1;
+  int r = 0;
+  while (!(d & 1)) d >>= 1, r++;
+  for (u64 a : bases) {
+    u64 x = h_pow(a, d, n);
+    if (x == 1 || x == n - 1) continue;
+    bool composite = true;
+    for (int i = 1; i < r && composite; i++) {
+      x = h_mul(x, x, n);
+      if (x == n - 1) composite = false;
+    }
+    if (composite) return false;
+  }
+  return true;
+}
+inline u32 h_brev(u32 x, u32 bits) {
+  u32 r = 0;
+  for (u32 i = 0; i < bits; i++) r |= ((x >> i) & 1) << (bits - 1 - i);
+  return r;
+}
+
+struct Pass {
+  u32 s0, k, logC, tile_log;
+};
+
+// Base-conversion constants for ciphertexts at one limb count.
+struct LevelTables {
+  u32 nlimbs = 0, beta = 0, next = 0;
+  ulonglong2* up_inv = nullptr;  // [beta][alpha]
+  u64* up_mat = nullptr;         // [beta][alpha+1][next]
+  ulonglong2* dn_inv = nullptr;  // [K]
+  u64* dn_mat = nullptr;         // [K+1][nlimbs]
+  ulonglong2* pinv = nullptr;    // [nlimbs]
+};
+
+}  // namespace
+
+struct ckks_ctx {
+  int device = 0;
+  u32 logN = 0, N = 0, nq = 0, np = 0, nm = 0, dnum = 0, alpha = 0;
+  std::vector<u64> mod, psi;
+  ModInfo* d_mods = nullptr;
+  ulonglong2* d_tw_fwd = nullptr;
+  ulonglong2* d_tw_inv = nullptr;
+  std::vector<Pass> passes;  // forward order
+  std::mutex mu;
+  std::map<u32, LevelTables> levels;
+};
+
+namespace {
+
+template <class T>
+int upload(T** dst, const std::vector<T>& src) {
+  HIP_TRY(hipMalloc((void**)dst, std::max<size_t>(1, src.size()) * sizeof(T)));
+  if (!src.empty()) HIP_TRY(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+  return CKKS_OK;
+}
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
+  std::lock_guard<std::mutex> lock(c->mu);
+  auto it = c->levels.find(nlimbs);
+  if (it != c->levels.end()) {
+    *out = &it->second;
+    return CKKS_OK;
+  }
+  LevelTables t;
+  t.nlimbs = nlimbs;
+  t.beta = (nlimbs + c->alpha - 1) / c->alpha;
+  t.next = nlimbs + c->np;
+  const u32 alpha = c->alpha, K = c->np, next = t.next;
+  auto ext_mod = [&](u32 s) { return s < nlimbs ? c->mod[s] : c->mod[c->nq + (s - nlimbs)]; };
+
+  std::vector<ulonglong2> up_inv((size_t)t.beta * alpha, ulonglong2{0, 0});
+  std::vector<u64> up_mat((size_t)t.beta * (alpha + 1) * next, 0);
+  for (u32 j = 0; j < t.beta; j++) {
+    u32 lo = j * alpha, hi = std::min(lo + alpha, nlimbs);
+    for (u32 i = lo; i < hi; i++) {
+      u64 qi = c->mod[i], h = 1;
+      for (u32 k = lo; k < hi; k++)
+        if (k != i) h = h_mul(h, c->mod[k] % qi, qi);
+      u64 inv = h_inv(h, qi);
+      up_inv[(size_t)j * alpha + (i - lo)] = ulonglong2{inv, h_shoup(inv, qi)};
+      for (u32 s = 0; s < next; s++) {
+        u64 m = ext_mod(s), v = 1;
+        for (u32 k = lo; k < hi; k++)
+          if (k != i) v = h_mul(v, c->mod[k] % m, m);
+        up_mat[((size_t)j * (alpha + 1) + (i - lo)) * next + s] = v;
+      }
+    }
+    for (u32 s = 0; s < next; s++) {
+      u64 m = ext_mod(s), v = 1;
+      for (u32 k = lo; k < hi; k++) v = h_mul(v, c->mod[k] % m, m);
+      up_mat[((size_t)j * (alpha + 1) + alpha) * next + s] = v ? m - v : 0;
+    }
+  }
+  std::vector<ulonglong2> dn_inv(K), pinv(nlimbs);
+  std::vector<u64> dn_mat((size_t)(K + 1) * nlimbs, 0);
+  for (u32 k = 0; k < K; k++) {
+    u64 pk = c->mod[c->nq + k], h = 1;
+    for (u32 r = 0; r < K; r++)
+      if (r != k) h = h_mul(h, c->mod[c->nq + r] % pk, pk);
+    u64 inv = h_inv(h, pk);
+    dn_inv[k] = ulonglong2{inv, h_shoup(inv, pk)};
+    for (u32 i = 0; i < nlimbs; i++) {
+      u64 m = c->mod[i], v = 1;
+      for (u32 r = 0; r < K; r++)
+        if (r != k) v = h_mul(v, c->mod[c->nq + r] % m, m);
+      dn_mat[(size_t)k * nlimbs + i] = v;
+    }
+  }
+  for (u32 i = 0; i < nlimbs; i++) {
+    u64 m = c->mod[i], v = 1;
+    for (u32 r = 0; r < K; r++) v = h_mul(v, c->mod[c->nq + r] % m, m);
+    dn_mat[(size_t)K * nlimbs + i] = v ? m - v : 0;
+    u64 inv = h_inv(v, m);
+    pinv[i] = ulonglong2{inv, h_shoup(inv, m)};
+  }
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  int rc;
+  if ((rc = upload(&t.up_inv, up_inv)) || (rc = upload(&t.up_mat, up_mat)) || (rc = upload(&t.dn_inv, dn_inv)) ||
+      (rc = upload(&t.dn_mat, dn_mat)) || (rc = upload(&t.pinv, pinv)))
+    return rc;
+  auto res = c->levels.emplace(nlimbs, t);
+  *out = &res.first->second;
+  return CKKS_OK;
+}
+
+LimbMap identity_map(u32 n) {
+  LimbMap m;
+  for (u32 i = 0; i < CKKS_MAX_SLOTS; i++) m.id[i] = (unsigned char)(i < n ? i : 0);
+  return m;
+}
+// slots 0..nlimbs-1 -> q ids, then the K special primes
+LimbMap ext_map(const ckks_ctx* c, u32 nlimbs) {
+  LimbMap m = identity_map(nlimbs);
+  for (u32 k = 0; k < c->np; k++) m.id[nlimbs + k] = (unsigned char)(c->nq + k);
+  return m;
+}
+
+// Enqueue a transform over data[npoly] x slots [slot0, slot0+nslots) of rows that are poly_stride apart.
+int launch_ntt(const ckks_ctx* c, bool inverse, u64* data, u32 npoly, u64 poly_stride, u32 slot0, u32 nslots,
+               const LimbMap& ids_from_slot0, u32 skip_beta, u32 skip_nq, hipStream_t st) {
+  if (npoly == 0 || nslots == 0) return CKKS_OK;
+  NttArgs a;
+  a.data = data + (size_t)slot0 * c->N;
+  a.tw = inverse ? c->d_tw_inv : c->d_tw_fwd;
+  a.mods = c->d_mods;
+  a.poly_stride = poly_stride;
+  a.logN = c->logN;
+  a.skip_beta = skip_beta;
+  a.skip_alpha = c->alpha;
+  a.skip_nq = skip_nq;
+  a.ids = ids_from_slot0;
+  const size_t np = c->passes.size();
+  for (size_t i = 0; i < np; i++) {
+    const Pass& p = c->passes[inverse ? np - 1 - i : i];
+    a.s0 = p.s0;
+    a.k = p.k;
+    a.logC = p.logC;
+    a.tile_log = p.tile_log;
+    dim3 grid(npoly, c->N >> p.tile_log, nslots);
+    size_t lds = sizeof(u64) << p.tile_log;
+    if (inverse)
+      hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, dim3(NTT_THREADS), lds, st, a);
+    else
+      hipLaunchKernelGGL(ntt_pass_kernel<false>, grid, dim3(NTT_THREADS), lds, st, a);
+  }
+  HIP_TRY(hipGetLastError());
+  return CKKS_OK;
+}
+
+u32 inv_mod_pow2(u32 g, u32 bits) {  // inverse of odd g modulo 2^bits
+  u32 x = 1;
+  for (int i = 0; i < 6; i++) x *= 2 - g * x;
+  return x & ((bits >= 32) ? 0xFFFFFFFFu : ((1u << bits) - 1));
+}
+
+int launch_automorph(const ckks_ctx* c, u64* out, u64 out_stride, const u64* in, u64 in_stride, u32 npoly, u32 nslots,
+                     const LimbMap& ids, u32 g, bool eval_domain, hipStream_t st) {
+  if (npoly == 0 || nslots == 0) return CKKS_OK;
+  AutoArgs a;
+  a.out = out;
+  a.in = in;
+  a.mods = c->d_mods;
+  a.out_poly_stride = out_stride;
+  a.in_poly_stride = in_stride;
+  a.logN = c->logN;
+  a.g = g;
+  a.g_inv = inv_mod_pow2(g, c->logN + 1);
+  a.eval_domain = eval_domain ? 1 : 0;
+  a.ids = ids;
+  hipLaunchKernelGGL(automorph_kernel, dim3(c->N / 256, nslots, npoly), dim3(256), 0, st, a);
+  HIP_TRY(hipGetLastError());
+  return CKKS_OK;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct KsLayout {
+  size_t dcoef, ext, acc, tq, total;
+};
+KsLayout ks_layout(const ckks_ctx* c, u32 B, u32 nlimbs) {
+  const size_t N = c->N, next = nlimbs + c->np, beta = (nlimbs + c->alpha - 1) / c->alpha;
+  KsLayout L;
+  size_t off = 0;
+  L.dcoef = off; off += align256((size_t)B * nlimbs * N * 8);
+  L.ext = off;   off += align256((size_t)B * beta * next * N * 8);
+  L.acc = off;   off += align256((size_t)B * 2 * next * N * 8);
+  L.tq = off;    off += align256((size_t)B * 2 * nlimbs * N * 8);
+  L.total = off;
+  return L;
+}
+
+// Key switch of d (eval domain) with evk into out; add_mask bit c set: out[.,c] += ks instead of = ks.
+int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const u64* evk, u32 add_mask, char* ws,
+                   hipStream_t st) {
+  const LevelTables* lt;
+  int rc = get_level(c, nlimbs, &lt);
+  if (rc) return rc;
+  const u32 N = c->N, next = lt->next, beta = lt->beta, K = c->np;
+  KsLayout L = ks_layout(c, B, nlimbs);
+  u64* dcoef = (u64*)(ws + L.dcoef);
+  u64* ext = (u64*)(ws + L.ext);
+  u64* acc = (u64*)(ws + L.acc);
+  u64* tq = (u64*)(ws + L.tq);
+  const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
+
+  // 1. coefficient form of d
+  HIP_TRY(hipMemcpyAsync(dcoef, d, (size_t)B * nlimbs * N * 8, hipMemcpyDeviceToDevice, st));
+  if ((rc = launch_ntt(c, true, dcoef, B, (u64)nlimbs * N, 0, nlimbs, qmap, 0, 0, st))) return rc;
+  // 2. ModUp every digit to the slots it does not own
+  {
+    ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
+    hipLaunchKernelGGL(modup_kernel, dim3(N / BCONV_THREADS, beta, B), dim3(BCONV_THREADS),
+                       (size_t)c->alpha * BCONV_THREADS * 8, st, a);
+    HIP_TRY(hipGetLastError());
+  }
+  // 3. forward transform of the converted slots
+  if ((rc = launch_ntt(c, false, ext, B * beta, (u64)next * N, 0, next, emap, beta, nlimbs, st))) return rc;
+  // 4. inner product with the key
+  {
+    InnerArgs a{d, ext, evk, acc, c->d_mods, c->logN, nlimbs, c->nq, c->nm, c->alpha, beta, next};
+    hipLaunchKernelGGL(inner_kernel, dim3(B, N / 256, next), dim3(256), 0, st, a);
+    HIP_TRY(hipGetLastError());
+  }
+  // 5. special limbs of both accumulators back to coefficient form
+  {
+    LimbMap pmap;
+    for (u32 k = 0; k < CKKS_MAX_SLOTS; k++) pmap.id[k] = (unsigned char)(k < K ? c->nq + k : 0);
+    if ((rc = launch_ntt(c, true, acc, B * 2, (u64)next * N, nlimbs, K, pmap, 0, 0, st))) return rc;
+  }
+  // 6. ModDown base conversion P -> Q_l
+  {
+    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat, c->logN, nlimbs, c->nq, K, next};
+    hipLaunchKernelGGL(moddown_kernel, dim3(N / BCONV_THREADS, B * 2), dim3(BCONV_THREADS),
+                       (size_t)std::max<u32>(1, K) * BCONV_THREADS * 8, st, a);
+    HIP_TRY(hipGetLastError());
+  }
+  // 7. its forward transform, 8. subtract, scale by P^-1, assemble
+  if ((rc = launch_ntt(c, false, tq, B * 2, (u64)nlimbs * N, 0, nlimbs, qmap, 0, 0, st))) return rc;
+  {
+    FinalArgs a{acc, tq, out, c->d_mods, lt->pinv, c->logN, nlimbs, next, add_mask};
+    hipLaunchKernelGGL(ks_final_kernel, dim3(N / 256, nlimbs, B * 2), dim3(256), 0, st, a);
+    HIP_TRY(hipGetLastError());
+  }
+  return CKKS_OK;
+}
+
+int check_common(const ckks_ctx* c, u32 B, u32 nlimbs) {
+  if (!c) return fail(CKKS_EINVAL, "null context");
+  if (nlimbs == 0 || nlimbs > c->nq) return fail(CKKS_ESHAPE, "nlimbs must be in [1, L+1]");
+  if (B == 0 || B > 32767) return fail(CKKS_ESHAPE, "batch must be in [1, 32767]");
+  if (c->np == 0) return fail(CKKS_ESHAPE, "key switching needs at least one special prime");
+  return CKKS_OK;
+}
+int check_ws(const ckks_ctx* c, int op, u32 B, u32 nlimbs, u32 n1, const void* ws, size_t ws_bytes) {
+  if (!ws || ((uintptr_t)ws & 255)) return fail(CKKS_EWORKSPACE, "workspace is null or not 256-byte aligned");
+  size_t need = ckks_workspace_bytes(c, op, B, nlimbs, n1);
+  if (ws_bytes < need)
+    return fail(CKKS_EWORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes, got " + std::to_string(ws_bytes));
+  return CKKS_OK;
+}
+bool overlap(const void* a, size_t na, const void* b, size_t nb) {
+  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+int check_ids(const ckks_ctx* c, const uint32_t* ids, u32 n, LimbMap* out) {
+  if (!ids) return fail(CKKS_EINVAL, "null limb_ids");
+  if (n == 0 || n > CKKS_MAX_SLOTS) return fail(CKKS_ESHAPE, "nlimbs must be in [1, 128]");
+  for (u32 i = 0; i < CKKS_MAX_SLOTS; i++) out->id[i] = 0;
+  for (u32 i = 0; i < n; i++) {
+    if (ids[i] >= c->nm) return fail(CKKS_EINVAL, "limb id out of range");
+    out->id[i] = (unsigned char)ids[i];
+  }
+  return CKKS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ckks_last_error(void) { return g_err.c_str(); }
+
+int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t nq, const uint64_t* p, uint32_t np,
+                    uint32_t dnum, const uint64_t* psi, int device) {
+  if (!out || !q || !psi || (np && !p)) return fail(CKKS_EINVAL, "null argument");
+  if (logN < 10 || logN > 17) return fail(CKKS_ESHAPE, "logN must be in [10, 17]");
+  if (nq == 0 || dnum == 0 || dnum > nq || nq + np > CKKS_MAX_SLOTS) return fail(CKKS_ESHAPE, "bad prime or digit count");
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  if (device < 0 || device >= ndev) return fail(CKKS_EINVAL, "no such device");
+  ckks_ctx* c = new ckks_ctx;
+  c->device = device;
+  c->logN = logN;
+  c->N = 1u << logN;
+  c->nq = nq;
+  c->np = np;
+  c->nm = nq + np;
+  c->dnum = dnum;
+  c->alpha = (nq + dnum - 1) / dnum;
+  for (u32 i = 0; i < nq; i++) c->mod.push_back(q[i]);
+  for (u32 i = 0; i < np; i++) c->mod.push_back(p[i]);
+  c->psi.assign(psi, psi + c->nm);
+  const u64 N = c->N;
+  for (u32 i = 0; i < c->nm; i++) {
+    u64 m = c->mod[i];
+    bool ok = m < (1ull << 61) && m > 2 * N && (m - 1) % (2 * N) == 0 && h_is_prime(m) && c->psi[i] < m &&
+              h_pow(c->psi[i], N, m) == m - 1;
+    for (u32 k = 0; k < i && ok; k++) ok = c->mod[k] != m;
+    if (!ok) {
+      delete c;
+      return fail(CKKS_EINVAL, "modulus " + std::to_string(i) +
+                                   " must be a distinct prime < 2^61, = 1 mod 2N, with psi^N = -1");
+    }
+  }
+  // pass plan
+  if (logN <= 12) {
+    c->passes.push_back(Pass{0, logN, 0, logN});
+  } else {
+    u32 k1 = logN - 8;
+    c->passes.push_back(Pass{0, k1, 12 - k1, 12});
+    c->passes.push_back(Pass{k1, 8, 0, 12});
+  }
+  // tables
+  std::vector<ModInfo> mods(c->nm);
+  std::vector<ulonglong2> fwd((size_t)c->nm * N), inv((size_t)c->nm * N);
+  std::vector<u64> pw(N);
+  for (u32 i = 0; i < c->nm; i++) {
+    u64 m = c->mod[i];
+    ModInfo& mi = mods[i];
+    mi.m = m;
+    mi.mu64 = (u64)((((u128)1) << 64) / m);
+    mi.c64 = (u64)((((u128)1) << 64) % m);
+    mi.c64s = h_shoup(mi.c64, m);
+    mi.ninv = h_inv(N % m, m);
+    mi.ninvs = h_shoup(mi.ninv, m);
+    pw[0] = 1;
+    for (u64 k = 1; k < N; k++) pw[k] = h_mul(pw[k - 1], c->psi[i], m);
+    for (u32 k = 0; k < N; k++) {
+      u64 w = pw[h_brev(k, logN)];
+      fwd[(size_t)i * N + k] = ulonglong2{w, h_shoup(w, m)};
+      // psi^-e = -psi^(N-e)
+      u32 e = h_brev(k, logN);
+      u64 wi = e == 0 ? 1 : m - pw[N - e];
+      inv[(size_t)i * N + k] = ulonglong2{wi, h_shoup(wi, m)};
+    }
+  }
+  DeviceGuard guard(device);
+  int rc = guard.ok ? CKKS_OK : fail(CKKS_EHIP, "cannot select device");
+  if (!rc) rc = upload(&c->d_mods, mods);
+  if (!rc) rc = upload(&c->d_tw_fwd, fwd);
+  if (!rc) rc = upload(&c->d_tw_inv, inv);
+  if (rc) {
+    ckks_ctx_destroy(c);
+    return rc;
+  }
+  *out = c;
+  return CKKS_OK;
+}
+
+int ckks_ctx_destroy(ckks_ctx* c) {
+  if (!c) return CKKS_OK;
+  DeviceGuard guard(c->device);
+  (void)hipFree(c->d_mods);
+  (void)hipFree(c->d_tw_fwd);
+  (void)hipFree(c->d_tw_inv);
+  for (auto& kv : c->levels) {
+    (void)hipFree(kv.second.up_inv);
+    (void)hipFree(kv.second.up_mat);
+    (void)hipFree(kv.second.dn_inv);
+    (void)hipFree(kv.second.dn_mat);
+    (void)hipFree(kv.second.pinv);
+  }
+  delete c;
+  return CKKS_OK;
+}
+
+size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlimbs, uint32_t n1) {
+  if (!c || B == 0 || nlimbs == 0 || nlimbs > c->nq) return 0;
+  const size_t ks = ks_layout(c, B, nlimbs).total;
+  const size_t poly = align256((size_t)B * nlimbs * c->N * 8);
+  switch (op) {
+    case CKKS_OP_KEYSWITCH: return ks;
+    case CKKS_OP_HROT: return ks + poly;
+    case CKKS_OP_HMULT_RELIN: return ks + poly;
+    case CKKS_OP_PCMM_BSGS:
+      if (n1 == 0) return 0;
+      // baby steps 1..n1-1, inner sum, rotated inner sum, HRot workspace
+      return (size_t)(n1 - 1) * 2 * poly + 2 * poly + 2 * poly + ks + poly;
+    default: return 0;
+  }
+}
+
+static int transform_entry(ckks_ctx* c, bool inverse, uint64_t* data, uint32_t npoly, const uint32_t* limb_ids,
+                           uint32_t nlimbs, void* stream) {
+  if (!c || !data) return fail(CKKS_EINVAL, "null argument");
+  LimbMap ids;
+  int rc = check_ids(c, limb_ids, nlimbs, &ids);
+  if (rc) return rc;
+  if (npoly == 0) return CKKS_OK;
+  if (npoly > 65535 * 16) return fail(CKKS_ESHAPE, "too many polynomials in one call");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  // grid.x carries the polynomial index; split very large batches
+  const u32 chunk = 32768;
+  for (u32 p0 = 0; p0 < npoly; p0 += chunk) {
+    u32 n = std::min(chunk, npoly - p0);
+    rc = launch_ntt(c, inverse, (u64*)data + (size_t)p0 * nlimbs * c->N, n, (u64)nlimbs * c->N, 0, nlimbs, ids, 0, 0,
+                    (hipStream_t)stream);
+    if (rc) return rc;
+  }
+  return CKKS_OK;
+}
+
+int ckks_ntt(ckks_ctx* c, uint64_t* data, uint32_t npoly, const uint32_t* limb_ids, uint32_t nlimbs, void* stream) {
+  return transform_entry(c, false, data, npoly, limb_ids, nlimbs, stream);
+}
+int ckks_intt(ckks_ctx* c, uint64_t* data, uint32_t npoly, const uint32_t* limb_ids, uint32_t nlimbs, void* stream) {
+  return transform_entry(c, true, data, npoly, limb_ids, nlimbs, stream);
+}
+
+int ckks_automorph(ckks_ctx* c, uint64_t* out, const uint64_t* in, uint32_t npoly, const uint32_t* limb_ids,
+                   uint32_t nlimbs, uint32_t g, int eval_domain, void* stream) {
+  if (!c || !out || !in) return fail(CKKS_EINVAL, "null argument");
+  LimbMap ids;
+  int rc = check_ids(c, limb_ids, nlimbs, &ids);
+  if (rc) return rc;
+  if (!(g & 1) || g >= 2 * c->N) return fail(CKKS_EINVAL, "galois_elt must be odd and < 2N");
+  if (npoly == 0) return CKKS_OK;
+  if (npoly > 65535) return fail(CKKS_ESHAPE, "too many polynomials in one call");
+  size_t bytes = (size_t)npoly * nlimbs * c->N * 8;
+  if (overlap(out, bytes, in, bytes)) return fail(CKKS_EINVAL, "out overlaps in");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  return launch_automorph(c, (u64*)out, (u64)nlimbs * c->N, (const u64*)in, (u64)nlimbs * c->N, npoly, nlimbs, ids, g,
+                          eval_domain != 0, (hipStream_t)stream);
+}
+
+int ckks_keyswitch(ckks_ctx* c, uint64_t* ks_out, const uint64_t* d, uint32_t B, uint32_t nlimbs, const uint64_t* evk,
+                   uint32_t galois_elt, uint32_t dnum, void* ws, size_t ws_bytes, void* stream) {
+  (void)galois_elt;
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!ks_out || !d || !evk) return fail(CKKS_EINVAL, "null argument");
+  if (dnum != c->dnum) return fail(CKKS_ESHAPE, "dnum does not match the context");
+  if ((rc = check_ws(c, CKKS_OP_KEYSWITCH, B, nlimbs, 0, ws, ws_bytes))) return rc;
+  size_t poly = (size_t)B * nlimbs * c->N * 8;
+  if (overlap(ks_out, 2 * poly, d, poly)) return fail(CKKS_EINVAL, "ks_out overlaps d");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  return keyswitch_impl(c, (u64*)ks_out, (const u64*)d, B, nlimbs, (const u64*)evk, 0, (char*)ws, (hipStream_t)stream);
+}
+
+int ckks_hrot(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
+              const uint64_t* evk, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!ct_out || !ct_in || !evk) return fail(CKKS_EINVAL, "null argument");
+  if (!(g & 1) || g >= 2 * c->N) return fail(CKKS_EINVAL, "galois_elt must be odd and < 2N");
+  if ((rc = check_ws(c, CKKS_OP_HROT, B, nlimbs, 0, ws, ws_bytes))) return rc;
+  const size_t polyN = (size_t)nlimbs * c->N, ct_bytes = (size_t)B * 2 * polyN * 8;
+  if (overlap(ct_out, ct_bytes, ct_in, ct_bytes)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  const size_t ks = ks_layout(c, B, nlimbs).total;
+  u64* d = (u64*)((char*)ws + ks);
+  const LimbMap qmap = identity_map(nlimbs);
+  // sigma(c0) -> out[.,0]; sigma(c1) -> d
+  if ((rc = launch_automorph(c, (u64*)ct_out, 2 * polyN, (const u64*)ct_in, 2 * polyN, B, nlimbs, qmap, g, true, st)))
+    return rc;
+  if ((rc = launch_automorph(c, d, polyN, (const u64*)ct_in + polyN, 2 * polyN, B, nlimbs, qmap, g, true, st))) return rc;
+  return keyswitch_impl(c, (u64*)ct_out, d, B, nlimbs, (const u64*)evk, /*add_mask=*/1, (char*)ws, st);
+}
+
+int ckks_hmult_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_a, const uint64_t* ct_b, uint32_t B,
+                     uint32_t nlimbs, const uint64_t* evk, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!ct_out || !ct_a || !ct_b || !evk) return fail(CKKS_EINVAL, "null argument");
+  if ((rc = check_ws(c, CKKS_OP_HMULT_RELIN, B, nlimbs, 0, ws, ws_bytes))) return rc;
+  const size_t ct_bytes = (size_t)B * 2 * nlimbs * c->N * 8;
+  if (overlap(ct_out, ct_bytes, ct_a, ct_bytes) || overlap(ct_out, ct_bytes, ct_b, ct_bytes))
+    return fail(CKKS_EINVAL, "ct_out overlaps an input");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  const size_t ks = ks_layout(c, B, nlimbs).total;
+  u64* d2 = (u64*)((char*)ws + ks);
+  TensorArgs a{(const u64*)ct_a, (const u64*)ct_b, (u64*)ct_out, d2, c->d_mods, c->logN, nlimbs};
+  hipLaunchKernelGGL(tensor_kernel, dim3(c->N / 256, nlimbs, B), dim3(256), 0, st, a);
+  HIP_TRY(hipGetLastError());
+  return keyswitch_impl(c, (u64*)ct_out, d2, B, nlimbs, (const u64*)evk, /*add_mask=*/3, (char*)ws, st);
+}
+
+int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                   const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
+                   const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!ct_out || !ct_in || !pt) return fail(CKKS_EINVAL, "null argument");
+  if (n1 == 0 || n2 == 0 || stride == 0) return fail(CKKS_ESHAPE, "n1, n2 and stride must be positive");
+  if ((n1 > 1 && !evk_baby) || (n2 > 1 && !evk_giant)) return fail(CKKS_EINVAL, "null key array");
+  for (u32 b = 1; b < n1; b++)
+    if (!evk_baby[b - 1]) return fail(CKKS_EINVAL, "null baby-step key");
+  for (u32 g = 1; g < n2; g++)
+    if (!evk_giant[g - 1]) return fail(CKKS_EINVAL, "null giant-step key");
+  if (2 * B > 65535) return fail(CKKS_ESHAPE, "batch too large for one call");
+  if ((rc = check_ws(c, CKKS_OP_PCMM_BSGS, B, nlimbs, n1, ws, ws_bytes))) return rc;
+  const size_t N = c->N, polyN = (size_t)nlimbs * N, ct_bytes = (size_t)B * 2 * polyN * 8;
+  if (overlap(ct_out, ct_bytes, ct_in, ct_bytes)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  const size_t ct_al = 2 * align256((size_t)B * polyN * 8);
+  char* w = (char*)ws;
+  u64* baby = (u64*)w;                  w += (size_t)(n1 - 1) * ct_al;
+  u64* inner = (u64*)w;                 w += ct_al;
+  u64* rot = (u64*)w;                   w += ct_al;
+  char* hws = w;
+  const size_t hws_bytes = ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0);
+  const u64 twoN = 2 * N;
+  auto galois = [&](u64 r) {  // 5^r mod 2N
+    u64 g = 1, b = 5;
+    for (; r; r >>= 1) {
+      if (r & 1) g = g * b % twoN;
+      b = b * b % twoN;
+    }
+    return (u32)g;
+  };
+  const size_t ct_elems = ct_al / 8;
+  for (u32 b = 1; b < n1; b++) {
+    rc = ckks_hrot(c, (uint64_t*)(baby + (size_t)(b - 1) * ct_elems), ct_in, B, nlimbs, galois((u64)b * stride), evk_baby[b - 1], hws,
+                   hws_bytes, stream);
+    if (rc) return rc;
+  }
+  for (u32 g = 0; g < n2; g++) {
+    u64* dst = g == 0 ? (u64*)ct_out : inner;
+    PmaccArgs a{(const u64*)ct_in, baby, (const u64*)pt + (size_t)g * n1 * polyN, dst, c->d_mods, c->logN, nlimbs, n1, B};
+    // baby rows are ct_elems apart; pmacc indexes them with B*2*nlimbs*N, which equals ct_elems when that is 256-aligned
+    hipLaunchKernelGGL(pmacc_kernel, dim3(N / 256, nlimbs, 2 * B), dim3(256), 0, st, a);
+    HIP_TRY(hipGetLastError());
+    if (g > 0) {
+      rc = ckks_hrot(c, (uint64_t*)rot, (const uint64_t*)inner, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws, hws_bytes, stream);
+      if (rc) return rc;
+      AddArgs ad{(u64*)ct_out, rot, c->d_mods, c->logN, nlimbs};
+      hipLaunchKernelGGL(addto_kernel, dim3(N / 256, nlimbs, 2 * B), dim3(256), 0, st, ad);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+  return CKKS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,319 @@
+// Device kernels of the RNS-CKKS hot path (gfx950, wave64).
+#pragma once
+#include "modarith.cuh"
+
+#define CKKS_MAX_SLOTS 128   // limb slots addressable by one launch (L+1+K <= 128)
+#define NTT_THREADS 256
+
+struct LimbMap {
+  unsigned char id[CKKS_MAX_SLOTS];
+};
+
+// One pass of a multi-pass transform: stages [s0, s0+k) of the logN-stage butterfly network,
+// on tiles of 2^tile_log elements = (hi blocks) x (2^k "mid" values) x (2^logC consecutive "lo" values).
+struct NttArgs {
+  u64* data;
+  const ulonglong2* tw;  // [nm][N] (w, floor(w*2^64/m)); entry 2^s + i is the twiddle of group i at stage s
+  const ModInfo* mods;
+  u64 poly_stride;       // elements between consecutive polynomials
+  u32 logN, s0, k, logC, tile_log;
+  u32 skip_beta, skip_alpha, skip_nq;  // skip_beta != 0: poly p is digit p % skip_beta; its own limbs are not touched
+  LimbMap ids;
+};
+
+// Butterflies are done stage by stage in LDS; values stay canonical in [0, m).
+template <bool INV>
+__global__ void __launch_bounds__(NTT_THREADS) ntt_pass_kernel(NttArgs a) {
+  extern __shared__ u64 sm[];
+  const u32 poly = blockIdx.x, tile_id = blockIdx.y, slot = blockIdx.z;
+  if (a.skip_beta) {
+    u32 j = poly % a.skip_beta;
+    u32 lo = j * a.skip_alpha, hi = min(lo + a.skip_alpha, a.skip_nq);
+    if (slot >= lo && slot < hi) return;
+  }
+  const u32 id = a.ids.id[slot];
+  const ModInfo mi = a.mods[id];
+  const u64 m = mi.m;
+  const u32 N = 1u << a.logN;
+  const ulonglong2* tw = a.tw + (size_t)id * N;
+  u64* base = a.data + (size_t)poly * a.poly_stride + (size_t)slot * N;
+
+  const u32 tile = 1u << a.tile_log;
+  const u32 k = a.k, logC = a.logC;
+  const u32 lo_bits = a.logN - a.s0 - k;          // index bits below the stages of this pass
+  const u32 tiles_lo = 1u << (lo_bits - logC);
+  const u32 hl_log = a.tile_log - k - logC;        // log2(hi blocks per tile)
+  const u32 hi0 = (tile_id / tiles_lo) << hl_log;
+  const u32 lo0 = (tile_id % tiles_lo) << logC;
+  const u32 cmask = (1u << logC) - 1, kmask = (1u << k) - 1;
+
+  for (u32 e = threadIdx.x; e < tile; e += NTT_THREADS) {
+    u32 lo = e & cmask, mid = (e >> logC) & kmask, hl = e >> (logC + k);
+    size_t g = ((size_t)(hi0 + hl) << (a.logN - a.s0)) | ((size_t)mid << lo_bits) | (lo0 + lo);
+    sm[e] = base[g];
+  }
+  __syncthreads();
+
+  for (u32 uu = 0; uu < k; uu++) {
+    const u32 u = INV ? (k - 1 - uu) : uu;
+    const u32 sh = k - 1 - u;
+    for (u32 bf = threadIdx.x; bf < tile / 2; bf += NTT_THREADS) {
+      u32 lo = bf & cmask, pi = (bf >> logC) & (kmask >> 1), hl = bf >> (logC + k - 1);
+      u32 grp = pi >> sh, pos = pi & ((1u << sh) - 1);
+      u32 mid_a = (grp << (sh + 1)) | pos;
+      u32 ea = (((hl << k) | mid_a) << logC) | lo;
+      u32 eb = ea + ((1u << sh) << logC);
+      ulonglong2 w = tw[(1u << (a.s0 + u)) + ((hi0 + hl) << u) + grp];
+      u64 U = sm[ea], V = sm[eb];
+      if (!INV) {
+        V = shoup(V, w.x, w.y, m);
+        sm[ea] = addmod(U, V, m);
+        sm[eb] = submod(U, V, m);
+      } else {
+        sm[ea] = addmod(U, V, m);
+        sm[eb] = shoup(submod(U, V, m), w.x, w.y, m);
+      }
+    }
+    __syncthreads();
+  }
+
+  const bool scale = INV && a.s0 == 0;
+  for (u32 e = threadIdx.x; e < tile; e += NTT_THREADS) {
+    u32 lo = e & cmask, mid = (e >> logC) & kmask, hl = e >> (logC + k);
+    size_t g = ((size_t)(hi0 + hl) << (a.logN - a.s0)) | ((size_t)mid << lo_bits) | (lo0 + lo);
+    u64 v = sm[e];
+    if (scale) v = shoup(v, mi.ninv, mi.ninvs, m);
+    base[g] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Galois automorphism.
+// Evaluation domain (bit-reversed order): out[k] = in[k'], 2*brev(k')+1 = (2*brev(k)+1)*g mod 2N.
+__device__ __forceinline__ u32 galois_src_index(u32 k, u32 g, u32 logN) {
+  u32 e = 2 * (__brev(k) >> (32 - logN)) + 1;
+  u32 t = (e * g) & ((2u << logN) - 1);
+  return __brev(t >> 1) >> (32 - logN);
+}
+
+struct AutoArgs {
+  u64* out;
+  const u64* in;
+  const ModInfo* mods;
+  u64 out_poly_stride, in_poly_stride;
+  u32 logN, g, g_inv, eval_domain;
+  LimbMap ids;
+};
+__global__ void __launch_bounds__(256) automorph_kernel(AutoArgs a) {
+  const u32 poly = blockIdx.z, slot = blockIdx.y;
+  const u32 N = 1u << a.logN;
+  const u32 k = blockIdx.x * blockDim.x + threadIdx.x;
+  const u64* in = a.in + (size_t)poly * a.in_poly_stride + (size_t)slot * N;
+  u64* out = a.out + (size_t)poly * a.out_poly_stride + (size_t)slot * N;
+  if (a.eval_domain) {
+    out[k] = in[galois_src_index(k, a.g, a.logN)];
+  } else {
+    // out[t] = +-in[j] with t = j*g mod 2N; gather form: j = t*g^-1 mod 2N, sign from whether j*g wraps oddly.
+    const u64 m = a.mods[a.ids.id[slot]].m;
+    u32 j2 = (k * a.g_inv) & (2 * N - 1);   // index in [0, 2N) whose image is X^k (up to sign)
+    u32 j = j2 & (N - 1);
+    // X^j -> X^(j*g mod 2N); the image lands on +X^k if (j*g mod 2N) == k, on -X^k if it equals k + N.
+    u32 t = (j * a.g) & (2 * N - 1);
+    u64 v = in[j];
+    out[k] = (t == k) ? v : (v ? m - v : 0);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// ModUp base conversion: for digit j (limbs [lo_j, hi_j) of the coefficient-domain input), write every
+// other slot of the extended basis. Row layout of `mat` per digit: [alpha+1][next]; row i < len holds
+// (Q_j/q_i) mod m_t, row alpha holds (-Q_j) mod m_t which is multiplied by the count of negative
+// centred representatives.
+struct ModUpArgs {
+  const u64* dcoef;         // [B][nlimbs][N]
+  u64* ext;                 // [B][beta][next][N]
+  const ModInfo* mods;
+  const ulonglong2* inv;    // [beta][alpha]  ((Q_j/q_i)^-1 mod q_i, shoup)
+  const u64* mat;           // [beta][alpha+1][next]
+  u32 logN, nlimbs, nq, alpha, beta, next;
+};
+#define BCONV_THREADS 256
+__global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a) {
+  extern __shared__ u64 ys[];  // [alpha][BCONV_THREADS]
+  const u32 N = 1u << a.logN;
+  const u32 n = blockIdx.x * BCONV_THREADS + threadIdx.x;
+  const u32 j = blockIdx.y, b = blockIdx.z;
+  const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs), len = hi - lo;
+  const u64* d = a.dcoef + ((size_t)b * a.nlimbs + lo) * N + n;
+  u64 nneg = 0;
+  for (u32 i = 0; i < len; i++) {
+    const u64 m = a.mods[lo + i].m;
+    ulonglong2 c = a.inv[j * a.alpha + i];
+    u64 y = shoup(d[(size_t)i * N], c.x, c.y, m);
+    nneg += (y > (m >> 1)) ? 1 : 0;
+    ys[i * BCONV_THREADS + threadIdx.x] = y;
+  }
+  const u64* mat = a.mat + (size_t)j * (a.alpha + 1) * a.next;
+  u64* out = a.ext + (((size_t)b * a.beta + j) * a.next) * N + n;
+  for (u32 t = 0; t < a.next; t++) {
+    if (t >= lo && t < hi) continue;
+    const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+    const ModInfo mi = a.mods[id];
+    Acc128 acc = {0, 0};
+    for (u32 i = 0; i < len; i++) mac128(acc, ys[i * BCONV_THREADS + threadIdx.x], mat[i * a.next + t]);
+    mac128(acc, nneg, mat[a.alpha * a.next + t]);
+    out[(size_t)t * N] = reduce128(acc, mi);
+  }
+}
+
+// Inner product with the evaluation key over the extended basis, eval domain:
+// acc[b][c][t][n] = sum_j D_j[t][n] * evk[j][c][id(t)][n], D_j[t] = d[b][t] on digit j's own limbs, ext[b][j][t] else.
+struct InnerArgs {
+  const u64* d;     // [B][nlimbs][N] eval
+  const u64* ext;   // [B][beta][next][N] eval
+  const u64* evk;   // [dnum][2][nm][N]
+  u64* acc;         // [B][2][next][N]
+  const ModInfo* mods;
+  u32 logN, nlimbs, nq, nm, alpha, beta, next;
+};
+__global__ void __launch_bounds__(256) inner_kernel(InnerArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 b = blockIdx.x, t = blockIdx.z;
+  const u32 n = blockIdx.y * 256 + threadIdx.x;
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  Acc128 sb = {0, 0}, sa = {0, 0};
+  for (u32 j = 0; j < a.beta; j++) {
+    const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs);
+    u64 x = (t >= lo && t < hi) ? a.d[((size_t)b * a.nlimbs + t) * N + n]
+                                : a.ext[(((size_t)b * a.beta + j) * a.next + t) * N + n];
+    mac128(sb, x, a.evk[(((size_t)j * 2 + 0) * a.nm + id) * N + n]);
+    mac128(sa, x, a.evk[(((size_t)j * 2 + 1) * a.nm + id) * N + n]);
+  }
+  a.acc[(((size_t)b * 2 + 0) * a.next + t) * N + n] = reduce128(sb, mi);
+  a.acc[(((size_t)b * 2 + 1) * a.next + t) * N + n] = reduce128(sa, mi);
+}
+
+// ModDown base conversion P -> Q_l of the special limbs of acc (coefficient domain after INTT):
+// tq[bc][i][n] = sum_k y_k * (P/p_k mod q_i) - nneg * (P mod q_i), y_k = [x_k (P/p_k)^-1]_{p_k}.
+struct ModDownArgs {
+  const u64* acc;         // [B*2][next][N]; special limbs at slots nlimbs..next-1, coefficient domain
+  u64* tq;                // [B*2][nlimbs][N]
+  const ModInfo* mods;
+  const ulonglong2* inv;  // [K]
+  const u64* mat;         // [K+1][nlimbs]
+  u32 logN, nlimbs, nq, K, next;
+};
+__global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
+  extern __shared__ u64 ys[];
+  const u32 N = 1u << a.logN;
+  const u32 n = blockIdx.x * BCONV_THREADS + threadIdx.x;
+  const u32 bc = blockIdx.y;
+  const u64* x = a.acc + ((size_t)bc * a.next + a.nlimbs) * N + n;
+  u64 nneg = 0;
+  for (u32 k = 0; k < a.K; k++) {
+    const u64 m = a.mods[a.nq + k].m;
+    ulonglong2 c = a.inv[k];
+    u64 y = shoup(x[(size_t)k * N], c.x, c.y, m);
+    nneg += (y > (m >> 1)) ? 1 : 0;
+    ys[k * BCONV_THREADS + threadIdx.x] = y;
+  }
+  u64* out = a.tq + (size_t)bc * a.nlimbs * N + n;
+  for (u32 i = 0; i < a.nlimbs; i++) {
+    const ModInfo mi = a.mods[i];
+    Acc128 acc = {0, 0};
+    for (u32 k = 0; k < a.K; k++) mac128(acc, ys[k * BCONV_THREADS + threadIdx.x], a.mat[k * a.nlimbs + i]);
+    mac128(acc, nneg, a.mat[a.K * a.nlimbs + i]);
+    out[(size_t)i * N] = reduce128(acc, mi);
+  }
+}
+
+// Final assembly, eval domain: r = (acc - tq) * P^-1 mod q_i;  out = r (+ out if add_mask bit c is set).
+struct FinalArgs {
+  const u64* acc;   // [B][2][next][N]
+  const u64* tq;    // [B][2][nlimbs][N] (eval domain)
+  u64* out;         // [B][2][nlimbs][N]
+  const ModInfo* mods;
+  const ulonglong2* pinv;  // [nlimbs]
+  u32 logN, nlimbs, next, add_mask;
+};
+__global__ void __launch_bounds__(256) ks_final_kernel(FinalArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = blockIdx.x * 256 + threadIdx.x;
+  const u32 i = blockIdx.y, bc = blockIdx.z, c = bc & 1;
+  const u64 m = a.mods[i].m;
+  ulonglong2 pv = a.pinv[i];
+  u64 x = a.acc[((size_t)bc * a.next + i) * N + n];
+  u64 t = a.tq[((size_t)bc * a.nlimbs + i) * N + n];
+  u64 r = shoup(submod(x, t, m), pv.x, pv.y, m);
+  size_t o = ((size_t)bc * a.nlimbs + i) * N + n;
+  if ((a.add_mask >> c) & 1) r = addmod(r, a.out[o], m);
+  a.out[o] = r;
+}
+
+// HMult tensor product: d0 -> out[b][0], d1 -> out[b][1], d2 -> d2[b].
+struct TensorArgs {
+  const u64 *cta, *ctb;
+  u64 *out, *d2;
+  const ModInfo* mods;
+  u32 logN, nlimbs;
+};
+__global__ void __launch_bounds__(256) tensor_kernel(TensorArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = blockIdx.x * 256 + threadIdx.x;
+  const u32 i = blockIdx.y, b = blockIdx.z;
+  const ModInfo mi = a.mods[i];
+  size_t o0 = (((size_t)b * 2 + 0) * a.nlimbs + i) * N + n, o1 = o0 + (size_t)a.nlimbs * N;
+  u64 a0 = a.cta[o0], a1 = a.cta[o1], b0 = a.ctb[o0], b1 = a.ctb[o1];
+  a.out[o0] = mulmod(a0, b0, mi);
+  Acc128 s = {0, 0};
+  mac128(s, a0, b1);
+  mac128(s, a1, b0);
+  a.out[o1] = reduce128(s, mi);
+  a.d2[((size_t)b * a.nlimbs + i) * N + n] = mulmod(a1, b1, mi);
+}
+
+// BSGS inner sum: out[b][c][i][n] = sum_{s<n1} src_s[b][c][i][n] * pt[s][i][n], src_0 = ct_in, src_s = baby[s-1].
+struct PmaccArgs {
+  const u64* ct_in;   // [B][2][nlimbs][N]
+  const u64* baby;    // [n1-1][B][2][nlimbs][N]
+  const u64* pt;      // [n1][nlimbs][N] (row g of the diagonal tensor)
+  u64* out;           // [B][2][nlimbs][N]
+  const ModInfo* mods;
+  u32 logN, nlimbs, n1, B;
+};
+__global__ void __launch_bounds__(256) pmacc_kernel(PmaccArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = blockIdx.x * 256 + threadIdx.x;
+  const u32 i = blockIdx.y, bc = blockIdx.z;
+  const ModInfo mi = a.mods[i];
+  const size_t ct_sz = (size_t)a.B * 2 * a.nlimbs * N;
+  const size_t o = ((size_t)bc * a.nlimbs + i) * N + n;
+  Acc128 s = {0, 0};
+  for (u32 k = 0; k < a.n1; k++) {
+    u64 x = k == 0 ? a.ct_in[o] : a.baby[(size_t)(k - 1) * ct_sz + o];
+    mac128(s, x, a.pt[((size_t)k * a.nlimbs + i) * N + n]);
+    if ((k & 7) == 7) {  // keep the 128-bit sum far from overflow for any n1
+      u64 r = reduce128(s, mi);
+      s.lo = r;
+      s.hi = 0;
+    }
+  }
+  a.out[o] = reduce128(s, mi);
+}
+
+// out = out + in (mod q_i) on [npoly][nlimbs][N]
+struct AddArgs {
+  u64* out;
+  const u64* in;
+  const ModInfo* mods;
+  u32 logN, nlimbs;
+};
+__global__ void __launch_bounds__(256) addto_kernel(AddArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = blockIdx.x * 256 + threadIdx.x;
+  const u32 i = blockIdx.y, p = blockIdx.z;
+  const u64 m = a.mods[i].m;
+  size_t o = ((size_t)p * a.nlimbs + i) * N + n;
+  a.out[o] = addmod(a.out[o], a.in[o], m);
+}
