@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the RNS-CKKS key-switching hot path on one MI355X.
+
+Workload ("keyswitch_micro"): N = 2^16, 24 main primes of 50 bits, 8 special primes of 60
+bits, dnum = 3; 64 ciphertexts with uniform residues and seeded uniform evaluation keys.
+One step = HRot of all 64 ciphertexts (in `--groups` groups, each group with its own Galois
+element and key, one library call per group) followed by HMult+relinearize of 32 ciphertext
+pairs (one call): 96 key switches. Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job key switches per second, the roofline figures of the kernel
+kind that dominates the timed region (HIP-event durations of every launch, taken by the
+library on the launch stream), and the CPU oracle timed on a bounded sample of the same work.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_ALU_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
+
+# Algorithmic 32-bit lane-op counts (stated in the design doc): one 64-bit Shoup butterfly = 10 multiply-class
+# + 14 add/compare/select ops; one 64x64->128 multiply-accumulate = 4 + 4; one 128->64 reduction = 27;
+# one Shoup constant multiply = 14.
+OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 27, 14, 4
+
+
+def keyswitch_model(p, B, nl, hrot, hmult, passes, evk_shared_by):
+    """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B."""
+    N, K, alpha = p.N, len(p.p), p.alpha
+    nxt, beta = nl + K, p.beta(nl)
+    lens = [min(alpha, nl - j * alpha) for j in range(beta)]
+    new_limbs = sum(nxt - l for l in lens)
+    limb = 8 * N
+    stages_per_pass = p.logN / passes
+    m = {}
+
+    def ntt(kind, limbs):
+        m[kind] = dict(units=limbs * passes, bytes=limbs * passes * 2 * limb,
+                       ops=limbs * passes * (N / 2) * stages_per_pass * OPS_BUTTERFLY)
+    ntt("ntt_fwd_pass", B * (new_limbs + 2 * nl))
+    ntt("ntt_inv_pass", B * (nl + 2 * K))
+    m["copy"] = dict(units=1, bytes=B * nl * 2 * limb, ops=0)
+    m["modup_bconv"] = dict(units=1, bytes=B * (nl + new_limbs) * limb,
+                            ops=B * N * sum(l * OPS_SHOUP + (nxt - l) * ((l + 1) * OPS_MAC + OPS_REDUCE) for l in lens))
+    m["evk_inner"] = dict(units=1, bytes=(B * (beta * nxt + 2 * nxt) + 2 * beta * nxt) * limb,
+                          ops=B * N * nxt * (2 * beta * OPS_MAC + 2 * OPS_REDUCE))
+    m["moddown_bconv"] = dict(units=1, bytes=2 * B * (K + nl) * limb,
+                              ops=2 * B * N * (K * OPS_SHOUP + nl * ((K + 1) * OPS_MAC + OPS_REDUCE)))
+    m["ks_final"] = dict(units=1, bytes=(6 + (1 if hrot else 2 if hmult else 0)) * B * nl * limb,
+                         ops=2 * B * nl * N * (OPS_SHOUP + 2 * OPS_ADD))
+    if hrot:
+        m["automorph"] = dict(units=2, bytes=2 * B * nl * 2 * limb, ops=2 * B * nl * N * 6)
+    if hmult:
+        m["tensor"] = dict(units=1, bytes=B * nl * 7 * limb, ops=B * nl * N * (4 * OPS_MAC + 3 * OPS_REDUCE))
+    return m
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--groups", type=int, default=8, help="distinct (Galois element, key) groups among the 64 HRots")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers one GPU's share of the work; --gpus %d is not supported (use --gpus 1)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_03425_amd as ck
+    from ckks_inputs import config_params, galois_element, seeded_rotation_steps
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    p = config_params("keyswitch_micro")
+    N, nl, B, G = p.N, len(p.q), 64, args.groups
+    assert B % G == 0
+    ctx = ck.Context(p, 0)
+    gen = torch.Generator(device=dev).manual_seed(0xC0FFEE)
+
+    def uniform(prefix, moduli):
+        t = torch.empty(tuple(prefix) + (len(moduli), N), dtype=torch.int64, device=dev)
+        for i, m in enumerate(moduli):
+            t[..., i, :] = torch.randint(0, m, tuple(prefix) + (N,), dtype=torch.int64, device=dev, generator=gen)
+        return t
+
+    ct = uniform((B, 2), p.q)
+    evks = [uniform((p.dnum, 2), p.moduli) for _ in range(G)]
+    evk_mult = uniform((p.dnum, 2), p.moduli)
+    steps_r = seeded_rotation_steps(7, G, 1, N // 2 - 1)
+    gal = [galois_element(r, p.logN) for r in steps_r]
+    ct_a = ct[0::2].contiguous()
+    ct_b = ct[1::2].contiguous()
+    out_rot = torch.empty_like(ct)
+    out_mul = torch.empty_like(ct_a)
+    Bg = B // G
+    ws = ctx.workspace(ck.OP_HROT, max(Bg, B // 2), nl)
+
+    def step():
+        for g in range(G):
+            ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g], ws)
+        ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ck.ckks_prof_reset(ctx)
+    ck.ckks_prof_enable(ctx, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ck.ckks_prof_enable(ctx, False)
+    prof = ck.ckks_prof_collect(ctx)
+    sec = t1 - t0
+    ks_per_step = B + B // 2
+    value = ks_per_step * args.steps / sec
+
+    # --- per-kind roofline figures from the event durations of the timed region ---
+    passes = 1 if p.logN <= 12 else 2
+    model = {}
+    for (b, hrot, hmult, calls) in ((Bg, True, False, G), (B // 2, False, True, 1)):
+        for kind, v in keyswitch_model(p, b, nl, hrot, hmult, passes, b).items():
+            acc = model.setdefault(kind, dict(bytes=0.0, ops=0.0))
+            acc["bytes"] += v["bytes"] * calls
+            acc["ops"] += v["ops"] * calls
+    phases = {}
+    for kind, (ms, n) in prof.items():
+        per_step_ms = ms / args.steps
+        mdl = model.get(kind, dict(bytes=0.0, ops=0.0))
+        phases[kind] = dict(ms_per_step=round(per_step_ms, 4), launches_per_step=n / args.steps,
+                            avg_launch_us=round(1e3 * ms / n, 2),
+                            GBps=round(mdl["bytes"] / per_step_ms / 1e6, 1) if per_step_ms else None,
+                            Tops=round(mdl["ops"] / per_step_ms / 1e9, 2) if per_step_ms else None)
+    dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
+    d = phases[dom]
+    hbm_frac = (d["GBps"] or 0) / PEAK_HBM_GBS
+    alu_frac = (d["Tops"] or 0) / PEAK_ALU_TOPS
+    if alu_frac >= hbm_frac:
+        roofline = dict(bound="alu", kernel=dom, achieved=d["Tops"], peak=round(PEAK_ALU_TOPS, 1), unit="Tlane-op/s",
+                        frac=round(alu_frac, 4), traffic=None, avg_launch_us=d["avg_launch_us"])
+    else:
+        roofline = dict(bound="hbm", kernel=dom, achieved=d["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(hbm_frac, 4), traffic=None, avg_launch_us=d["avg_launch_us"])
+    total_bytes = sum(v["bytes"] for v in model.values())
+    compulsory = (G * (Bg * (2 * nl + 2 * nl) + 2 * p.dnum * (nl + len(p.p))) +
+                  (B // 2) * (4 * nl + 2 * nl) + 2 * p.dnum * (nl + len(p.p))) * 8 * N
+
+    # --- separate short measurements: transforms alone, HRot alone, HMult alone ---
+    def timed(fn, iters):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / iters
+    ids = list(range(nl))
+    scratch = ct.clone()
+    t_ntt = timed(lambda: ck.ckks_ntt(ctx, scratch, B * 2, ids), 5)
+    t_intt = timed(lambda: ck.ckks_intt(ctx, scratch, B * 2, ids), 5)
+    t_rot = timed(lambda: [ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g], ws)
+                           for g in range(G)], 3)
+    t_rot1 = timed(lambda: ck.ckks_hrot(ctx, out_rot, ct, B, nl, gal[0], evks[0],
+                                        ctx.workspace(ck.OP_HROT, B, nl)), 3)
+    t_mul = timed(lambda: ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws), 3)
+    extra = dict(ntt_limbs_per_s=round(B * 2 * nl / t_ntt), intt_limbs_per_s=round(B * 2 * nl / t_intt),
+                 hrot_per_s=round(B / t_rot, 1), hrot_per_s_one_group=round(B / t_rot1, 1),
+                 hmult_relin_per_s=round(B / 2 / t_mul, 1),
+                 ntt_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
+                 hbm_frac_compulsory_bytes=round(compulsory * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),
+                 hbm_frac_modelled_bytes=round(total_bytes * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4))
+
+    # --- CPU oracle on a bounded sample of the same workload ---
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        import numpy as np
+        ns = max(2, args.cpu_sample // 2 * 2)
+        threads = min(16, os.cpu_count() or 1, ns)
+        ref.set_threads(threads)
+        rctx = ref.RefContext(p)
+        h_ct = ct[:ns].cpu().numpy().view(np.uint64)
+        h_evk = evks[0].cpu().numpy().view(np.uint64)
+        h_mul = evk_mult.cpu().numpy().view(np.uint64)
+        t = time.perf_counter()
+        r1 = rctx.hrot(h_ct, gal[0], h_evk)
+        r2 = rctx.hmult_relin(h_ct[0::2], h_ct[1::2], h_mul)
+        cpu_sec = time.perf_counter() - t
+        cpu = dict(value=round((ns + ns // 2) / cpu_sec, 3), unit="key-switches/s", cores=threads, kind="oracle",
+                   sample="%d HRot + %d HMult+relin of the same workload (N=2^16, 24 limbs, dnum=3), %.1f s" % (ns, ns // 2, cpu_sec))
+        # the sample doubles as an end-of-run parity check of the timed configuration
+        ck.ckks_hrot(ctx, out_rot[:Bg], ct[:Bg], Bg, nl, gal[0], evks[0], ws)
+        ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws)
+        torch.cuda.synchronize()
+        nchk = min(ns, Bg)
+        ok = bool((out_rot[:nchk].cpu().numpy().view(np.uint64) == r1[:nchk]).all() and
+                  (out_mul[:ns // 2].cpu().numpy().view(np.uint64) == r2).all())
+        cpu["gpu_matches_oracle_on_sample"] = ok
+        if not ok:
+            print("bench.py: GPU output differs from the oracle on the sample", file=sys.stderr)
+            sys.exit(3)
+
+    line = {
+        "metric": "key_switches_per_s (HRot x64 + HMult+relin x32 per step; N=2^16, 24 limbs, dnum=3)",
+        "value": round(value, 2), "unit": "key-switches/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * sec / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "keyswitch_micro: N=2^16, 24x50-bit + 8x60-bit primes, dnum=3, 64 cts, %d HRot groups, 32 HMult pairs" % G,
+                   "global_batch": B, "parallelism": "single-gpu"},
+        "roofline": roofline, "cpu_baseline": cpu, "phases": phases, "extra": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

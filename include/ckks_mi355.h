@@ -151,6 +151,21 @@ int ckks_pcmm_bsgs(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint3
                    const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws, size_t ws_bytes,
                    void* stream);
 
+/*
+ * Measurement support (not part of the paper's operator set). While enabled, every kernel
+ * launch the library makes is bracketed by two HIP events on the stream it is launched on;
+ * ckks_prof_collect() waits for the recorded events and adds their elapsed times to
+ * per-kernel-kind totals, which ckks_prof_read() returns (total milliseconds and number of
+ * launches). Kinds are 0..ckks_prof_num_kinds()-1 with names from ckks_prof_kind_name().
+ * Not thread-safe: use one thread per context while profiling.
+ */
+int ckks_prof_enable(ckks_ctx* ctx, int on);
+int ckks_prof_num_kinds(void);
+const char* ckks_prof_kind_name(int kind);
+int ckks_prof_collect(ckks_ctx* ctx);
+int ckks_prof_read(ckks_ctx* ctx, int kind, double* total_ms, uint64_t* launches);
+int ckks_prof_reset(ckks_ctx* ctx);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,7 +14,9 @@ _LIB_PATH = os.path.join(_HERE, "libckks_mi355.so")
 OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS = 1, 2, 3, 4
 
 _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
-            "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs"]
+            "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
+            "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
+            "ckks_prof_reset"]
 
 
 class CkksError(RuntimeError):
@@ -52,6 +54,12 @@ def _load():
     lib.ckks_hmult_relin.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
+    lib.ckks_prof_enable.argtypes = [vp, C.c_int]
+    lib.ckks_prof_kind_name.restype = C.c_char_p
+    lib.ckks_prof_kind_name.argtypes = [C.c_int]
+    lib.ckks_prof_collect.argtypes = [vp]
+    lib.ckks_prof_reset.argtypes = [vp]
+    lib.ckks_prof_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     for name in _SYMBOLS:
         getattr(lib, name)
     return lib
@@ -110,6 +118,26 @@ class Context:
         if n == 0:
             raise CkksError(-2, "bad shape for workspace query")
         return torch.empty(n // 8, dtype=torch.int64, device="cuda:%d" % self.device)
+
+
+def ckks_prof_enable(ctx, on):
+    _check(_lib.ckks_prof_enable(ctx.handle, 1 if on else 0))
+
+
+def ckks_prof_reset(ctx):
+    _check(_lib.ckks_prof_reset(ctx.handle))
+
+
+def ckks_prof_collect(ctx):
+    """Per-kernel-kind totals since the last reset: {name: (total_ms, launches)}."""
+    _check(_lib.ckks_prof_collect(ctx.handle))
+    out = {}
+    for k in range(_lib.ckks_prof_num_kinds()):
+        ms, n = C.c_double(), C.c_uint64()
+        _check(_lib.ckks_prof_read(ctx.handle, k, C.byref(ms), C.byref(n)))
+        if n.value:
+            out[_lib.ckks_prof_kind_name(k).decode()] = (ms.value, n.value)
+    return out
 
 
 def ckks_workspace_bytes(ctx, op, batch, nlimbs, n1=0):

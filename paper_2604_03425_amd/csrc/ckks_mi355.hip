@@ -82,7 +82,23 @@ struct LevelTables {
 
 }  // namespace
 
+enum ProfKind {
+  PK_NTT_FWD = 0, PK_NTT_INV, PK_AUTOMORPH, PK_MODUP, PK_INNER, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
+  PK_COPY, PK_COUNT
+};
+static const char* const kProfNames[PK_COUNT] = {"ntt_fwd_pass", "ntt_inv_pass", "automorph", "modup_bconv", "evk_inner",
+                                                 "moddown_bconv", "ks_final", "tensor", "pmult_acc", "add", "copy"};
+struct ProfRec {
+  int kind;
+  hipEvent_t start, stop;
+};
+
 struct ckks_ctx {
+  bool prof_on = false;
+  std::vector<ProfRec> prof_recs;
+  std::vector<hipEvent_t> prof_pool;
+  double prof_ms[PK_COUNT] = {0};
+  uint64_t prof_n[PK_COUNT] = {0};
   int device = 0;
   u32 logN = 0, N = 0, nq = 0, np = 0, nm = 0, dnum = 0, alpha = 0;
   std::vector<u64> mod, psi;
@@ -111,6 +127,37 @@ struct DeviceGuard {
   }
   ~DeviceGuard() {
     if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+// Brackets the launches made during its lifetime with two events on their stream (only when profiling is on).
+struct ProfScope {
+  ckks_ctx* c;
+  hipStream_t st;
+  ProfRec rec;
+  bool active = false;
+  ProfScope(const ckks_ctx* cc, int kind, hipStream_t s) : c(const_cast<ckks_ctx*>(cc)), st(s) {
+    if (!c->prof_on) return;
+    auto get = [&](hipEvent_t* e) {
+      if (!c->prof_pool.empty()) {
+        *e = c->prof_pool.back();
+        c->prof_pool.pop_back();
+        return true;
+      }
+      return hipEventCreate(e) == hipSuccess;
+    };
+    rec.kind = kind;
+    if (!get(&rec.start)) return;
+    if (!get(&rec.stop)) {
+      c->prof_pool.push_back(rec.start);
+      return;
+    }
+    active = hipEventRecord(rec.start, st) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (!active) return;
+    (void)hipEventRecord(rec.stop, st);
+    c->prof_recs.push_back(rec);
   }
 };
 
@@ -219,6 +266,7 @@ int launch_ntt(const ckks_ctx* c, bool inverse, u64* data, u32 npoly, u64 poly_s
     a.tile_log = p.tile_log;
     dim3 grid(npoly, c->N >> p.tile_log, nslots);
     size_t lds = sizeof(u64) << p.tile_log;
+    ProfScope ps(c, inverse ? PK_NTT_INV : PK_NTT_FWD, st);
     if (inverse)
       hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, dim3(NTT_THREADS), lds, st, a);
     else
@@ -248,6 +296,7 @@ int launch_automorph(const ckks_ctx* c, u64* out, u64 out_stride, const u64* in,
   a.g_inv = inv_mod_pow2(g, c->logN + 1);
   a.eval_domain = eval_domain ? 1 : 0;
   a.ids = ids;
+  ProfScope ps(c, PK_AUTOMORPH, st);
   hipLaunchKernelGGL(automorph_kernel, dim3(c->N / 256, nslots, npoly), dim3(256), 0, st, a);
   HIP_TRY(hipGetLastError());
   return CKKS_OK;
@@ -285,11 +334,15 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
 
   // 1. coefficient form of d
-  HIP_TRY(hipMemcpyAsync(dcoef, d, (size_t)B * nlimbs * N * 8, hipMemcpyDeviceToDevice, st));
+  {
+    ProfScope ps(c, PK_COPY, st);
+    HIP_TRY(hipMemcpyAsync(dcoef, d, (size_t)B * nlimbs * N * 8, hipMemcpyDeviceToDevice, st));
+  }
   if ((rc = launch_ntt(c, true, dcoef, B, (u64)nlimbs * N, 0, nlimbs, qmap, 0, 0, st))) return rc;
   // 2. ModUp every digit to the slots it does not own
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
+    ProfScope ps(c, PK_MODUP, st);
     hipLaunchKernelGGL(modup_kernel, dim3(N / BCONV_THREADS, beta, B), dim3(BCONV_THREADS),
                        (size_t)c->alpha * BCONV_THREADS * 8, st, a);
     HIP_TRY(hipGetLastError());
@@ -299,6 +352,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   // 4. inner product with the key
   {
     InnerArgs a{d, ext, evk, acc, c->d_mods, c->logN, nlimbs, c->nq, c->nm, c->alpha, beta, next};
+    ProfScope ps(c, PK_INNER, st);
     hipLaunchKernelGGL(inner_kernel, dim3(B, N / 256, next), dim3(256), 0, st, a);
     HIP_TRY(hipGetLastError());
   }
@@ -311,6 +365,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   // 6. ModDown base conversion P -> Q_l
   {
     ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat, c->logN, nlimbs, c->nq, K, next};
+    ProfScope ps(c, PK_MODDOWN, st);
     hipLaunchKernelGGL(moddown_kernel, dim3(N / BCONV_THREADS, B * 2), dim3(BCONV_THREADS),
                        (size_t)std::max<u32>(1, K) * BCONV_THREADS * 8, st, a);
     HIP_TRY(hipGetLastError());
@@ -319,6 +374,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   if ((rc = launch_ntt(c, false, tq, B * 2, (u64)nlimbs * N, 0, nlimbs, qmap, 0, 0, st))) return rc;
   {
     FinalArgs a{acc, tq, out, c->d_mods, lt->pinv, c->logN, nlimbs, next, add_mask};
+    ProfScope ps(c, PK_FINAL, st);
     hipLaunchKernelGGL(ks_final_kernel, dim3(N / 256, nlimbs, B * 2), dim3(256), 0, st, a);
     HIP_TRY(hipGetLastError());
   }
@@ -444,6 +500,11 @@ int ckks_ctx_destroy(ckks_ctx* c) {
   (void)hipFree(c->d_mods);
   (void)hipFree(c->d_tw_fwd);
   (void)hipFree(c->d_tw_inv);
+  for (auto& r : c->prof_recs) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  for (auto& e : c->prof_pool) (void)hipEventDestroy(e);
   for (auto& kv : c->levels) {
     (void)hipFree(kv.second.up_inv);
     (void)hipFree(kv.second.up_mat);
@@ -453,6 +514,41 @@ int ckks_ctx_destroy(ckks_ctx* c) {
   }
   delete c;
   return CKKS_OK;
+}
+
+int ckks_prof_enable(ckks_ctx* c, int on) {
+  if (!c) return fail(CKKS_EINVAL, "null context");
+  c->prof_on = on != 0;
+  return CKKS_OK;
+}
+int ckks_prof_num_kinds(void) { return PK_COUNT; }
+const char* ckks_prof_kind_name(int kind) { return kind >= 0 && kind < PK_COUNT ? kProfNames[kind] : ""; }
+int ckks_prof_collect(ckks_ctx* c) {
+  if (!c) return fail(CKKS_EINVAL, "null context");
+  DeviceGuard guard(c->device);
+  for (auto& r : c->prof_recs) {
+    HIP_TRY(hipEventSynchronize(r.stop));
+    float ms = 0;
+    HIP_TRY(hipEventElapsedTime(&ms, r.start, r.stop));
+    c->prof_ms[r.kind] += ms;
+    c->prof_n[r.kind] += 1;
+    c->prof_pool.push_back(r.start);
+    c->prof_pool.push_back(r.stop);
+  }
+  c->prof_recs.clear();
+  return CKKS_OK;
+}
+int ckks_prof_read(ckks_ctx* c, int kind, double* total_ms, uint64_t* launches) {
+  if (!c || kind < 0 || kind >= PK_COUNT || !total_ms || !launches) return fail(CKKS_EINVAL, "bad argument");
+  *total_ms = c->prof_ms[kind];
+  *launches = c->prof_n[kind];
+  return CKKS_OK;
+}
+int ckks_prof_reset(ckks_ctx* c) {
+  if (!c) return fail(CKKS_EINVAL, "null context");
+  int rc = ckks_prof_collect(c);
+  for (int k = 0; k < PK_COUNT; k++) c->prof_ms[k] = 0, c->prof_n[k] = 0;
+  return rc;
 }
 
 size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlimbs, uint32_t n1) {
@@ -568,7 +664,10 @@ int ckks_hmult_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_a, const 
   const size_t ks = ks_layout(c, B, nlimbs).total;
   u64* d2 = (u64*)((char*)ws + ks);
   TensorArgs a{(const u64*)ct_a, (const u64*)ct_b, (u64*)ct_out, d2, c->d_mods, c->logN, nlimbs};
-  hipLaunchKernelGGL(tensor_kernel, dim3(c->N / 256, nlimbs, B), dim3(256), 0, st, a);
+  {
+    ProfScope ps(c, PK_TENSOR, st);
+    hipLaunchKernelGGL(tensor_kernel, dim3(c->N / 256, nlimbs, B), dim3(256), 0, st, a);
+  }
   HIP_TRY(hipGetLastError());
   return keyswitch_impl(c, (u64*)ct_out, d2, B, nlimbs, (const u64*)evk, /*add_mask=*/3, (char*)ws, st);
 }
@@ -618,12 +717,16 @@ int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_
     u64* dst = g == 0 ? (u64*)ct_out : inner;
     PmaccArgs a{(const u64*)ct_in, baby, (const u64*)pt + (size_t)g * n1 * polyN, dst, c->d_mods, c->logN, nlimbs, n1, B};
     // baby rows are ct_elems apart; pmacc indexes them with B*2*nlimbs*N, which equals ct_elems when that is 256-aligned
+    {
+    ProfScope ps(c, PK_PMACC, st);
     hipLaunchKernelGGL(pmacc_kernel, dim3(N / 256, nlimbs, 2 * B), dim3(256), 0, st, a);
+    }
     HIP_TRY(hipGetLastError());
     if (g > 0) {
       rc = ckks_hrot(c, (uint64_t*)rot, (const uint64_t*)inner, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws, hws_bytes, stream);
       if (rc) return rc;
       AddArgs ad{(u64*)ct_out, rot, c->d_mods, c->logN, nlimbs};
+      ProfScope ps(c, PK_ADD, st);
       hipLaunchKernelGGL(addto_kernel, dim3(N / 256, nlimbs, 2 * B), dim3(256), 0, st, ad);
       HIP_TRY(hipGetLastError());
     }
