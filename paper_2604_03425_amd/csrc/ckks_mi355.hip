@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "kernels.cuh"
+#include "ntt16.cuh"
 
 typedef unsigned __int128 u128;
 
@@ -243,15 +244,50 @@ LimbMap ext_map(const ckks_ctx* c, u32 nlimbs) {
   return m;
 }
 
-// Enqueue a transform over data[npoly] x slots [slot0, slot0+nslots) of rows that are poly_stride apart.
-int launch_ntt(const ckks_ctx* c, bool inverse, u64* data, u32 npoly, u64 poly_stride, u32 slot0, u32 nslots,
-               const LimbMap& ids_from_slot0, u32 skip_beta, u32 skip_nq, hipStream_t st) {
+// Enqueue a transform of npoly polynomials x slots [slot0, slot0+nslots): reads src, writes dst (src == dst for an
+// in-place transform; out of place is supported only on the N = 2^16 path). Rows are *_stride elements apart.
+int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, u64* dst, u64 dst_stride, u32 npoly,
+               u32 slot0, u32 nslots, const LimbMap& ids_from_slot0, u32 skip_beta, u32 skip_nq, hipStream_t st) {
   if (npoly == 0 || nslots == 0) return CKKS_OK;
+  const int kind = inverse ? PK_NTT_INV : PK_NTT_FWD;
+  if (c->logN == 16) {
+    Ntt16Args a;
+    a.src = src + (size_t)slot0 * c->N;
+    a.dst = dst + (size_t)slot0 * c->N;
+    a.tw = inverse ? c->d_tw_inv : c->d_tw_fwd;
+    a.mods = c->d_mods;
+    a.src_poly_stride = src_stride;
+    a.dst_poly_stride = dst_stride;
+    a.skip_beta = skip_beta;
+    a.skip_alpha = c->alpha;
+    a.skip_nq = skip_nq;
+    for (u32 i = 0; i < 128; i++) a.id[i] = ids_from_slot0.id[i];
+    dim3 grid(npoly, 16, nslots), block(NTT16_THREADS);
+    Ntt16Args b = a;  // second pass: in place on dst
+    b.src = a.dst;
+    b.src_poly_stride = dst_stride;
+    if (!inverse) {
+      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_fwd_rows_kernel, grid, block, 0, st, a); }
+      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_fwd_blocks_kernel, grid, block, 0, st, b); }
+    } else {
+      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_inv_blocks_kernel, grid, block, 0, st, a); }
+      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_inv_rows_kernel, grid, block, 0, st, b); }
+    }
+    HIP_TRY(hipGetLastError());
+    return CKKS_OK;
+  }
+  if (src != dst) {
+    if (src_stride != dst_stride) return fail(CKKS_EINVAL, "internal: strided out-of-place transform");
+    ProfScope ps(c, PK_COPY, st);
+    // generic path is in place: copy the slots first (rows may be strided)
+    HIP_TRY(hipMemcpy2DAsync(dst + (size_t)slot0 * c->N, dst_stride * 8, src + (size_t)slot0 * c->N, src_stride * 8,
+                             (size_t)nslots * c->N * 8, npoly, hipMemcpyDeviceToDevice, st));
+  }
   NttArgs a;
-  a.data = data + (size_t)slot0 * c->N;
+  a.data = dst + (size_t)slot0 * c->N;
   a.tw = inverse ? c->d_tw_inv : c->d_tw_fwd;
   a.mods = c->d_mods;
-  a.poly_stride = poly_stride;
+  a.poly_stride = dst_stride;
   a.logN = c->logN;
   a.skip_beta = skip_beta;
   a.skip_alpha = c->alpha;
@@ -266,7 +302,7 @@ int launch_ntt(const ckks_ctx* c, bool inverse, u64* data, u32 npoly, u64 poly_s
     a.tile_log = p.tile_log;
     dim3 grid(npoly, c->N >> p.tile_log, nslots);
     size_t lds = sizeof(u64) << p.tile_log;
-    ProfScope ps(c, inverse ? PK_NTT_INV : PK_NTT_FWD, st);
+    ProfScope ps(c, kind, st);
     if (inverse)
       hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, dim3(NTT_THREADS), lds, st, a);
     else
@@ -334,11 +370,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
 
   // 1. coefficient form of d
-  {
-    ProfScope ps(c, PK_COPY, st);
-    HIP_TRY(hipMemcpyAsync(dcoef, d, (size_t)B * nlimbs * N * 8, hipMemcpyDeviceToDevice, st));
-  }
-  if ((rc = launch_ntt(c, true, dcoef, B, (u64)nlimbs * N, 0, nlimbs, qmap, 0, 0, st))) return rc;
+  if ((rc = launch_ntt(c, true, d, (u64)nlimbs * N, dcoef, (u64)nlimbs * N, B, 0, nlimbs, qmap, 0, 0, st))) return rc;
   // 2. ModUp every digit to the slots it does not own
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
@@ -348,7 +380,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
     HIP_TRY(hipGetLastError());
   }
   // 3. forward transform of the converted slots
-  if ((rc = launch_ntt(c, false, ext, B * beta, (u64)next * N, 0, next, emap, beta, nlimbs, st))) return rc;
+  if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st))) return rc;
   // 4. inner product with the key
   {
     InnerArgs a{d, ext, evk, acc, c->d_mods, c->logN, nlimbs, c->nq, c->nm, c->alpha, beta, next};
@@ -360,7 +392,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   {
     LimbMap pmap;
     for (u32 k = 0; k < CKKS_MAX_SLOTS; k++) pmap.id[k] = (unsigned char)(k < K ? c->nq + k : 0);
-    if ((rc = launch_ntt(c, true, acc, B * 2, (u64)next * N, nlimbs, K, pmap, 0, 0, st))) return rc;
+    if ((rc = launch_ntt(c, true, acc, (u64)next * N, acc, (u64)next * N, B * 2, nlimbs, K, pmap, 0, 0, st))) return rc;
   }
   // 6. ModDown base conversion P -> Q_l
   {
@@ -371,7 +403,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
     HIP_TRY(hipGetLastError());
   }
   // 7. its forward transform, 8. subtract, scale by P^-1, assemble
-  if ((rc = launch_ntt(c, false, tq, B * 2, (u64)nlimbs * N, 0, nlimbs, qmap, 0, 0, st))) return rc;
+  if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st))) return rc;
   {
     FinalArgs a{acc, tq, out, c->d_mods, lt->pinv, c->logN, nlimbs, next, add_mask};
     ProfScope ps(c, PK_FINAL, st);
@@ -581,7 +613,8 @@ static int transform_entry(ckks_ctx* c, bool inverse, uint64_t* data, uint32_t n
   const u32 chunk = 32768;
   for (u32 p0 = 0; p0 < npoly; p0 += chunk) {
     u32 n = std::min(chunk, npoly - p0);
-    rc = launch_ntt(c, inverse, (u64*)data + (size_t)p0 * nlimbs * c->N, n, (u64)nlimbs * c->N, 0, nlimbs, ids, 0, 0,
+    u64* base = (u64*)data + (size_t)p0 * nlimbs * c->N;
+    rc = launch_ntt(c, inverse, base, (u64)nlimbs * c->N, base, (u64)nlimbs * c->N, n, 0, nlimbs, ids, 0, 0,
                     (hipStream_t)stream);
     if (rc) return rc;
   }
