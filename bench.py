@@ -24,39 +24,36 @@ PEAK_HBM_GBS = 8000.0
 PEAK_ALU_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
 
 # Algorithmic 32-bit lane-op counts (stated in the design doc): one 64-bit Shoup butterfly = 10 multiply-class
-# + 14 add/compare/select ops; one 64x64->128 multiply-accumulate = 4 + 4; one 128->64 reduction = 27;
-# one Shoup constant multiply = 14.
-OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 27, 14, 4
+# + 14 add/compare/select ops; one 64x64->128 multiply-accumulate = 4 multiplies + 4 adds; one 128->64
+# Montgomery reduction = 7 multiplies + 9 adds/selects; one Shoup constant multiply = 10 + 4.
+OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 16, 14, 4
 
 
-def keyswitch_model(p, B, nl, hrot, hmult, passes, evk_shared_by):
-    """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B."""
+def keyswitch_model(p, B, nl, hrot, hmult):
+    """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B (N = 2^16 path)."""
     N, K, alpha = p.N, len(p.p), p.alpha
     nxt, beta = nl + K, p.beta(nl)
     lens = [min(alpha, nl - j * alpha) for j in range(beta)]
-    new_limbs = sum(nxt - l for l in lens)
+    new_limbs = sum(nxt - l for l in lens)          # limbs produced by ModUp, per ciphertext
     limb = 8 * N
-    stages_per_pass = p.logN / passes
+    bf_pass = (N / 2) * 8 * OPS_BUTTERFLY          # one 8-stage pass over one limb
+    mul_redc = 2 * OPS_MAC + OPS_REDUCE            # one variable x variable product reduced
     m = {}
-
-    def ntt(kind, limbs):
-        m[kind] = dict(units=limbs * passes, bytes=limbs * passes * 2 * limb,
-                       ops=limbs * passes * (N / 2) * stages_per_pass * OPS_BUTTERFLY)
-    ntt("ntt_fwd_pass", B * (new_limbs + 2 * nl))
-    ntt("ntt_inv_pass", B * (nl + 2 * K))
-    m["copy"] = dict(units=1, bytes=B * nl * 2 * limb, ops=0)
-    m["modup_bconv"] = dict(units=1, bytes=B * (nl + new_limbs) * limb,
-                            ops=B * N * sum(l * OPS_SHOUP + (nxt - l) * ((l + 1) * OPS_MAC + OPS_REDUCE) for l in lens))
-    m["evk_inner"] = dict(units=1, bytes=(B * (beta * nxt + 2 * nxt) + 2 * beta * nxt) * limb,
-                          ops=B * N * nxt * (2 * beta * OPS_MAC + 2 * OPS_REDUCE))
-    m["moddown_bconv"] = dict(units=1, bytes=2 * B * (K + nl) * limb,
-                              ops=2 * B * N * (K * OPS_SHOUP + nl * ((K + 1) * OPS_MAC + OPS_REDUCE)))
-    m["ks_final"] = dict(units=1, bytes=(6 + (1 if hrot else 2 if hmult else 0)) * B * nl * limb,
-                         ops=2 * B * nl * N * (OPS_SHOUP + 2 * OPS_ADD))
-    if hrot:
-        m["automorph"] = dict(units=2, bytes=2 * B * nl * 2 * limb, ops=2 * B * nl * N * 6)
+    n_inv = B * (nl + 2 * K)
+    m["ntt16_inv_blocks"] = dict(bytes=n_inv * 2 * limb, ops=n_inv * bf_pass)
+    m["ntt16_inv_rows"] = dict(bytes=n_inv * 2 * limb, ops=n_inv * (bf_pass + N * OPS_SHOUP))
+    m["modup_bconv"] = dict(bytes=B * (nl + new_limbs) * limb,
+                            ops=B * N * sum((nxt - l) * ((l + 1) * OPS_MAC + OPS_REDUCE) for l in lens))
+    n_rows = B * (new_limbs + 2 * nl)
+    m["ntt16_fwd_rows"] = dict(bytes=n_rows * 2 * limb, ops=n_rows * bf_pass)
+    m["ntt16_fwd_blocks_inner"] = dict(bytes=(B * (new_limbs + nl + 2 * nxt) + 2 * beta * nxt) * limb,
+                                       ops=B * (new_limbs * bf_pass + N * nxt * beta * 2 * mul_redc))
+    m["moddown_bconv"] = dict(bytes=2 * B * (K + nl) * limb, ops=2 * B * N * nl * ((K + 1) * OPS_MAC + OPS_REDUCE))
+    addend = 1 if hrot else 2 if hmult else 0
+    m["ntt16_fwd_blocks_final"] = dict(bytes=B * nl * (6 + addend) * limb,
+                                       ops=2 * B * nl * (bf_pass + N * (OPS_SHOUP + 2 * OPS_ADD)))
     if hmult:
-        m["tensor"] = dict(units=1, bytes=B * nl * 7 * limb, ops=B * nl * N * (4 * OPS_MAC + 3 * OPS_REDUCE))
+        m["tensor"] = dict(bytes=B * nl * 7 * limb, ops=B * nl * N * 4 * mul_redc)
     return m
 
 
@@ -67,6 +64,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--groups", type=int, default=8, help="distinct (Galois element, key) groups among the 64 HRots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--map-mode", type=int, default=None, help="experiment: workgroup mapping mode of the 2^16 transforms")
+    ap.add_argument("--no-extras", action="store_true", help="skip the separate NTT / HRot / HMult timings (profiling runs)")
     ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -86,6 +85,8 @@ def main():
     N, nl, B, G = p.N, len(p.q), 64, args.groups
     assert B % G == 0
     ctx = ck.Context(p, 0)
+    if args.map_mode is not None:
+        ck.ckks_tune_set(ctx, 0, args.map_mode)
     gen = torch.Generator(device=dev).manual_seed(0xC0FFEE)
 
     def uniform(prefix, moduli):
@@ -129,10 +130,9 @@ def main():
     value = ks_per_step * args.steps / sec
 
     # --- per-kind roofline figures from the event durations of the timed region ---
-    passes = 1 if p.logN <= 12 else 2
     model = {}
     for (b, hrot, hmult, calls) in ((Bg, True, False, G), (B // 2, False, True, 1)):
-        for kind, v in keyswitch_model(p, b, nl, hrot, hmult, passes, b).items():
+        for kind, v in keyswitch_model(p, b, nl, hrot, hmult).items():
             acc = model.setdefault(kind, dict(bytes=0.0, ops=0.0))
             acc["bytes"] += v["bytes"] * calls
             acc["ops"] += v["ops"] * calls
@@ -155,6 +155,8 @@ def main():
         roofline = dict(bound="hbm", kernel=dom, achieved=d["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=round(hbm_frac, 4), traffic=None, avg_launch_us=d["avg_launch_us"])
     total_bytes = sum(v["bytes"] for v in model.values())
+    total_ops = sum(v["ops"] for v in model.values())
+    # compulsory traffic of a step: read every input ciphertext and key once, write every output once
     compulsory = (G * (Bg * (2 * nl + 2 * nl) + 2 * p.dnum * (nl + len(p.p))) +
                   (B // 2) * (4 * nl + 2 * nl) + 2 * p.dnum * (nl + len(p.p))) * 8 * N
 
@@ -167,21 +169,25 @@ def main():
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / iters
-    ids = list(range(nl))
-    scratch = ct.clone()
-    t_ntt = timed(lambda: ck.ckks_ntt(ctx, scratch, B * 2, ids), 5)
-    t_intt = timed(lambda: ck.ckks_intt(ctx, scratch, B * 2, ids), 5)
-    t_rot = timed(lambda: [ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g], ws)
-                           for g in range(G)], 3)
-    t_rot1 = timed(lambda: ck.ckks_hrot(ctx, out_rot, ct, B, nl, gal[0], evks[0],
-                                        ctx.workspace(ck.OP_HROT, B, nl)), 3)
-    t_mul = timed(lambda: ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws), 3)
-    extra = dict(ntt_limbs_per_s=round(B * 2 * nl / t_ntt), intt_limbs_per_s=round(B * 2 * nl / t_intt),
-                 hrot_per_s=round(B / t_rot, 1), hrot_per_s_one_group=round(B / t_rot1, 1),
-                 hmult_relin_per_s=round(B / 2 / t_mul, 1),
-                 ntt_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
-                 hbm_frac_compulsory_bytes=round(compulsory * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),
-                 hbm_frac_modelled_bytes=round(total_bytes * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4))
+    extra = None
+    if not args.no_extras:
+      ids = list(range(nl))
+      scratch = ct.clone()
+      t_ntt = timed(lambda: ck.ckks_ntt(ctx, scratch, B * 2, ids), 5)
+      t_intt = timed(lambda: ck.ckks_intt(ctx, scratch, B * 2, ids), 5)
+      t_rot = timed(lambda: [ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g], ws)
+                             for g in range(G)], 3)
+      t_rot1 = timed(lambda: ck.ckks_hrot(ctx, out_rot, ct, B, nl, gal[0], evks[0],
+                                          ctx.workspace(ck.OP_HROT, B, nl)), 3)
+      t_mul = timed(lambda: ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws), 3)
+      extra = dict(ntt_limbs_per_s=round(B * 2 * nl / t_ntt), intt_limbs_per_s=round(B * 2 * nl / t_intt),
+                   hrot_per_s=round(B / t_rot, 1), hrot_per_s_one_group=round(B / t_rot1, 1),
+                   hmult_relin_per_s=round(B / 2 / t_mul, 1),
+                   ntt_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
+                 ntt_hbm_frac=round(B * 2 * nl * 4 * 8 * N / t_ntt / 1e9 / PEAK_HBM_GBS, 4),
+                   hbm_frac_compulsory_bytes=round(compulsory * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),
+                   hbm_frac_modelled_bytes=round(total_bytes * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),
+                 alu_frac_modelled_ops=round(total_ops * args.steps / sec / 1e12 / PEAK_ALU_TOPS, 4))
 
     # --- CPU oracle on a bounded sample of the same workload ---
     cpu = None

@@ -69,7 +69,7 @@ const char* ckks_last_error(void);
  * (digit width alpha = ceil(nq/dnum) limbs; paper Sec. 2.1: special primes "used for digit
  * decomposition"). psi[i] is a primitive 2N-th root of unity modulo the i-th modulus
  * (q first, then p). All three arrays are host pointers. Every modulus must be a distinct
- * prime < 2^61 congruent to 1 mod 2N, and psi[i]^N must be -1; otherwise CKKS_EINVAL.
+ * prime < 2^60 congruent to 1 mod 2N, and psi[i]^N must be -1; otherwise CKKS_EINVAL.
  * Builds twiddle tables and base-conversion constants in device memory owned by the context.
  */
 int ckks_ctx_create(ckks_ctx** ctx, uint32_t logN, const uint64_t* q, uint32_t nq, const uint64_t* p, uint32_t np,
@@ -160,6 +160,8 @@ int ckks_pcmm_bsgs(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint3
  * Not thread-safe: use one thread per context while profiling.
  */
 int ckks_prof_enable(ckks_ctx* ctx, int on);
+/* Tuning knob for experiments: knob 0 = workgroup-to-tile mapping of the N = 2^16 transforms (0..3). */
+int ckks_tune_set(ckks_ctx* ctx, int knob, int value);
 int ckks_prof_num_kinds(void);
 const char* ckks_prof_kind_name(int kind);
 int ckks_prof_collect(ckks_ctx* ctx);

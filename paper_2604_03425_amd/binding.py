@@ -16,7 +16,7 @@ OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS = 1, 2, 3, 4
 _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
-            "ckks_prof_reset"]
+            "ckks_prof_reset", "ckks_tune_set"]
 
 
 class CkksError(RuntimeError):
@@ -55,6 +55,7 @@ def _load():
     lib.ckks_pcmm_bsgs.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_prof_enable.argtypes = [vp, C.c_int]
+    lib.ckks_tune_set.argtypes = [vp, C.c_int, C.c_int]
     lib.ckks_prof_kind_name.restype = C.c_char_p
     lib.ckks_prof_kind_name.argtypes = [C.c_int]
     lib.ckks_prof_collect.argtypes = [vp]
@@ -118,6 +119,10 @@ class Context:
         if n == 0:
             raise CkksError(-2, "bad shape for workspace query")
         return torch.empty(n // 8, dtype=torch.int64, device="cuda:%d" % self.device)
+
+
+def ckks_tune_set(ctx, knob, value):
+    _check(_lib.ckks_tune_set(ctx.handle, knob, value))
 
 
 def ckks_prof_enable(ctx, on):

@@ -41,6 +41,7 @@ u64 h_pow(u64 a, u64 e, u64 m) {
 }
 inline u64 h_inv(u64 a, u64 m) { return h_pow(a, m - 2, m); }
 inline u64 h_shoup(u64 w, u64 m) { return (u64)(((u128)w << 64) / m); }
+inline u64 h_mont(u64 v, u64 m) { return (u64)(((u128)v << 64) % m); }  // v * 2^64 mod m
 bool h_is_prime(u64 n) {
   if (n < 2) return false;
   const u64 bases[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
@@ -71,6 +72,9 @@ struct Pass {
   u32 s0, k, logC, tile_log;
 };
 
+// Number of source rows the base-conversion kernels are instantiated for (the smallest that covers n).
+inline u32 bconv_rows(u32 n) { return n <= 4 ? 4 : n <= 8 ? 8 : n <= 15 ? 15 : 45; }
+
 // Base-conversion constants for ciphertexts at one limb count.
 struct LevelTables {
   u32 nlimbs = 0, beta = 0, next = 0;
@@ -79,15 +83,20 @@ struct LevelTables {
   ulonglong2* dn_inv = nullptr;  // [K]
   u64* dn_mat = nullptr;         // [K+1][nlimbs]
   ulonglong2* pinv = nullptr;    // [nlimbs]
+  // N = 2^16 fused path
+  ulonglong2* up_scale = nullptr;  // [nlimbs]  (Q_j/q_i)^-1 / N mod q_i
+  ulonglong2* dn_scale = nullptr;  // [K]       2^64 (P/p_k)^-1 / N mod p_k
+  u64* dn_mat_plain = nullptr;     // dn_mat without the Montgomery factor
+  ulonglong2* pinv2 = nullptr;     // [nlimbs]  2^64 / P mod q_i
 };
 
 }  // namespace
 
 enum ProfKind {
-  PK_NTT_FWD = 0, PK_NTT_INV, PK_AUTOMORPH, PK_MODUP, PK_INNER, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
+  PK_NTT_FWD = 0, PK_NTT_INV, PK_FWD_ROWS, PK_FWD_BLOCKS, PK_INV_BLOCKS, PK_INV_ROWS, PK_FWD_INNER, PK_FWD_FINAL, PK_AUTOMORPH, PK_MODUP, PK_INNER, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
   PK_COPY, PK_COUNT
 };
-static const char* const kProfNames[PK_COUNT] = {"ntt_fwd_pass", "ntt_inv_pass", "automorph", "modup_bconv", "evk_inner",
+static const char* const kProfNames[PK_COUNT] = {"ntt_fwd_pass", "ntt_inv_pass", "ntt16_fwd_rows", "ntt16_fwd_blocks", "ntt16_inv_blocks", "ntt16_inv_rows", "ntt16_fwd_blocks_inner", "ntt16_fwd_blocks_final", "automorph", "modup_bconv", "evk_inner",
                                                  "moddown_bconv", "ks_final", "tensor", "pmult_acc", "add", "copy"};
 struct ProfRec {
   int kind;
@@ -95,6 +104,7 @@ struct ProfRec {
 };
 
 struct ckks_ctx {
+  int tune[8] = {4, 0, 0, 0, 0, 0, 0, 0};  // knob 0: workgroup mapping of the 2^16 transforms
   bool prof_on = false;
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
@@ -176,8 +186,10 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
   const u32 alpha = c->alpha, K = c->np, next = t.next;
   auto ext_mod = [&](u32 s) { return s < nlimbs ? c->mod[s] : c->mod[c->nq + (s - nlimbs)]; };
 
+  // constants of one output are contiguous: [digit][target][R+1], rows >= digit length are zero, row R = -Q_j
+  const u32 R = bconv_rows(alpha), RK = bconv_rows(K);
   std::vector<ulonglong2> up_inv((size_t)t.beta * alpha, ulonglong2{0, 0});
-  std::vector<u64> up_mat((size_t)t.beta * (alpha + 1) * next, 0);
+  std::vector<u64> up_mat((size_t)t.beta * next * (R + 1), 0);
   for (u32 j = 0; j < t.beta; j++) {
     u32 lo = j * alpha, hi = std::min(lo + alpha, nlimbs);
     for (u32 i = lo; i < hi; i++) {
@@ -190,17 +202,17 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
         u64 m = ext_mod(s), v = 1;
         for (u32 k = lo; k < hi; k++)
           if (k != i) v = h_mul(v, c->mod[k] % m, m);
-        up_mat[((size_t)j * (alpha + 1) + (i - lo)) * next + s] = v;
+        up_mat[((size_t)j * next + s) * (R + 1) + (i - lo)] = h_mont(v, m);
       }
     }
     for (u32 s = 0; s < next; s++) {
       u64 m = ext_mod(s), v = 1;
       for (u32 k = lo; k < hi; k++) v = h_mul(v, c->mod[k] % m, m);
-      up_mat[((size_t)j * (alpha + 1) + alpha) * next + s] = v ? m - v : 0;
+      up_mat[((size_t)j * next + s) * (R + 1) + R] = h_mont(v ? m - v : 0, m);
     }
   }
   std::vector<ulonglong2> dn_inv(K), pinv(nlimbs);
-  std::vector<u64> dn_mat((size_t)(K + 1) * nlimbs, 0);
+  std::vector<u64> dn_mat((size_t)nlimbs * (RK + 1), 0);
   for (u32 k = 0; k < K; k++) {
     u64 pk = c->mod[c->nq + k], h = 1;
     for (u32 r = 0; r < K; r++)
@@ -211,19 +223,41 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
       u64 m = c->mod[i], v = 1;
       for (u32 r = 0; r < K; r++)
         if (r != k) v = h_mul(v, c->mod[c->nq + r] % m, m);
-      dn_mat[(size_t)k * nlimbs + i] = v;
+      dn_mat[(size_t)i * (RK + 1) + k] = h_mont(v, m);
     }
   }
   for (u32 i = 0; i < nlimbs; i++) {
     u64 m = c->mod[i], v = 1;
     for (u32 r = 0; r < K; r++) v = h_mul(v, c->mod[c->nq + r] % m, m);
-    dn_mat[(size_t)K * nlimbs + i] = v ? m - v : 0;
+    dn_mat[(size_t)i * (RK + 1) + RK] = h_mont(v ? m - v : 0, m);
     u64 inv = h_inv(v, m);
     pinv[i] = ulonglong2{inv, h_shoup(inv, m)};
+  }
+  std::vector<ulonglong2> up_scale(nlimbs), dn_scale(K), pinv2(nlimbs);
+  std::vector<u64> dn_mat_plain(dn_mat.size(), 0);
+  for (u32 i = 0; i < nlimbs; i++) {
+    u64 m = c->mod[i], ninv = h_inv(c->N % m, m);
+    u64 v = h_mul(up_inv[(size_t)(i / alpha) * alpha + (i % alpha)].x, ninv, m);
+    up_scale[i] = ulonglong2{v, h_shoup(v, m)};
+    u64 w = h_mont(pinv[i].x, m);
+    pinv2[i] = ulonglong2{w, h_shoup(w, m)};
+    for (u32 k = 0; k <= RK; k++) {
+      // undo the Montgomery factor: stored value is v * 2^64, multiply by 2^-64
+      u64 r64 = h_mont(1, m);
+      dn_mat_plain[(size_t)i * (RK + 1) + k] = h_mul(dn_mat[(size_t)i * (RK + 1) + k], h_inv(r64, m), m);
+    }
+  }
+  for (u32 k = 0; k < K; k++) {
+    u64 m = c->mod[c->nq + k], ninv = h_inv(c->N % m, m);
+    u64 v = h_mont(h_mul(dn_inv[k].x, ninv, m), m);
+    dn_scale[k] = ulonglong2{v, h_shoup(v, m)};
   }
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
   int rc;
+  if ((rc = upload(&t.up_scale, up_scale)) || (rc = upload(&t.dn_scale, dn_scale)) ||
+      (rc = upload(&t.dn_mat_plain, dn_mat_plain)) || (rc = upload(&t.pinv2, pinv2)))
+    return rc;
   if ((rc = upload(&t.up_inv, up_inv)) || (rc = upload(&t.up_mat, up_mat)) || (rc = upload(&t.dn_inv, dn_inv)) ||
       (rc = upload(&t.dn_mat, dn_mat)) || (rc = upload(&t.pinv, pinv)))
     return rc;
@@ -246,8 +280,14 @@ LimbMap ext_map(const ckks_ctx* c, u32 nlimbs) {
 
 // Enqueue a transform of npoly polynomials x slots [slot0, slot0+nslots): reads src, writes dst (src == dst for an
 // in-place transform; out of place is supported only on the N = 2^16 path). Rows are *_stride elements apart.
+struct NttOpts {
+  u32 galois = 0;                     // N = 2^16 inverse only: read src through the eval-domain Galois map
+  const ulonglong2* scale = nullptr;  // N = 2^16 inverse only: per-slot constants (from slot0) replacing N^-1
+  bool rows_only = false;             // N = 2^16 forward only: stop after the row pass (a fused kernel does the rest)
+};
 int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, u64* dst, u64 dst_stride, u32 npoly,
-               u32 slot0, u32 nslots, const LimbMap& ids_from_slot0, u32 skip_beta, u32 skip_nq, hipStream_t st) {
+               u32 slot0, u32 nslots, const LimbMap& ids_from_slot0, u32 skip_beta, u32 skip_nq, hipStream_t st,
+               const NttOpts& opt = NttOpts()) {
   if (npoly == 0 || nslots == 0) return CKKS_OK;
   const int kind = inverse ? PK_NTT_INV : PK_NTT_FWD;
   if (c->logN == 16) {
@@ -262,16 +302,22 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     a.skip_alpha = c->alpha;
     a.skip_nq = skip_nq;
     for (u32 i = 0; i < 128; i++) a.id[i] = ids_from_slot0.id[i];
+    a.map_mode = c->tune[0];
+    a.galois = opt.galois;
+    a.scale = opt.scale;
     dim3 grid(npoly, 16, nslots), block(NTT16_THREADS);
     Ntt16Args b = a;  // second pass: in place on dst
     b.src = a.dst;
     b.src_poly_stride = dst_stride;
     if (!inverse) {
-      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_fwd_rows_kernel, grid, block, 0, st, a); }
-      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_fwd_blocks_kernel, grid, block, 0, st, b); }
+      { ProfScope ps(c, PK_FWD_ROWS, st); hipLaunchKernelGGL(ntt16_fwd_rows_kernel, grid, block, 0, st, a); }
+      if (!opt.rows_only) {
+        ProfScope ps(c, PK_FWD_BLOCKS, st);
+        hipLaunchKernelGGL(ntt16_fwd_blocks_kernel, grid, block, 0, st, b);
+      }
     } else {
-      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_inv_blocks_kernel, grid, block, 0, st, a); }
-      { ProfScope ps(c, kind, st); hipLaunchKernelGGL(ntt16_inv_rows_kernel, grid, block, 0, st, b); }
+      { ProfScope ps(c, PK_INV_BLOCKS, st); hipLaunchKernelGGL(ntt16_inv_blocks_kernel, grid, block, 0, st, a); }
+      { ProfScope ps(c, PK_INV_ROWS, st); hipLaunchKernelGGL(ntt16_inv_rows_kernel, grid, block, 0, st, b); }
     }
     HIP_TRY(hipGetLastError());
     return CKKS_OK;
@@ -355,12 +401,131 @@ KsLayout ks_layout(const ckks_ctx* c, u32 B, u32 nlimbs) {
   return L;
 }
 
-// Key switch of d (eval domain) with evk into out; add_mask bit c set: out[.,c] += ks instead of = ks.
-int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const u64* evk, u32 add_mask, char* ws,
-                   hipStream_t st) {
+template <bool PRESCALED>
+void launch_modup(const ckks_ctx* c, const ModUpArgs& a, dim3 grid, hipStream_t st) {
+  dim3 block(BCONV_THREADS);
+  if (c->alpha <= 4) hipLaunchKernelGGL((modup_kernel<4, PRESCALED>), grid, block, 0, st, a);
+  else if (c->alpha <= 8) hipLaunchKernelGGL((modup_kernel<8, PRESCALED>), grid, block, 0, st, a);
+  else if (c->alpha <= 15) hipLaunchKernelGGL((modup_kernel<15, PRESCALED>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((modup_kernel<45, PRESCALED>), grid, block, 0, st, a);
+}
+template <bool PRESCALED>
+void launch_moddown(const ckks_ctx* c, const ModDownArgs& a, dim3 grid, hipStream_t st) {
+  dim3 block(BCONV_THREADS);
+  const u32 K = c->np;
+  if (K <= 4) hipLaunchKernelGGL((moddown_kernel<4, PRESCALED>), grid, block, 0, st, a);
+  else if (K <= 8) hipLaunchKernelGGL((moddown_kernel<8, PRESCALED>), grid, block, 0, st, a);
+  else if (K <= 15) hipLaunchKernelGGL((moddown_kernel<15, PRESCALED>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((moddown_kernel<45, PRESCALED>), grid, block, 0, st, a);
+}
+
+// What a key switch reads and how its result is assembled.
+struct KsIo {
+  const u64* d;          // polynomial to switch, eval domain; limb-vector (b, i) at d + b*d_stride + i*N
+  u64 d_stride;
+  u32 d_galois;          // != 0: d is read through the eval-domain Galois map (HRot's sigma(c1)); N = 2^16 path only
+  u64* out;              // [B][2][nlimbs][N]
+  u32 mode[2];           // per component: 0 out = ks; 1 out += ks; 2 out = ks + sigma_g(add_src) (N = 2^16 path only)
+  const u64* add_src;    // [B][2][nlimbs][N]
+  u32 add_galois;
+};
+
+// N = 2^16: transforms fused with their neighbours.
+//   INTT(d) with (Q_j/q_i)^-1/N folded in -> ModUp -> row pass -> [block pass + evk inner product] (x 2^-64)
+//   -> INTT of the special limbs with 2^64 (P/p_k)^-1/N folded in -> ModDown (x 2^-64) -> row pass
+//   -> [block pass + (acc - t) * 2^64/P + addend].
+int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, const u64* evk, char* ws,
+                      hipStream_t st) {
+  int rc;
+  const u32 N = c->N, next = lt->next, beta = lt->beta, K = c->np;
+  KsLayout L = ks_layout(c, B, nlimbs);
+  u64* dcoef = (u64*)(ws + L.dcoef);
+  u64* ext = (u64*)(ws + L.ext);
+  u64* acc = (u64*)(ws + L.acc);
+  u64* tq = (u64*)(ws + L.tq);
+  const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
+  NttOpts o1;
+  o1.galois = io.d_galois;
+  o1.scale = lt->up_scale;
+  if ((rc = launch_ntt(c, true, io.d, io.d_stride, dcoef, (u64)nlimbs * N, B, 0, nlimbs, qmap, 0, 0, st, o1))) return rc;
+  {
+    ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
+    ProfScope ps(c, PK_MODUP, st);
+    launch_modup<true>(c, a, dim3(N / BCONV_THREADS, beta, B), st);
+    HIP_TRY(hipGetLastError());
+  }
+  NttOpts o2;
+  o2.rows_only = true;
+  if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, o2)))
+    return rc;
+  {
+    FwdInnerArgs a;
+    a.ext = ext;
+    a.d = io.d;
+    a.d_poly_stride = io.d_stride;
+    a.evk = evk;
+    a.acc = acc;
+    a.tw = c->d_tw_fwd;
+    a.mods = c->d_mods;
+    a.nlimbs = nlimbs;
+    a.nq = c->nq;
+    a.nm = c->nm;
+    a.alpha = c->alpha;
+    a.beta = beta;
+    a.next = next;
+    a.map_mode = c->tune[0];
+    a.galois = io.d_galois;
+    ProfScope ps(c, PK_FWD_INNER, st);
+    hipLaunchKernelGGL(ntt16_fwd_blocks_inner_kernel, dim3(B, 16, next), dim3(NTT16_THREADS), 0, st, a);
+    HIP_TRY(hipGetLastError());
+  }
+  {
+    LimbMap pmap;
+    for (u32 k = 0; k < CKKS_MAX_SLOTS; k++) pmap.id[k] = (unsigned char)(k < K ? c->nq + k : 0);
+    NttOpts o3;
+    o3.scale = lt->dn_scale;
+    if ((rc = launch_ntt(c, true, acc, (u64)next * N, acc, (u64)next * N, B * 2, nlimbs, K, pmap, 0, 0, st, o3))) return rc;
+  }
+  {
+    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next};
+    ProfScope ps(c, PK_MODDOWN, st);
+    launch_moddown<true>(c, a, dim3(N / BCONV_THREADS, B * 2), st);
+    HIP_TRY(hipGetLastError());
+  }
+  if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st, o2))) return rc;
+  {
+    FwdFinalArgs a;
+    a.tq = tq;
+    a.acc = acc;
+    a.out = io.out;
+    a.add_src = io.add_src;
+    a.tw = c->d_tw_fwd;
+    a.mods = c->d_mods;
+    a.pinv2 = lt->pinv2;
+    a.nlimbs = nlimbs;
+    a.next = next;
+    a.mode0 = io.mode[0];
+    a.mode1 = io.mode[1];
+    a.galois = io.add_galois;
+    a.map_mode = c->tune[0];
+    ProfScope ps(c, PK_FWD_FINAL, st);
+    hipLaunchKernelGGL(ntt16_fwd_blocks_final_kernel, dim3(B * 2, 16, nlimbs), dim3(NTT16_THREADS), 0, st, a);
+    HIP_TRY(hipGetLastError());
+  }
+  return CKKS_OK;
+}
+
+// Key switch of io.d with evk into io.out (see KsIo). Other ring degrees: one kernel per step.
+int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* evk, char* ws, hipStream_t st) {
   const LevelTables* lt;
   int rc = get_level(c, nlimbs, &lt);
   if (rc) return rc;
+  if (c->logN == 16) return keyswitch_fused16(c, lt, io, B, nlimbs, evk, ws, st);
+  if (io.d_galois || io.mode[0] == 2 || io.mode[1] == 2 || io.d_stride != (u64)nlimbs * c->N)
+    return fail(CKKS_EINVAL, "internal: gather modes need the N = 2^16 path");
+  const u64* d = io.d;
+  u64* out = io.out;
+  const u32 add_mask = (io.mode[0] ? 1u : 0u) | (io.mode[1] ? 2u : 0u);
   const u32 N = c->N, next = lt->next, beta = lt->beta, K = c->np;
   KsLayout L = ks_layout(c, B, nlimbs);
   u64* dcoef = (u64*)(ws + L.dcoef);
@@ -375,8 +540,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
     ProfScope ps(c, PK_MODUP, st);
-    hipLaunchKernelGGL(modup_kernel, dim3(N / BCONV_THREADS, beta, B), dim3(BCONV_THREADS),
-                       (size_t)c->alpha * BCONV_THREADS * 8, st, a);
+    launch_modup<false>(c, a, dim3(N / BCONV_THREADS, beta, B), st);
     HIP_TRY(hipGetLastError());
   }
   // 3. forward transform of the converted slots
@@ -398,8 +562,7 @@ int keyswitch_impl(ckks_ctx* c, u64* out, const u64* d, u32 B, u32 nlimbs, const
   {
     ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat, c->logN, nlimbs, c->nq, K, next};
     ProfScope ps(c, PK_MODDOWN, st);
-    hipLaunchKernelGGL(moddown_kernel, dim3(N / BCONV_THREADS, B * 2), dim3(BCONV_THREADS),
-                       (size_t)std::max<u32>(1, K) * BCONV_THREADS * 8, st, a);
+    launch_moddown<false>(c, a, dim3(N / BCONV_THREADS, B * 2), st);
     HIP_TRY(hipGetLastError());
   }
   // 7. its forward transform, 8. subtract, scale by P^-1, assemble
@@ -453,7 +616,8 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
                     uint32_t dnum, const uint64_t* psi, int device) {
   if (!out || !q || !psi || (np && !p)) return fail(CKKS_EINVAL, "null argument");
   if (logN < 10 || logN > 17) return fail(CKKS_ESHAPE, "logN must be in [10, 17]");
-  if (nq == 0 || dnum == 0 || dnum > nq || nq + np > CKKS_MAX_SLOTS) return fail(CKKS_ESHAPE, "bad prime or digit count");
+  if (nq == 0 || dnum == 0 || dnum > nq || nq + np > CKKS_MAX_SLOTS || nq > 45 || np > 45)
+    return fail(CKKS_ESHAPE, "bad prime or digit count (at most 45 main and 45 special primes)");
   int ndev = 0;
   HIP_TRY(hipGetDeviceCount(&ndev));
   if (device < 0 || device >= ndev) return fail(CKKS_EINVAL, "no such device");
@@ -472,13 +636,13 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
   const u64 N = c->N;
   for (u32 i = 0; i < c->nm; i++) {
     u64 m = c->mod[i];
-    bool ok = m < (1ull << 61) && m > 2 * N && (m - 1) % (2 * N) == 0 && h_is_prime(m) && c->psi[i] < m &&
+    bool ok = m < (1ull << 60) && m > 2 * N && (m - 1) % (2 * N) == 0 && h_is_prime(m) && c->psi[i] < m &&
               h_pow(c->psi[i], N, m) == m - 1;
     for (u32 k = 0; k < i && ok; k++) ok = c->mod[k] != m;
     if (!ok) {
       delete c;
       return fail(CKKS_EINVAL, "modulus " + std::to_string(i) +
-                                   " must be a distinct prime < 2^61, = 1 mod 2N, with psi^N = -1");
+                                   " must be a distinct prime < 2^60, = 1 mod 2N, with psi^N = -1");
     }
   }
   // pass plan
@@ -502,6 +666,12 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
     mi.c64s = h_shoup(mi.c64, m);
     mi.ninv = h_inv(N % m, m);
     mi.ninvs = h_shoup(mi.ninv, m);
+    {
+      u64 x = 1;  // Newton iteration for m^-1 mod 2^64 (m odd)
+      for (int it = 0; it < 6; it++) x *= 2 - m * x;
+      mi.minv = (u64)0 - x;
+      mi.pad = 0;
+    }
     pw[0] = 1;
     for (u64 k = 1; k < N; k++) pw[k] = h_mul(pw[k - 1], c->psi[i], m);
     for (u32 k = 0; k < N; k++) {
@@ -543,11 +713,20 @@ int ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(kv.second.dn_inv);
     (void)hipFree(kv.second.dn_mat);
     (void)hipFree(kv.second.pinv);
+    (void)hipFree(kv.second.up_scale);
+    (void)hipFree(kv.second.dn_scale);
+    (void)hipFree(kv.second.dn_mat_plain);
+    (void)hipFree(kv.second.pinv2);
   }
   delete c;
   return CKKS_OK;
 }
 
+int ckks_tune_set(ckks_ctx* c, int knob, int value) {
+  if (!c || knob < 0 || knob >= 8) return fail(CKKS_EINVAL, "bad knob");
+  c->tune[knob] = value;
+  return CKKS_OK;
+}
 int ckks_prof_enable(ckks_ctx* c, int on) {
   if (!c) return fail(CKKS_EINVAL, "null context");
   c->prof_on = on != 0;
@@ -657,7 +836,8 @@ int ckks_keyswitch(ckks_ctx* c, uint64_t* ks_out, const uint64_t* d, uint32_t B,
   if (overlap(ks_out, 2 * poly, d, poly)) return fail(CKKS_EINVAL, "ks_out overlaps d");
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
-  return keyswitch_impl(c, (u64*)ks_out, (const u64*)d, B, nlimbs, (const u64*)evk, 0, (char*)ws, (hipStream_t)stream);
+  KsIo io{(const u64*)d, (u64)nlimbs * c->N, 0, (u64*)ks_out, {0, 0}, nullptr, 0};
+  return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, (hipStream_t)stream);
 }
 
 int ckks_hrot(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
@@ -672,6 +852,12 @@ int ckks_hrot(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, 
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
   hipStream_t st = (hipStream_t)stream;
+  if (c->logN == 16) {
+    // the permutation is applied where the ciphertext is read: by the first inverse pass and the fused inner product
+    // (sigma(c1)) and by the final assembly (sigma(c0))
+    KsIo io{(const u64*)ct_in + polyN, 2 * polyN, g, (u64*)ct_out, {2, 0}, (const u64*)ct_in, g};
+    return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
+  }
   const size_t ks = ks_layout(c, B, nlimbs).total;
   u64* d = (u64*)((char*)ws + ks);
   const LimbMap qmap = identity_map(nlimbs);
@@ -679,7 +865,8 @@ int ckks_hrot(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, 
   if ((rc = launch_automorph(c, (u64*)ct_out, 2 * polyN, (const u64*)ct_in, 2 * polyN, B, nlimbs, qmap, g, true, st)))
     return rc;
   if ((rc = launch_automorph(c, d, polyN, (const u64*)ct_in + polyN, 2 * polyN, B, nlimbs, qmap, g, true, st))) return rc;
-  return keyswitch_impl(c, (u64*)ct_out, d, B, nlimbs, (const u64*)evk, /*add_mask=*/1, (char*)ws, st);
+  KsIo io{d, polyN, 0, (u64*)ct_out, {1, 0}, nullptr, 0};
+  return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
 }
 
 int ckks_hmult_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_a, const uint64_t* ct_b, uint32_t B,
@@ -702,7 +889,8 @@ int ckks_hmult_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_a, const 
     hipLaunchKernelGGL(tensor_kernel, dim3(c->N / 256, nlimbs, B), dim3(256), 0, st, a);
   }
   HIP_TRY(hipGetLastError());
-  return keyswitch_impl(c, (u64*)ct_out, d2, B, nlimbs, (const u64*)evk, /*add_mask=*/3, (char*)ws, st);
+  KsIo io{d2, (u64)nlimbs * c->N, 0, (u64*)ct_out, {1, 1}, nullptr, 0};
+  return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
 }
 
 int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,

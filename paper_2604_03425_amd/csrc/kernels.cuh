@@ -125,44 +125,90 @@ __global__ void __launch_bounds__(256) automorph_kernel(AutoArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// ModUp base conversion: for digit j (limbs [lo_j, hi_j) of the coefficient-domain input), write every
-// other slot of the extended basis. Row layout of `mat` per digit: [alpha+1][next]; row i < len holds
-// (Q_j/q_i) mod m_t, row alpha holds (-Q_j) mod m_t which is multiplied by the count of negative
-// centred representatives.
+// Base conversion. For a source basis {c_i} and one coefficient with residues x_i:
+//   y_i = [x_i * (C/c_i)^-1]_{c_i};  nneg = #{i : y_i > c_i/2}  (those have centred representative y_i - c_i)
+//   out_t = sum_i y_i * [(C/c_i)]_{m_t} + nneg * [-C]_{m_t}   (mod m_t)
+// The constants are stored in Montgomery form (times 2^64 mod m_t); the lazy sum of 30-bit partial products is
+// reduced once per output by a Montgomery reduction, which gives the plain product sum back.
+#define BCONV_THREADS 256
+#define M30 0x3FFFFFFFu
+
+// Sum over up to MAXLEN sources (+ the nneg term) for target column `col` of a constant matrix with row pitch
+// `pitch`; row `nneg_row` holds [-C]. Returns the canonical residue.
+template <int MAXLEN>
+__device__ __forceinline__ u64 bconv_dot(const u32 (&y0)[MAXLEN], const u32 (&y1)[MAXLEN], u32 nneg,
+                                         const u64* __restrict__ crow, const ModInfo& mi) {
+  // crow: the MAXLEN + 1 constants of this output, contiguous; rows beyond the source count are zero.
+  Acc128 V = {0, 0};
+#pragma unroll
+  for (int i0 = 0; i0 < MAXLEN; i0 += 15) {
+    Dot30 dd;
+    dot30_init(dd);
+#pragma unroll
+    for (int i = i0; i < i0 + 15 && i < MAXLEN; i++) {
+      const u64 c = crow[i];
+      dot30_mac(dd, y0[i], y1[i], (u32)c & M30, (u32)(c >> 30));
+    }
+    if (i0 == 0) {
+      const u64 c = crow[MAXLEN];
+      dd.s00 += (u64)nneg * ((u32)c & M30);
+      dd.s01 += (u64)nneg * (u32)(c >> 30);
+    }
+    Acc128 part = dot30_value(dd);
+    if (i0 == 0) {
+      V = part;
+    } else {
+      V.lo += part.lo;
+      V.hi += part.hi + (V.lo < part.lo ? 1ull : 0ull);
+    }
+  }
+  u64 r = redc(V, mi.m, mi.minv);
+  if (MAXLEN > 15) r = csub(r, 2 * mi.m);  // three chunks of 15 products: r < 4m
+  return csub(r, mi.m);
+}
+
+// ModUp: for digit j (limbs [lo_j, hi_j) of the coefficient-domain input), write every other slot of the extended
+// basis. Constants: [digit][target][MAXLEN+1]: entry i < len = (Q_j/q_i), entries len..MAXLEN-1 = 0, entry MAXLEN = -Q_j,
+// all in Montgomery form.
 struct ModUpArgs {
   const u64* dcoef;         // [B][nlimbs][N]
   u64* ext;                 // [B][beta][next][N]
   const ModInfo* mods;
   const ulonglong2* inv;    // [beta][alpha]  ((Q_j/q_i)^-1 mod q_i, shoup)
-  const u64* mat;           // [beta][alpha+1][next]
+  const u64* mat;           // [beta][next][MAXLEN+1]
   u32 logN, nlimbs, nq, alpha, beta, next;
 };
-#define BCONV_THREADS 256
+// PRESCALED: the input already holds y_i (the inverse transform folded (Q_j/q_i)^-1 into its 1/N scaling).
+template <int MAXLEN, bool PRESCALED>
 __global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a) {
-  extern __shared__ u64 ys[];  // [alpha][BCONV_THREADS]
   const u32 N = 1u << a.logN;
   const u32 n = blockIdx.x * BCONV_THREADS + threadIdx.x;
   const u32 j = blockIdx.y, b = blockIdx.z;
   const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs), len = hi - lo;
   const u64* d = a.dcoef + ((size_t)b * a.nlimbs + lo) * N + n;
-  u64 nneg = 0;
-  for (u32 i = 0; i < len; i++) {
-    const u64 m = a.mods[lo + i].m;
-    ulonglong2 c = a.inv[j * a.alpha + i];
-    u64 y = shoup(d[(size_t)i * N], c.x, c.y, m);
-    nneg += (y > (m >> 1)) ? 1 : 0;
-    ys[i * BCONV_THREADS + threadIdx.x] = y;
+  u32 y0[MAXLEN], y1[MAXLEN], nneg = 0;
+#pragma unroll
+  for (int i = 0; i < MAXLEN; i++) {
+    y0[i] = y1[i] = 0;
+    if ((u32)i < len) {
+      const u64 m = a.mods[lo + i].m;
+      u64 y = d[(size_t)i * N];
+      if (!PRESCALED) {
+        ulonglong2 c = a.inv[j * a.alpha + i];
+        y = shoup(y, c.x, c.y, m);
+      }
+      nneg += (y > (m >> 1)) ? 1u : 0u;
+      y0[i] = (u32)y & M30;
+      y1[i] = (u32)(y >> 30);
+    }
   }
-  const u64* mat = a.mat + (size_t)j * (a.alpha + 1) * a.next;
+  const u64* mat = a.mat + (size_t)j * a.next * (MAXLEN + 1);
   u64* out = a.ext + (((size_t)b * a.beta + j) * a.next) * N + n;
   for (u32 t = 0; t < a.next; t++) {
     if (t >= lo && t < hi) continue;
     const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
     const ModInfo mi = a.mods[id];
-    Acc128 acc = {0, 0};
-    for (u32 i = 0; i < len; i++) mac128(acc, ys[i * BCONV_THREADS + threadIdx.x], mat[i * a.next + t]);
-    mac128(acc, nneg, mat[a.alpha * a.next + t]);
-    out[(size_t)t * N] = reduce128(acc, mi);
+    out[(size_t)t * N] = bconv_dot<MAXLEN>(y0, y1, nneg, mat + (size_t)t * (MAXLEN + 1), mi);
   }
 }
 
@@ -178,8 +224,9 @@ struct InnerArgs {
 };
 __global__ void __launch_bounds__(256) inner_kernel(InnerArgs a) {
   const u32 N = 1u << a.logN;
-  const u32 b = blockIdx.x, t = blockIdx.z;
-  const u32 n = blockIdx.y * 256 + threadIdx.x;
+  const u32 lin = xcd_swizzled_linear_id();   // batch-innermost, and workgroups sharing a key slice share an XCD
+  const u32 b = lin % gridDim.x, t = lin / (gridDim.x * gridDim.y);
+  const u32 n = ((lin / gridDim.x) % gridDim.y) * 256 + threadIdx.x;
   const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
   const ModInfo mi = a.mods[id];
   Acc128 sb = {0, 0}, sa = {0, 0};
@@ -195,36 +242,41 @@ __global__ void __launch_bounds__(256) inner_kernel(InnerArgs a) {
 }
 
 // ModDown base conversion P -> Q_l of the special limbs of acc (coefficient domain after INTT):
-// tq[bc][i][n] = sum_k y_k * (P/p_k mod q_i) - nneg * (P mod q_i), y_k = [x_k (P/p_k)^-1]_{p_k}.
+// tq[bc][i][n] = sum_k y_k * (P/p_k mod q_i) + nneg * (-P mod q_i), y_k = [x_k (P/p_k)^-1]_{p_k}.
 struct ModDownArgs {
   const u64* acc;         // [B*2][next][N]; special limbs at slots nlimbs..next-1, coefficient domain
   u64* tq;                // [B*2][nlimbs][N]
   const ModInfo* mods;
   const ulonglong2* inv;  // [K]
-  const u64* mat;         // [K+1][nlimbs]
+  const u64* mat;         // [nlimbs][MAXLEN+1], Montgomery form
   u32 logN, nlimbs, nq, K, next;
 };
+template <int MAXLEN, bool PRESCALED>
 __global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
-  extern __shared__ u64 ys[];
   const u32 N = 1u << a.logN;
   const u32 n = blockIdx.x * BCONV_THREADS + threadIdx.x;
   const u32 bc = blockIdx.y;
   const u64* x = a.acc + ((size_t)bc * a.next + a.nlimbs) * N + n;
-  u64 nneg = 0;
-  for (u32 k = 0; k < a.K; k++) {
-    const u64 m = a.mods[a.nq + k].m;
-    ulonglong2 c = a.inv[k];
-    u64 y = shoup(x[(size_t)k * N], c.x, c.y, m);
-    nneg += (y > (m >> 1)) ? 1 : 0;
-    ys[k * BCONV_THREADS + threadIdx.x] = y;
+  u32 y0[MAXLEN], y1[MAXLEN], nneg = 0;
+#pragma unroll
+  for (int k = 0; k < MAXLEN; k++) {
+    y0[k] = y1[k] = 0;
+    if ((u32)k < a.K) {
+      const u64 m = a.mods[a.nq + k].m;
+      u64 y = x[(size_t)k * N];
+      if (!PRESCALED) {
+        ulonglong2 c = a.inv[k];
+        y = shoup(y, c.x, c.y, m);
+      }
+      nneg += (y > (m >> 1)) ? 1u : 0u;
+      y0[k] = (u32)y & M30;
+      y1[k] = (u32)(y >> 30);
+    }
   }
   u64* out = a.tq + (size_t)bc * a.nlimbs * N + n;
   for (u32 i = 0; i < a.nlimbs; i++) {
     const ModInfo mi = a.mods[i];
-    Acc128 acc = {0, 0};
-    for (u32 k = 0; k < a.K; k++) mac128(acc, ys[k * BCONV_THREADS + threadIdx.x], a.mat[k * a.nlimbs + i]);
-    mac128(acc, nneg, a.mat[a.K * a.nlimbs + i]);
-    out[(size_t)i * N] = reduce128(acc, mi);
+    out[(size_t)i * N] = bconv_dot<MAXLEN>(y0, y1, nneg, a.mat + (size_t)i * (MAXLEN + 1), mi);
   }
 }
 

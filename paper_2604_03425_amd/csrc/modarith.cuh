@@ -15,6 +15,8 @@ struct ModInfo {
   u64 c64s;   // floor(c64 * 2^64 / m)
   u64 ninv;   // N^-1 mod m
   u64 ninvs;  // floor(ninv * 2^64 / m)
+  u64 minv;   // -m^-1 mod 2^64 (Montgomery)
+  u64 pad;
 };
 
 __device__ __forceinline__ u64 mul_hi64(u64 a, u64 b) { return __umul64hi(a, b); }
@@ -47,4 +49,47 @@ __device__ __forceinline__ u64 mulmod(u64 a, u64 b, const ModInfo& mi) {
   Acc128 acc = {0, 0};
   mac128(acc, a, b);
   return reduce128(acc, mi);
+}
+
+// ---- lazy dot products with 30-bit operand halves ----
+// A value v < 2^61 is split as v = v1 * 2^30 + v0 (v0 < 2^30, v1 < 2^31). The four partial products of two such
+// values are accumulated in four 64-bit sums by v_mad_u64_u32 with no carry handling; up to 16 products of
+// operands < 2^60 fit. The sum is then V = s00 + (s01 + s10) * 2^30 + s11 * 2^60.
+struct Dot30 {
+  u64 s00, s01, s10, s11;
+};
+__device__ __forceinline__ void dot30_init(Dot30& d) { d.s00 = d.s01 = d.s10 = d.s11 = 0; }
+__device__ __forceinline__ void dot30_mac(Dot30& d, u32 y0, u32 y1, u32 c0, u32 c1) {
+  d.s00 += (u64)y0 * c0;
+  d.s01 += (u64)y0 * c1;
+  d.s10 += (u64)y1 * c0;
+  d.s11 += (u64)y1 * c1;
+}
+__device__ __forceinline__ Acc128 dot30_value(const Dot30& d) {
+  Acc128 v;
+  u64 mid = d.s01 + d.s10;
+  u64 carry = mid < d.s01 ? 1ull : 0ull;       // the 65th bit of the middle sum
+  u64 mlo = mid << 30, mhi = (mid >> 34) | (carry << 30);
+  u64 hlo = d.s11 << 60, hhi = d.s11 >> 4;
+  v.lo = d.s00 + mlo;
+  v.hi = mhi + (v.lo < mlo ? 1ull : 0ull);
+  u64 lo2 = v.lo + hlo;
+  v.hi += hhi + (lo2 < hlo ? 1ull : 0ull);
+  v.lo = lo2;
+  return v;
+}
+// Montgomery reduction: V * 2^-64 mod m, in [0, V/2^64 + m). minv = -m^-1 mod 2^64.
+__device__ __forceinline__ u64 redc(Acc128 v, u64 m, u64 minv) {
+  u64 u = v.lo * minv;
+  return v.hi + mul_hi64(u, m) + (v.lo != 0 ? 1ull : 0ull);
+}
+
+// Workgroup index remapped so that consecutive logical indices run on the same XCD (the dispatcher deals
+// workgroups to the 8 XCDs round-robin in linear order). Returns the logical linear index for this workgroup.
+__device__ __forceinline__ u32 xcd_swizzled_linear_id() {
+  const u32 total = gridDim.x * gridDim.y * gridDim.z;
+  const u32 lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const u32 xcd = lin & 7, k = lin >> 3;
+  const u32 q = total >> 3, r = total & 7;
+  return xcd * q + min(xcd, r) + k;
 }
