@@ -1,0 +1,140 @@
+"""GPU parity at the shapes of the remaining workloads: BSGS PCMM with 32x24 diagonals, the attention
+QK^T unit (HMult+relin followed by log2(64) rotate-and-sum steps), and points of the level/dnum sweep."""
+import numpy as np
+import pytest
+
+from ckks_inputs import config_params, galois_element, make_params, uniform_residues, uniform_slots, normal_slots
+from oracle import ref
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    import paper_2604_03425_amd as pkg
+    return pkg
+
+
+def test_pcmm_768_diagonals_small_ring(gpu):
+    """FFN-layer packing (x||x||0 per 2048-slot segment, 768x768 weight slice, baby 32 x giant 24) on the
+    N=2^12 ring: one token per ciphertext. Bit-exact against the oracle, and the decrypted result is x W."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    from harness import Keys, encode_plain_eval
+    p = make_params(12, 4, 40, 2, 50, 2)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    keys = Keys(p, rc, 71)
+    dim, n1, n2, nl, B = 768, 32, 24, 4, 2
+    S = p.N // 2
+    rng = np.random.default_rng(3)
+    X = rng.uniform(-1, 1, (B, dim))
+    W = rng.normal(0, 0.02, (dim, dim))
+    cts = []
+    for b in range(B):
+        z = np.zeros(S)
+        z[:dim] = X[b]
+        z[dim:2 * dim] = X[b]
+        cts.append(keys.encrypt_slots(z, 2.0**30, nl))
+    ct = np.stack(cts)
+    pts = np.empty((n2, n1, nl, p.N), dtype=np.uint64)
+    jj = np.arange(dim)
+    for g in range(n2):
+        for b in range(n1):
+            dvec = np.zeros(S)
+            dvec[jj + g * n1] = W[(jj + g * n1 + b) % dim, jj]
+            pts[g, b] = encode_plain_eval(rc, dvec, 2.0**30, nl)
+    baby = [keys.rotation_key(galois_element(b, p.logN)) for b in range(1, n1)]
+    giant = [keys.rotation_key(galois_element(g * n1, p.logN)) for g in range(1, n2)]
+    ref.set_threads(2)
+    want = rc.pcmm_bsgs(ct, pts, n1, n2, 1, baby, giant)
+    ref.set_threads(1)
+    out = torch.empty((B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_pcmm_bsgs(gc, out, to_dev(ct), B, nl, to_dev(pts), n1, n2, 1, [to_dev(k) for k in baby],
+                       [to_dev(k) for k in giant], gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
+    got = to_host(out)
+    assert_same(got, want, "pcmm 32x24")
+    Y = X @ W
+    for b in range(B):
+        y = keys.decrypt_slots(got[b], 2.0**60).real
+        assert np.max(np.abs(y[:dim] - Y[b])) < 2.0**-12     # slots beyond 768 hold partial sums, not results
+
+
+def test_pcmm_full_ring_small_bsgs(gpu):
+    """N=2^16, 24 limbs, dnum=3: PCMM with 3 baby and 2 giant steps, bit-exact."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = config_params("keyswitch_micro")
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    B, nl, n1, n2 = 2, 24, 3, 2
+    ct = uniform_residues(81, p.q, (B, 2), p.N)
+    pt = uniform_residues(82, p.q, (n2, n1), p.N)
+    baby = [uniform_residues(83 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n1 - 1)]
+    giant = [uniform_residues(93 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n2 - 1)]
+    ref.set_threads(2)
+    want = rc.pcmm_bsgs(ct, pt, n1, n2, 1, baby, giant)
+    ref.set_threads(1)
+    out = torch.empty((B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_pcmm_bsgs(gc, out, to_dev(ct), B, nl, to_dev(pt), n1, n2, 1, [to_dev(k) for k in baby],
+                       [to_dev(k) for k in giant], gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
+    assert_same(to_host(out), want, "pcmm N=2^16")
+
+
+def test_attention_unit_full_ring(gpu):
+    """N=2^16, 20 limbs, dnum=4, 5 special primes: one QK^T unit = HMult+relin, then rotate-and-sum by
+    1,2,4,...,32 (six HRot + add steps)."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = config_params("attention_qk")
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    B, nl = 2, 20
+    qa = uniform_residues(91, p.q, (B, 2), p.N)
+    kb = uniform_residues(92, p.q, (B, 2), p.N)
+    relin = uniform_residues(93, p.moduli, (p.dnum, 2), p.N)
+    rot = [uniform_residues(100 + i, p.moduli, (p.dnum, 2), p.N) for i in range(6)]
+    ids = list(range(nl))
+    ref.set_threads(2)
+    want = rc.hmult_relin(qa, kb, relin)
+    for i in range(6):
+        r = rc.hrot(want, galois_element(1 << i, p.logN), rot[i])
+        want = rc.pointwise(want, r, ids, "add")
+    ref.set_threads(1)
+    ws = gc.workspace(gpu.OP_HROT, B, nl)
+    acc = torch.empty((B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    tmp = torch.empty_like(acc)
+    gpu.ckks_hmult_relin(gc, acc, to_dev(qa), to_dev(kb), B, nl, to_dev(relin), ws)
+    mods = torch.tensor(np.array(p.q, dtype=np.int64), device="cuda").view(1, 1, nl, 1)
+    for i in range(6):
+        gpu.ckks_hrot(gc, tmp, acc, B, nl, galois_element(1 << i, p.logN), to_dev(rot[i]), ws)
+        s = acc + tmp                      # residues < 2^50: no int64 overflow; test-side modular add
+        acc = torch.where(s >= mods, s - mods, s)
+    assert_same(to_host(acc), want, "attention unit")
+
+
+SWEEP = [
+    # limbs, dnum  (alpha = K = ceil(limbs/dnum))
+    (4, 3),      # ragged: digits 2,2 (beta = 2 < dnum)
+    (12, 6),
+    (36, 6),
+    (36, 1),     # one 36-limb digit, 36 special primes
+    (20, 3),     # ragged: 7,7,6
+]
+
+
+@pytest.mark.parametrize("limbs,dnum", SWEEP)
+def test_sweep_point_keyswitch(gpu, limbs, dnum):
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    K = -(-limbs // dnum)
+    p = make_params(16, limbs, 50, K, 60, dnum)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    B = 1
+    d = uniform_residues(limbs * 10 + dnum, p.q, (B,), p.N)
+    evk = uniform_residues(limbs * 10 + dnum + 1, p.moduli, (p.dnum, 2), p.N)
+    want = rc.keyswitch(d, evk)
+    out = torch.empty((B, 2, limbs, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_keyswitch(gc, out, to_dev(d), B, limbs, to_dev(evk), 0, dnum, gc.workspace(gpu.OP_KEYSWITCH, B, limbs))
+    assert_same(to_host(out), want, "sweep point %d limbs dnum %d" % (limbs, dnum))
+    gc.close()

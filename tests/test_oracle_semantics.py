@@ -189,3 +189,26 @@ def test_hrot_rotates_slots_at_full_size():
     out = c.hrot(ct[None], g, keys.rotation_key(g))[0]
     err = np.max(np.abs(keys.decrypt_slots(out, 2.0**40) - np.roll(z, -k)))
     assert err < 2.0**-20, err
+
+
+def test_attention_unit_scores():
+    """QK^T unit: HMult+relin of token-major packed Q and K (64 slots per token), then rotate-and-sum over
+    the 64 slots of a token: slot 64t holds the dot product <q_t, k_t>."""
+    p = make_params(10, 4, 40, 2, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 61)
+    S, hd = p.N // 2, 64
+    ntok = S // hd
+    rng = np.random.default_rng(1)
+    Q = rng.normal(0, 1, (ntok, hd)) * 0.1
+    Kmat = rng.normal(0, 1, (ntok, hd)) * 0.1
+    cq = keys.encrypt_slots(Q.reshape(-1), 2.0**30, 4)[None]
+    ck = keys.encrypt_slots(Kmat.reshape(-1), 2.0**30, 4)[None]
+    acc = c.hmult_relin(cq, ck, keys.relin_key())
+    ids = [0, 1, 2, 3]
+    for i in range(6):
+        g = galois_element(1 << i, p.logN)
+        acc = c.pointwise(acc, c.hrot(acc, g, keys.rotation_key(g)), ids, "add")
+    z = keys.decrypt_slots(acc[0], 2.0**60).real
+    want = np.sum(Q * Kmat, axis=1)
+    assert np.max(np.abs(z[::hd] - want)) < 2.0**-14
