@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--groups", type=int, default=8, help="distinct (Galois element, key) groups among the 64 HRots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--map-mode", type=int, default=None, help="experiment: workgroup mapping mode of the 2^16 transforms")
+    ap.add_argument("--int-only", action="store_true", help="experiment: integer bodies for every modulus")
+    ap.add_argument("--tune", type=str, default="", help="experiment: comma-separated knob=value pairs")
+    ap.add_argument("--streams", type=int, default=1, help="HIP streams the independent calls of a step are spread over")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate NTT / HRot / HMult timings (profiling runs)")
     ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
     args = ap.parse_args()
@@ -87,6 +90,11 @@ def main():
     ctx = ck.Context(p, 0)
     if args.map_mode is not None:
         ck.ckks_tune_set(ctx, 0, args.map_mode)
+    if args.int_only:
+        ck.ckks_tune_set(ctx, 1, 1)
+    for kv in filter(None, args.tune.split(",")):
+        k, v = kv.split("=")
+        ck.ckks_tune_set(ctx, int(k), int(v))
     gen = torch.Generator(device=dev).manual_seed(0xC0FFEE)
 
     def uniform(prefix, moduli):
@@ -105,12 +113,26 @@ def main():
     out_rot = torch.empty_like(ct)
     out_mul = torch.empty_like(ct_a)
     Bg = B // G
-    ws = ctx.workspace(ck.OP_HROT, max(Bg, B // 2), nl)
+    # the calls of a step are independent of each other; with more than one stream they are dealt round-robin to
+    # the streams (default priority), each stream with its own workspace, so one call's tail overlaps another's start
+    nstreams = max(1, args.streams)
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(nstreams - 1)]
+    wss = [ctx.workspace(ck.OP_HROT, max(Bg, B // 2), nl) for _ in range(nstreams)]
+    ws = wss[0]
 
     def step():
+        if nstreams > 1:
+            for s_ in streams[1:]:
+                s_.wait_stream(streams[0])
         for g in range(G):
-            ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g], ws)
-        ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws)
+            with torch.cuda.stream(streams[g % nstreams]):
+                ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g],
+                             wss[g % nstreams])
+        with torch.cuda.stream(streams[G % nstreams]):
+            ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, wss[G % nstreams])
+        if nstreams > 1:
+            for s_ in streams[1:]:
+                streams[0].wait_stream(s_)
 
     for _ in range(args.warmup):
         step()

@@ -160,7 +160,8 @@ int ckks_pcmm_bsgs(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint3
  * Not thread-safe: use one thread per context while profiling.
  */
 int ckks_prof_enable(ckks_ctx* ctx, int on);
-/* Tuning knob for experiments: knob 0 = workgroup-to-tile mapping of the N = 2^16 transforms (0..3). */
+/* Tuning knobs for experiments: knob 0 = workgroup-to-tile mapping of the N = 2^16 transforms (0..4);
+ * knob 1 != 0 turns the double-precision bodies for primes < 2^50 off (integer bodies everywhere). */
 int ckks_tune_set(ckks_ctx* ctx, int knob, int value);
 int ckks_prof_num_kinds(void);
 const char* ckks_prof_kind_name(int kind);

@@ -4,13 +4,14 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstring>
 #include <map>
 #include <mutex>
 #include <string>
 #include <vector>
 
 #include "kernels.cuh"
-#include "ntt16.cuh"
+#include "ntt16_kernels.cuh"
 
 typedef unsigned __int128 u128;
 
@@ -116,6 +117,8 @@ struct ckks_ctx {
   ModInfo* d_mods = nullptr;
   ulonglong2* d_tw_fwd = nullptr;
   ulonglong2* d_tw_inv = nullptr;
+  double* d_twfp_fwd = nullptr;  // N = 2^16 only: the twiddles as doubles for moduli < 2^50
+  double* d_twfp_inv = nullptr;
   std::vector<Pass> passes;  // forward order
   std::mutex mu;
   std::map<u32, LevelTables> levels;
@@ -174,7 +177,10 @@ struct ProfScope {
 
 int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
   std::lock_guard<std::mutex> lock(c->mu);
-  auto it = c->levels.find(nlimbs);
+  const bool fp_on = c->tune[1] == 0;
+  const u32 key = nlimbs * 2 + (fp_on ? 1 : 0);
+  auto is_fp = [&](u64 m) { return fp_on && (m >> 50) == 0; };
+  auto it = c->levels.find(key);
   if (it != c->levels.end()) {
     *out = &it->second;
     return CKKS_OK;
@@ -233,24 +239,43 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
     u64 inv = h_inv(v, m);
     pinv[i] = ulonglong2{inv, h_shoup(inv, m)};
   }
+  // Constants of the fused N = 2^16 path. 16-byte slots hold a Shoup pair (integer-class modulus) or the doubles
+  // (c, c/q) (double-precision class). Integer-class accumulators carry a factor 2^-64 (Montgomery products), which
+  // dn_scale and pinv2 undo; double-precision accumulators are plain.
   std::vector<ulonglong2> up_scale(nlimbs), dn_scale(K), pinv2(nlimbs);
   std::vector<u64> dn_mat_plain(dn_mat.size(), 0);
+  auto as_fp = [](u64 v, u64 m) {
+    double2 d{(double)v, (double)v / (double)m};
+    ulonglong2 r;
+    memcpy(&r, &d, sizeof(r));
+    return r;
+  };
   for (u32 i = 0; i < nlimbs; i++) {
     u64 m = c->mod[i], ninv = h_inv(c->N % m, m);
     u64 v = h_mul(up_inv[(size_t)(i / alpha) * alpha + (i % alpha)].x, ninv, m);
-    up_scale[i] = ulonglong2{v, h_shoup(v, m)};
-    u64 w = h_mont(pinv[i].x, m);
-    pinv2[i] = ulonglong2{w, h_shoup(w, m)};
-    for (u32 k = 0; k <= RK; k++) {
-      // undo the Montgomery factor: stored value is v * 2^64, multiply by 2^-64
-      u64 r64 = h_mont(1, m);
-      dn_mat_plain[(size_t)i * (RK + 1) + k] = h_mul(dn_mat[(size_t)i * (RK + 1) + k], h_inv(r64, m), m);
+    u64 r64_inv = h_inv(h_mont(1, m), m);
+    if (is_fp(m)) {
+      up_scale[i] = as_fp(v, m);
+      pinv2[i] = as_fp(pinv[i].x, m);
+      for (u32 k = 0; k <= RK; k++) dn_mat_plain[(size_t)i * (RK + 1) + k] = dn_mat[(size_t)i * (RK + 1) + k];
+    } else {
+      up_scale[i] = ulonglong2{v, h_shoup(v, m)};
+      u64 w = h_mont(pinv[i].x, m);
+      pinv2[i] = ulonglong2{w, h_shoup(w, m)};
+      // stored constants are c * 2^64; multiply by 2^-64 so the Montgomery reduction leaves t * 2^-64
+      for (u32 k = 0; k <= RK; k++)
+        dn_mat_plain[(size_t)i * (RK + 1) + k] = h_mul(dn_mat[(size_t)i * (RK + 1) + k], r64_inv, m);
     }
   }
   for (u32 k = 0; k < K; k++) {
     u64 m = c->mod[c->nq + k], ninv = h_inv(c->N % m, m);
-    u64 v = h_mont(h_mul(dn_inv[k].x, ninv, m), m);
-    dn_scale[k] = ulonglong2{v, h_shoup(v, m)};
+    u64 v = h_mul(dn_inv[k].x, ninv, m);
+    if (is_fp(m)) {
+      dn_scale[k] = as_fp(v, m);
+    } else {
+      u64 w = h_mont(v, m);
+      dn_scale[k] = ulonglong2{w, h_shoup(w, m)};
+    }
   }
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
@@ -261,7 +286,7 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
   if ((rc = upload(&t.up_inv, up_inv)) || (rc = upload(&t.up_mat, up_mat)) || (rc = upload(&t.dn_inv, dn_inv)) ||
       (rc = upload(&t.dn_mat, dn_mat)) || (rc = upload(&t.pinv, pinv)))
     return rc;
-  auto res = c->levels.emplace(nlimbs, t);
+  auto res = c->levels.emplace(key, t);
   *out = &res.first->second;
   return CKKS_OK;
 }
@@ -280,6 +305,24 @@ LimbMap ext_map(const ckks_ctx* c, u32 nlimbs) {
 
 // Enqueue a transform of npoly polynomials x slots [slot0, slot0+nslots): reads src, writes dst (src == dst for an
 // in-place transform; out of place is supported only on the N = 2^16 path). Rows are *_stride elements apart.
+// Modulus class on the N = 2^16 path (must match mod_class() on the device).
+inline int host_class(const ckks_ctx* c, u64 m) {
+  if (c->tune[1] == 0 && (m >> 50) == 0) return 0;
+  return (m >> 52) == 0 ? 1 : 2;
+}
+// Launch KERNEL<cls> once per modulus class present among `nslots` slots, with ARGS.slots listing that class's slots.
+#define LAUNCH_BY_CLASS(KERNEL, ARGS, NX, NSLOTS, CLASS_OF_SLOT, STREAM)                                   \
+  for (int cls_ = 0; cls_ < 3; cls_++) {                                                                    \
+    u32 cnt_ = 0;                                                                                           \
+    for (u32 s_ = 0; s_ < (NSLOTS); s_++)                                                                   \
+      if ((CLASS_OF_SLOT(s_)) == cls_) (ARGS).slots[cnt_++] = (unsigned char)s_;                            \
+    if (!cnt_) continue;                                                                                    \
+    dim3 grid_((NX), 16, cnt_), block_(NTT16_THREADS);                                                      \
+    if (cls_ == 0) hipLaunchKernelGGL((KERNEL<0>), grid_, block_, 0, (STREAM), (ARGS));                     \
+    else if (cls_ == 1) hipLaunchKernelGGL((KERNEL<1>), grid_, block_, 0, (STREAM), (ARGS));                \
+    else hipLaunchKernelGGL((KERNEL<2>), grid_, block_, 0, (STREAM), (ARGS));                               \
+  }
+
 struct NttOpts {
   u32 galois = 0;                     // N = 2^16 inverse only: read src through the eval-domain Galois map
   const ulonglong2* scale = nullptr;  // N = 2^16 inverse only: per-slot constants (from slot0) replacing N^-1
@@ -295,6 +338,7 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     a.src = src + (size_t)slot0 * c->N;
     a.dst = dst + (size_t)slot0 * c->N;
     a.tw = inverse ? c->d_tw_inv : c->d_tw_fwd;
+    a.twfp = inverse ? c->d_twfp_inv : c->d_twfp_fwd;
     a.mods = c->d_mods;
     a.src_poly_stride = src_stride;
     a.dst_poly_stride = dst_stride;
@@ -305,19 +349,28 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     a.map_mode = c->tune[0];
     a.galois = opt.galois;
     a.scale = opt.scale;
-    dim3 grid(npoly, 16, nslots), block(NTT16_THREADS);
     Ntt16Args b = a;  // second pass: in place on dst
     b.src = a.dst;
     b.src_poly_stride = dst_stride;
+    auto cls_of = [&](u32 s) { return host_class(c, c->mod[ids_from_slot0.id[s]]); };
     if (!inverse) {
-      { ProfScope ps(c, PK_FWD_ROWS, st); hipLaunchKernelGGL(ntt16_fwd_rows_kernel, grid, block, 0, st, a); }
+      {
+        ProfScope ps(c, PK_FWD_ROWS, st);
+        LAUNCH_BY_CLASS(ntt16_fwd_rows_kernel, a, npoly, nslots, cls_of, st)
+      }
       if (!opt.rows_only) {
         ProfScope ps(c, PK_FWD_BLOCKS, st);
-        hipLaunchKernelGGL(ntt16_fwd_blocks_kernel, grid, block, 0, st, b);
+        LAUNCH_BY_CLASS(ntt16_fwd_blocks_kernel, b, npoly, nslots, cls_of, st)
       }
     } else {
-      { ProfScope ps(c, PK_INV_BLOCKS, st); hipLaunchKernelGGL(ntt16_inv_blocks_kernel, grid, block, 0, st, a); }
-      { ProfScope ps(c, PK_INV_ROWS, st); hipLaunchKernelGGL(ntt16_inv_rows_kernel, grid, block, 0, st, b); }
+      {
+        ProfScope ps(c, PK_INV_BLOCKS, st);
+        LAUNCH_BY_CLASS(ntt16_inv_blocks_kernel, a, npoly, nslots, cls_of, st)
+      }
+      {
+        ProfScope ps(c, PK_INV_ROWS, st);
+        LAUNCH_BY_CLASS(ntt16_inv_rows_kernel, b, npoly, nslots, cls_of, st)
+      }
     }
     HIP_TRY(hipGetLastError());
     return CKKS_OK;
@@ -466,6 +519,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     a.evk = evk;
     a.acc = acc;
     a.tw = c->d_tw_fwd;
+    a.twfp = c->d_twfp_fwd;
     a.mods = c->d_mods;
     a.nlimbs = nlimbs;
     a.nq = c->nq;
@@ -476,7 +530,12 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     a.map_mode = c->tune[0];
     a.galois = io.d_galois;
     ProfScope ps(c, PK_FWD_INNER, st);
-    hipLaunchKernelGGL(ntt16_fwd_blocks_inner_kernel, dim3(B, 16, next), dim3(NTT16_THREADS), 0, st, a);
+    auto cls_of = [&](u32 s) { return host_class(c, c->mod[emap.id[s]]); };
+    if (c->tune[2]) {
+      LAUNCH_BY_CLASS(ntt16_fwd_blocks_inner_occ3_kernel, a, B, next, cls_of, st)
+    } else {
+      LAUNCH_BY_CLASS(ntt16_fwd_blocks_inner_kernel, a, B, next, cls_of, st)
+    }
     HIP_TRY(hipGetLastError());
   }
   {
@@ -500,8 +559,9 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     a.out = io.out;
     a.add_src = io.add_src;
     a.tw = c->d_tw_fwd;
+    a.twfp = c->d_twfp_fwd;
     a.mods = c->d_mods;
-    a.pinv2 = lt->pinv2;
+    a.pinv = lt->pinv2;
     a.nlimbs = nlimbs;
     a.next = next;
     a.mode0 = io.mode[0];
@@ -509,7 +569,8 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     a.galois = io.add_galois;
     a.map_mode = c->tune[0];
     ProfScope ps(c, PK_FWD_FINAL, st);
-    hipLaunchKernelGGL(ntt16_fwd_blocks_final_kernel, dim3(B * 2, 16, nlimbs), dim3(NTT16_THREADS), 0, st, a);
+    auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
+    LAUNCH_BY_CLASS(ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
     HIP_TRY(hipGetLastError());
   }
   return CKKS_OK;
@@ -656,6 +717,11 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
   // tables
   std::vector<ModInfo> mods(c->nm);
   std::vector<ulonglong2> fwd((size_t)c->nm * N), inv((size_t)c->nm * N);
+  std::vector<double> fwdfp, invfp;
+  if (logN == 16) {
+    fwdfp.assign((size_t)c->nm * N, 0.0);
+    invfp.assign((size_t)c->nm * N, 0.0);
+  }
   std::vector<u64> pw(N);
   for (u32 i = 0; i < c->nm; i++) {
     u64 m = c->mod[i];
@@ -672,6 +738,10 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
       mi.minv = (u64)0 - x;
       mi.pad = 0;
     }
+    mi.qd = (double)m;
+    mi.qinv = 1.0 / (double)m;
+    mi.ninvd = (double)mi.ninv;
+    mi.ninvq = (double)mi.ninv / (double)m;
     pw[0] = 1;
     for (u64 k = 1; k < N; k++) pw[k] = h_mul(pw[k - 1], c->psi[i], m);
     for (u32 k = 0; k < N; k++) {
@@ -681,6 +751,10 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
       u32 e = h_brev(k, logN);
       u64 wi = e == 0 ? 1 : m - pw[N - e];
       inv[(size_t)i * N + k] = ulonglong2{wi, h_shoup(wi, m)};
+      if (logN == 16 && (m >> 50) == 0) {
+        fwdfp[(size_t)i * N + k] = (double)w;
+        invfp[(size_t)i * N + k] = (double)wi;
+      }
     }
   }
   DeviceGuard guard(device);
@@ -688,6 +762,8 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
   if (!rc) rc = upload(&c->d_mods, mods);
   if (!rc) rc = upload(&c->d_tw_fwd, fwd);
   if (!rc) rc = upload(&c->d_tw_inv, inv);
+  if (!rc) rc = upload(&c->d_twfp_fwd, fwdfp);
+  if (!rc) rc = upload(&c->d_twfp_inv, invfp);
   if (rc) {
     ckks_ctx_destroy(c);
     return rc;
@@ -702,6 +778,8 @@ int ckks_ctx_destroy(ckks_ctx* c) {
   (void)hipFree(c->d_mods);
   (void)hipFree(c->d_tw_fwd);
   (void)hipFree(c->d_tw_inv);
+  (void)hipFree(c->d_twfp_fwd);
+  (void)hipFree(c->d_twfp_inv);
   for (auto& r : c->prof_recs) {
     (void)hipEventDestroy(r.start);
     (void)hipEventDestroy(r.stop);

@@ -17,7 +17,46 @@ struct ModInfo {
   u64 ninvs;  // floor(ninv * 2^64 / m)
   u64 minv;   // -m^-1 mod 2^64 (Montgomery)
   u64 pad;
+  // double-precision view, used for primes < 2^50 (every residue and every lazy value below 2^53 is exact)
+  double qd;     // m
+  double qinv;   // 1/m rounded
+  double ninvd;  // N^-1 mod m
+  double ninvq;  // ninvd / m rounded
 };
+
+// ---- exact modular arithmetic in double precision for primes q < 2^50 ----
+// Values are integers held in doubles with magnitude < 2^53 = 8q. The product a*w is formed exactly as h + l
+// (rounded product + fma error term), the quotient estimate c = rint(a * (w/q)) is off by at most
+// 0.5 + |a| 2^-52 from a*w/q, and h - c q + l is exact. All operations are IEEE and deterministic.
+__device__ __forceinline__ double fp_mulmod_const(double a, double w, double wq, double q) {
+  double h = a * w;
+  double l = __builtin_fma(a, w, -h);
+  double c = __builtin_rint(a * wq);
+  return __builtin_fma(-c, q, h) + l;  // |result| <= (0.5 + |a|/2^52) q
+}
+// a * e mod q for two variables (no precomputed e/q): quotient from the rounded product.
+__device__ __forceinline__ double fp_mulmod_var(double a, double e, double qinv, double q) {
+  double h = a * e;
+  double l = __builtin_fma(a, e, -h);
+  double c = __builtin_rint(h * qinv);
+  return __builtin_fma(-c, q, h) + l;
+}
+__device__ __forceinline__ double fp_reduce(double x, double qinv, double q) {  // |result| <= q/2 (+1)
+  return __builtin_fma(-__builtin_rint(x * qinv), q, x);
+}
+__device__ __forceinline__ double u2d(u64 v) {  // exact for v < 2^52
+  return __longlong_as_double((long long)(v | 0x4330000000000000ull)) - 4503599627370496.0;
+}
+__device__ __forceinline__ u64 d2u_canon(double r, double q) {  // r an integer in (-q, 2q) -> canonical residue
+  r = r < 0.0 ? r + q : r;
+  r = r >= q ? r - q : r;
+  return (u64)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
+}
+// 0: double-precision path (q < 2^50), 1: integer path without butterfly corrections (q < 2^52), 2: Harvey (q < 2^60)
+__device__ __forceinline__ int mod_class(u64 m, u32 fp_on) {
+  if (fp_on && (m >> 50) == 0) return 0;
+  return (m >> 52) == 0 ? 1 : 2;
+}
 
 __device__ __forceinline__ u64 mul_hi64(u64 a, u64 b) { return __umul64hi(a, b); }
 __device__ __forceinline__ u64 csub(u64 x, u64 m) { return x >= m ? x - m : x; }
@@ -92,4 +131,16 @@ __device__ __forceinline__ u32 xcd_swizzled_linear_id() {
   const u32 xcd = lin & 7, k = lin >> 3;
   const u32 q = total >> 3, r = total & 7;
   return xcd * q + min(xcd, r) + k;
+}
+
+// Workgroup barrier that orders LDS traffic only: waits for this wave's LDS operations, not for its outstanding
+// global loads and stores, so those stay in flight across the barrier (a plain __syncthreads() drains them).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Ordering point for LDS exchanges that stay inside one wavefront (here: inside a group of 16 adjacent lanes):
+// the wave's own LDS operations complete in order, so waiting for them is enough; no workgroup barrier.
+__device__ __forceinline__ void wave_lds_sync() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }

@@ -1,0 +1,354 @@
+// Kernels of the N = 2^16 path: the four transform passes and the two fused last-pass kernels of key switching.
+// Each kernel picks, per modulus (uniform per workgroup), the double-precision bodies (q < 2^50), the integer
+// bodies without butterfly corrections (q < 2^52) or the Harvey bodies (q < 2^60). The class also fixes the
+// format of the data between the two passes of a transform (reduced doubles / lazy integers) and of the
+// constants passed in 16-byte slots (double2 / Shoup pair).
+#pragma once
+#include "ntt16.cuh"
+#include "ntt16fp.cuh"
+
+// ---- standalone passes: grid = (polynomials, 16 tiles, limb slots) ----
+struct Ntt16Args {
+  const u64* src;
+  u64* dst;
+  const ulonglong2* tw;     // integer table (forward or inverse), [nm][65536]
+  const double* twfp;       // double table, same indexing (rows of moduli >= 2^50 unused)
+  const ModInfo* mods;
+  u64 src_poly_stride, dst_poly_stride;  // elements between polynomials
+  u32 skip_beta, skip_alpha, skip_nq;    // digit p % skip_beta leaves its own limbs alone (ModUp'ed digits)
+  u32 map_mode;                          // workgroup -> (poly, tile, slot) mapping, see ntt16_map
+  u32 galois;                            // inverse first pass only: != 0 reads src through the eval-domain Galois map
+  const ulonglong2* scale;               // inverse second pass only: per-slot constant replacing N^-1 (NULL = N^-1);
+                                         // a double2 (c, c/q) for double-precision moduli, a Shoup pair otherwise
+  unsigned char id[128];                 // slot -> modulus id
+  unsigned char slots[128];              // grid.z index -> slot (the launch covers the slots of one modulus class)
+};
+
+__device__ __forceinline__ bool ntt16_skip(const Ntt16Args& a, u32 poly, u32 slot) {
+  if (!a.skip_beta) return false;
+  u32 j = poly % a.skip_beta, lo = j * a.skip_alpha, hi = min(lo + a.skip_alpha, a.skip_nq);
+  return slot >= lo && slot < hi;
+}
+#define NTT16_PROLOGUE                                                              \
+  __shared__ u64 sm[NTT16_LDS_BYTES / 8];                                           \
+  u32 poly, tile, zi;                                                               \
+  ntt16_map(a.map_mode, poly, tile, zi);                                            \
+  const u32 slot = a.slots[zi];                                                     \
+  if (ntt16_skip(a, poly, slot)) return;                                            \
+  const u32 id = a.id[slot];                                                        \
+  const ModInfo mi = a.mods[id];                                                    \
+  const ulonglong2* tw = a.tw + (size_t)id * 65536;                                 \
+  const double* twfp = a.twfp + (size_t)id * 65536;                                 \
+  const u64* src = a.src + (size_t)poly * a.src_poly_stride + (size_t)slot * 65536; \
+  u64* dst = a.dst + (size_t)poly * a.dst_poly_stride + (size_t)slot * 65536;       \
+  const int cls = CLS;
+
+// CLS: modulus class of every slot of the launch (0 double precision, 1 integer uncorrected, 2 Harvey); one
+// instantiation per class so that each gets its own register allocation.
+template <int CLS>
+__global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_rows_kernel(Ntt16Args a) {
+  NTT16_PROLOGUE
+  if (cls == 0) ntt16_fwd_rows_fp(src, (double*)dst, twfp, mi.qd, mi.qinv, tile, (double*)sm);
+  else if (cls == 2) ntt16_fwd_rows<true>(src, dst, tw, mi.m, tile, sm);
+  else ntt16_fwd_rows<false>(src, dst, tw, mi.m, tile, sm);
+}
+template <int CLS>
+__global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_kernel(Ntt16Args a) {
+  NTT16_PROLOGUE
+  const u32 t = threadIdx.x, j0 = t & 15, h = tile * 16 + (t >> 4);
+  u64 x[16];
+  if (cls == 0) {
+    double xd[16];
+    ntt16_fwd_blocks_fp(xd, (const double*)src, twfp, mi.qd, mi.qinv, tile, (double*)sm);
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = d2u_canon(xd[i], mi.qd);
+  } else if (cls == 2) {
+    ntt16_fwd_blocks<true>(x, src, tw, mi.m, mi.mu64, tile, sm);
+  } else {
+    ntt16_fwd_blocks<false>(x, src, tw, mi.m, mi.mu64, tile, sm);
+  }
+#pragma unroll
+  for (int i = 0; i < 16; i++) dst[(size_t)h * 256 + i * 16 + j0] = x[i];
+}
+template <int CLS>
+__global__ void __launch_bounds__(NTT16_THREADS) ntt16_inv_blocks_kernel(Ntt16Args a) {
+  NTT16_PROLOGUE
+  const u32 t = threadIdx.x, j0 = t & 15, h = tile * 16 + (t >> 4);
+  u64 x[16];
+  if (a.galois) {
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = src[galois_src_index16(h * 256 + i * 16 + j0, a.galois)];
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = src[(size_t)h * 256 + i * 16 + j0];
+  }
+  if (cls == 0) {
+    double xd[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) xd[i] = u2d(x[i]);
+    ntt16_inv_blocks_fp(xd, twfp, mi.qd, mi.qinv, tile, (double*)sm);
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = (u64)__double_as_longlong(xd[i]);
+  } else if (cls == 2) {
+    ntt16_inv_blocks<true>(x, tw, mi.m, mi.mu64, tile, sm);
+  } else {
+    ntt16_inv_blocks<false>(x, tw, mi.m, mi.mu64, tile, sm);
+  }
+#pragma unroll
+  for (int i = 0; i < 16; i++) dst[(size_t)h * 256 + i * 16 + j0] = x[i];
+}
+template <int CLS>
+__global__ void __launch_bounds__(NTT16_THREADS) ntt16_inv_rows_kernel(Ntt16Args a) {
+  NTT16_PROLOGUE
+  u64 x[16];
+  if (cls == 0) {
+    double sc = mi.ninvd, scq = mi.ninvq;
+    if (a.scale) {
+      const double2 v = ((const double2*)a.scale)[slot];
+      sc = v.x;
+      scq = v.y;
+    }
+    ntt16_inv_rows_fp(x, (const double*)src, twfp, mi.qd, mi.qinv, sc, scq, tile, (double*)sm);
+  } else {
+    u64 sc = mi.ninv, scs = mi.ninvs;
+    if (a.scale) {
+      const ulonglong2 v = a.scale[slot];
+      sc = v.x;
+      scs = v.y;
+    }
+    if (cls == 2) ntt16_inv_rows<true>(x, src, tw, mi.m, sc, scs, tile, sm);
+    else ntt16_inv_rows<false>(x, src, tw, mi.m, sc, scs, tile, sm);
+  }
+  const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
+#pragma unroll
+  for (int i = 0; i < 16; i++) dst[(size_t)(i * 16 + r0) * 256 + col0 + col] = x[i];
+}
+
+// ---- fused: last forward pass of the ModUp'ed digits + inner product with the evaluation key ----
+// For (ciphertext b, extended slot t, tile): acc[b][c][t] = sum_j D_j * evk[j][c][id(t)], where D_j is the forward
+// transform of ext[b][j][t] (slots the digit does not own) or d[b][t] itself (the digit's own limbs, already in
+// the evaluation domain). Output canonical. On integer-class moduli the products go through a Montgomery
+// reduction, so acc carries a factor 2^-64 there, which the later stages absorb into their constants; on
+// double-precision moduli acc is the plain sum.
+struct FwdInnerArgs {
+  const u64* ext;   // [B][beta][next][N], after the row pass
+  const u64* d;     // eval domain, limb-vector (b, t) at d + b*d_poly_stride + t*N; read through the Galois map if galois != 0
+  u64 d_poly_stride;
+  const u64* evk;   // [dnum][2][nm][N]
+  u64* acc;         // [B][2][next][N]
+  const ulonglong2* tw;
+  const double* twfp; 
+  const ModInfo* mods;
+  u32 nlimbs, nq, nm, alpha, beta, next, map_mode, galois;
+  unsigned char slots[128];  // grid.z index -> extended slot (one modulus class per launch)
+};
+
+// Raw 64-bit words of the tile that digit j contributes to slot t: the digit's own limb read from d (through the
+// Galois map if asked), else the row-pass output in ext. Lane (hb, j0) gets positions i*16 + j0 of block h.
+__device__ __forceinline__ void fwd_inner_load(u64 (&raw)[16], const FwdInnerArgs& a, u32 b, u32 t, u32 j, bool own, u32 h,
+                                               u32 j0) {
+  const size_t N = 65536;
+  if (own) {
+    const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+    if (a.galois) {
+#pragma unroll
+      for (int i = 0; i < 16; i++) raw[i] = src[galois_src_index16(h * 256 + i * 16 + j0, a.galois)];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; i++) raw[i] = src[(size_t)h * 256 + i * 16 + j0];
+    }
+  } else {
+    const u64* src = a.ext + (((size_t)b * a.beta + j) * a.next + t) * N + (size_t)h * 256 + j0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) raw[i] = src[i * 16];
+  }
+}
+__device__ __forceinline__ bool fwd_inner_owns(const FwdInnerArgs& a, u32 t, u32 j) {
+  const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs);
+  return t >= lo && t < hi;
+}
+
+// Software pipeline per digit: the next digit's tile is requested together with this digit's key words, before
+// the multiply-accumulate, so it arrives while the ALUs work (the LDS barriers inside the transform do not wait
+// for global loads).
+template <bool BIG>
+__device__ __forceinline__ void fwd_inner_body(const FwdInnerArgs& a, u32 b, u32 tile, u32 t, u32 id, const ModInfo& mi,
+                                               u64* sm) {
+  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
+  const size_t N = 65536;
+  const u64 q = mi.m, q2 = 2 * mi.m;
+  const ulonglong2* tw = a.tw + (size_t)id * N;
+  u64 acc0[16], acc1[16], x[16], xn[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) acc0[i] = acc1[i] = 0;
+  bool own = fwd_inner_owns(a, t, 0);
+  fwd_inner_load(xn, a, b, t, 0, own, h, j0);
+  for (u32 j = 0; j < a.beta; j++) {
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = xn[i];
+    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
+    const u64* ka = kb + (size_t)a.nm * N;
+    if (!own) {
+      if (j) wave_lds_sync();  // the previous digit's transposes (inside 16-lane groups) are done with the LDS tile
+      ntt16_fwd_blocks_loaded<BIG, false>(x, tw, q, mi.mu64, tile, sm);
+    }
+    const bool own_next = j + 1 < a.beta && fwd_inner_owns(a, t, j + 1);
+    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      const u64 eb = kb[i * 16], ea = ka[i * 16];
+      Acc128 p0, p1;
+      p0.lo = x[i] * eb;
+      p0.hi = mul_hi64(x[i], eb);
+      p1.lo = x[i] * ea;
+      p1.hi = mul_hi64(x[i], ea);
+      acc0[i] = csub(acc0[i] + redc(p0, q, mi.minv), q2);
+      acc1[i] = csub(acc1[i] + redc(p1, q, mi.minv), q2);
+    }
+    own = own_next;
+  }
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + (size_t)h * 256 + j0;
+  u64* o1 = o0 + (size_t)a.next * N;
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    o0[i * 16] = csub(acc0[i], q);
+    o1[i * 16] = csub(acc1[i], q);
+  }
+}
+
+__device__ __forceinline__ void fwd_inner_body_fp(const FwdInnerArgs& a, u32 b, u32 tile, u32 t, u32 id, const ModInfo& mi,
+                                                  double* sm) {
+  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
+  const size_t N = 65536;
+  const double q = mi.qd, qinv = mi.qinv;
+  const double* tw = a.twfp + (size_t)id * N;
+  double acc0[16], acc1[16], x[16];
+  u64 xn[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) acc0[i] = acc1[i] = 0.0;
+  bool own = fwd_inner_owns(a, t, 0);
+  fwd_inner_load(xn, a, b, t, 0, own, h, j0);
+  for (u32 j = 0; j < a.beta; j++) {
+    // own limbs arrive as canonical residues, converted digits as the reduced doubles the row pass left
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = own ? u2d(xn[i]) : __longlong_as_double((long long)xn[i]);
+    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
+    const u64* ka = kb + (size_t)a.nm * N;
+    if (!own) {
+      if (j) wave_lds_sync();
+      ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm);
+    }
+    const bool own_next = j + 1 < a.beta && fwd_inner_owns(a, t, j + 1);
+    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0);
+    __builtin_amdgcn_sched_barrier(0);
+    // each product is below 0.9 q in magnitude; bring the sums back before they can reach 2^53
+    const bool fold = (j & 3) == 3;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      acc0[i] += fp_mulmod_var(x[i], u2d(kb[i * 16]), qinv, q);
+      acc1[i] += fp_mulmod_var(x[i], u2d(ka[i * 16]), qinv, q);
+      if (fold) {
+        acc0[i] = fp_reduce(acc0[i], qinv, q);
+        acc1[i] = fp_reduce(acc1[i], qinv, q);
+      }
+    }
+    own = own_next;
+  }
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + (size_t)h * 256 + j0;
+  u64* o1 = o0 + (size_t)a.next * N;
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    o0[i * 16] = d2u_canon(fp_reduce(acc0[i], qinv, q), q);
+    o1[i * 16] = d2u_canon(fp_reduce(acc1[i], qinv, q), q);
+  }
+}
+
+// Two builds of the same kernel: the default register allocation (2 waves per SIMD), and one held to 3 waves per
+// SIMD at the price of a few spilled accumulators; the host picks one (tuning knob 2).
+#define DEFINE_FWD_INNER_KERNEL(NAME, ATTR)                                                      \
+  template <int CLS>                                                                             \
+  __global__ void __launch_bounds__(NTT16_THREADS) ATTR NAME(FwdInnerArgs a) {                   \
+    __shared__ u64 sm[NTT16_LDS_BYTES / 8];                                                      \
+    u32 b, tile, zi;                                                                             \
+    ntt16_map(a.map_mode, b, tile, zi);                                                          \
+    const u32 t = a.slots[zi];                                                                   \
+    const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;                                       \
+    const ModInfo mi = a.mods[id];                                                               \
+    if (CLS == 0) fwd_inner_body_fp(a, b, tile, t, id, mi, (double*)sm);                         \
+    else if (CLS == 2) fwd_inner_body<true>(a, b, tile, t, id, mi, sm);                          \
+    else fwd_inner_body<false>(a, b, tile, t, id, mi, sm);                                       \
+  }
+DEFINE_FWD_INNER_KERNEL(ntt16_fwd_blocks_inner_kernel, )
+DEFINE_FWD_INNER_KERNEL(ntt16_fwd_blocks_inner_occ3_kernel, __attribute__((amdgpu_waves_per_eu(3, 3))))
+
+// ---- fused: last forward pass of the ModDown correction + final assembly ----
+// out[bc][i] = (acc[bc][i] - NTT(tq[bc][i])) * pinv[i]  (+ addend). On integer-class moduli acc and tq carry the
+// factor 2^-64 and pinv = 2^64/P; on double-precision moduli they are plain and pinv = (1/P, (1/P)/q).
+// addend modes per component c = bc & 1: 0 none; 1 the value already in out (in place); 2 add_src read through
+// the Galois map g (HRot's sigma(c0)).
+struct FwdFinalArgs {
+  const u64* tq;      // [B*2][nlimbs][N], after the row pass
+  const u64* acc;     // [B*2][next][N]
+  u64* out;           // [B*2][nlimbs][N]
+  const u64* add_src; // [B][2][nlimbs][N] (mode 2)
+  const ulonglong2* tw;
+  const double* twfp; 
+  const ModInfo* mods;
+  const ulonglong2* pinv;  // [nlimbs]
+  u32 nlimbs, next, mode0, mode1, galois, map_mode;
+  unsigned char slots[128];  // grid.z index -> limb (one modulus class per launch)
+};
+template <bool BIG>
+__device__ __forceinline__ void fwd_final_body(const FwdFinalArgs& a, u32 bc, u32 tile, u32 i_limb, const ModInfo& mi, u64* sm) {
+  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
+  const size_t N = 65536;
+  const u64 q = mi.m, q2 = 2 * mi.m;
+  u64 x[16];
+  ntt16_fwd_blocks<BIG, false>(x, a.tq + ((size_t)bc * a.nlimbs + i_limb) * N, a.tw + (size_t)i_limb * N, q, mi.mu64, tile, sm);
+  const ulonglong2 pv = a.pinv[i_limb];
+  const u64* ac = a.acc + ((size_t)bc * a.next + i_limb) * N + (size_t)h * 256 + j0;
+  u64* o = a.out + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
+  const u32 mode = (bc & 1) ? a.mode1 : a.mode0;
+  const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    u64 r = shoup(ac[i * 16] + q2 - x[i], pv.x, pv.y, q);
+    if (mode == 1) r = addmod(r, o[i * 16], q);
+    else if (mode == 2) r = addmod(r, as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)], q);
+    o[i * 16] = r;
+  }
+}
+__device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc, u32 tile, u32 i_limb, const ModInfo& mi,
+                                                  double* sm) {
+  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
+  const size_t N = 65536;
+  const double q = mi.qd, qinv = mi.qinv;
+  double x[16];
+  ntt16_fwd_blocks_fp(x, (const double*)(a.tq + ((size_t)bc * a.nlimbs + i_limb) * N), a.twfp + (size_t)i_limb * N, q, qinv,
+                      tile, sm);
+  const double2 pv = ((const double2*)a.pinv)[i_limb];
+  const u64* ac = a.acc + ((size_t)bc * a.next + i_limb) * N + (size_t)h * 256 + j0;
+  u64* o = a.out + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
+  const u32 mode = (bc & 1) ? a.mode1 : a.mode0;
+  const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    double r = fp_mulmod_const(u2d(ac[i * 16]) - x[i], pv.x, pv.y, q);  // |r| <= 0.9 q
+    if (mode == 1) r += u2d(o[i * 16]);
+    else if (mode == 2) r += u2d(as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)]);
+    o[i * 16] = d2u_canon(r, q);
+  }
+}
+template <int CLS>
+__global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_final_kernel(FwdFinalArgs a) {
+  __shared__ u64 sm[NTT16_LDS_BYTES / 8];
+  u32 bc, tile, zi;
+  ntt16_map(a.map_mode, bc, tile, zi);
+  const u32 i_limb = a.slots[zi];
+  const ModInfo mi = a.mods[i_limb];
+  const int cls = CLS;
+  if (cls == 0) fwd_final_body_fp(a, bc, tile, i_limb, mi, (double*)sm);
+  else if (cls == 2) fwd_final_body<true>(a, bc, tile, i_limb, mi, sm);
+  else fwd_final_body<false>(a, bc, tile, i_limb, mi, sm);
+}

@@ -1,0 +1,163 @@
+// Double-precision variants of the N = 2^16 pass bodies of ntt16.cuh, for primes q < 2^50.
+// On gfx950 the vector FP64 units run at full rate, and a modular multiply by a constant is 6 FP64
+// instructions (against ~23 integer instructions for the 64-bit Shoup form), exact because every value is an
+// integer below 2^53. Same tiles, lane layouts and LDS transposes as the integer bodies.
+//
+// Twiddles are single doubles (the quotient estimate uses the rounded product and 1/q, so no companion constant
+// is stored). Ranges (in units of q): a multiply returns at most (0.5 + 0.375 |y|) q, so a radix-16 round of four
+// forward stages takes |x| <= 1 to |x| <= 7.0 < 8; values are brought back to |x| <= 0.5 after every round. Inverse rounds double the
+// sums, so they are brought back after every two stages. Between the two passes of a transform the data lives in
+// global memory as reduced doubles.
+#pragma once
+#include "ntt16.cuh"
+
+template <class TW>
+__device__ __forceinline__ void radix16_fwd_fp(double (&x)[16], double q, double qinv, TW tw) {
+#pragma unroll
+  for (int s = 0; s < 4; s++) {
+    const int half = 8 >> s;
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      const double w = tw(s, g);
+#pragma unroll
+      for (int p = 0; p < half; p++) {
+        double& X = x[g * 2 * half + p];
+        double& Y = x[g * 2 * half + p + half];
+        const double T = fp_mulmod_var(Y, w, qinv, q);
+        Y = X - T;
+        X = X + T;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = fp_reduce(x[i], qinv, q);
+}
+template <class TW>
+__device__ __forceinline__ void radix16_inv_fp(double (&x)[16], double q, double qinv, TW tw) {
+#pragma unroll
+  for (int s = 3; s >= 0; s--) {
+    const int half = 8 >> s;
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      const double w = tw(s, g);
+#pragma unroll
+      for (int p = 0; p < half; p++) {
+        double& X = x[g * 2 * half + p];
+        double& Y = x[g * 2 * half + p + half];
+        const double D = X - Y;
+        X = X + Y;
+        Y = fp_mulmod_var(D, w, qinv, q);
+      }
+    }
+    if (s == 2 || s == 0) {
+#pragma unroll
+      for (int i = 0; i < 16; i++) x[i] = fp_reduce(x[i], qinv, q);
+    }
+  }
+}
+
+// Forward, stages 0..7. src holds canonical residues (uint64); dst receives reduced doubles.
+__device__ __forceinline__ void ntt16_fwd_rows_fp(const u64* __restrict__ src, double* __restrict__ dst,
+                                                  const double* __restrict__ tw, double q, double qinv, u32 tile, double* sm) {
+  const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
+  double x[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = u2d(src[(size_t)(i * 16 + r0) * 256 + col0 + col]);
+  const u32 i0 = r0;
+  double twb[15];  // second-round twiddles, requested before the first round
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) twb[(1 << s) - 1 + g] = tw[(16 << s) + (i0 << s) + g];
+  radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return tw[(1 << s) + g]; });
+#pragma unroll
+  for (int i = 0; i < 16; i++) sm[i * 256 + t] = x[i];
+  lds_barrier();
+#pragma unroll
+  for (int j = 0; j < 16; j++) x[j] = sm[(i0 * 16 + j) * 16 + col];
+  radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return twb[(1 << s) - 1 + g]; });
+#pragma unroll
+  for (int j = 0; j < 16; j++) dst[(size_t)(i0 * 16 + j) * 256 + col0 + col] = x[j];
+}
+
+// Forward, stages 8..15 on reduced doubles. Leaves x (|x| <= q/2) in the i-layout of ntt16_fwd_blocks.
+// `x` must already hold the tile in the i-layout (lane (hb, j0) holds positions i*16 + j0 of block h).
+__device__ __forceinline__ void ntt16_fwd_blocks_fp_loaded(double (&x)[16], const double* __restrict__ tw, double q,
+                                                           double qinv, u32 tile, double* sm) {
+  const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
+  const u32 i0 = j0;
+  // the second round's 15 twiddles are requested up front so they arrive during the first round
+  double twb[15];
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) twb[(1 << s) - 1 + g] = tw[(4096 << s) + (h << (4 + s)) + (i0 << s) + g];
+  radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
+#pragma unroll
+  for (int i = 0; i < 16; i++) sm[hb * 272 + i * 17 + j0] = x[i];
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) x[j] = sm[hb * 272 + i0 * 17 + j];
+  radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return twb[(1 << s) - 1 + g]; });
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) sm[hb * 272 + i0 * 17 + j] = x[j];
+  wave_lds_sync();
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = sm[hb * 272 + i * 17 + j0];
+}
+
+// Inverse, stages 15..8. In: x = canonical residues as doubles, i-layout. Out: reduced doubles, i-layout.
+__device__ __forceinline__ void ntt16_inv_blocks_fp(double (&x)[16], const double* __restrict__ twi, double q, double qinv,
+                                                    u32 tile, double* sm) {
+  const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
+  const u32 i0 = j0;
+  double twa[15], twb[15];  // both rounds' twiddles, requested before the first transpose
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      twa[(1 << s) - 1 + g] = twi[(4096 << s) + (h << (4 + s)) + (i0 << s) + g];
+      twb[(1 << s) - 1 + g] = twi[(256 << s) + (h << s) + g];
+    }
+#pragma unroll
+  for (int i = 0; i < 16; i++) sm[hb * 272 + i * 17 + j0] = x[i];
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) x[j] = sm[hb * 272 + i0 * 17 + j];
+  radix16_inv_fp(x, q, qinv, [&](int s, int g) { return twa[(1 << s) - 1 + g]; });
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) sm[hb * 272 + i0 * 17 + j] = x[j];
+  wave_lds_sync();
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = sm[hb * 272 + i * 17 + j0];
+  radix16_inv_fp(x, q, qinv, [&](int s, int g) { return twb[(1 << s) - 1 + g]; });
+}
+
+// Inverse, stages 7..0, then multiplication by (sc, sc/q); x receives canonical residues (uint64), row layout.
+__device__ __forceinline__ void ntt16_inv_rows_fp(u64 (&out)[16], const double* __restrict__ src, const double* __restrict__ twi,
+                                                  double q, double qinv, double sc, double scq, u32 tile, double* sm) {
+  const u32 t = threadIdx.x, col = t & 15, i0 = t >> 4, col0 = tile * 16;
+  double x[16];
+#pragma unroll
+  for (int j = 0; j < 16; j++) x[j] = src[(size_t)(i0 * 16 + j) * 256 + col0 + col];
+  radix16_inv_fp(x, q, qinv, [&](int s, int g) { return twi[(16 << s) + (i0 << s) + g]; });
+#pragma unroll
+  for (int j = 0; j < 16; j++) sm[(i0 * 16 + j) * 16 + col] = x[j];
+  lds_barrier();
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = sm[i * 256 + t];
+  radix16_inv_fp(x, q, qinv, [&](int s, int g) { return twi[(1 << s) + g]; });
+#pragma unroll
+  for (int i = 0; i < 16; i++) out[i] = d2u_canon(fp_mulmod_const(x[i], sc, scq, q), q);
+}
+
+__device__ __forceinline__ void ntt16_fwd_blocks_fp(double (&x)[16], const double* __restrict__ src,
+                                                    const double* __restrict__ tw, double q, double qinv, u32 tile, double* sm) {
+  const u32 t = threadIdx.x, j0 = t & 15, h = tile * 16 + (t >> 4);
+  const double* blk = src + (size_t)h * 256;
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = blk[i * 16 + j0];
+  ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm);
+}

@@ -252,3 +252,36 @@ def test_argument_errors(gpu):
     bad.q[0] += 2
     with pytest.raises(gpu.CkksError):
         gpu.Context(bad)
+
+
+def test_integer_bodies_only_at_full_ring(gpu):
+    """The double-precision bodies (primes < 2^50) can be switched off; the integer bodies must give the same bits."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = config_params("keyswitch_micro")
+    rc = ref.RefContext(p)
+    gc = gpu.Context(p)
+    gpu.ckks_tune_set(gc, 1, 1)
+    B, nl = 2, 24
+    ct = uniform_residues(61, p.q, (B, 2), p.N)
+    evk = uniform_residues(62, p.moduli, (p.dnum, 2), p.N)
+    g = galois_element(99, p.logN)
+    ref.set_threads(2)
+    want_rot = rc.hrot(ct, g, evk)
+    want_mul = rc.hmult_relin(ct[:1], ct[1:], evk)
+    ref.set_threads(1)
+    ws = gc.workspace(gpu.OP_HROT, B, nl)
+    out = torch.empty((B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_hrot(gc, out, to_dev(ct), B, nl, g, to_dev(evk), ws)
+    assert_same(to_host(out), want_rot, "hrot, integer bodies")
+    out2 = torch.empty((1, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_hmult_relin(gc, out2, to_dev(ct[:1]), to_dev(ct[1:]), 1, nl, to_dev(evk), ws)
+    assert_same(to_host(out2), want_mul, "hmult, integer bodies")
+    x = uniform_residues(63, p.moduli, (2,), p.N)
+    ids = list(range(len(p.moduli)))
+    d = to_dev(x)
+    gpu.ckks_ntt(gc, d, 2, ids)
+    assert_same(to_host(d), rc.ntt(x, ids), "ntt, integer bodies")
+    gpu.ckks_intt(gc, d, 2, ids)
+    assert_same(to_host(d), x, "intt, integer bodies")
+    gc.close()
