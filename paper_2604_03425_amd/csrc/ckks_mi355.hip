@@ -105,7 +105,7 @@ struct ProfRec {
 };
 
 struct ckks_ctx {
-  int tune[8] = {4, 0, 0, 0, 0, 0, 0, 0};  // knob 0: workgroup mapping of the 2^16 transforms
+  int tune[8] = {4, 0, 0, 1, 0, 0, 0, 0};  // 0: workgroup mapping of the 2^16 transforms; 3: unfused FP inner product
   bool prof_on = false;
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
@@ -327,6 +327,9 @@ struct NttOpts {
   u32 galois = 0;                     // N = 2^16 inverse only: read src through the eval-domain Galois map
   const ulonglong2* scale = nullptr;  // N = 2^16 inverse only: per-slot constants (from slot0) replacing N^-1
   bool rows_only = false;             // N = 2^16 forward only: stop after the row pass (a fused kernel does the rest)
+  bool blocks_only = false;           // N = 2^16 forward only: only the block pass, in place on dst
+  bool raw_out = false;               // with blocks_only: leave reduced doubles on double-precision moduli
+  int only_class = -1;                // >= 0: touch only the slots of this modulus class
 };
 int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, u64* dst, u64 dst_stride, u32 npoly,
                u32 slot0, u32 nslots, const LimbMap& ids_from_slot0, u32 skip_beta, u32 skip_nq, hipStream_t st,
@@ -349,12 +352,16 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     a.map_mode = c->tune[0];
     a.galois = opt.galois;
     a.scale = opt.scale;
+    a.raw_out = opt.raw_out ? 1 : 0;
     Ntt16Args b = a;  // second pass: in place on dst
     b.src = a.dst;
     b.src_poly_stride = dst_stride;
-    auto cls_of = [&](u32 s) { return host_class(c, c->mod[ids_from_slot0.id[s]]); };
+    auto cls_of = [&](u32 s) {
+      int k = host_class(c, c->mod[ids_from_slot0.id[s]]);
+      return (opt.only_class >= 0 && k != opt.only_class) ? -1 : k;
+    };
     if (!inverse) {
-      {
+      if (!opt.blocks_only) {
         ProfScope ps(c, PK_FWD_ROWS, st);
         LAUNCH_BY_CLASS(ntt16_fwd_rows_kernel, a, npoly, nslots, cls_of, st)
       }
@@ -454,22 +461,23 @@ KsLayout ks_layout(const ckks_ctx* c, u32 B, u32 nlimbs) {
   return L;
 }
 
+// Base-conversion launches: two adjacent coefficients per lane up to 15 sources, one beyond (register budget).
 template <bool PRESCALED>
-void launch_modup(const ckks_ctx* c, const ModUpArgs& a, dim3 grid, hipStream_t st) {
-  dim3 block(BCONV_THREADS);
-  if (c->alpha <= 4) hipLaunchKernelGGL((modup_kernel<4, PRESCALED>), grid, block, 0, st, a);
-  else if (c->alpha <= 8) hipLaunchKernelGGL((modup_kernel<8, PRESCALED>), grid, block, 0, st, a);
-  else if (c->alpha <= 15) hipLaunchKernelGGL((modup_kernel<15, PRESCALED>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((modup_kernel<45, PRESCALED>), grid, block, 0, st, a);
+void launch_modup(const ckks_ctx* c, const ModUpArgs& a, u32 beta, u32 B, hipStream_t st) {
+  dim3 block(BCONV_THREADS), g2(c->N / BCONV_THREADS / 2, beta, B), g1(c->N / BCONV_THREADS, beta, B);
+  if (c->alpha <= 4) hipLaunchKernelGGL((modup_kernel<4, PRESCALED, 2>), g2, block, 0, st, a);
+  else if (c->alpha <= 8) hipLaunchKernelGGL((modup_kernel<8, PRESCALED, 2>), g2, block, 0, st, a);
+  else if (c->alpha <= 15) hipLaunchKernelGGL((modup_kernel<15, PRESCALED, 2>), g2, block, 0, st, a);
+  else hipLaunchKernelGGL((modup_kernel<45, PRESCALED, 1>), g1, block, 0, st, a);
 }
 template <bool PRESCALED>
-void launch_moddown(const ckks_ctx* c, const ModDownArgs& a, dim3 grid, hipStream_t st) {
-  dim3 block(BCONV_THREADS);
+void launch_moddown(const ckks_ctx* c, const ModDownArgs& a, u32 B2, hipStream_t st) {
+  dim3 block(BCONV_THREADS), g2(c->N / BCONV_THREADS / 2, B2), g1(c->N / BCONV_THREADS, B2);
   const u32 K = c->np;
-  if (K <= 4) hipLaunchKernelGGL((moddown_kernel<4, PRESCALED>), grid, block, 0, st, a);
-  else if (K <= 8) hipLaunchKernelGGL((moddown_kernel<8, PRESCALED>), grid, block, 0, st, a);
-  else if (K <= 15) hipLaunchKernelGGL((moddown_kernel<15, PRESCALED>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((moddown_kernel<45, PRESCALED>), grid, block, 0, st, a);
+  if (K <= 4) hipLaunchKernelGGL((moddown_kernel<4, PRESCALED, 2>), g2, block, 0, st, a);
+  else if (K <= 8) hipLaunchKernelGGL((moddown_kernel<8, PRESCALED, 2>), g2, block, 0, st, a);
+  else if (K <= 15) hipLaunchKernelGGL((moddown_kernel<15, PRESCALED, 2>), g2, block, 0, st, a);
+  else hipLaunchKernelGGL((moddown_kernel<45, PRESCALED, 1>), g1, block, 0, st, a);
 }
 
 // What a key switch reads and how its result is assembled.
@@ -504,7 +512,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
     ProfScope ps(c, PK_MODUP, st);
-    launch_modup<true>(c, a, dim3(N / BCONV_THREADS, beta, B), st);
+    launch_modup<true>(c, a, beta, B, st);
     HIP_TRY(hipGetLastError());
   }
   NttOpts o2;
@@ -529,8 +537,28 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     a.next = next;
     a.map_mode = c->tune[0];
     a.galois = io.d_galois;
+    const bool unfused_fp = c->tune[3] != 0;
+    if (unfused_fp) {
+      // double-precision slots: plain block pass leaving doubles, then a streaming multiply-accumulate
+      NttOpts o;
+      o.blocks_only = true;
+      o.raw_out = true;
+      o.only_class = 0;
+      if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, o)))
+        return rc;
+      u32 cnt = 0;
+      for (u32 s_ = 0; s_ < next; s_++)
+        if (host_class(c, c->mod[emap.id[s_]]) == 0) a.slots[cnt++] = (unsigned char)s_;
+      if (cnt) {
+        ProfScope ps(c, PK_INNER, st);
+        hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 256, cnt), dim3(256), 0, st, a);
+      }
+    }
     ProfScope ps(c, PK_FWD_INNER, st);
-    auto cls_of = [&](u32 s) { return host_class(c, c->mod[emap.id[s]]); };
+    auto cls_of = [&](u32 s) {
+      int k = host_class(c, c->mod[emap.id[s]]);
+      return (unfused_fp && k == 0) ? -1 : k;
+    };
     if (c->tune[2]) {
       LAUNCH_BY_CLASS(ntt16_fwd_blocks_inner_occ3_kernel, a, B, next, cls_of, st)
     } else {
@@ -548,7 +576,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   {
     ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next};
     ProfScope ps(c, PK_MODDOWN, st);
-    launch_moddown<true>(c, a, dim3(N / BCONV_THREADS, B * 2), st);
+    launch_moddown<true>(c, a, B * 2, st);
     HIP_TRY(hipGetLastError());
   }
   if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st, o2))) return rc;
@@ -601,7 +629,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
     ProfScope ps(c, PK_MODUP, st);
-    launch_modup<false>(c, a, dim3(N / BCONV_THREADS, beta, B), st);
+    launch_modup<false>(c, a, beta, B, st);
     HIP_TRY(hipGetLastError());
   }
   // 3. forward transform of the converted slots
@@ -623,7 +651,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   {
     ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat, c->logN, nlimbs, c->nq, K, next};
     ProfScope ps(c, PK_MODDOWN, st);
-    launch_moddown<false>(c, a, dim3(N / BCONV_THREADS, B * 2), st);
+    launch_moddown<false>(c, a, B * 2, st);
     HIP_TRY(hipGetLastError());
   }
   // 7. its forward transform, 8. subtract, scale by P^-1, assemble

@@ -179,27 +179,43 @@ struct ModUpArgs {
   u32 logN, nlimbs, nq, alpha, beta, next;
 };
 // PRESCALED: the input already holds y_i (the inverse transform folded (Q_j/q_i)^-1 into its 1/N scaling).
-template <int MAXLEN, bool PRESCALED>
+// EPT: adjacent coefficients per lane (16-byte accesses for EPT = 2); the constants of an output are fetched once
+// per lane through scalar loads and reused for all of them.
+template <int MAXLEN, bool PRESCALED, int EPT>
 __global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a) {
   const u32 N = 1u << a.logN;
-  const u32 n = blockIdx.x * BCONV_THREADS + threadIdx.x;
+  const u32 n = (blockIdx.x * BCONV_THREADS + threadIdx.x) * EPT;
   const u32 j = blockIdx.y, b = blockIdx.z;
   const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs), len = hi - lo;
   const u64* d = a.dcoef + ((size_t)b * a.nlimbs + lo) * N + n;
-  u32 y0[MAXLEN], y1[MAXLEN], nneg = 0;
+  u32 y0[EPT][MAXLEN], y1[EPT][MAXLEN], nneg[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; e++) nneg[e] = 0;
 #pragma unroll
   for (int i = 0; i < MAXLEN; i++) {
-    y0[i] = y1[i] = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; e++) y0[e][i] = y1[e][i] = 0;
     if ((u32)i < len) {
       const u64 m = a.mods[lo + i].m;
-      u64 y = d[(size_t)i * N];
-      if (!PRESCALED) {
-        ulonglong2 c = a.inv[j * a.alpha + i];
-        y = shoup(y, c.x, c.y, m);
+      u64 yv[EPT];
+      if (EPT == 2) {
+        const ulonglong2 v = *(const ulonglong2*)(d + (size_t)i * N);
+        yv[0] = v.x;
+        yv[EPT - 1] = v.y;
+      } else {
+        yv[0] = d[(size_t)i * N];
       }
-      nneg += (y > (m >> 1)) ? 1u : 0u;
-      y0[i] = (u32)y & M30;
-      y1[i] = (u32)(y >> 30);
+#pragma unroll
+      for (int e = 0; e < EPT; e++) {
+        u64 y = yv[e];
+        if (!PRESCALED) {
+          ulonglong2 c = a.inv[j * a.alpha + i];
+          y = shoup(y, c.x, c.y, m);
+        }
+        nneg[e] += (y > (m >> 1)) ? 1u : 0u;
+        y0[e][i] = (u32)y & M30;
+        y1[e][i] = (u32)(y >> 30);
+      }
     }
   }
   const u64* mat = a.mat + (size_t)j * a.next * (MAXLEN + 1);
@@ -208,7 +224,11 @@ __global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a) {
     if (t >= lo && t < hi) continue;
     const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
     const ModInfo mi = a.mods[id];
-    out[(size_t)t * N] = bconv_dot<MAXLEN>(y0, y1, nneg, mat + (size_t)t * (MAXLEN + 1), mi);
+    u64 r[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; e++) r[e] = bconv_dot<MAXLEN>(y0[e], y1[e], nneg[e], mat + (size_t)t * (MAXLEN + 1), mi);
+    if (EPT == 2) *(ulonglong2*)(out + (size_t)t * N) = ulonglong2{r[0], r[EPT - 1]};
+    else out[(size_t)t * N] = r[0];
   }
 }
 
@@ -251,32 +271,50 @@ struct ModDownArgs {
   const u64* mat;         // [nlimbs][MAXLEN+1], Montgomery form
   u32 logN, nlimbs, nq, K, next;
 };
-template <int MAXLEN, bool PRESCALED>
+template <int MAXLEN, bool PRESCALED, int EPT>
 __global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
   const u32 N = 1u << a.logN;
-  const u32 n = blockIdx.x * BCONV_THREADS + threadIdx.x;
+  const u32 n = (blockIdx.x * BCONV_THREADS + threadIdx.x) * EPT;
   const u32 bc = blockIdx.y;
   const u64* x = a.acc + ((size_t)bc * a.next + a.nlimbs) * N + n;
-  u32 y0[MAXLEN], y1[MAXLEN], nneg = 0;
+  u32 y0[EPT][MAXLEN], y1[EPT][MAXLEN], nneg[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; e++) nneg[e] = 0;
 #pragma unroll
   for (int k = 0; k < MAXLEN; k++) {
-    y0[k] = y1[k] = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; e++) y0[e][k] = y1[e][k] = 0;
     if ((u32)k < a.K) {
       const u64 m = a.mods[a.nq + k].m;
-      u64 y = x[(size_t)k * N];
-      if (!PRESCALED) {
-        ulonglong2 c = a.inv[k];
-        y = shoup(y, c.x, c.y, m);
+      u64 yv[EPT];
+      if (EPT == 2) {
+        const ulonglong2 v = *(const ulonglong2*)(x + (size_t)k * N);
+        yv[0] = v.x;
+        yv[EPT - 1] = v.y;
+      } else {
+        yv[0] = x[(size_t)k * N];
       }
-      nneg += (y > (m >> 1)) ? 1u : 0u;
-      y0[k] = (u32)y & M30;
-      y1[k] = (u32)(y >> 30);
+#pragma unroll
+      for (int e = 0; e < EPT; e++) {
+        u64 y = yv[e];
+        if (!PRESCALED) {
+          ulonglong2 c = a.inv[k];
+          y = shoup(y, c.x, c.y, m);
+        }
+        nneg[e] += (y > (m >> 1)) ? 1u : 0u;
+        y0[e][k] = (u32)y & M30;
+        y1[e][k] = (u32)(y >> 30);
+      }
     }
   }
   u64* out = a.tq + (size_t)bc * a.nlimbs * N + n;
   for (u32 i = 0; i < a.nlimbs; i++) {
     const ModInfo mi = a.mods[i];
-    out[(size_t)i * N] = bconv_dot<MAXLEN>(y0, y1, nneg, a.mat + (size_t)i * (MAXLEN + 1), mi);
+    u64 r[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; e++) r[e] = bconv_dot<MAXLEN>(y0[e], y1[e], nneg[e], a.mat + (size_t)i * (MAXLEN + 1), mi);
+    if (EPT == 2) *(ulonglong2*)(out + (size_t)i * N) = ulonglong2{r[0], r[EPT - 1]};
+    else out[(size_t)i * N] = r[0];
   }
 }
 

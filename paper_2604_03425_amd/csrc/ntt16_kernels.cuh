@@ -17,6 +17,7 @@ struct Ntt16Args {
   u64 src_poly_stride, dst_poly_stride;  // elements between polynomials
   u32 skip_beta, skip_alpha, skip_nq;    // digit p % skip_beta leaves its own limbs alone (ModUp'ed digits)
   u32 map_mode;                          // workgroup -> (poly, tile, slot) mapping, see ntt16_map
+  u32 raw_out;                           // forward last pass, double-precision class only: != 0 leaves reduced doubles
   u32 galois;                            // inverse first pass only: != 0 reads src through the eval-domain Galois map
   const ulonglong2* scale;               // inverse second pass only: per-slot constant replacing N^-1 (NULL = N^-1);
                                          // a double2 (c, c/q) for double-precision moduli, a Shoup pair otherwise
@@ -60,8 +61,13 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_kernel(Ntt16Ar
   if (cls == 0) {
     double xd[16];
     ntt16_fwd_blocks_fp(xd, (const double*)src, twfp, mi.qd, mi.qinv, tile, (double*)sm);
+    if (a.raw_out) {
 #pragma unroll
-    for (int i = 0; i < 16; i++) x[i] = d2u_canon(xd[i], mi.qd);
+      for (int i = 0; i < 16; i++) x[i] = (u64)__double_as_longlong(xd[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; i++) x[i] = d2u_canon(xd[i], mi.qd);
+    }
   } else if (cls == 2) {
     ntt16_fwd_blocks<true>(x, src, tw, mi.m, mi.mu64, tile, sm);
   } else {
@@ -351,4 +357,39 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_final_kernel(F
   if (cls == 0) fwd_final_body_fp(a, bc, tile, i_limb, mi, (double*)sm);
   else if (cls == 2) fwd_final_body<true>(a, bc, tile, i_limb, mi, sm);
   else fwd_final_body<false>(a, bc, tile, i_limb, mi, sm);
+}
+
+// ---- streaming inner product for double-precision moduli (the unfused alternative to the kernel above) ----
+// acc[b][c][t][n] = sum_j D_j[n] * evk[j][c][id(t)][n] with D_j = ext[b][j][t] (reduced doubles, evaluation domain)
+// or d[b][t] (canonical residues, read through the Galois map if asked). One lane per coefficient; grid =
+// (B, N/256, slots of the class), batch innermost so that consecutive workgroups share the key slice.
+__global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
+  const size_t N = 65536;
+  u32 b, blk, zi;
+  ntt16_map(a.map_mode, b, blk, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const double q = mi.qd, qinv = mi.qinv;
+  const u32 n = blk * 256 + threadIdx.x;
+  double s0 = 0.0, s1 = 0.0;
+  for (u32 j = 0; j < a.beta; j++) {
+    double x;
+    if (fwd_inner_owns(a, t, j)) {
+      const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+      x = u2d(src[a.galois ? galois_src_index16(n, a.galois) : n]);
+    } else {
+      x = __longlong_as_double((long long)a.ext[(((size_t)b * a.beta + j) * a.next + t) * N + n]);
+    }
+    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
+    s0 += fp_mulmod_var(x, u2d(kb[0]), qinv, q);
+    s1 += fp_mulmod_var(x, u2d(kb[(size_t)a.nm * N]), qinv, q);
+    if ((j & 3) == 3) {
+      s0 = fp_reduce(s0, qinv, q);
+      s1 = fp_reduce(s1, qinv, q);
+    }
+  }
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
+  o0[0] = d2u_canon(fp_reduce(s0, qinv, q), q);
+  o0[(size_t)a.next * N] = d2u_canon(fp_reduce(s1, qinv, q), q);
 }
