@@ -551,7 +551,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
         if (host_class(c, c->mod[emap.id[s_]]) == 0) a.slots[cnt++] = (unsigned char)s_;
       if (cnt) {
         ProfScope ps(c, PK_INNER, st);
-        hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 256, cnt), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
       }
     }
     ProfScope ps(c, PK_FWD_INNER, st);

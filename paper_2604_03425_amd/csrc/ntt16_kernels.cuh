@@ -364,6 +364,7 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_final_kernel(F
 // or d[b][t] (canonical residues, read through the Galois map if asked). One lane per coefficient; grid =
 // (B, N/256, slots of the class), batch innermost so that consecutive workgroups share the key slice.
 __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
+  // two adjacent coefficients per lane (16-byte accesses); grid.y = N / 512
   const size_t N = 65536;
   u32 b, blk, zi;
   ntt16_map(a.map_mode, b, blk, zi);
@@ -371,25 +372,42 @@ __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
   const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
   const ModInfo mi = a.mods[id];
   const double q = mi.qd, qinv = mi.qinv;
-  const u32 n = blk * 256 + threadIdx.x;
-  double s0 = 0.0, s1 = 0.0;
+  const u32 n = (blk * 256 + threadIdx.x) * 2;
+  double s0[2] = {0.0, 0.0}, s1[2] = {0.0, 0.0};
   for (u32 j = 0; j < a.beta; j++) {
-    double x;
+    double x[2];
     if (fwd_inner_owns(a, t, j)) {
       const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
-      x = u2d(src[a.galois ? galois_src_index16(n, a.galois) : n]);
+      if (a.galois) {
+        x[0] = u2d(src[galois_src_index16(n, a.galois)]);
+        x[1] = u2d(src[galois_src_index16(n + 1, a.galois)]);
+      } else {
+        const ulonglong2 v = *(const ulonglong2*)(src + n);
+        x[0] = u2d(v.x);
+        x[1] = u2d(v.y);
+      }
     } else {
-      x = __longlong_as_double((long long)a.ext[(((size_t)b * a.beta + j) * a.next + t) * N + n]);
+      const double2 v = *(const double2*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N + n);
+      x[0] = v.x;
+      x[1] = v.y;
     }
     const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
-    s0 += fp_mulmod_var(x, u2d(kb[0]), qinv, q);
-    s1 += fp_mulmod_var(x, u2d(kb[(size_t)a.nm * N]), qinv, q);
+    const ulonglong2 eb = *(const ulonglong2*)kb;
+    const ulonglong2 ea = *(const ulonglong2*)(kb + (size_t)a.nm * N);
+    s0[0] += fp_mulmod_var(x[0], u2d(eb.x), qinv, q);
+    s0[1] += fp_mulmod_var(x[1], u2d(eb.y), qinv, q);
+    s1[0] += fp_mulmod_var(x[0], u2d(ea.x), qinv, q);
+    s1[1] += fp_mulmod_var(x[1], u2d(ea.y), qinv, q);
     if ((j & 3) == 3) {
-      s0 = fp_reduce(s0, qinv, q);
-      s1 = fp_reduce(s1, qinv, q);
+#pragma unroll
+      for (int e = 0; e < 2; e++) {
+        s0[e] = fp_reduce(s0[e], qinv, q);
+        s1[e] = fp_reduce(s1[e], qinv, q);
+      }
     }
   }
   u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
-  o0[0] = d2u_canon(fp_reduce(s0, qinv, q), q);
-  o0[(size_t)a.next * N] = d2u_canon(fp_reduce(s1, qinv, q), q);
+  *(ulonglong2*)o0 = ulonglong2{d2u_canon(fp_reduce(s0[0], qinv, q), q), d2u_canon(fp_reduce(s0[1], qinv, q), q)};
+  *(ulonglong2*)(o0 + (size_t)a.next * N) =
+      ulonglong2{d2u_canon(fp_reduce(s1[0], qinv, q), q), d2u_canon(fp_reduce(s1[1], qinv, q), q)};
 }
