@@ -27,34 +27,159 @@ PEAK_ALU_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T
 # + 14 add/compare/select ops; one 64x64->128 multiply-accumulate = 4 multiplies + 4 adds; one 128->64
 # Montgomery reduction = 7 multiplies + 9 adds/selects; one Shoup constant multiply = 10 + 4.
 OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 16, 14, 4
+# Double-precision bodies (primes < 2^50; FP64 instructions issue at the same one-per-lane-per-clock rate):
+# butterfly = 6 (exact product, quotient, remainder) + 2 (add, sub) + 1.5 (range reduction every 4 stages);
+# variable x variable product reduced = 7; constant multiply = 6.
+OPS_BUTTERFLY_FP, OPS_MULRED_FP, OPS_SHOUP_FP = 9.5, 7, 6
 
 
 def keyswitch_model(p, B, nl, hrot, hmult):
-    """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B (N = 2^16 path)."""
+    """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B (N = 2^16 path:
+    double-precision bodies on primes < 2^50, with their inner product as a separate streaming kernel)."""
     N, K, alpha = p.N, len(p.p), p.alpha
     nxt, beta = nl + K, p.beta(nl)
-    lens = [min(alpha, nl - j * alpha) for j in range(beta)]
-    new_limbs = sum(nxt - l for l in lens)          # limbs produced by ModUp, per ciphertext
+    ext_mod = list(p.q[:nl]) + list(p.p)
+    fp = [m < (1 << 50) for m in ext_mod]
+    digits = [range(j * alpha, min(nl, (j + 1) * alpha)) for j in range(beta)]
+    new_fp = sum(1 for dg in digits for t in range(nxt) if t not in dg and fp[t])      # converted limbs per ciphertext
+    new_int = sum(1 for dg in digits for t in range(nxt) if t not in dg and not fp[t])
+    own_fp = sum(1 for t in range(nl) if fp[t])
+    own_int = nl - own_fp
+    n_fp, n_int = sum(fp), nxt - sum(fp)
+    new_limbs = new_fp + new_int
     limb = 8 * N
-    bf_pass = (N / 2) * 8 * OPS_BUTTERFLY          # one 8-stage pass over one limb
+    bf_pass = (N / 2) * 8 * OPS_BUTTERFLY          # one 8-stage pass over one limb, integer bodies
+    bf_pass_fp = (N / 2) * 8 * OPS_BUTTERFLY_FP    # same, double-precision bodies
     mul_redc = 2 * OPS_MAC + OPS_REDUCE            # one variable x variable product reduced
     m = {}
-    n_inv = B * (nl + 2 * K)
-    m["ntt16_inv_blocks"] = dict(bytes=n_inv * 2 * limb, ops=n_inv * bf_pass)
-    m["ntt16_inv_rows"] = dict(bytes=n_inv * 2 * limb, ops=n_inv * (bf_pass + N * OPS_SHOUP))
+    inv_fp, inv_int = B * own_fp, B * (own_int + 2 * sum(1 for x in p.p if x >= (1 << 50)))
+    inv_fp += B * 2 * sum(1 for x in p.p if x < (1 << 50))
+    n_inv = inv_fp + inv_int
+    m["ntt16_inv_blocks"] = dict(bytes=n_inv * 2 * limb, ops=inv_int * bf_pass + inv_fp * bf_pass_fp)
+    m["ntt16_inv_rows"] = dict(bytes=n_inv * 2 * limb,
+                               ops=inv_int * (bf_pass + N * OPS_SHOUP) + inv_fp * (bf_pass_fp + N * OPS_SHOUP_FP))
     m["modup_bconv"] = dict(bytes=B * (nl + new_limbs) * limb,
-                            ops=B * N * sum((nxt - l) * ((l + 1) * OPS_MAC + OPS_REDUCE) for l in lens))
-    n_rows = B * (new_limbs + 2 * nl)
-    m["ntt16_fwd_rows"] = dict(bytes=n_rows * 2 * limb, ops=n_rows * bf_pass)
-    m["ntt16_fwd_blocks_inner"] = dict(bytes=(B * (new_limbs + nl + 2 * nxt) + 2 * beta * nxt) * limb,
-                                       ops=B * (new_limbs * bf_pass + N * nxt * beta * 2 * mul_redc))
+                            ops=B * N * sum((nxt - len(dg)) * ((len(dg) + 1) * OPS_MAC + OPS_REDUCE) for dg in digits))
+    rows_fp, rows_int = B * (new_fp + 2 * own_fp), B * (new_int + 2 * own_int)
+    m["ntt16_fwd_rows"] = dict(bytes=(rows_fp + rows_int) * 2 * limb, ops=rows_fp * bf_pass_fp + rows_int * bf_pass)
+    m["ntt16_fwd_blocks"] = dict(bytes=B * new_fp * 2 * limb, ops=B * new_fp * bf_pass_fp)
+    m["evk_inner"] = dict(bytes=(B * (new_fp + own_fp + 2 * n_fp) + 2 * beta * n_fp) * limb,
+                          ops=B * N * n_fp * beta * 2 * OPS_MULRED_FP)
+    m["ntt16_fwd_blocks_inner"] = dict(bytes=(B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
+                                       ops=B * (new_int * bf_pass + N * n_int * beta * 2 * mul_redc))
     m["moddown_bconv"] = dict(bytes=2 * B * (K + nl) * limb, ops=2 * B * N * nl * ((K + 1) * OPS_MAC + OPS_REDUCE))
     addend = 1 if hrot else 2 if hmult else 0
     m["ntt16_fwd_blocks_final"] = dict(bytes=B * nl * (6 + addend) * limb,
-                                       ops=2 * B * nl * (bf_pass + N * (OPS_SHOUP + 2 * OPS_ADD)))
+                                       ops=2 * B * (own_fp * (bf_pass_fp + N * (OPS_SHOUP_FP + 2)) +
+                                                    own_int * (bf_pass + N * (OPS_SHOUP + 2 * OPS_ADD))))
     if hmult:
         m["tensor"] = dict(bytes=B * nl * 7 * limb, ops=B * nl * N * 4 * mul_redc)
     return m
+
+
+def _uniform(torch, gen, dev, prefix, moduli, N):
+    t = torch.empty(tuple(prefix) + (len(moduli), N), dtype=torch.int64, device=dev)
+    for i, m in enumerate(moduli):
+        t[..., i, :] = torch.randint(0, m, tuple(prefix) + (N,), dtype=torch.int64, device=dev, generator=gen)
+    return t
+
+
+def _time(torch, fn, iters):
+    fn()
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t) / iters
+
+
+def other_workloads(args):
+    """Secondary workloads (not the headline metric): `pcmm` = the FFN layer share, `attention` = QK^T units,
+    `sweep` = level/dnum sweep. Each prints its own JSON line(s)."""
+    import torch
+    import paper_2604_03425_amd as ck
+    from ckks_inputs import config_params, galois_element, make_params
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev).manual_seed(0xFEED)
+    if args.workload == "pcmm":
+        # 2048 tokens x 768 hidden in 128 ciphertexts (16 tokens each), 768x768 weight slice as 32 x 24 diagonals,
+        # processed in calls of `--pcmm-batch` ciphertexts; 31 baby + 23 giant rotation keys shared by all
+        p = config_params("keyswitch_micro")
+        N, nl, n1, n2, total = p.N, len(p.q), 32, 24, 128
+        Bc = args.pcmm_batch
+        ctx = ck.Context(p, 0)
+        ct = _uniform(torch, gen, dev, (Bc, 2), p.q, N)
+        pt = _uniform(torch, gen, dev, (n2, n1), p.q, N)
+        baby = [_uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N) for _ in range(n1 - 1)]
+        giant = [_uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N) for _ in range(n2 - 1)]
+        out = torch.empty_like(ct)
+        ws = ctx.workspace(ck.OP_PCMM_BSGS, Bc, nl, n1)
+        dt = _time(torch, lambda: ck.ckks_pcmm_bsgs(ctx, out, ct, Bc, nl, pt, n1, n2, 1, baby, giant, ws), 2)
+        ck.ckks_prof_reset(ctx)
+        ck.ckks_prof_enable(ctx, True)
+        ck.ckks_pcmm_bsgs(ctx, out, ct, Bc, nl, pt, n1, n2, 1, baby, giant, ws)
+        ck.ckks_prof_enable(ctx, False)
+        prof = {k: round(v[0], 2) for k, v in ck.ckks_prof_collect(ctx).items()}
+        rots = Bc * (n1 - 1 + n2 - 1)
+        print(json.dumps({"workload": "pcmm_ffn_share", "ciphertexts_per_call": Bc, "seconds_per_call": round(dt, 4),
+                          "seconds_for_128_ciphertexts": round(dt * total / Bc, 3), "hrot_per_s": round(rots / dt, 1),
+                          "pmult_acc_per_s": round(Bc * n1 * n2 / dt, 1), "kernel_ms_per_call": prof,
+                          "note": "2048 tokens x 768 -> 768 slice; 54 HRot + 768 PMult-acc per ciphertext, no hoisting"}))
+    elif args.workload == "attention":
+        # one (a,b) block pair per head, 3 heads: unit = HMult+relin + 6 rotate-and-sum HRots; 20 limbs, dnum 4, K 5
+        p = config_params("attention_qk")
+        N, nl, B = p.N, len(p.q), args.att_batch
+        ctx = ck.Context(p, 0)
+        qa = _uniform(torch, gen, dev, (B, 2), p.q, N)
+        kb = _uniform(torch, gen, dev, (B, 2), p.q, N)
+        relin = _uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N)
+        rot = [_uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N) for _ in range(6)]
+        acc = torch.empty_like(qa)
+        tmp = torch.empty_like(qa)
+        ws = ctx.workspace(ck.OP_HROT, B, nl)
+        mods = torch.tensor(list(p.q), dtype=torch.int64, device=dev).view(1, 1, nl, 1)
+
+        def units():
+            ck.ckks_hmult_relin(ctx, acc, qa, kb, B, nl, relin, ws)
+            cur = acc
+            for i in range(6):
+                ck.ckks_hrot(ctx, tmp, cur, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
+                s = cur + tmp                                  # harness-side modular add of the rotate-and-sum
+                cur = torch.where(s >= mods, s - mods, s)
+        dt = _time(torch, units, 2)
+        print(json.dumps({"workload": "attention_qk_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
+                          "key_switches_per_s": round(7 * B / dt, 1),
+                          "note": "unit = HMult+relin + 6 rotate-and-sum HRot at 20 limbs, dnum=4, K=5; "
+                                  "1536 units per (head, block pair) x 3 heads scale linearly"}))
+    elif args.workload == "sweep":
+        B = 32
+        for limbs in (4, 8, 12, 16, 20, 24, 28, 32, 36):
+            for dnum in (1, 2, 3, 4, 6):
+                if dnum > limbs:
+                    continue
+                K = -(-limbs // dnum)
+                p = make_params(16, limbs, 50, K, 60, dnum)
+                ctx = ck.Context(p, 0)
+                d = _uniform(torch, gen, dev, (B,), p.q, p.N)
+                evk = _uniform(torch, gen, dev, (p.dnum, 2), p.moduli, p.N)
+                out = torch.empty((B, 2, limbs, p.N), dtype=torch.int64, device=dev)
+                ws = ctx.workspace(ck.OP_KEYSWITCH, B, limbs)
+                dt = _time(torch, lambda: ck.ckks_keyswitch(ctx, out, d, B, limbs, evk, 0, dnum, ws), 2)
+                x = _uniform(torch, gen, dev, (B * 2,), p.q, p.N)
+                ids = list(range(limbs))
+                dn = _time(torch, lambda: ck.ckks_ntt(ctx, x, B * 2, ids), 2)
+                model = keyswitch_model(p, B, limbs, False, False)
+                nbytes = sum(v["bytes"] for v in model.values())
+                nops = sum(v["ops"] for v in model.values())
+                print(json.dumps({"workload": "sweep", "limbs": limbs, "dnum": dnum, "K": K, "batch": B,
+                                  "key_switches_per_s": round(B / dt, 1), "ntt_limbs_per_s": round(B * 2 * limbs / dn),
+                                  "hbm_frac_modelled_bytes": round(nbytes / dt / 1e9 / PEAK_HBM_GBS, 3),
+                                  "alu_frac_modelled_ops": round(nops / dt / 1e12 / PEAK_ALU_TOPS, 3),
+                                  "ntt_hbm_frac": round(B * 2 * limbs * 4 * 8 * p.N / dn / 1e9 / PEAK_HBM_GBS, 3)}), flush=True)
+                ctx.close()
+                del d, evk, out, ws, x
+                torch.cuda.empty_cache()
 
 
 def main():
@@ -69,6 +194,9 @@ def main():
     ap.add_argument("--tune", type=str, default="", help="experiment: comma-separated knob=value pairs")
     ap.add_argument("--streams", type=int, default=1, help="HIP streams the independent calls of a step are spread over")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate NTT / HRot / HMult timings (profiling runs)")
+    ap.add_argument("--workload", default="keyswitch_micro", choices=["keyswitch_micro", "pcmm", "attention", "sweep"])
+    ap.add_argument("--pcmm-batch", type=int, default=16)
+    ap.add_argument("--att-batch", type=int, default=32)
     ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -83,6 +211,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.workload != "keyswitch_micro":
+        other_workloads(args)
+        return
     dev = "cuda:0"
     p = config_params("keyswitch_micro")
     N, nl, B, G = p.N, len(p.q), 64, args.groups
@@ -205,7 +336,7 @@ def main():
       extra = dict(ntt_limbs_per_s=round(B * 2 * nl / t_ntt), intt_limbs_per_s=round(B * 2 * nl / t_intt),
                    hrot_per_s=round(B / t_rot, 1), hrot_per_s_one_group=round(B / t_rot1, 1),
                    hmult_relin_per_s=round(B / 2 / t_mul, 1),
-                   ntt_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
+                   ntt_int32_equiv_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
                  ntt_hbm_frac=round(B * 2 * nl * 4 * 8 * N / t_ntt / 1e9 / PEAK_HBM_GBS, 4),
                    hbm_frac_compulsory_bytes=round(compulsory * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),
                    hbm_frac_modelled_bytes=round(total_bytes * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),

@@ -610,7 +610,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   int rc = get_level(c, nlimbs, &lt);
   if (rc) return rc;
   if (c->logN == 16) return keyswitch_fused16(c, lt, io, B, nlimbs, evk, ws, st);
-  if (io.d_galois || io.mode[0] == 2 || io.mode[1] == 2 || io.d_stride != (u64)nlimbs * c->N)
+  if (io.d_galois || io.mode[0] >= 2 || io.mode[1] >= 2 || io.d_stride != (u64)nlimbs * c->N)
     return fail(CKKS_EINVAL, "internal: gather modes need the N = 2^16 path");
   const u64* d = io.d;
   u64* out = io.out;
@@ -878,8 +878,8 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlim
     case CKKS_OP_HMULT_RELIN: return ks + poly;
     case CKKS_OP_PCMM_BSGS:
       if (n1 == 0) return 0;
-      // baby steps 1..n1-1, inner sum, rotated inner sum, HRot workspace
-      return (size_t)(n1 - 1) * 2 * poly + 2 * poly + 2 * poly + ks + poly;
+      // baby steps 1..n1-1, PMACC_GT inner sums, rotated inner sum, HRot workspace
+      return (size_t)(n1 - 1) * 2 * poly + (size_t)PMACC_GT * 2 * poly + 2 * poly + ks + poly;
     default: return 0;
   }
 }
@@ -946,8 +946,15 @@ int ckks_keyswitch(ckks_ctx* c, uint64_t* ks_out, const uint64_t* d, uint32_t B,
   return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, (hipStream_t)stream);
 }
 
+static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
+                     const uint64_t* evk, void* ws, size_t ws_bytes, void* stream, bool accumulate);
 int ckks_hrot(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
               const uint64_t* evk, void* ws, size_t ws_bytes, void* stream) {
+  return hrot_impl(c, ct_out, ct_in, B, nlimbs, g, evk, ws, ws_bytes, stream, false);
+}
+// accumulate (N = 2^16 path only): ct_out += HRot(ct_in) instead of ct_out = HRot(ct_in).
+static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
+                     const uint64_t* evk, void* ws, size_t ws_bytes, void* stream, bool accumulate) {
   int rc = check_common(c, B, nlimbs);
   if (rc) return rc;
   if (!ct_out || !ct_in || !evk) return fail(CKKS_EINVAL, "null argument");
@@ -961,9 +968,11 @@ int ckks_hrot(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, 
   if (c->logN == 16) {
     // the permutation is applied where the ciphertext is read: by the first inverse pass and the fused inner product
     // (sigma(c1)) and by the final assembly (sigma(c0))
-    KsIo io{(const u64*)ct_in + polyN, 2 * polyN, g, (u64*)ct_out, {2, 0}, (const u64*)ct_in, g};
+    KsIo io{(const u64*)ct_in + polyN, 2 * polyN, g, (u64*)ct_out, {accumulate ? 3u : 2u, accumulate ? 1u : 0u},
+            (const u64*)ct_in, g};
     return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
   }
+  if (accumulate) return fail(CKKS_EINVAL, "internal: accumulating HRot needs the N = 2^16 path");
   const size_t ks = ks_layout(c, B, nlimbs).total;
   u64* d = (u64*)((char*)ws + ks);
   const LimbMap qmap = identity_map(nlimbs);
@@ -1021,7 +1030,7 @@ int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_
   const size_t ct_al = 2 * align256((size_t)B * polyN * 8);
   char* w = (char*)ws;
   u64* baby = (u64*)w;                  w += (size_t)(n1 - 1) * ct_al;
-  u64* inner = (u64*)w;                 w += ct_al;
+  u64* inner = (u64*)w;                 w += (size_t)PMACC_GT * ct_al;   // inner sums of one tile of giant steps
   u64* rot = (u64*)w;                   w += ct_al;
   char* hws = w;
   const size_t hws_bytes = ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0);
@@ -1034,28 +1043,49 @@ int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_
     }
     return (u32)g;
   };
-  const size_t ct_elems = ct_al / 8;
+  const size_t ct_elems = ct_al / 8;  // == B*2*nlimbs*N: a limb-vector is a multiple of 256 bytes
   for (u32 b = 1; b < n1; b++) {
     rc = ckks_hrot(c, (uint64_t*)(baby + (size_t)(b - 1) * ct_elems), ct_in, B, nlimbs, galois((u64)b * stride), evk_baby[b - 1], hws,
                    hws_bytes, stream);
     if (rc) return rc;
   }
-  for (u32 g = 0; g < n2; g++) {
-    u64* dst = g == 0 ? (u64*)ct_out : inner;
-    PmaccArgs a{(const u64*)ct_in, baby, (const u64*)pt + (size_t)g * n1 * polyN, dst, c->d_mods, c->logN, nlimbs, n1, B};
-    // baby rows are ct_elems apart; pmacc indexes them with B*2*nlimbs*N, which equals ct_elems when that is 256-aligned
+  for (u32 g0 = 0; g0 < n2; g0 += PMACC_GT) {
+    const u32 ng = std::min<u32>(PMACC_GT, n2 - g0);
+    // giant step 0 needs no rotation: its inner sum is written straight into the output
+    PmaccArgs a{(const u64*)ct_in, baby, (const u64*)pt, g0 == 0 ? (u64*)ct_out : inner, inner + ct_elems, c->d_mods,
+                c->logN, nlimbs, n1, B, g0, ng};
     {
-    ProfScope ps(c, PK_PMACC, st);
-    hipLaunchKernelGGL(pmacc_kernel, dim3(N / 256, nlimbs, 2 * B), dim3(256), 0, st, a);
+      ProfScope ps(c, PK_PMACC, st);
+      dim3 grid(2 * B, N / 512, nlimbs), block(256);
+      switch (ng) {
+        case 8: hipLaunchKernelGGL(pmacc_kernel<8>, grid, block, 0, st, a); break;
+        case 7: hipLaunchKernelGGL(pmacc_kernel<7>, grid, block, 0, st, a); break;
+        case 6: hipLaunchKernelGGL(pmacc_kernel<6>, grid, block, 0, st, a); break;
+        case 5: hipLaunchKernelGGL(pmacc_kernel<5>, grid, block, 0, st, a); break;
+        case 4: hipLaunchKernelGGL(pmacc_kernel<4>, grid, block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL(pmacc_kernel<3>, grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL(pmacc_kernel<2>, grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL(pmacc_kernel<1>, grid, block, 0, st, a); break;
+      }
     }
     HIP_TRY(hipGetLastError());
-    if (g > 0) {
-      rc = ckks_hrot(c, (uint64_t*)rot, (const uint64_t*)inner, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws, hws_bytes, stream);
-      if (rc) return rc;
-      AddArgs ad{(u64*)ct_out, rot, c->d_mods, c->logN, nlimbs};
-      ProfScope ps(c, PK_ADD, st);
-      hipLaunchKernelGGL(addto_kernel, dim3(N / 256, nlimbs, 2 * B), dim3(256), 0, st, ad);
-      HIP_TRY(hipGetLastError());
+    for (u32 k = 0; k < ng; k++) {
+      const u32 g = g0 + k;
+      if (g == 0) continue;
+      const u64* src = inner + (size_t)k * ct_elems;
+      if (c->logN == 16) {
+        rc = hrot_impl(c, ct_out, (const uint64_t*)src, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws,
+                       hws_bytes, stream, /*accumulate=*/true);
+        if (rc) return rc;
+      } else {
+        rc = ckks_hrot(c, (uint64_t*)rot, (const uint64_t*)src, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws,
+                       hws_bytes, stream);
+        if (rc) return rc;
+        AddArgs ad{(u64*)ct_out, rot, c->d_mods, c->logN, nlimbs};
+        ProfScope ps(c, PK_ADD, st);
+        hipLaunchKernelGGL(addto_kernel, dim3(N / 256, nlimbs, 2 * B), dim3(256), 0, st, ad);
+        HIP_TRY(hipGetLastError());
+      }
     }
   }
   return CKKS_OK;

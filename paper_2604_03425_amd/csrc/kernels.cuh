@@ -363,33 +363,89 @@ __global__ void __launch_bounds__(256) tensor_kernel(TensorArgs a) {
   a.d2[((size_t)b * a.nlimbs + i) * N + n] = mulmod(a1, b1, mi);
 }
 
-// BSGS inner sum: out[b][c][i][n] = sum_{s<n1} src_s[b][c][i][n] * pt[s][i][n], src_0 = ct_in, src_s = baby[s-1].
+// BSGS inner sums for GT consecutive giant steps at once:
+//   out_g[b][c][i][n] = sum_{s<n1} src_s[b][c][i][n] * pt[g][s][i][n],  src_0 = ct_in, src_s = baby[s-1],
+// so every baby ciphertext word is read once per GT giant steps instead of once per giant step. Two adjacent
+// coefficients per lane (16-byte accesses); one lazy 128-bit sum per output, folded every 8 terms.
 struct PmaccArgs {
   const u64* ct_in;   // [B][2][nlimbs][N]
   const u64* baby;    // [n1-1][B][2][nlimbs][N]
-  const u64* pt;      // [n1][nlimbs][N] (row g of the diagonal tensor)
-  u64* out;           // [B][2][nlimbs][N]
+  const u64* pt;      // [n2][n1][nlimbs][N]
+  u64* out0;          // destination of giant step g0 (the caller's output when g0 == 0)
+  u64* out_rest;      // [GT-1][B][2][nlimbs][N]: destinations of giant steps g0+1 .. g0+GT-1
   const ModInfo* mods;
-  u32 logN, nlimbs, n1, B;
+  u32 logN, nlimbs, n1, B, g0, ng;  // ng <= GT giant steps are computed
 };
+#define PMACC_GT 4
+template <int NG>
 __global__ void __launch_bounds__(256) pmacc_kernel(PmaccArgs a) {
   const u32 N = 1u << a.logN;
-  const u32 n = blockIdx.x * 256 + threadIdx.x;
-  const u32 i = blockIdx.y, bc = blockIdx.z;
+  // grid = (2B, N/512, nlimbs): the polynomial index is innermost so that the workgroups sharing a plaintext tile
+  // run together; when the number of (block, limb) groups allows, a whole group is placed on one XCD (whose L2
+  // then serves the tile to all of them) and eight consecutive groups run side by side.
+  const u32 lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  u32 bc, group;
+  if (((gridDim.y * gridDim.z) & 7) == 0) {
+    const u32 rest = lin >> 3;
+    bc = rest % gridDim.x;
+    group = (lin & 7) + 8 * (rest / gridDim.x);
+  } else {
+    bc = lin % gridDim.x;
+    group = lin / gridDim.x;
+  }
+  const u32 nb = group % gridDim.y, i = group / gridDim.y;
+  const u32 n = (nb * 256 + threadIdx.x) * 2;
   const ModInfo mi = a.mods[i];
   const size_t ct_sz = (size_t)a.B * 2 * a.nlimbs * N;
   const size_t o = ((size_t)bc * a.nlimbs + i) * N + n;
-  Acc128 s = {0, 0};
-  for (u32 k = 0; k < a.n1; k++) {
-    u64 x = k == 0 ? a.ct_in[o] : a.baby[(size_t)(k - 1) * ct_sz + o];
-    mac128(s, x, a.pt[((size_t)k * a.nlimbs + i) * N + n]);
-    if ((k & 7) == 7) {  // keep the 128-bit sum far from overflow for any n1
-      u64 r = reduce128(s, mi);
-      s.lo = r;
-      s.hi = 0;
+  const size_t pt_g = (size_t)a.n1 * a.nlimbs * N;
+  // per output: four carry-free sums of 30-bit partial products (at most 15 terms), folded into a canonical
+  // running sum
+  Dot30 dd[NG][2];
+  u64 run[NG][2];
+#pragma unroll
+  for (int g = 0; g < NG; g++)
+#pragma unroll
+    for (int e = 0; e < 2; e++) {
+      dot30_init(dd[g][e]);
+      run[g][e] = 0;
     }
+  // baby steps in chunks of 8 with all loads of a chunk issued together (memory-level parallelism), one fold per chunk
+  auto term = [&](u32 k) {
+    const ulonglong2 x = *(const ulonglong2*)(k == 0 ? a.ct_in + o : a.baby + (size_t)(k - 1) * ct_sz + o);
+    const u64* w = a.pt + (size_t)a.g0 * pt_g + ((size_t)k * a.nlimbs + i) * N + n;
+    const u32 x0[2] = {(u32)x.x & M30, (u32)x.y & M30}, x1[2] = {(u32)(x.x >> 30), (u32)(x.y >> 30)};
+#pragma unroll
+    for (int g = 0; g < NG; g++) {
+      const ulonglong2 c = *(const ulonglong2*)(w + (size_t)g * pt_g);
+      dot30_mac(dd[g][0], x0[0], x1[0], (u32)c.x & M30, (u32)(c.x >> 30));
+      dot30_mac(dd[g][1], x0[1], x1[1], (u32)c.y & M30, (u32)(c.y >> 30));
+    }
+  };
+  auto fold = [&]() {
+#pragma unroll
+    for (int g = 0; g < NG; g++)
+#pragma unroll
+      for (int e = 0; e < 2; e++) {
+        run[g][e] = addmod(run[g][e], reduce128(dot30_value(dd[g][e]), mi), mi.m);
+        dot30_init(dd[g][e]);
+      }
+  };
+  u32 k = 0;
+  for (; k + 8 <= a.n1; k += 8) {
+#pragma unroll
+    for (int kk = 0; kk < 8; kk++) term(k + kk);
+    fold();
   }
-  a.out[o] = reduce128(s, mi);
+  if (k < a.n1) {
+    for (; k < a.n1; k++) term(k);
+    fold();
+  }
+#pragma unroll
+  for (int g = 0; g < NG; g++) {
+    u64* dst = g == 0 ? a.out0 + o : a.out_rest + (size_t)(g - 1) * ct_sz + o;
+    *(ulonglong2*)dst = ulonglong2{run[g][0], run[g][1]};
+  }
 }
 
 // out = out + in (mod q_i) on [npoly][nlimbs][N]

@@ -292,7 +292,7 @@ DEFINE_FWD_INNER_KERNEL(ntt16_fwd_blocks_inner_occ3_kernel, __attribute__((amdgp
 // out[bc][i] = (acc[bc][i] - NTT(tq[bc][i])) * pinv[i]  (+ addend). On integer-class moduli acc and tq carry the
 // factor 2^-64 and pinv = 2^64/P; on double-precision moduli they are plain and pinv = (1/P, (1/P)/q).
 // addend modes per component c = bc & 1: 0 none; 1 the value already in out (in place); 2 add_src read through
-// the Galois map g (HRot's sigma(c0)).
+// the Galois map g (HRot's sigma(c0)); 3 both (an HRot accumulated into out).
 struct FwdFinalArgs {
   const u64* tq;      // [B*2][nlimbs][N], after the row pass
   const u64* acc;     // [B*2][next][N]
@@ -320,8 +320,8 @@ __device__ __forceinline__ void fwd_final_body(const FwdFinalArgs& a, u32 bc, u3
 #pragma unroll
   for (int i = 0; i < 16; i++) {
     u64 r = shoup(ac[i * 16] + q2 - x[i], pv.x, pv.y, q);
-    if (mode == 1) r = addmod(r, o[i * 16], q);
-    else if (mode == 2) r = addmod(r, as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)], q);
+    if (mode & 1) r = addmod(r, o[i * 16], q);
+    if (mode & 2) r = addmod(r, as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)], q);
     o[i * 16] = r;
   }
 }
@@ -341,8 +341,9 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
 #pragma unroll
   for (int i = 0; i < 16; i++) {
     double r = fp_mulmod_const(u2d(ac[i * 16]) - x[i], pv.x, pv.y, q);  // |r| <= 0.9 q
-    if (mode == 1) r += u2d(o[i * 16]);
-    else if (mode == 2) r += u2d(as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)]);
+    if (mode & 1) r += u2d(o[i * 16]);
+    if (mode & 2) r += u2d(as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)]);
+    if (mode == 3) r = r >= q ? r - q : r;  // two addends: bring the sum back below 2q first
     o[i * 16] = d2u_canon(r, q);
   }
 }
