@@ -33,6 +33,19 @@ OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 16, 14, 4
 OPS_BUTTERFLY_FP, OPS_MULRED_FP, OPS_SHOUP_FP = 9.5, 7, 6
 
 
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload (bytes, average
+# over the launches of a step, fetch scaled by the copy-kernel calibration); see profiles/keyswitch_micro_hbm_traffic.md.
+MEASURED_TRAFFIC = {
+    "ntt16_inv_blocks_kernel<0>": 281151296, "ntt16_inv_rows_kernel<0>": 269048650,
+    "ntt16_inv_blocks_kernel<2>": 187583914, "ntt16_inv_rows_kernel<2>": 179521159,
+    "modup_kernel": 537268760, "moddown_kernel": 358057340,
+    "ntt16_fwd_rows_kernel<0>": 537455765, "ntt16_fwd_rows_kernel<2>": 268969112,
+    "ntt16_fwd_blocks_kernel<0>": 549574400, "inner16_fp_kernel": 746709269,
+    "ntt16_fwd_blocks_inner_kernel<2>": 260386936, "ntt16_fwd_blocks_final_kernel<0>": 997051317,
+    "tensor_kernel": 2818660832,
+}
+
+
 def keyswitch_model(p, B, nl, hrot, hmult):
     """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B (N = 2^16 path:
     double-precision bodies on primes < 2^50, with their inner product as a separate streaming kernel)."""
@@ -52,28 +65,35 @@ def keyswitch_model(p, B, nl, hrot, hmult):
     bf_pass_fp = (N / 2) * 8 * OPS_BUTTERFLY_FP    # same, double-precision bodies
     mul_redc = 2 * OPS_MAC + OPS_REDUCE            # one variable x variable product reduced
     m = {}
-    inv_fp, inv_int = B * own_fp, B * (own_int + 2 * sum(1 for x in p.p if x >= (1 << 50)))
-    inv_fp += B * 2 * sum(1 for x in p.p if x < (1 << 50))
-    n_inv = inv_fp + inv_int
-    m["ntt16_inv_blocks"] = dict(bytes=n_inv * 2 * limb, ops=inv_int * bf_pass + inv_fp * bf_pass_fp)
-    m["ntt16_inv_rows"] = dict(bytes=n_inv * 2 * limb,
-                               ops=inv_int * (bf_pass + N * OPS_SHOUP) + inv_fp * (bf_pass_fp + N * OPS_SHOUP_FP))
-    m["modup_bconv"] = dict(bytes=B * (nl + new_limbs) * limb,
-                            ops=B * N * sum((nxt - len(dg)) * ((len(dg) + 1) * OPS_MAC + OPS_REDUCE) for dg in digits))
+    kfp = sum(1 for x in p.p if x < (1 << 50))
+    inv_fp, inv_int = B * (own_fp + 2 * kfp), B * (own_int + 2 * (K - kfp))
+
+    def put(name, cls, nbytes, nops):
+        if nbytes or nops:
+            m["%s<%d>" % (name, cls) if cls is not None else name] = dict(bytes=nbytes, ops=nops)
+    # class 0 = double-precision bodies; the 60-bit special primes are class 2 (Harvey integer bodies)
+    put("ntt16_inv_blocks_kernel", 0, inv_fp * 2 * limb, inv_fp * bf_pass_fp)
+    put("ntt16_inv_blocks_kernel", 2, inv_int * 2 * limb, inv_int * bf_pass)
+    put("ntt16_inv_rows_kernel", 0, inv_fp * 2 * limb, inv_fp * (bf_pass_fp + N * OPS_SHOUP_FP))
+    put("ntt16_inv_rows_kernel", 2, inv_int * 2 * limb, inv_int * (bf_pass + N * OPS_SHOUP))
+    put("modup_kernel", None, B * (nl + new_limbs) * limb,
+        B * N * sum((nxt - len(dg)) * ((len(dg) + 1) * OPS_MAC + OPS_REDUCE) for dg in digits))
     rows_fp, rows_int = B * (new_fp + 2 * own_fp), B * (new_int + 2 * own_int)
-    m["ntt16_fwd_rows"] = dict(bytes=(rows_fp + rows_int) * 2 * limb, ops=rows_fp * bf_pass_fp + rows_int * bf_pass)
-    m["ntt16_fwd_blocks"] = dict(bytes=B * new_fp * 2 * limb, ops=B * new_fp * bf_pass_fp)
-    m["evk_inner"] = dict(bytes=(B * (new_fp + own_fp + 2 * n_fp) + 2 * beta * n_fp) * limb,
-                          ops=B * N * n_fp * beta * 2 * OPS_MULRED_FP)
-    m["ntt16_fwd_blocks_inner"] = dict(bytes=(B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
-                                       ops=B * (new_int * bf_pass + N * n_int * beta * 2 * mul_redc))
-    m["moddown_bconv"] = dict(bytes=2 * B * (K + nl) * limb, ops=2 * B * N * nl * ((K + 1) * OPS_MAC + OPS_REDUCE))
+    put("ntt16_fwd_rows_kernel", 0, rows_fp * 2 * limb, rows_fp * bf_pass_fp)
+    put("ntt16_fwd_rows_kernel", 2, rows_int * 2 * limb, rows_int * bf_pass)
+    put("ntt16_fwd_blocks_kernel", 0, B * new_fp * 2 * limb, B * new_fp * bf_pass_fp)
+    put("inner16_fp_kernel", None, (B * (new_fp + own_fp + 2 * n_fp) + 2 * beta * n_fp) * limb,
+        B * N * n_fp * beta * 2 * OPS_MULRED_FP)
+    put("ntt16_fwd_blocks_inner_kernel", 2, (B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
+        B * (new_int * bf_pass + N * n_int * beta * 2 * mul_redc))
+    put("moddown_kernel", None, 2 * B * (K + nl) * limb, 2 * B * N * nl * ((K + 1) * OPS_MAC + OPS_REDUCE))
     addend = 1 if hrot else 2 if hmult else 0
-    m["ntt16_fwd_blocks_final"] = dict(bytes=B * nl * (6 + addend) * limb,
-                                       ops=2 * B * (own_fp * (bf_pass_fp + N * (OPS_SHOUP_FP + 2)) +
-                                                    own_int * (bf_pass + N * (OPS_SHOUP + 2 * OPS_ADD))))
+    put("ntt16_fwd_blocks_final_kernel", 0, B * own_fp * (6 + addend) * limb,
+        2 * B * own_fp * (bf_pass_fp + N * (OPS_SHOUP_FP + 2)))
+    put("ntt16_fwd_blocks_final_kernel", 2, B * own_int * (6 + addend) * limb,
+        2 * B * own_int * (bf_pass + N * (OPS_SHOUP + 2 * OPS_ADD)))
     if hmult:
-        m["tensor"] = dict(bytes=B * nl * 7 * limb, ops=B * nl * N * 4 * mul_redc)
+        put("tensor_kernel", None, B * nl * 7 * limb, B * nl * N * 4 * mul_redc)
     return m
 
 
@@ -303,10 +323,10 @@ def main():
     alu_frac = (d["Tops"] or 0) / PEAK_ALU_TOPS
     if alu_frac >= hbm_frac:
         roofline = dict(bound="alu", kernel=dom, achieved=d["Tops"], peak=round(PEAK_ALU_TOPS, 1), unit="Tlane-op/s",
-                        frac=round(alu_frac, 4), traffic=None, avg_launch_us=d["avg_launch_us"])
+                        frac=round(alu_frac, 4), traffic=MEASURED_TRAFFIC.get(dom), avg_launch_us=d["avg_launch_us"])
     else:
         roofline = dict(bound="hbm", kernel=dom, achieved=d["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(hbm_frac, 4), traffic=None, avg_launch_us=d["avg_launch_us"])
+                        frac=round(hbm_frac, 4), traffic=MEASURED_TRAFFIC.get(dom), avg_launch_us=d["avg_launch_us"])
     total_bytes = sum(v["bytes"] for v in model.values())
     total_ops = sum(v["ops"] for v in model.values())
     # compulsory traffic of a step: read every input ciphertext and key once, write every output once

@@ -94,11 +94,23 @@ struct LevelTables {
 }  // namespace
 
 enum ProfKind {
-  PK_NTT_FWD = 0, PK_NTT_INV, PK_FWD_ROWS, PK_FWD_BLOCKS, PK_INV_BLOCKS, PK_INV_ROWS, PK_FWD_INNER, PK_FWD_FINAL, PK_AUTOMORPH, PK_MODUP, PK_INNER, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
+  PK_NTT_FWD = 0, PK_NTT_INV,
+  // N = 2^16 kernels: three consecutive kinds each, one per modulus class (the kernel's template argument)
+  PK_FWD_ROWS, PK_FWD_BLOCKS = PK_FWD_ROWS + 3, PK_INV_BLOCKS = PK_FWD_BLOCKS + 3, PK_INV_ROWS = PK_INV_BLOCKS + 3,
+  PK_FWD_INNER = PK_INV_ROWS + 3, PK_FWD_FINAL = PK_FWD_INNER + 3,
+  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
   PK_COPY, PK_COUNT
 };
-static const char* const kProfNames[PK_COUNT] = {"ntt_fwd_pass", "ntt_inv_pass", "ntt16_fwd_rows", "ntt16_fwd_blocks", "ntt16_inv_blocks", "ntt16_inv_rows", "ntt16_fwd_blocks_inner", "ntt16_fwd_blocks_final", "automorph", "modup_bconv", "evk_inner",
-                                                 "moddown_bconv", "ks_final", "tensor", "pmult_acc", "add", "copy"};
+static const char* const kProfNames[PK_COUNT] = {
+    "ntt_fwd_pass", "ntt_inv_pass",
+    "ntt16_fwd_rows_kernel<0>", "ntt16_fwd_rows_kernel<1>", "ntt16_fwd_rows_kernel<2>",
+    "ntt16_fwd_blocks_kernel<0>", "ntt16_fwd_blocks_kernel<1>", "ntt16_fwd_blocks_kernel<2>",
+    "ntt16_inv_blocks_kernel<0>", "ntt16_inv_blocks_kernel<1>", "ntt16_inv_blocks_kernel<2>",
+    "ntt16_inv_rows_kernel<0>", "ntt16_inv_rows_kernel<1>", "ntt16_inv_rows_kernel<2>",
+    "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
+    "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
+    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
+    "pmacc_kernel", "addto_kernel", "copy"};
 struct ProfRec {
   int kind;
   hipEvent_t start, stop;
@@ -311,13 +323,14 @@ inline int host_class(const ckks_ctx* c, u64 m) {
   return (m >> 52) == 0 ? 1 : 2;
 }
 // Launch KERNEL<cls> once per modulus class present among `nslots` slots, with ARGS.slots listing that class's slots.
-#define LAUNCH_BY_CLASS(KERNEL, ARGS, NX, NSLOTS, CLASS_OF_SLOT, STREAM)                                   \
+#define LAUNCH_BY_CLASS(CTX, PKBASE, KERNEL, ARGS, NX, NSLOTS, CLASS_OF_SLOT, STREAM)                      \
   for (int cls_ = 0; cls_ < 3; cls_++) {                                                                    \
     u32 cnt_ = 0;                                                                                           \
     for (u32 s_ = 0; s_ < (NSLOTS); s_++)                                                                   \
       if ((CLASS_OF_SLOT(s_)) == cls_) (ARGS).slots[cnt_++] = (unsigned char)s_;                            \
     if (!cnt_) continue;                                                                                    \
     dim3 grid_((NX), 16, cnt_), block_(NTT16_THREADS);                                                      \
+    ProfScope ps_((CTX), (PKBASE) + cls_, (STREAM));                                                        \
     if (cls_ == 0) hipLaunchKernelGGL((KERNEL<0>), grid_, block_, 0, (STREAM), (ARGS));                     \
     else if (cls_ == 1) hipLaunchKernelGGL((KERNEL<1>), grid_, block_, 0, (STREAM), (ARGS));                \
     else hipLaunchKernelGGL((KERNEL<2>), grid_, block_, 0, (STREAM), (ARGS));                               \
@@ -362,22 +375,14 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     };
     if (!inverse) {
       if (!opt.blocks_only) {
-        ProfScope ps(c, PK_FWD_ROWS, st);
-        LAUNCH_BY_CLASS(ntt16_fwd_rows_kernel, a, npoly, nslots, cls_of, st)
+        LAUNCH_BY_CLASS(c, PK_FWD_ROWS, ntt16_fwd_rows_kernel, a, npoly, nslots, cls_of, st)
       }
       if (!opt.rows_only) {
-        ProfScope ps(c, PK_FWD_BLOCKS, st);
-        LAUNCH_BY_CLASS(ntt16_fwd_blocks_kernel, b, npoly, nslots, cls_of, st)
+        LAUNCH_BY_CLASS(c, PK_FWD_BLOCKS, ntt16_fwd_blocks_kernel, b, npoly, nslots, cls_of, st)
       }
     } else {
-      {
-        ProfScope ps(c, PK_INV_BLOCKS, st);
-        LAUNCH_BY_CLASS(ntt16_inv_blocks_kernel, a, npoly, nslots, cls_of, st)
-      }
-      {
-        ProfScope ps(c, PK_INV_ROWS, st);
-        LAUNCH_BY_CLASS(ntt16_inv_rows_kernel, b, npoly, nslots, cls_of, st)
-      }
+      LAUNCH_BY_CLASS(c, PK_INV_BLOCKS, ntt16_inv_blocks_kernel, a, npoly, nslots, cls_of, st)
+      LAUNCH_BY_CLASS(c, PK_INV_ROWS, ntt16_inv_rows_kernel, b, npoly, nslots, cls_of, st)
     }
     HIP_TRY(hipGetLastError());
     return CKKS_OK;
@@ -550,19 +555,18 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
       for (u32 s_ = 0; s_ < next; s_++)
         if (host_class(c, c->mod[emap.id[s_]]) == 0) a.slots[cnt++] = (unsigned char)s_;
       if (cnt) {
-        ProfScope ps(c, PK_INNER, st);
+        ProfScope ps(c, PK_INNER16, st);
         hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
       }
     }
-    ProfScope ps(c, PK_FWD_INNER, st);
     auto cls_of = [&](u32 s) {
       int k = host_class(c, c->mod[emap.id[s]]);
       return (unfused_fp && k == 0) ? -1 : k;
     };
     if (c->tune[2]) {
-      LAUNCH_BY_CLASS(ntt16_fwd_blocks_inner_occ3_kernel, a, B, next, cls_of, st)
+      LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_occ3_kernel, a, B, next, cls_of, st)
     } else {
-      LAUNCH_BY_CLASS(ntt16_fwd_blocks_inner_kernel, a, B, next, cls_of, st)
+      LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_kernel, a, B, next, cls_of, st)
     }
     HIP_TRY(hipGetLastError());
   }
@@ -596,9 +600,8 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     a.mode1 = io.mode[1];
     a.galois = io.add_galois;
     a.map_mode = c->tune[0];
-    ProfScope ps(c, PK_FWD_FINAL, st);
     auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
-    LAUNCH_BY_CLASS(ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
+    LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
     HIP_TRY(hipGetLastError());
   }
   return CKKS_OK;
