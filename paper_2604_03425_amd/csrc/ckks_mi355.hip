@@ -131,6 +131,8 @@ struct ckks_ctx {
   ulonglong2* d_tw_inv = nullptr;
   double* d_twfp_fwd = nullptr;  // N = 2^16 only: the twiddles as doubles for moduli < 2^50
   double* d_twfp_inv = nullptr;
+  hipStream_t side = nullptr;       // second stream for the fork/join inside a key switch (default priority)
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   std::vector<Pass> passes;  // forward order
   std::mutex mu;
   std::map<u32, LevelTables> levels;
@@ -343,6 +345,7 @@ struct NttOpts {
   bool blocks_only = false;           // N = 2^16 forward only: only the block pass, in place on dst
   bool raw_out = false;               // with blocks_only: leave reduced doubles on double-precision moduli
   int only_class = -1;                // >= 0: touch only the slots of this modulus class
+  int exclude_class = -1;             // >= 0: leave the slots of this modulus class alone
 };
 int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, u64* dst, u64 dst_stride, u32 npoly,
                u32 slot0, u32 nslots, const LimbMap& ids_from_slot0, u32 skip_beta, u32 skip_nq, hipStream_t st,
@@ -371,7 +374,9 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     b.src_poly_stride = dst_stride;
     auto cls_of = [&](u32 s) {
       int k = host_class(c, c->mod[ids_from_slot0.id[s]]);
-      return (opt.only_class >= 0 && k != opt.only_class) ? -1 : k;
+      if (opt.only_class >= 0 && k != opt.only_class) return -1;
+      if (opt.exclude_class >= 0 && k == opt.exclude_class) return -1;
+      return k;
     };
     if (!inverse) {
       if (!opt.blocks_only) {
@@ -522,43 +527,75 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   }
   NttOpts o2;
   o2.rows_only = true;
-  if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, o2)))
-    return rc;
-  {
-    FwdInnerArgs a;
-    a.ext = ext;
-    a.d = io.d;
-    a.d_poly_stride = io.d_stride;
-    a.evk = evk;
-    a.acc = acc;
-    a.tw = c->d_tw_fwd;
-    a.twfp = c->d_twfp_fwd;
-    a.mods = c->d_mods;
-    a.nlimbs = nlimbs;
-    a.nq = c->nq;
-    a.nm = c->nm;
-    a.alpha = c->alpha;
-    a.beta = beta;
-    a.next = next;
-    a.map_mode = c->tune[0];
-    a.galois = io.d_galois;
-    const bool unfused_fp = c->tune[3] != 0;
-    if (unfused_fp) {
-      // double-precision slots: plain block pass leaving doubles, then a streaming multiply-accumulate
-      NttOpts o;
-      o.blocks_only = true;
-      o.raw_out = true;
-      o.only_class = 0;
-      if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, o)))
-        return rc;
-      u32 cnt = 0;
-      for (u32 s_ = 0; s_ < next; s_++)
-        if (host_class(c, c->mod[emap.id[s_]]) == 0) a.slots[cnt++] = (unsigned char)s_;
-      if (cnt) {
-        ProfScope ps(c, PK_INNER16, st);
-        hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
-      }
+  // Double-precision slots take the plain block pass + streaming inner product (memory-bound); integer-class slots
+  // (the special primes) take the fused block pass + inner product and then feed ModDown (ALU-bound). The two
+  // chains touch disjoint slots, so they run side by side on two streams and join before the result is assembled.
+  const bool unfused_fp = c->tune[3] != 0;
+  bool any_fp = false, any_int = false, special_fp = false;
+  for (u32 s_ = 0; s_ < next; s_++) {
+    const bool fp = host_class(c, c->mod[emap.id[s_]]) == 0;
+    any_fp |= fp;
+    any_int |= !fp;
+    if (s_ >= nlimbs) special_fp |= fp;
+  }
+  const bool fork = unfused_fp && any_fp && any_int && c->tune[4] == 0;
+  hipStream_t sb = st;  // stream of the double-precision chain
+  if (fork) {
+    if (!c->side) {
+      HIP_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+      HIP_TRY(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
     }
+    sb = c->side;
+    HIP_TRY(hipEventRecord(c->ev_fork, st));
+    HIP_TRY(hipStreamWaitEvent(sb, c->ev_fork, 0));
+  }
+  FwdInnerArgs ia;
+  ia.ext = ext;
+  ia.d = io.d;
+  ia.d_poly_stride = io.d_stride;
+  ia.evk = evk;
+  ia.acc = acc;
+  ia.tw = c->d_tw_fwd;
+  ia.twfp = c->d_twfp_fwd;
+  ia.mods = c->d_mods;
+  ia.nlimbs = nlimbs;
+  ia.nq = c->nq;
+  ia.nm = c->nm;
+  ia.alpha = c->alpha;
+  ia.beta = beta;
+  ia.next = next;
+  ia.map_mode = c->tune[0];
+  ia.galois = io.d_galois;
+  if (unfused_fp && any_fp) {
+    NttOpts o = o2;
+    o.only_class = 0;
+    if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
+      return rc;
+    o = NttOpts();
+    o.blocks_only = true;
+    o.raw_out = true;
+    o.only_class = 0;
+    if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
+      return rc;
+    FwdInnerArgs a = ia;
+    u32 cnt = 0;
+    for (u32 s_ = 0; s_ < next; s_++)
+      if (host_class(c, c->mod[emap.id[s_]]) == 0) a.slots[cnt++] = (unsigned char)s_;
+    {
+      ProfScope ps(c, PK_INNER16, sb);
+      hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, sb, a);
+    }
+    HIP_TRY(hipGetLastError());
+    if (fork) HIP_TRY(hipEventRecord(c->ev_join, sb));
+  }
+  bool joined = !fork;
+  {
+    NttOpts o = o2;
+    if (unfused_fp) o.exclude_class = 0;
+    if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, o)))
+      return rc;
+    FwdInnerArgs a = ia;
     auto cls_of = [&](u32 s) {
       int k = host_class(c, c->mod[emap.id[s]]);
       return (unfused_fp && k == 0) ? -1 : k;
@@ -569,6 +606,10 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
       LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_kernel, a, B, next, cls_of, st)
     }
     HIP_TRY(hipGetLastError());
+  }
+  if (!joined && special_fp) {  // a special prime's accumulator came from the other chain
+    HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
+    joined = true;
   }
   {
     LimbMap pmap;
@@ -584,6 +625,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     HIP_TRY(hipGetLastError());
   }
   if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st, o2))) return rc;
+  if (!joined) HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
   {
     FwdFinalArgs a;
     a.tq = tq;
@@ -811,6 +853,9 @@ int ckks_ctx_destroy(ckks_ctx* c) {
   (void)hipFree(c->d_tw_inv);
   (void)hipFree(c->d_twfp_fwd);
   (void)hipFree(c->d_twfp_inv);
+  if (c->side) (void)hipStreamSynchronize(c->side), (void)hipStreamDestroy(c->side);
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   for (auto& r : c->prof_recs) {
     (void)hipEventDestroy(r.start);
     (void)hipEventDestroy(r.stop);
