@@ -353,9 +353,20 @@ def main():
       t_rot1 = timed(lambda: ck.ckks_hrot(ctx, out_rot, ct, B, nl, gal[0], evks[0],
                                           ctx.workspace(ck.OP_HROT, B, nl)), 3)
       t_mul = timed(lambda: ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws), 3)
+      # the step after a product: Rescale (and the PMult / Add building blocks), same batch
+      ws_rs = ctx.workspace(ck.OP_RESCALE, B, nl)
+      out_rs = torch.empty((B, 2, nl - 1, N), dtype=torch.int64, device=dev)
+      t_rs = timed(lambda: ck.ckks_rescale(ctx, out_rs, ct, B, nl, ws_rs), 3)
+      pt1 = ct[0, 0].contiguous()
+      t_pm = timed(lambda: ck.ckks_pmult(ctx, out_rot, ct, pt1, B, nl), 3)
+      t_ad = timed(lambda: ck.ckks_add(ctx, out_rot, ct, out_rot, B * 2, nl), 3)
       extra = dict(ntt_limbs_per_s=round(B * 2 * nl / t_ntt), intt_limbs_per_s=round(B * 2 * nl / t_intt),
                    hrot_per_s=round(B / t_rot, 1), hrot_per_s_one_group=round(B / t_rot1, 1),
                    hmult_relin_per_s=round(B / 2 / t_mul, 1),
+                 rescale_per_s=round(B / t_rs, 1),
+                 rescale_hbm_frac=round(B * 2 * (4 + 3 * (nl - 1) + 4 * (nl - 1)) * 8 * N / t_rs / 1e9 / PEAK_HBM_GBS, 4),
+                 pmult_hbm_frac=round(B * 2 * nl * 2 * 8 * N / t_pm / 1e9 / PEAK_HBM_GBS, 4),
+                 add_hbm_frac=round(B * 2 * nl * 3 * 8 * N / t_ad / 1e9 / PEAK_HBM_GBS, 4),
                    ntt_int32_equiv_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
                  ntt_hbm_frac=round(B * 2 * nl * 4 * 8 * N / t_ntt / 1e9 / PEAK_HBM_GBS, 4),
                    hbm_frac_compulsory_bytes=round(compulsory * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),

@@ -60,6 +60,7 @@ extern "C" {
 #define CKKS_OP_HROT 2
 #define CKKS_OP_HMULT_RELIN 3
 #define CKKS_OP_PCMM_BSGS 4
+#define CKKS_OP_RESCALE 5
 
 typedef struct ckks_ctx ckks_ctx;
 
@@ -153,6 +154,25 @@ int ckks_pcmm_bsgs(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint3
                    const uint64_t* pt_diag, uint32_t n1, uint32_t n2, uint32_t stride,
                    const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws, size_t ws_bytes,
                    void* stream);
+
+/*
+ * Rescale (paper Sec. 2.1: "divides by the last modulus q_L to reduce scale and remove one prime"): for
+ * ct_in [B][2][nlimbs][N] (device, evaluation domain, nlimbs >= 2) writes ct_out [B][2][nlimbs-1][N] with
+ * every coefficient c replaced by round(c / q_{nlimbs-1}) (centred representatives, exact). ct_out must not
+ * overlap ct_in.
+ */
+int ckks_rescale(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, void* ws,
+                 size_t ws_bytes, void* stream);
+
+/*
+ * PMult (paper Sec. 2.1): ct_out[b][c][i] = ct_in[b][c][i] (.) pt[i], pt device [nlimbs][N], evaluation domain,
+ * pre-encoded (Sec. 2.4). May run in place (ct_out == ct_in).
+ * CAdd / PAdd building block: out = a + b on device tensors [npoly][nlimbs][N]. May run in place.
+ */
+int ckks_pmult(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, const uint64_t* pt, uint32_t B, uint32_t nlimbs,
+               void* stream);
+int ckks_add(ckks_ctx* ctx, uint64_t* out, const uint64_t* a, const uint64_t* b, uint32_t npoly, uint32_t nlimbs,
+             void* stream);
 
 /*
  * Measurement support (not part of the paper's operator set). While enabled, every kernel

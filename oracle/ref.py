@@ -197,6 +197,19 @@ class RefContext:
                                    C.c_uint32(n1), C.c_uint32(n2), C.c_uint32(stride), baby, giant))
         return out
 
+    def rescale(self, ct):
+        ct, cp = _u64(ct)
+        B, two, nl, _ = ct.shape
+        out = np.empty((B, 2, nl - 1, self.N), dtype=np.uint64)
+        _check(lib().ref_rescale(self._h, out.ctypes.data_as(u64p), cp, C.c_uint32(B), C.c_uint32(nl)))
+        return out
+
+    def pmult(self, ct, pt):
+        """ct [B][2][nl][N] times plaintext pt [nl][N], pointwise per limb."""
+        B, two, nl, N = ct.shape
+        ids = list(range(nl))
+        return self.pointwise(ct.reshape(B * 2, nl, N), np.asarray(pt).reshape(1, nl, N), ids, "mul").reshape(ct.shape)
+
     # ---- keys / encryption (semantic pins) ----
     def gen_evk(self, s, s_from, a_eval, e):
         """evk [dnum][2][nm][N] switching s_from -> s. a_eval [dnum][nm][N] uniform, e [dnum][N] signed."""

@@ -634,6 +634,33 @@ int ref_pcmm_bsgs(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, ui
   return 0;
 }
 
+// Rescale (paper Sec. 2.1: divide by the last modulus and drop it). For each polynomial of ct [B][2][nlimbs][N]
+// (eval domain): c_L = INTT(last limb), centred to (-q_L/2, q_L/2]; out_i = NTT((INTT(c_i) - c_L) * q_L^-1 mod q_i)
+// for i < nlimbs-1. On the integers this is exactly round(c / q_L).
+int ref_rescale(const RefCtx* c, u64* out, const u64* ct, uint32_t B, uint32_t nlimbs) {
+  if (nlimbs < 2 || nlimbs > (uint32_t)c->nq) return fail("rescale needs 2..L+1 limbs");
+  const size_t N = c->N;
+  const uint32_t last = nlimbs - 1;
+  const u64 qL = c->mod[last];
+  parallel_for((size_t)B * 2, [&](size_t p) {
+    std::vector<u64> cl(ct + (p * nlimbs + last) * N, ct + (p * nlimbs + last + 1) * N);
+    intt_fast(c, cl.data(), last);
+    for (uint32_t i = 0; i < last; i++) {
+      const u64 m = c->mod[i], qinv = invm(qL % m, m);
+      std::vector<u64> x(ct + (p * nlimbs + i) * N, ct + (p * nlimbs + i + 1) * N);
+      intt_fast(c, x.data(), i);
+      for (size_t n = 0; n < N; n++) {
+        u64 v = cl[n];
+        u64 t = v > qL / 2 ? subm(v % m, qL % m, m) : v % m;  // centred representative of c_L, reduced mod q_i
+        x[n] = mulm(subm(x[n], t, m), qinv, m);
+      }
+      ntt_fast(c, x.data(), i);
+      std::copy(x.begin(), x.end(), out + (p * last + i) * N);
+    }
+  });
+  return 0;
+}
+
 // ---- keys, encryption, decryption (harness side of the semantic pins) ----
 // evk[j] = (b_j, a_j) over all nq+np moduli, eval domain: b_j = -a_j*s + e_j + W_j*s_from, where W_j = P mod q_i on the
 // limbs of digit j (top level digits of width alpha), 0 on every other modulus.

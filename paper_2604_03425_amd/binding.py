@@ -11,12 +11,12 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libckks_mi355.so")
 
-OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS = 1, 2, 3, 4
+OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS, OP_RESCALE = 1, 2, 3, 4, 5
 
 _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
-            "ckks_prof_reset", "ckks_tune_set"]
+            "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add"]
 
 
 class CkksError(RuntimeError):
@@ -54,6 +54,9 @@ def _load():
     lib.ckks_hmult_relin.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
+    lib.ckks_rescale.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, vp, C.c_size_t, vp]
+    lib.ckks_pmult.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
+    lib.ckks_add.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
     lib.ckks_prof_enable.argtypes = [vp, C.c_int]
     lib.ckks_tune_set.argtypes = [vp, C.c_int, C.c_int]
     lib.ckks_prof_kind_name.restype = C.c_char_p
@@ -188,3 +191,16 @@ def ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_b
     _check(_lib.ckks_pcmm_bsgs(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs,
                                _ptr(pt_diag, "pt_diag"), n1, n2, stride, baby, giant, _ptr(ws, "ws"), ws.numel() * 8,
                                _stream()))
+
+
+def ckks_rescale(ctx, ct_out, ct_in, B, nlimbs, ws):
+    _check(_lib.ckks_rescale(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, _ptr(ws, "ws"),
+                             ws.numel() * 8, _stream()))
+
+
+def ckks_pmult(ctx, ct_out, ct_in, pt, B, nlimbs):
+    _check(_lib.ckks_pmult(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), _ptr(pt, "pt"), B, nlimbs, _stream()))
+
+
+def ckks_add(ctx, out, a, b, npoly, nlimbs):
+    _check(_lib.ckks_add(ctx.handle, _ptr(out, "out"), _ptr(a, "a"), _ptr(b, "b"), npoly, nlimbs, _stream()))

@@ -89,6 +89,11 @@ struct LevelTables {
   ulonglong2* dn_scale = nullptr;  // [K]       2^64 (P/p_k)^-1 / N mod p_k
   u64* dn_mat_plain = nullptr;     // dn_mat without the Montgomery factor
   ulonglong2* pinv2 = nullptr;     // [nlimbs]  2^64 / P mod q_i
+  // rescale from this limb count: drop q_{nlimbs-1}
+  ulonglong2* rs_one = nullptr;    // [1]          Shoup pair of 1 (the single source needs no pre-scaling)
+  u64* rs_mat = nullptr;           // [nlimbs-1][5] row i = (1, 0, 0, 0, -q_last) mod q_i, Montgomery form
+  ulonglong2* rs_qinv = nullptr;   // [nlimbs-1]   q_last^-1 mod q_i, Shoup pair
+  ulonglong2* rs_qinv16 = nullptr; // same for the N = 2^16 kernels: (c, c/q) doubles on double-precision moduli
 };
 
 }  // namespace
@@ -291,9 +296,26 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
       dn_scale[k] = ulonglong2{w, h_shoup(w, m)};
     }
   }
+  std::vector<ulonglong2> rs_one(1), rs_qinv(nlimbs > 1 ? nlimbs - 1 : 0), rs_qinv16(rs_qinv.size());
+  std::vector<u64> rs_mat(rs_qinv.size() * 5, 0);
+  rs_one[0] = ulonglong2{1, 0};  // floor(1 * 2^64 / q) is filled per use below; with x < q the product x*1 needs no reduction
+  if (nlimbs > 1) {
+    const u64 qL = c->mod[nlimbs - 1];
+    rs_one[0] = ulonglong2{1, h_shoup(1, qL)};
+    for (u32 i = 0; i + 1 < nlimbs; i++) {
+      u64 m = c->mod[i], ql = qL % m, inv = h_inv(ql, m);
+      rs_mat[(size_t)i * 5 + 0] = h_mont(1, m);
+      rs_mat[(size_t)i * 5 + 4] = h_mont(ql ? m - ql : 0, m);
+      rs_qinv[i] = ulonglong2{inv, h_shoup(inv, m)};
+      rs_qinv16[i] = is_fp(m) ? as_fp(inv, m) : rs_qinv[i];
+    }
+  }
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
   int rc;
+  if ((rc = upload(&t.rs_one, rs_one)) || (rc = upload(&t.rs_mat, rs_mat)) || (rc = upload(&t.rs_qinv, rs_qinv)) ||
+      (rc = upload(&t.rs_qinv16, rs_qinv16)))
+    return rc;
   if ((rc = upload(&t.up_scale, up_scale)) || (rc = upload(&t.dn_scale, dn_scale)) ||
       (rc = upload(&t.dn_mat_plain, dn_mat_plain)) || (rc = upload(&t.pinv2, pinv2)))
     return rc;
@@ -393,7 +415,6 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     return CKKS_OK;
   }
   if (src != dst) {
-    if (src_stride != dst_stride) return fail(CKKS_EINVAL, "internal: strided out-of-place transform");
     ProfScope ps(c, PK_COPY, st);
     // generic path is in place: copy the slots first (rows may be strided)
     HIP_TRY(hipMemcpy2DAsync(dst + (size_t)slot0 * c->N, dst_stride * 8, src + (size_t)slot0 * c->N, src_stride * 8,
@@ -483,7 +504,7 @@ void launch_modup(const ckks_ctx* c, const ModUpArgs& a, u32 beta, u32 B, hipStr
 template <bool PRESCALED>
 void launch_moddown(const ckks_ctx* c, const ModDownArgs& a, u32 B2, hipStream_t st) {
   dim3 block(BCONV_THREADS), g2(c->N / BCONV_THREADS / 2, B2), g1(c->N / BCONV_THREADS, B2);
-  const u32 K = c->np;
+  const u32 K = a.K;
   if (K <= 4) hipLaunchKernelGGL((moddown_kernel<4, PRESCALED, 2>), g2, block, 0, st, a);
   else if (K <= 8) hipLaunchKernelGGL((moddown_kernel<8, PRESCALED, 2>), g2, block, 0, st, a);
   else if (K <= 15) hipLaunchKernelGGL((moddown_kernel<15, PRESCALED, 2>), g2, block, 0, st, a);
@@ -619,7 +640,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     if ((rc = launch_ntt(c, true, acc, (u64)next * N, acc, (u64)next * N, B * 2, nlimbs, K, pmap, 0, 0, st, o3))) return rc;
   }
   {
-    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next};
+    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
     ProfScope ps(c, PK_MODDOWN, st);
     launch_moddown<true>(c, a, B * 2, st);
     HIP_TRY(hipGetLastError());
@@ -694,7 +715,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   }
   // 6. ModDown base conversion P -> Q_l
   {
-    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat, c->logN, nlimbs, c->nq, K, next};
+    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
     ProfScope ps(c, PK_MODDOWN, st);
     launch_moddown<false>(c, a, B * 2, st);
     HIP_TRY(hipGetLastError());
@@ -871,6 +892,10 @@ int ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(kv.second.dn_scale);
     (void)hipFree(kv.second.dn_mat_plain);
     (void)hipFree(kv.second.pinv2);
+    (void)hipFree(kv.second.rs_one);
+    (void)hipFree(kv.second.rs_mat);
+    (void)hipFree(kv.second.rs_qinv);
+    (void)hipFree(kv.second.rs_qinv16);
   }
   delete c;
   return CKKS_OK;
@@ -924,6 +949,9 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlim
     case CKKS_OP_KEYSWITCH: return ks;
     case CKKS_OP_HROT: return ks + poly;
     case CKKS_OP_HMULT_RELIN: return ks + poly;
+    case CKKS_OP_RESCALE:
+      // coefficient form of the dropped limb, its image on the remaining limbs
+      return nlimbs < 2 ? 0 : align256((size_t)B * 2 * c->N * 8) + align256((size_t)B * 2 * (nlimbs - 1) * c->N * 8);
     case CKKS_OP_PCMM_BSGS:
       if (n1 == 0) return 0;
       // baby steps 1..n1-1, PMACC_GT inner sums, rotated inner sum, HRot workspace
@@ -1137,6 +1165,94 @@ int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_
     }
   }
   return CKKS_OK;
+}
+
+int ckks_rescale(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, void* ws,
+                 size_t ws_bytes, void* stream) {
+  if (!c || !ct_out || !ct_in) return fail(CKKS_EINVAL, "null argument");
+  if (nlimbs < 2 || nlimbs > c->nq) return fail(CKKS_ESHAPE, "rescale needs 2..L+1 limbs");
+  if (B == 0 || B > 32767) return fail(CKKS_ESHAPE, "batch must be in [1, 32767]");
+  int rc = check_ws(c, CKKS_OP_RESCALE, B, nlimbs, 0, ws, ws_bytes);
+  if (rc) return rc;
+  const u32 N = c->N, nl1 = nlimbs - 1;
+  if (overlap(ct_out, (size_t)B * 2 * nl1 * N * 8, ct_in, (size_t)B * 2 * nlimbs * N * 8))
+    return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
+  const LevelTables* lt;
+  if ((rc = get_level(c, nlimbs, &lt))) return rc;
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  u64* last = (u64*)ws;
+  u64* tq = (u64*)((char*)ws + align256((size_t)B * 2 * N * 8));
+  // 1. coefficient form of the last limb of every polynomial (rows of ct_in are nlimbs*N apart)
+  LimbMap lmap = identity_map(0);
+  lmap.id[0] = (unsigned char)nl1;
+  if ((rc = launch_ntt(c, true, (const u64*)ct_in + (size_t)nl1 * N, (u64)nlimbs * N, last, (u64)N, B * 2, 0, 1, lmap, 0, 0, st)))
+    return rc;
+  // 2. its centred representative on the remaining limbs (a one-source base conversion)
+  {
+    ModDownArgs a{last, tq, c->d_mods, lt->rs_one, lt->rs_mat, c->logN, nl1, c->nq, 1, 1, 0, nl1};
+    ProfScope ps(c, PK_MODDOWN, st);
+    launch_moddown<true>(c, a, B * 2, st);
+    HIP_TRY(hipGetLastError());
+  }
+  // 3. back to the evaluation domain, subtract, divide by q_last
+  const LimbMap qmap = identity_map(nl1);
+  if (c->logN == 16) {
+    NttOpts o;
+    o.rows_only = true;
+    if ((rc = launch_ntt(c, false, tq, (u64)nl1 * N, tq, (u64)nl1 * N, B * 2, 0, nl1, qmap, 0, 0, st, o))) return rc;
+    FwdFinalArgs a;
+    a.tq = tq;
+    a.acc = (const u64*)ct_in;
+    a.out = (u64*)ct_out;
+    a.add_src = nullptr;
+    a.tw = c->d_tw_fwd;
+    a.twfp = c->d_twfp_fwd;
+    a.mods = c->d_mods;
+    a.pinv = lt->rs_qinv16;
+    a.nlimbs = nl1;
+    a.next = nlimbs;
+    a.mode0 = a.mode1 = 0;
+    a.galois = 0;
+    a.map_mode = c->tune[0];
+    auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
+    LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nl1, cls_of, st)
+    HIP_TRY(hipGetLastError());
+    return CKKS_OK;
+  }
+  if ((rc = launch_ntt(c, false, tq, (u64)nl1 * N, tq, (u64)nl1 * N, B * 2, 0, nl1, qmap, 0, 0, st))) return rc;
+  FinalArgs a{(const u64*)ct_in, tq, (u64*)ct_out, c->d_mods, lt->rs_qinv, c->logN, nl1, nlimbs, 0};
+  ProfScope ps(c, PK_FINAL, st);
+  hipLaunchKernelGGL(ks_final_kernel, dim3(N / 256, nl1, B * 2), dim3(256), 0, st, a);
+  HIP_TRY(hipGetLastError());
+  return CKKS_OK;
+}
+
+static int pointwise_entry(ckks_ctx* c, bool mul, uint64_t* out, const uint64_t* a, const uint64_t* b, uint32_t npoly,
+                           uint32_t nlimbs, bool broadcast, void* stream) {
+  if (!c || !out || !a || !b) return fail(CKKS_EINVAL, "null argument");
+  if (nlimbs == 0 || nlimbs > c->nq) return fail(CKKS_ESHAPE, "nlimbs must be in [1, L+1]");
+  if (npoly == 0) return CKKS_OK;
+  if (npoly > 65535) return fail(CKKS_ESHAPE, "too many polynomials in one call");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  PointwiseArgs pa{(u64*)out, (const u64*)a, (const u64*)b, c->d_mods, c->logN, nlimbs, broadcast ? 1u : 0u};
+  ProfScope ps(c, mul ? PK_TENSOR : PK_ADD, (hipStream_t)stream);
+  dim3 grid(c->N / 512, nlimbs, npoly), block(256);
+  if (mul) hipLaunchKernelGGL(pmult_kernel, grid, block, 0, (hipStream_t)stream, pa);
+  else hipLaunchKernelGGL(add_kernel, grid, block, 0, (hipStream_t)stream, pa);
+  HIP_TRY(hipGetLastError());
+  return CKKS_OK;
+}
+int ckks_pmult(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, const uint64_t* pt, uint32_t B, uint32_t nlimbs,
+               void* stream) {
+  if (B > 32767) return fail(CKKS_ESHAPE, "batch must be in [1, 32767]");
+  return pointwise_entry(c, true, ct_out, ct_in, pt, B * 2, nlimbs, true, stream);
+}
+int ckks_add(ckks_ctx* c, uint64_t* out, const uint64_t* a, const uint64_t* b, uint32_t npoly, uint32_t nlimbs,
+             void* stream) {
+  return pointwise_entry(c, false, out, a, b, npoly, nlimbs, false, stream);
 }
 
 }  // extern "C"

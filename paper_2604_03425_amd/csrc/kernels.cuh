@@ -270,13 +270,15 @@ struct ModDownArgs {
   const ulonglong2* inv;  // [K]
   const u64* mat;         // [nlimbs][MAXLEN+1], Montgomery form
   u32 logN, nlimbs, nq, K, next;
+  u32 src_slot;           // slot of the first source limb inside a row of `acc` (nlimbs for a key switch)
+  u32 src_id0;            // modulus id of the first source limb (nq for a key switch)
 };
 template <int MAXLEN, bool PRESCALED, int EPT>
 __global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
   const u32 N = 1u << a.logN;
   const u32 n = (blockIdx.x * BCONV_THREADS + threadIdx.x) * EPT;
   const u32 bc = blockIdx.y;
-  const u64* x = a.acc + ((size_t)bc * a.next + a.nlimbs) * N + n;
+  const u64* x = a.acc + ((size_t)bc * a.next + a.src_slot) * N + n;
   u32 y0[EPT][MAXLEN], y1[EPT][MAXLEN], nneg[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; e++) nneg[e] = 0;
@@ -285,7 +287,7 @@ __global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
 #pragma unroll
     for (int e = 0; e < EPT; e++) y0[e][k] = y1[e][k] = 0;
     if ((u32)k < a.K) {
-      const u64 m = a.mods[a.nq + k].m;
+      const u64 m = a.mods[a.src_id0 + k].m;
       u64 yv[EPT];
       if (EPT == 2) {
         const ulonglong2 v = *(const ulonglong2*)(x + (size_t)k * N);
@@ -462,4 +464,32 @@ __global__ void __launch_bounds__(256) addto_kernel(AddArgs a) {
   const u64 m = a.mods[i].m;
   size_t o = ((size_t)p * a.nlimbs + i) * N + n;
   a.out[o] = addmod(a.out[o], a.in[o], m);
+}
+
+// Pointwise helpers of the public calls: out = ct * pt (plaintext broadcast over the polynomials) and out = a + b.
+struct PointwiseArgs {
+  u64* out;
+  const u64 *a, *b;
+  const ModInfo* mods;
+  u32 logN, nlimbs, b_broadcast;  // b_broadcast: b is [nlimbs][N], shared by every polynomial
+};
+__global__ void __launch_bounds__(256) pmult_kernel(PointwiseArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = (blockIdx.x * 256 + threadIdx.x) * 2;
+  const u32 i = blockIdx.y, p = blockIdx.z;
+  const ModInfo mi = a.mods[i];
+  const size_t o = ((size_t)p * a.nlimbs + i) * N + n;
+  const ulonglong2 x = *(const ulonglong2*)(a.a + o);
+  const ulonglong2 y = *(const ulonglong2*)(a.b + (a.b_broadcast ? (size_t)i * N + n : o));
+  *(ulonglong2*)(a.out + o) = ulonglong2{mulmod(x.x, y.x, mi), mulmod(x.y, y.y, mi)};
+}
+__global__ void __launch_bounds__(256) add_kernel(PointwiseArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = (blockIdx.x * 256 + threadIdx.x) * 2;
+  const u32 i = blockIdx.y, p = blockIdx.z;
+  const u64 m = a.mods[i].m;
+  const size_t o = ((size_t)p * a.nlimbs + i) * N + n;
+  const ulonglong2 x = *(const ulonglong2*)(a.a + o);
+  const ulonglong2 y = *(const ulonglong2*)(a.b + o);
+  *(ulonglong2*)(a.out + o) = ulonglong2{addmod(x.x, y.x, m), addmod(x.y, y.y, m)};
 }

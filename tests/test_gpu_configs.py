@@ -138,3 +138,29 @@ def test_sweep_point_keyswitch(gpu, limbs, dnum):
     gpu.ckks_keyswitch(gc, out, to_dev(d), B, limbs, to_dev(evk), 0, dnum, gc.workspace(gpu.OP_KEYSWITCH, B, limbs))
     assert_same(to_host(out), want, "sweep point %d limbs dnum %d" % (limbs, dnum))
     gc.close()
+
+
+@pytest.mark.parametrize("shape,nlimbs,B", [((12, 4, 40, 1, 50, 2), 4, 3), ((12, 5, 50, 2, 60, 2), 3, 2),
+                                            ((16, 6, 50, 2, 60, 2), 6, 2), ((16, 3, 60, 1, 60, 1), 3, 1)])
+def test_rescale_pmult_add(gpu, shape, nlimbs, B):
+    """Rescale (incl. 60-bit main primes on the integer bodies), PMult and Add, bit-exact."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(*shape)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    ct = uniform_residues(71, p.q[:nlimbs], (B, 2), p.N)
+    pt = uniform_residues(72, p.q[:nlimbs], (), p.N)
+    ids = list(range(nlimbs))
+    d_ct = to_dev(ct)
+    prod = torch.empty_like(d_ct)
+    gpu.ckks_pmult(gc, prod, d_ct, to_dev(pt), B, nlimbs)
+    want_prod = rc.pmult(ct, pt)
+    assert_same(to_host(prod), want_prod, "pmult")
+    s = torch.empty_like(d_ct)
+    gpu.ckks_add(gc, s, prod, d_ct, B * 2, nlimbs)
+    want_sum = rc.pointwise(want_prod.reshape(B * 2, nlimbs, p.N), ct.reshape(B * 2, nlimbs, p.N), ids, "add").reshape(ct.shape)
+    assert_same(to_host(s), want_sum, "add")
+    out = torch.empty((B, 2, nlimbs - 1, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_rescale(gc, out, s, B, nlimbs, gc.workspace(gpu.OP_RESCALE, B, nlimbs))
+    assert_same(to_host(out), rc.rescale(want_sum), "rescale")
+    gc.close()

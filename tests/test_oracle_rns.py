@@ -106,3 +106,25 @@ def test_moddown_is_rounded_division_by_P(shape):
             assert diff == 0
         if K == 1:
             assert diff == 0
+
+
+def test_rescale_is_exact_rounded_division_by_last_prime():
+    """CRT(rescale(c)) = round(c / q_L) on the centred integers, every coefficient (coefficient domain via INTT)."""
+    p = make_params(4, 4, 50, 1, 60, 2)
+    c = ref.RefContext(p)
+    rng = np.random.default_rng(5)
+    nl = 4
+    ids = list(range(nl))
+    Q, qL = prod(p.q), p.q[-1]
+    vals = [[centre(int.from_bytes(rng.bytes(32), "little"), Q) for _ in range(p.N)] for _ in range(2)]
+    vals[0][0], vals[0][1], vals[0][2] = 0, qL // 2, -(qL // 2) - 1
+    coeff = np.stack([residues(v, p.q) for v in vals])[None]                 # [1][2][nl][N] coefficient domain
+    ct = c.ntt(coeff.reshape(2, nl, p.N), ids).reshape(1, 2, nl, p.N)
+    out = c.rescale(ct)
+    back = c.intt(out.reshape(2, nl - 1, p.N), ids[:-1])
+    Qp = Q // qL
+    for comp in range(2):
+        got = ref.crt_centred(back[comp], p.q[:-1])
+        for x, g in zip(vals[comp], got):
+            want = (x - centre(x, qL)) // qL
+            assert (g - want) % Qp == 0

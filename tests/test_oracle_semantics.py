@@ -212,3 +212,18 @@ def test_attention_unit_scores():
     z = keys.decrypt_slots(acc[0], 2.0**60).real
     want = np.sum(Q * Kmat, axis=1)
     assert np.max(np.abs(z[::hd] - want)) < 2.0**-14
+
+
+def test_pmult_then_rescale_keeps_the_scale():
+    """PMult by an encoded plaintext then Rescale: slots hold z*w at scale Delta^2 / q_L."""
+    p = make_params(10, 4, 40, 2, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 91)
+    z = uniform_slots(1, p.N // 2)
+    w = uniform_slots(2, p.N // 2)
+    ct = keys.encrypt_slots(z, 2.0**40, 4)[None]
+    pt = encode_plain_eval(c, w, 2.0**40, 4)
+    out = c.rescale(c.pmult(ct, pt))
+    assert out.shape == (1, 2, 3, p.N)
+    got = keys.decrypt_slots(out[0], 2.0**80 / p.q[3]).real
+    assert np.max(np.abs(got - z * w)) < 2.0**-20
