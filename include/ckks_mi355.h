@@ -156,6 +156,23 @@ int ckks_pcmm_bsgs(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint3
                    void* stream);
 
 /*
+ * Hoisted variants (paper Sec. 5.1 names hoisting as the alternative it switches off by default to save memory on
+ * 48 GB GPUs): ckks_hrot_hoisted rotates the SAME batch by R Galois elements, ct_out[r] = HRot_{galois_elts[r]}(ct_in)
+ * with key evks[r] (galois_elts, evks: host arrays of R entries; ct_out device [R][B][2][nlimbs][N]), sharing the
+ * inverse transform, ModUp and forward transform of c1 among the rotations. ckks_pcmm_bsgs_hoisted is
+ * ckks_pcmm_bsgs with its baby steps computed that way. Results are bit-identical to the one-at-a-time calls
+ * (the Galois map commutes exactly with the centred base conversion); workspace sizes are those of
+ * CKKS_OP_HROT and CKKS_OP_PCMM_BSGS.
+ */
+int ckks_hrot_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                      const uint32_t* galois_elts, const uint64_t* const* evks, uint32_t R, void* ws, size_t ws_bytes,
+                      void* stream);
+int ckks_pcmm_bsgs_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                           const uint64_t* pt_diag, uint32_t n1, uint32_t n2, uint32_t stride,
+                           const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/*
  * Rescale (paper Sec. 2.1: "divides by the last modulus q_L to reduce scale and remove one prime"): for
  * ct_in [B][2][nlimbs][N] (device, evaluation domain, nlimbs >= 2) writes ct_out [B][2][nlimbs-1][N] with
  * every coefficient c replaced by round(c / q_{nlimbs-1}) (centred representatives, exact). ct_out must not

@@ -16,7 +16,8 @@ OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS, OP_RESCALE = 1, 2, 3, 4, 5
 _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
-            "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add"]
+            "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
+            "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted"]
 
 
 class CkksError(RuntimeError):
@@ -54,6 +55,9 @@ def _load():
     lib.ckks_hmult_relin.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
+    lib.ckks_hrot_hoisted.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), C.c_uint32, vp,
+                                      C.c_size_t, vp]
+    lib.ckks_pcmm_bsgs_hoisted.argtypes = lib.ckks_pcmm_bsgs.argtypes
     lib.ckks_rescale.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, vp, C.c_size_t, vp]
     lib.ckks_pmult.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
     lib.ckks_add.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
@@ -183,12 +187,23 @@ def ckks_hmult_relin(ctx, ct_out, ct_a, ct_b, B, nlimbs, evk_mult, ws):
                                  _ptr(evk_mult, "evk_mult"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
 
 
-def ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws):
+def ckks_hrot_hoisted(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
+    R = len(galois_elts)
+    if len(evks) != R:
+        raise ValueError("need one key per Galois element")
+    gs, _ = _ids(galois_elts)
+    keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk").value for k in evks])
+    _check(_lib.ckks_hrot_hoisted(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys, R,
+                                  _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws, hoisted=False):
     baby = (C.c_void_p * max(1, n1 - 1))(*[_ptr(k, "evk_baby").value for k in evk_baby])
     giant = (C.c_void_p * max(1, n2 - 1))(*[_ptr(k, "evk_giant").value for k in evk_giant])
     if len(evk_baby) != n1 - 1 or len(evk_giant) != n2 - 1:
         raise ValueError("need n1-1 baby-step keys and n2-1 giant-step keys")
-    _check(_lib.ckks_pcmm_bsgs(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs,
+    fn = _lib.ckks_pcmm_bsgs_hoisted if hoisted else _lib.ckks_pcmm_bsgs
+    _check(fn(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs,
                                _ptr(pt_diag, "pt_diag"), n1, n2, stride, baby, giant, _ptr(ws, "ws"), ws.numel() * 8,
                                _stream()))
 
@@ -204,3 +219,7 @@ def ckks_pmult(ctx, ct_out, ct_in, pt, B, nlimbs):
 
 def ckks_add(ctx, out, a, b, npoly, nlimbs):
     _check(_lib.ckks_add(ctx.handle, _ptr(out, "out"), _ptr(a, "a"), _ptr(b, "b"), npoly, nlimbs, _stream()))
+
+
+def ckks_pcmm_bsgs_hoisted(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws):
+    ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws, hoisted=True)

@@ -103,7 +103,7 @@ enum ProfKind {
   // N = 2^16 kernels: three consecutive kinds each, one per modulus class (the kernel's template argument)
   PK_FWD_ROWS, PK_FWD_BLOCKS = PK_FWD_ROWS + 3, PK_INV_BLOCKS = PK_FWD_BLOCKS + 3, PK_INV_ROWS = PK_INV_BLOCKS + 3,
   PK_FWD_INNER = PK_INV_ROWS + 3, PK_FWD_FINAL = PK_FWD_INNER + 3,
-  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
+  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
   PK_COPY, PK_COUNT
 };
 static const char* const kProfNames[PK_COUNT] = {
@@ -114,7 +114,7 @@ static const char* const kProfNames[PK_COUNT] = {
     "ntt16_inv_rows_kernel<0>", "ntt16_inv_rows_kernel<1>", "ntt16_inv_rows_kernel<2>",
     "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
     "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
-    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
+    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
     "pmacc_kernel", "addto_kernel", "copy"};
 struct ProfRec {
   int kind;
@@ -522,6 +522,57 @@ struct KsIo {
   u32 add_galois;
 };
 
+// Second half of a key switch on the N = 2^16 path: from the accumulators (acc, all slots) to the assembled output.
+// wait_before_assembly: event the stream must wait for before the last kernel reads the main-prime accumulators.
+int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, char* ws, hipStream_t st,
+                hipEvent_t wait_before_assembly) {
+  int rc;
+  const u32 N = c->N, next = lt->next, K = c->np;
+  KsLayout L = ks_layout(c, B, nlimbs);
+  u64* acc = (u64*)(ws + L.acc);
+  u64* tq = (u64*)(ws + L.tq);
+  const LimbMap qmap = identity_map(nlimbs);
+  NttOpts o2;
+  o2.rows_only = true;
+  {
+    LimbMap pmap;
+    for (u32 k = 0; k < CKKS_MAX_SLOTS; k++) pmap.id[k] = (unsigned char)(k < K ? c->nq + k : 0);
+    NttOpts o3;
+    o3.scale = lt->dn_scale;
+    if ((rc = launch_ntt(c, true, acc, (u64)next * N, acc, (u64)next * N, B * 2, nlimbs, K, pmap, 0, 0, st, o3))) return rc;
+  }
+  {
+    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
+    ProfScope ps(c, PK_MODDOWN, st);
+    launch_moddown<true>(c, a, B * 2, st);
+    HIP_TRY(hipGetLastError());
+  }
+  if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st, o2))) return rc;
+  if (wait_before_assembly) HIP_TRY(hipStreamWaitEvent(st, wait_before_assembly, 0));
+  {
+    FwdFinalArgs a;
+    a.tq = tq;
+    a.acc = acc;
+    a.out = io.out;
+    a.add_src = io.add_src;
+    a.tw = c->d_tw_fwd;
+    a.twfp = c->d_twfp_fwd;
+    a.mods = c->d_mods;
+    a.pinv = lt->pinv2;
+    a.nlimbs = nlimbs;
+    a.next = next;
+    a.mode0 = io.mode[0];
+    a.mode1 = io.mode[1];
+    a.galois = io.add_galois;
+    a.map_mode = c->tune[0];
+    auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
+    LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
+    HIP_TRY(hipGetLastError());
+  }
+  return CKKS_OK;
+}
+
+
 // N = 2^16: transforms fused with their neighbours.
 //   INTT(d) with (Q_j/q_i)^-1/N folded in -> ModUp -> row pass -> [block pass + evk inner product] (x 2^-64)
 //   -> INTT of the special limbs with 2^64 (P/p_k)^-1/N folded in -> ModDown (x 2^-64) -> row pass
@@ -529,12 +580,11 @@ struct KsIo {
 int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, const u64* evk, char* ws,
                       hipStream_t st) {
   int rc;
-  const u32 N = c->N, next = lt->next, beta = lt->beta, K = c->np;
+  const u32 N = c->N, next = lt->next, beta = lt->beta;
   KsLayout L = ks_layout(c, B, nlimbs);
   u64* dcoef = (u64*)(ws + L.dcoef);
   u64* ext = (u64*)(ws + L.ext);
   u64* acc = (u64*)(ws + L.acc);
-  u64* tq = (u64*)(ws + L.tq);
   const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
   NttOpts o1;
   o1.galois = io.d_galois;
@@ -588,6 +638,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   ia.next = next;
   ia.map_mode = c->tune[0];
   ia.galois = io.d_galois;
+  ia.ext_galois = 0;
   if (unfused_fp && any_fp) {
     NttOpts o = o2;
     o.only_class = 0;
@@ -632,40 +683,71 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
     joined = true;
   }
+  return ks16_finish(c, lt, io, B, nlimbs, ws, st, joined ? nullptr : c->ev_join);
+}
+
+// Hoisted rotations, N = 2^16: out[r] = HRot_{g_r}(ct_in) for r < R. The Galois map commutes exactly with the
+// centred base conversion (it permutes coefficients up to sign, and the conversion is odd), so INTT, ModUp and the
+// forward transform of c1 are done once on the un-rotated polynomial; each rotation then reads the transformed
+// digits through its own index map in the streaming inner product and finishes as usual.
+int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in, u32 B, u32 nlimbs, const u32* galois,
+                   const u64* const* evks, u32 R, char* ws, hipStream_t st) {
+  const LevelTables* lt;
+  int rc = get_level(c, nlimbs, &lt);
+  if (rc) return rc;
+  const u32 N = c->N, next = lt->next, beta = lt->beta;
+  const u64 polyN = (u64)nlimbs * N;
+  KsLayout L = ks_layout(c, B, nlimbs);
+  u64* dcoef = (u64*)(ws + L.dcoef);
+  u64* ext = (u64*)(ws + L.ext);
+  u64* acc = (u64*)(ws + L.acc);
+  const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
+  const u64* c1 = ct_in + polyN;
+  NttOpts o1;
+  o1.scale = lt->up_scale;
+  if ((rc = launch_ntt(c, true, c1, 2 * polyN, dcoef, polyN, B, 0, nlimbs, qmap, 0, 0, st, o1))) return rc;
   {
-    LimbMap pmap;
-    for (u32 k = 0; k < CKKS_MAX_SLOTS; k++) pmap.id[k] = (unsigned char)(k < K ? c->nq + k : 0);
-    NttOpts o3;
-    o3.scale = lt->dn_scale;
-    if ((rc = launch_ntt(c, true, acc, (u64)next * N, acc, (u64)next * N, B * 2, nlimbs, K, pmap, 0, 0, st, o3))) return rc;
-  }
-  {
-    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
-    ProfScope ps(c, PK_MODDOWN, st);
-    launch_moddown<true>(c, a, B * 2, st);
+    ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
+    ProfScope ps(c, PK_MODUP, st);
+    launch_modup<true>(c, a, beta, B, st);
     HIP_TRY(hipGetLastError());
   }
-  if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st, o2))) return rc;
-  if (!joined) HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
-  {
-    FwdFinalArgs a;
-    a.tq = tq;
-    a.acc = acc;
-    a.out = io.out;
-    a.add_src = io.add_src;
-    a.tw = c->d_tw_fwd;
-    a.twfp = c->d_twfp_fwd;
-    a.mods = c->d_mods;
-    a.pinv = lt->pinv2;
-    a.nlimbs = nlimbs;
-    a.next = next;
-    a.mode0 = io.mode[0];
-    a.mode1 = io.mode[1];
-    a.galois = io.add_galois;
-    a.map_mode = c->tune[0];
-    auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
-    LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
+  NttOpts of;
+  of.raw_out = true;  // reduced doubles on double-precision moduli, canonical residues elsewhere
+  if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, of)))
+    return rc;
+  FwdInnerArgs ia;
+  ia.ext = ext;
+  ia.d = c1;
+  ia.d_poly_stride = 2 * polyN;
+  ia.acc = acc;
+  ia.tw = c->d_tw_fwd;
+  ia.twfp = c->d_twfp_fwd;
+  ia.mods = c->d_mods;
+  ia.nlimbs = nlimbs;
+  ia.nq = c->nq;
+  ia.nm = c->nm;
+  ia.alpha = c->alpha;
+  ia.beta = beta;
+  ia.next = next;
+  ia.map_mode = c->tune[0];
+  for (u32 r = 0; r < R; r++) {
+    ia.evk = evks[r];
+    ia.galois = galois[r];
+    ia.ext_galois = galois[r];
+    for (int fp = 1; fp >= 0; fp--) {
+      FwdInnerArgs a = ia;
+      u32 cnt = 0;
+      for (u32 s_ = 0; s_ < next; s_++)
+        if ((host_class(c, c->mod[emap.id[s_]]) == 0) == (fp == 1)) a.slots[cnt++] = (unsigned char)s_;
+      if (!cnt) continue;
+      ProfScope ps(c, fp ? PK_INNER16 : PK_INNER16_INT, st);
+      if (fp) hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
+      else hipLaunchKernelGGL(inner16_int_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
+    }
     HIP_TRY(hipGetLastError());
+    KsIo io{c1, 2 * polyN, galois[r], out_base + (size_t)r * out_stride, {2, 0}, ct_in, galois[r]};
+    if ((rc = ks16_finish(c, lt, io, B, nlimbs, ws, st, nullptr))) return rc;
   }
   return CKKS_OK;
 }
@@ -1084,9 +1166,47 @@ int ckks_hmult_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_a, const 
   return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
 }
 
+static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                     const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
+                     const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream, bool hoisted);
 int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                    const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
                    const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream) {
+  return pcmm_impl(c, ct_out, ct_in, B, nlimbs, pt, n1, n2, stride, evk_baby, evk_giant, ws, ws_bytes, stream, false);
+}
+int ckks_pcmm_bsgs_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                           const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride,
+                           const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws, size_t ws_bytes,
+                           void* stream) {
+  return pcmm_impl(c, ct_out, ct_in, B, nlimbs, pt, n1, n2, stride, evk_baby, evk_giant, ws, ws_bytes, stream, true);
+}
+int ckks_hrot_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                      const uint32_t* galois_elts, const uint64_t* const* evks, uint32_t R, void* ws, size_t ws_bytes,
+                      void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!ct_out || !ct_in || !galois_elts || !evks) return fail(CKKS_EINVAL, "null argument");
+  if (R == 0) return CKKS_OK;
+  for (u32 r = 0; r < R; r++) {
+    if (!evks[r]) return fail(CKKS_EINVAL, "null key");
+    if (!(galois_elts[r] & 1) || galois_elts[r] >= 2 * c->N) return fail(CKKS_EINVAL, "galois_elt must be odd and < 2N");
+  }
+  if ((rc = check_ws(c, CKKS_OP_HROT, B, nlimbs, 0, ws, ws_bytes))) return rc;
+  const size_t ct_elems = (size_t)B * 2 * nlimbs * c->N;
+  if (overlap(ct_out, (size_t)R * ct_elems * 8, ct_in, ct_elems * 8)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  if (c->logN == 16)
+    return hrot_hoisted16(c, (u64*)ct_out, ct_elems, (const u64*)ct_in, B, nlimbs, galois_elts, (const u64* const*)evks, R,
+                          (char*)ws, (hipStream_t)stream);
+  for (u32 r = 0; r < R; r++)  // other ring degrees: the same result, one rotation at a time
+    if ((rc = ckks_hrot(c, ct_out + (size_t)r * ct_elems, ct_in, B, nlimbs, galois_elts[r], evks[r], ws, ws_bytes, stream)))
+      return rc;
+  return CKKS_OK;
+}
+static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                     const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
+                     const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream, bool hoisted) {
   int rc = check_common(c, B, nlimbs);
   if (rc) return rc;
   if (!ct_out || !ct_in || !pt) return fail(CKKS_EINVAL, "null argument");
@@ -1120,10 +1240,17 @@ int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_
     return (u32)g;
   };
   const size_t ct_elems = ct_al / 8;  // == B*2*nlimbs*N: a limb-vector is a multiple of 256 bytes
-  for (u32 b = 1; b < n1; b++) {
-    rc = ckks_hrot(c, (uint64_t*)(baby + (size_t)(b - 1) * ct_elems), ct_in, B, nlimbs, galois((u64)b * stride), evk_baby[b - 1], hws,
-                   hws_bytes, stream);
-    if (rc) return rc;
+  if (hoisted && n1 > 1) {
+    std::vector<u32> gs(n1 - 1);
+    for (u32 b = 1; b < n1; b++) gs[b - 1] = galois((u64)b * stride);
+    if ((rc = ckks_hrot_hoisted(c, (uint64_t*)baby, ct_in, B, nlimbs, gs.data(), evk_baby, n1 - 1, hws, hws_bytes, stream)))
+      return rc;
+  } else {
+    for (u32 b = 1; b < n1; b++) {
+      rc = ckks_hrot(c, (uint64_t*)(baby + (size_t)(b - 1) * ct_elems), ct_in, B, nlimbs, galois((u64)b * stride),
+                     evk_baby[b - 1], hws, hws_bytes, stream);
+      if (rc) return rc;
+    }
   }
   for (u32 g0 = 0; g0 < n2; g0 += PMACC_GT) {
     const u32 ng = std::min<u32>(PMACC_GT, n2 - g0);

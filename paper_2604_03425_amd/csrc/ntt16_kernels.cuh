@@ -146,6 +146,8 @@ struct FwdInnerArgs {
   const double* twfp; 
   const ModInfo* mods;
   u32 nlimbs, nq, nm, alpha, beta, next, map_mode, galois;
+  u32 ext_galois;            // streaming kernels only: != 0 reads ext through the Galois map too (hoisted digits:
+                             // ext holds the transform of the un-rotated polynomial, shared by many rotations)
   unsigned char slots[128];  // grid.z index -> extended slot (one modulus class per launch)
 };
 
@@ -388,9 +390,15 @@ __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
         x[1] = u2d(v.y);
       }
     } else {
-      const double2 v = *(const double2*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N + n);
-      x[0] = v.x;
-      x[1] = v.y;
+      const u64* e = a.ext + (((size_t)b * a.beta + j) * a.next + t) * N;
+      if (a.ext_galois) {
+        x[0] = __longlong_as_double((long long)e[galois_src_index16(n, a.ext_galois)]);
+        x[1] = __longlong_as_double((long long)e[galois_src_index16(n + 1, a.ext_galois)]);
+      } else {
+        const double2 v = *(const double2*)(e + n);
+        x[0] = v.x;
+        x[1] = v.y;
+      }
     }
     const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
     const ulonglong2 eb = *(const ulonglong2*)kb;
@@ -411,4 +419,50 @@ __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
   *(ulonglong2*)o0 = ulonglong2{d2u_canon(fp_reduce(s0[0], qinv, q), q), d2u_canon(fp_reduce(s0[1], qinv, q), q)};
   *(ulonglong2*)(o0 + (size_t)a.next * N) =
       ulonglong2{d2u_canon(fp_reduce(s1[0], qinv, q), q), d2u_canon(fp_reduce(s1[1], qinv, q), q)};
+}
+
+// Same for integer-class moduli (hoisted rotations only): ext holds canonical residues in the evaluation domain;
+// products go through a Montgomery reduction, so acc carries the factor 2^-64 like the fused kernel's.
+__global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
+  const size_t N = 65536;
+  u32 b, blk, zi;
+  ntt16_map(a.map_mode, b, blk, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const u64 q = mi.m, q2 = 2 * mi.m;
+  const u32 n = (blk * 256 + threadIdx.x) * 2;
+  u64 s0[2] = {0, 0}, s1[2] = {0, 0};
+  for (u32 j = 0; j < a.beta; j++) {
+    const bool own = fwd_inner_owns(a, t, j);
+    const u64* src = own ? a.d + (size_t)b * a.d_poly_stride + (size_t)t * N
+                         : a.ext + (((size_t)b * a.beta + j) * a.next + t) * N;
+    const u32 g = own ? a.galois : a.ext_galois;
+    u64 x[2];
+    if (g) {
+      x[0] = src[galois_src_index16(n, g)];
+      x[1] = src[galois_src_index16(n + 1, g)];
+    } else {
+      const ulonglong2 v = *(const ulonglong2*)(src + n);
+      x[0] = v.x;
+      x[1] = v.y;
+    }
+    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
+    const ulonglong2 eb = *(const ulonglong2*)kb;
+    const ulonglong2 ea = *(const ulonglong2*)(kb + (size_t)a.nm * N);
+    const u64 e0[2] = {eb.x, eb.y}, e1[2] = {ea.x, ea.y};
+#pragma unroll
+    for (int e = 0; e < 2; e++) {
+      Acc128 p0, p1;
+      p0.lo = x[e] * e0[e];
+      p0.hi = mul_hi64(x[e], e0[e]);
+      p1.lo = x[e] * e1[e];
+      p1.hi = mul_hi64(x[e], e1[e]);
+      s0[e] = csub(s0[e] + redc(p0, q, mi.minv), q2);
+      s1[e] = csub(s1[e] + redc(p1, q, mi.minv), q2);
+    }
+  }
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
+  *(ulonglong2*)o0 = ulonglong2{csub(s0[0], q), csub(s0[1], q)};
+  *(ulonglong2*)(o0 + (size_t)a.next * N) = ulonglong2{csub(s1[0], q), csub(s1[1], q)};
 }

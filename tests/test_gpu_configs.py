@@ -164,3 +164,44 @@ def test_rescale_pmult_add(gpu, shape, nlimbs, B):
     gpu.ckks_rescale(gc, out, s, B, nlimbs, gc.workspace(gpu.OP_RESCALE, B, nlimbs))
     assert_same(to_host(out), rc.rescale(want_sum), "rescale")
     gc.close()
+
+
+def test_hoisted_rotations_are_bit_identical(gpu):
+    """N=2^16, 24 limbs, dnum=3: three rotations of one batch with shared decomposition equal three HRots."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = config_params("keyswitch_micro")
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    B, nl = 2, 24
+    ct = uniform_residues(301, p.q, (B, 2), p.N)
+    gs = [galois_element(k, p.logN) for k in (1, 7, 31000)]
+    evks = [uniform_residues(310 + i, p.moduli, (p.dnum, 2), p.N) for i in range(3)]
+    out = torch.empty((3, B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_hrot_hoisted(gc, out, to_dev(ct), B, nl, gs, [to_dev(k) for k in evks], gc.workspace(gpu.OP_HROT, B, nl))
+    got = to_host(out)
+    ref.set_threads(2)
+    for r in range(3):
+        assert_same(got[r], rc.hrot(ct, gs[r], evks[r]), "hoisted rotation %d" % r)
+    ref.set_threads(1)
+    gc.close()
+
+
+def test_pcmm_hoisted_matches_oracle(gpu):
+    """Hoisted baby steps: N=2^16 (shared decomposition) and N=2^12 (falls back to single rotations)."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    for shape, B, nl, n1, n2 in (((16, 6, 50, 2, 60, 3), 2, 6, 4, 2), ((12, 4, 40, 2, 50, 2), 2, 4, 3, 3)):
+        p = make_params(*shape)
+        rc, gc = ref.RefContext(p), gpu.Context(p)
+        ct = uniform_residues(401, p.q, (B, 2), p.N)
+        pt = uniform_residues(402, p.q, (n2, n1), p.N)
+        baby = [uniform_residues(410 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n1 - 1)]
+        giant = [uniform_residues(420 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n2 - 1)]
+        ref.set_threads(2)
+        want = rc.pcmm_bsgs(ct, pt, n1, n2, 2, baby, giant)
+        ref.set_threads(1)
+        out = torch.empty((B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+        gpu.ckks_pcmm_bsgs_hoisted(gc, out, to_dev(ct), B, nl, to_dev(pt), n1, n2, 2, [to_dev(k) for k in baby],
+                                   [to_dev(k) for k in giant], gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
+        assert_same(to_host(out), want, "hoisted pcmm logN=%d" % shape[0])
+        gc.close()
