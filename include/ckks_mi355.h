@@ -30,10 +30,10 @@
  * library owns only the context and its constant tables.
  *
  * Streams: every call enqueues its kernels on `stream` (a hipStream_t passed as void*;
- * NULL = the default stream) and returns without synchronising. A key switch may run part of
- * its kernels on a second stream owned by the context, forked from and joined back into
- * `stream` with events, so everything is ordered as if it ran on `stream` alone; calls on one
- * context must therefore not be issued from several host threads at once. Workspace passed to a
+ * NULL = the default stream) and returns without synchronising. With tuning knob 4 set to 0 a
+ * key switch runs part of its kernels on a second stream owned by the context, forked from and
+ * joined back into `stream` with events, so everything is ordered as if it ran on `stream`
+ * alone. Calls on one context must not be issued from several host threads at once. Workspace passed to a
  * call must stay untouched until that stream has drained the call.
  *
  * Errors: calls return CKKS_OK or a negative code; they never throw or abort. After a
@@ -203,8 +203,9 @@ int ckks_prof_enable(ckks_ctx* ctx, int on);
 /* Tuning knobs for experiments: knob 0 = workgroup-to-tile mapping of the N = 2^16 transforms (0..4);
  * knob 1 != 0 turns the double-precision bodies for primes < 2^50 off (integer bodies everywhere);
  * knob 2 != 0 selects the 3-waves-per-SIMD build of the fused inner-product kernel; knob 3 == 0 uses the fused
- * inner product on double-precision moduli too; knob 4 != 0 keeps a key switch on the caller's stream only
- * (by default its two independent kernel chains fork onto a second internal stream and join before the end). */
+ * inner product on double-precision moduli too; knob 4 == 0 lets a key switch fork its two independent kernel
+ * chains (double-precision slots / special-prime slots) onto a second internal stream and join them before the
+ * result is assembled (default 1: everything on the caller's stream). */
 int ckks_tune_set(ckks_ctx* ctx, int knob, int value);
 int ckks_prof_num_kinds(void);
 const char* ckks_prof_kind_name(int kind);

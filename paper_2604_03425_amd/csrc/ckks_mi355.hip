@@ -122,7 +122,8 @@ struct ProfRec {
 };
 
 struct ckks_ctx {
-  int tune[8] = {4, 0, 0, 1, 0, 0, 0, 0};  // 0: workgroup mapping of the 2^16 transforms; 3: unfused FP inner product
+  int tune[8] = {4, 0, 0, 1, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 transforms; 3: unfused FP inner product;
+                                         // 4: 1 = one stream only (0 forks the two chains of a key switch)
   bool prof_on = false;
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
