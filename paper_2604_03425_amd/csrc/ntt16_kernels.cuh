@@ -333,18 +333,29 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
   const size_t N = 65536;
   const double q = mi.qd, qinv = mi.qinv;
   double x[16];
-  ntt16_fwd_blocks_fp(x, (const double*)(a.tq + ((size_t)bc * a.nlimbs + i_limb) * N), a.twfp + (size_t)i_limb * N, q, qinv,
-                      tile, sm);
-  const double2 pv = ((const double2*)a.pinv)[i_limb];
   const u64* ac = a.acc + ((size_t)bc * a.next + i_limb) * N + (size_t)h * 256 + j0;
+  u64 av[16];  // requested before the transform so that all of the workgroup's reads are in flight together
+#pragma unroll
+  for (int i = 0; i < 16; i++) av[i] = ac[i * 16];
   u64* o = a.out + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
   const u32 mode = (bc & 1) ? a.mode1 : a.mode0;
   const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
+  u64 ad[16];
+  if (mode == 1) {
+#pragma unroll
+    for (int i = 0; i < 16; i++) ad[i] = o[i * 16];
+  } else if (mode == 2) {
+#pragma unroll
+    for (int i = 0; i < 16; i++) ad[i] = as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)];
+  }
+  ntt16_fwd_blocks_fp(x, (const double*)(a.tq + ((size_t)bc * a.nlimbs + i_limb) * N), a.twfp + (size_t)i_limb * N, q, qinv,
+                      tile, sm);
+  const double2 pv = ((const double2*)a.pinv)[i_limb];
 #pragma unroll
   for (int i = 0; i < 16; i++) {
-    double r = fp_mulmod_const(u2d(ac[i * 16]) - x[i], pv.x, pv.y, q);  // |r| <= 0.9 q
-    if (mode & 1) r += u2d(o[i * 16]);
-    if (mode & 2) r += u2d(as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)]);
+    double r = fp_mulmod_const(u2d(av[i]) - x[i], pv.x, pv.y, q);  // |r| <= 0.9 q
+    if (mode == 1 || mode == 2) r += u2d(ad[i]);
+    if (mode == 3) r += u2d(o[i * 16]) + u2d(as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)]);
     if (mode == 3) r = r >= q ? r - q : r;  // two addends: bring the sum back below 2q first
     o[i * 16] = d2u_canon(r, q);
   }

@@ -1,0 +1,103 @@
+"""Call sequences of the attention workloads, written once against a small adapter so that the oracle and the
+C-ABI library are driven by the same sequence of calls (the adapter holds no arithmetic, only marshalling).
+
+Packing (token-major, `hd` slots per token, T = S/hd tokens per ciphertext): slot hd*t + j holds component j of
+token t. The r-th unit of a (query block, key block) pair works on the key/value ciphertext rotated left by r
+tokens, so it produces the r-th cyclic diagonal of the score block (Sec. 4.3: rotate-multiply-accumulate over
+local score slices; the aggregation with V is local).
+"""
+import numpy as np
+
+from ckks_inputs import galois_element
+
+
+class RefOps:
+    """Adapter over oracle.ref.RefContext (numpy arrays)."""
+
+    def __init__(self, ctx):
+        self.c = ctx
+
+    def hmult(self, a, b, relin):
+        return self.c.hmult_relin(a, b, relin)
+
+    def hrot(self, a, g, key):
+        return self.c.hrot(a, g, key)
+
+    def add(self, a, b):
+        return self.c.pointwise(a, b, list(range(a.shape[2])), "add")
+
+    def rescale(self, a):
+        return self.c.rescale(a)
+
+    def pmult(self, a, pt):
+        return self.c.pmult(a, pt)
+
+    def drop_to(self, a, nl):
+        return np.ascontiguousarray(a[:, :, :nl])
+
+
+class GpuOps:
+    """Adapter over the C-ABI binding (torch int64 device tensors)."""
+
+    def __init__(self, mod, ctx, batch, max_limbs):
+        self.m, self.c = mod, ctx
+        self.ws = ctx.workspace(mod.OP_HROT, batch, max_limbs)
+
+    def _new(self, like, nl=None):
+        import torch
+        B, two, n, N = like.shape
+        return torch.empty((B, two, nl or n, N), dtype=like.dtype, device=like.device)
+
+    def hmult(self, a, b, relin):
+        out = self._new(a)
+        self.m.ckks_hmult_relin(self.c, out, a, b, a.shape[0], a.shape[2], relin, self.ws)
+        return out
+
+    def hrot(self, a, g, key):
+        out = self._new(a)
+        self.m.ckks_hrot(self.c, out, a, a.shape[0], a.shape[2], g, key, self.ws)
+        return out
+
+    def add(self, a, b):
+        out = self._new(a)
+        self.m.ckks_add(self.c, out, a, b, a.shape[0] * 2, a.shape[2])
+        return out
+
+    def rescale(self, a):
+        out = self._new(a, a.shape[2] - 1)
+        self.m.ckks_rescale(self.c, out, a, a.shape[0], a.shape[2], self.ws)
+        return out
+
+    def pmult(self, a, pt):
+        out = self._new(a)
+        self.m.ckks_pmult(self.c, out, a, pt, a.shape[0], a.shape[2])
+        return out
+
+    def drop_to(self, a, nl):
+        return a[:, :, :nl].contiguous()
+
+
+def score_diagonal(ops, logN, q_ct, k_rot, relin, sum_keys, hd):
+    """QK^T unit: HMult+relin, then rotate-and-sum over the hd slots of a token. Slot hd*t of the result holds
+    <q_t, k_{t+r}> (scale Delta^2); the other slots hold partial sums."""
+    d = ops.hmult(q_ct, k_rot, relin)
+    for i in range(hd.bit_length() - 1):
+        d = ops.add(d, ops.hrot(d, galois_element(1 << i, logN), sum_keys[i]))
+    return d
+
+
+def mask_and_pack(ops, logN, d, mask_pt, rep_keys, hd):
+    """Keeps slot hd*t of every token (PMult by a 0/1 mask, then Rescale) and replicates it over the token's hd
+    slots by rotations to the right by 1, 2, 4, ...; mask_pt is at one limb fewer than d."""
+    m = ops.rescale(ops.pmult(ops.rescale(d), mask_pt))
+    for i in range(hd.bit_length() - 1):
+        m = ops.add(m, ops.hrot(m, galois_element(-(1 << i), logN), rep_keys[i]))
+    return m
+
+
+def av_unit(ops, logN, q_ct, k_rot, v_rot, relin, sum_keys, mask_pt, rep_keys, hd):
+    """One unit of A x V on raw scores: diagonal r of the score block, packed, times V rotated by the same r
+    tokens. Summing the units over r (and over key blocks) gives rows of (Q K^T) V. v_rot is at two limbs fewer
+    than q_ct."""
+    a = mask_and_pack(ops, logN, score_diagonal(ops, logN, q_ct, k_rot, relin, sum_keys, hd), mask_pt, rep_keys, hd)
+    return ops.hmult(a, v_rot, relin)
