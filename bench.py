@@ -126,7 +126,7 @@ def other_workloads(args):
         # 2048 tokens x 768 hidden in 128 ciphertexts (16 tokens each), 768x768 weight slice as 32 x 24 diagonals,
         # processed in calls of `--pcmm-batch` ciphertexts; 31 baby + 23 giant rotation keys shared by all
         p = config_params("keyswitch_micro")
-        N, nl, n1, n2, total = p.N, len(p.q), 32, 24, 128
+        N, nl, n1, n2, total = p.N, len(p.q), args.pcmm_n1, args.pcmm_n2, 128
         Bc = args.pcmm_batch
         ctx = ck.Context(p, 0)
         ct = _uniform(torch, gen, dev, (Bc, 2), p.q, N)
@@ -148,7 +148,9 @@ def other_workloads(args):
                           "hoisted_seconds_per_call": round(dth, 4),
                           "hoisted_seconds_for_128_ciphertexts": round(dth * total / Bc, 3),
                           "pmult_acc_per_s": round(Bc * n1 * n2 / dt, 1), "kernel_ms_per_call": prof,
-                          "note": "2048 tokens x 768 -> 768 slice; 54 HRot + 768 PMult-acc per ciphertext, no hoisting"}))
+                          "note": "%d x %d diagonals: %d HRot + %d PMult-acc per ciphertext (32 x 24 = 2048 tokens x 768 -> "
+                                  "768 slice of the FFN; the QKV / W_o projections are the same call with their own "
+                                  "diagonals)" % (n1, n2, n1 + n2 - 2, n1 * n2)}))
     elif args.workload == "attention":
         # one (a,b) block pair per head, 3 heads: unit = HMult+relin + 6 rotate-and-sum HRots; 20 limbs, dnum 4, K 5
         p = config_params("attention_qk")
@@ -175,6 +177,39 @@ def other_workloads(args):
                           "key_switches_per_s": round(7 * B / dt, 1),
                           "note": "unit = HMult+relin + 6 rotate-and-sum HRot at 20 limbs, dnum=4, K=5; "
                                   "1536 units per (head, block pair) x 3 heads scale linearly"}))
+    elif args.workload == "attention_av":
+        # second attention workload: score diagonal (as above), mask-and-pack (Rescale, PMult by the slot mask,
+        # Rescale, 6 replicating right rotations) and the product with V two limbs lower; 14 key switches per unit
+        p = config_params("attention_qk")
+        N, nl, B = p.N, len(p.q), args.att_batch
+        ctx = ck.Context(p, 0)
+        qa = _uniform(torch, gen, dev, (B, 2), p.q, N)
+        kb = _uniform(torch, gen, dev, (B, 2), p.q, N)
+        vb = _uniform(torch, gen, dev, (B, 2), p.q[:nl - 2], N)
+        mask = _uniform(torch, gen, dev, (), p.q[:nl - 1], N)
+        relin = _uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N)
+        rot = [_uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N) for _ in range(12)]
+        ws = ctx.workspace(ck.OP_HROT, B, nl)
+        new = lambda n: torch.empty((B, 2, n, N), dtype=torch.int64, device=dev)
+        d, tmp, d1, m1, m, tmp2, out = new(nl), new(nl), new(nl - 1), new(nl - 1), new(nl - 2), new(nl - 2), new(nl - 2)
+
+        def units():
+            ck.ckks_hmult_relin(ctx, d, qa, kb, B, nl, relin, ws)
+            for i in range(6):
+                ck.ckks_hrot(ctx, tmp, d, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
+                ck.ckks_add(ctx, d, d, tmp, B * 2, nl)
+            ck.ckks_rescale(ctx, d1, d, B, nl, ws)
+            ck.ckks_pmult(ctx, m1, d1, mask, B, nl - 1)
+            ck.ckks_rescale(ctx, m, m1, B, nl - 1, ws)
+            for i in range(6):
+                ck.ckks_hrot(ctx, tmp2, m, B, nl - 2, galois_element(-(1 << i), p.logN), rot[6 + i], ws)
+                ck.ckks_add(ctx, m, m, tmp2, B * 2, nl - 2)
+            ck.ckks_hmult_relin(ctx, out, m, vb, B, nl - 2, relin, ws)
+        dt = _time(torch, units, 2)
+        print(json.dumps({"workload": "attention_av_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
+                          "key_switches_per_s": round(14 * B / dt, 1),
+                          "note": "unit = score diagonal (HMult+relin + 6 HRot) + mask-and-pack (2 Rescale, PMult, "
+                                  "6 HRot) + HMult+relin with V, 20 -> 18 limbs, dnum=4, K=5"}))
     elif args.workload == "sweep":
         B = 32
         for limbs in (4, 8, 12, 16, 20, 24, 28, 32, 36):
@@ -217,8 +252,10 @@ def main():
     ap.add_argument("--tune", type=str, default="", help="experiment: comma-separated knob=value pairs")
     ap.add_argument("--streams", type=int, default=1, help="HIP streams the independent calls of a step are spread over")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate NTT / HRot / HMult timings (profiling runs)")
-    ap.add_argument("--workload", default="keyswitch_micro", choices=["keyswitch_micro", "pcmm", "attention", "sweep"])
+    ap.add_argument("--workload", default="keyswitch_micro", choices=["keyswitch_micro", "pcmm", "attention", "attention_av", "sweep"])
     ap.add_argument("--pcmm-batch", type=int, default=16)
+    ap.add_argument("--pcmm-n1", type=int, default=32, help="baby steps (32 x 24 = the FFN share; 8 x 8 = a 64-slot block)")
+    ap.add_argument("--pcmm-n2", type=int, default=24, help="giant steps")
     ap.add_argument("--att-batch", type=int, default=32)
     ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
     args = ap.parse_args()

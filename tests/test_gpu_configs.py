@@ -205,3 +205,32 @@ def test_pcmm_hoisted_matches_oracle(gpu):
                                    [to_dev(k) for k in giant], gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
         assert_same(to_host(out), want, "hoisted pcmm logN=%d" % shape[0])
         gc.close()
+
+
+def _av_inputs(p, B, nl, hd, seed):
+    """Uniform-residue stand-ins for Q, K (nl limbs), V (nl - 2 limbs), the mask plaintext (nl - 1 limbs) and keys."""
+    q_ct = uniform_residues(seed, p.q[:nl], (B, 2), p.N)
+    k_ct = uniform_residues(seed + 1, p.q[:nl], (B, 2), p.N)
+    v_ct = uniform_residues(seed + 2, p.q[:nl - 2], (B, 2), p.N)
+    mask = uniform_residues(seed + 3, p.q[:nl - 1], (), p.N)
+    nk = hd.bit_length() - 1
+    key = lambda i: uniform_residues(seed + 10 + i, p.moduli, (p.dnum, 2), p.N)
+    return q_ct, k_ct, v_ct, mask, key(0), [key(1 + i) for i in range(nk)], [key(20 + i) for i in range(nk)]
+
+
+@pytest.mark.parametrize("name,nl,B,hd", [("tiny_hrot_k2", 4, 3, 8), ((16, 8, 50, 2, 60, 4), 8, 2, 8)])
+def test_attention_av_unit(gpu, name, nl, B, hd):
+    """Second attention workload: score diagonal, mask-and-pack (PMult, two Rescales, replication by right
+    rotations) and the product with V, as one sequence of C-ABI calls against the same sequence on the oracle."""
+    from flows import GpuOps, RefOps, av_unit
+    from gpu_util import to_dev, to_host, assert_same
+    p = config_params(name) if isinstance(name, str) else make_params(*name)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    q_ct, k_ct, v_ct, mask, relin, sum_keys, rep_keys = _av_inputs(p, B, nl, hd, 300)
+    ref.set_threads(4)
+    want = av_unit(RefOps(rc), p.logN, q_ct, k_ct, v_ct, relin, sum_keys, mask, rep_keys, hd)
+    ref.set_threads(1)
+    got = av_unit(GpuOps(gpu, gc, B, nl), p.logN, to_dev(q_ct), to_dev(k_ct), to_dev(v_ct), to_dev(relin),
+                  [to_dev(k) for k in sum_keys], to_dev(mask), [to_dev(k) for k in rep_keys], hd)
+    assert got.shape == (B, 2, nl - 2, p.N)
+    assert_same(to_host(got), want, "attention A x V unit")

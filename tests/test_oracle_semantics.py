@@ -227,3 +227,44 @@ def test_pmult_then_rescale_keeps_the_scale():
     assert out.shape == (1, 2, 3, p.N)
     got = keys.decrypt_slots(out[0], 2.0**80 / p.q[3]).real
     assert np.max(np.abs(got - z * w)) < 2.0**-20
+
+
+def test_attention_av_block():
+    """Scores, mask-and-pack and A x V on one (query block, key block) pair (Sec. 4.3: after the scores the
+    aggregation with V is local): summing the units over all cyclic diagonals r gives (Q K^T) V. hd = 8 slots per
+    token, 64 tokens per ciphertext, Delta = 2^40 with 40-bit primes so that each Rescale keeps the scale near
+    Delta; max |err| < 2^-20."""
+    from flows import RefOps, av_unit
+    p = make_params(10, 5, 40, 3, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 71)
+    S, hd = p.N // 2, 8
+    T = S // hd
+    rng = np.random.default_rng(3)
+    Q, Kmat, V = (rng.normal(0, 1, (T, hd)) * 0.25 for _ in range(3))
+    D = 2.0**40
+    cq = keys.encrypt_slots(Q.reshape(-1), D, 5)[None]
+    ck = keys.encrypt_slots(Kmat.reshape(-1), D, 5)[None]
+    cv = keys.encrypt_slots(V.reshape(-1), D, 3)[None]
+    mask = np.zeros(S)
+    mask[::hd] = 1.0
+    mask_pt = encode_plain_eval(c, mask, D, 4)
+    relin = keys.relin_key()
+    rk = lambda k: keys.rotation_key(galois_element(k, p.logN))
+    sum_keys = [rk(1 << i) for i in range(3)]
+    rep_keys = [rk(-(1 << i)) for i in range(3)]
+    g_tok, tok_key = galois_element(hd, p.logN), rk(hd)
+    ops = RefOps(c)
+    out = None
+    for r in range(T):
+        if r:
+            ck = c.hrot(ck, g_tok, tok_key)
+            cv = c.hrot(cv, g_tok, tok_key)
+        u = av_unit(ops, p.logN, cq, ck, cv, relin, sum_keys, mask_pt, rep_keys, hd)
+        out = u if out is None else ops.add(out, u)
+    assert out.shape == (1, 2, 3, p.N)
+    scale = D**4 / (p.q[4] * p.q[3])
+    got = keys.decrypt_slots(out[0], scale).real.reshape(T, hd)
+    want = (Q @ Kmat.T) @ V
+    err = np.max(np.abs(got - want))
+    assert err < 2.0**-20, err
