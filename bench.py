@@ -31,6 +31,9 @@ OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 16, 14, 4
 # butterfly = 6 (exact product, quotient, remainder) + 2 (add, sub) + 1.5 (range reduction every 4 stages);
 # variable x variable product reduced = 7; constant multiply = 6.
 OPS_BUTTERFLY_FP, OPS_MULRED_FP, OPS_SHOUP_FP = 9.5, 7, 6
+# Base-conversion dot product on 30-bit operand halves: 4 multiply-adds per term, and per output a base-2^30
+# Montgomery reduction of the three sums (22) plus the final correction (5).
+OPS_DOT30, OPS_REDUCE90 = 4, 27
 
 
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload (bytes, average
@@ -76,8 +79,9 @@ def keyswitch_model(p, B, nl, hrot, hmult):
     put("ntt16_inv_blocks_kernel", 2, inv_int * 2 * limb, inv_int * bf_pass)
     put("ntt16_inv_rows_kernel", 0, inv_fp * 2 * limb, inv_fp * (bf_pass_fp + N * OPS_SHOUP_FP))
     put("ntt16_inv_rows_kernel", 2, inv_int * 2 * limb, inv_int * (bf_pass + N * OPS_SHOUP))
+    # base conversion, as executed: 4 multiply-adds per term on 30-bit halves + a 27-instruction reduction per output
     put("modup_kernel", None, B * (nl + new_limbs) * limb,
-        B * N * sum((nxt - len(dg)) * ((len(dg) + 1) * OPS_MAC + OPS_REDUCE) for dg in digits))
+        B * N * sum((nxt - len(dg)) * ((len(dg) + 1) * OPS_DOT30 + OPS_REDUCE90) for dg in digits))
     rows_fp, rows_int = B * (new_fp + 2 * own_fp), B * (new_int + 2 * own_int)
     put("ntt16_fwd_rows_kernel", 0, rows_fp * 2 * limb, rows_fp * bf_pass_fp)
     put("ntt16_fwd_rows_kernel", 2, rows_int * 2 * limb, rows_int * bf_pass)
@@ -86,7 +90,7 @@ def keyswitch_model(p, B, nl, hrot, hmult):
         B * N * n_fp * beta * 2 * OPS_MULRED_FP)
     put("ntt16_fwd_blocks_inner_kernel", 2, (B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
         B * (new_int * bf_pass + N * n_int * beta * 2 * mul_redc))
-    put("moddown_kernel", None, 2 * B * (K + nl) * limb, 2 * B * N * nl * ((K + 1) * OPS_MAC + OPS_REDUCE))
+    put("moddown_kernel", None, 2 * B * (K + nl) * limb, 2 * B * N * nl * ((K + 1) * OPS_DOT30 + OPS_REDUCE90))
     addend = 1 if hrot else 2 if hmult else 0
     put("ntt16_fwd_blocks_final_kernel", 0, B * own_fp * (6 + addend) * limb,
         2 * B * own_fp * (bf_pass_fp + N * (OPS_SHOUP_FP + 2)))

@@ -205,7 +205,9 @@ int ckks_prof_enable(ckks_ctx* ctx, int on);
  * knob 2 != 0 selects the 3-waves-per-SIMD build of the fused inner-product kernel; knob 3 == 0 uses the fused
  * inner product on double-precision moduli too; knob 4 == 0 lets a key switch fork its two independent kernel
  * chains (double-precision slots / special-prime slots) onto a second internal stream and join them before the
- * result is assembled (default 1: everything on the caller's stream). */
+ * result is assembled (default 1: everything on the caller's stream); knob 5 != 0 makes every base conversion
+ * use the general four-sum accumulation with a 128-bit Montgomery reduction, also where the bit sizes of the
+ * bases would allow the shorter three-sum form (set before the first call at a given limb count). */
 int ckks_tune_set(ckks_ctx* ctx, int knob, int value);
 int ckks_prof_num_kinds(void);
 const char* ckks_prof_kind_name(int kind);

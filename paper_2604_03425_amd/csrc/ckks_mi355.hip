@@ -43,6 +43,26 @@ u64 h_pow(u64 a, u64 e, u64 m) {
 inline u64 h_inv(u64 a, u64 m) { return h_pow(a, m - 2, m); }
 inline u64 h_shoup(u64 w, u64 m) { return (u64)(((u128)w << 64) / m); }
 inline u64 h_mont(u64 v, u64 m) { return (u64)(((u128)v << 64) % m); }  // v * 2^64 mod m
+inline u64 h_mont90(u64 v, u64 m) { return h_mul(h_mont(v, m), (u64)(1ull << 26) % m, m); }  // v * 2^90 mod m
+inline u32 h_bits(u64 v) {
+  u32 b = 0;
+  while (v) v >>= 1, b++;
+  return b;
+}
+// Whether a base conversion with at most `n` sources below 2^bs into targets below 2^bt may use the three-sum
+// accumulation and the base-2^30 reduction (dot30n_*): none of the three sums, including what the reduction adds
+// to them, may reach 2^64.
+inline bool bconv_narrow_ok(u32 n, u32 bs, u32 bt, u32 bt_min) {
+  if (bs > 60 || bt > 60 || bt_min < 36) return false;  // the result is below m + 2^34 and gets one correction
+  if (n > 15) n = 15;  // chunks of 15 terms are reduced separately
+  const u128 one = 1, w = (one << 30) - 1;
+  const u128 y1 = one << (bs > 30 ? bs - 30 : 0), c1 = one << (bt > 30 ? bt - 30 : 0);
+  const u128 amax = (u128)n * w * w + (u128)n * w + w * w;
+  const u128 bmax = (u128)n * (w * c1 + y1 * w) + (u128)n * c1 + (one << 34) + w * c1 + w * w;
+  const u128 cmax = (u128)n * y1 * c1 + (one << 34) + w * c1 + w * w;
+  const u128 lim = one << 64;
+  return amax < lim && bmax < lim && cmax < lim;
+}
 bool h_is_prime(u64 n) {
   if (n < 2) return false;
   const u64 bases[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
@@ -79,6 +99,7 @@ inline u32 bconv_rows(u32 n) { return n <= 4 ? 4 : n <= 8 ? 8 : n <= 15 ? 15 : 4
 // Base-conversion constants for ciphertexts at one limb count.
 struct LevelTables {
   u32 nlimbs = 0, beta = 0, next = 0;
+  bool narrow_up = false, narrow_dn = false, narrow_rs = false;  // which reduction the constants are scaled for
   ulonglong2* up_inv = nullptr;  // [beta][alpha]
   u64* up_mat = nullptr;         // [beta][alpha+1][next]
   ulonglong2* dn_inv = nullptr;  // [K]
@@ -123,7 +144,8 @@ struct ProfRec {
 
 struct ckks_ctx {
   int tune[8] = {4, 0, 0, 1, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 transforms; 3: unfused FP inner product;
-                                         // 4: 1 = one stream only (0 forks the two chains of a key switch)
+                                         // 4: 1 = one stream only (0 forks the two chains of a key switch);
+                                         // 5: 1 = base conversions always take the general (128-bit) reduction
   bool prof_on = false;
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
@@ -198,7 +220,7 @@ struct ProfScope {
 int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
   std::lock_guard<std::mutex> lock(c->mu);
   const bool fp_on = c->tune[1] == 0;
-  const u32 key = nlimbs * 2 + (fp_on ? 1 : 0);
+  const u32 key = nlimbs * 4 + (fp_on ? 1 : 0) + (c->tune[5] ? 2 : 0);
   auto is_fp = [&](u64 m) { return fp_on && (m >> 50) == 0; };
   auto it = c->levels.find(key);
   if (it != c->levels.end()) {
@@ -214,6 +236,16 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
 
   // constants of one output are contiguous: [digit][target][R+1], rows >= digit length are zero, row R = -Q_j
   const u32 R = bconv_rows(alpha), RK = bconv_rows(K);
+  u32 bq = 0, bq_min = 64, bp = 0, bp_min = 64;
+  for (u32 i = 0; i < nlimbs; i++) bq = std::max(bq, h_bits(c->mod[i])), bq_min = std::min(bq_min, h_bits(c->mod[i]));
+  for (u32 k = 0; k < K; k++)
+    bp = std::max(bp, h_bits(c->mod[c->nq + k])), bp_min = std::min(bp_min, h_bits(c->mod[c->nq + k]));
+  t.narrow_up = c->tune[5] == 0 && bconv_narrow_ok(std::min(alpha, nlimbs), bq, std::max(bq, bp), std::min(bq_min, bp_min));
+  t.narrow_dn = c->tune[5] == 0 && bconv_narrow_ok(K, bp, bq, bq_min);
+  t.narrow_rs = c->tune[5] == 0 && bconv_narrow_ok(1, bq, bq, bq_min);
+  auto mont_up = [&](u64 v, u64 m) { return t.narrow_up ? h_mont90(v, m) : h_mont(v, m); };
+  auto mont_dn = [&](u64 v, u64 m) { return t.narrow_dn ? h_mont90(v, m) : h_mont(v, m); };
+  auto mont_rs = [&](u64 v, u64 m) { return t.narrow_rs ? h_mont90(v, m) : h_mont(v, m); };
   std::vector<ulonglong2> up_inv((size_t)t.beta * alpha, ulonglong2{0, 0});
   std::vector<u64> up_mat((size_t)t.beta * next * (R + 1), 0);
   for (u32 j = 0; j < t.beta; j++) {
@@ -228,13 +260,13 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
         u64 m = ext_mod(s), v = 1;
         for (u32 k = lo; k < hi; k++)
           if (k != i) v = h_mul(v, c->mod[k] % m, m);
-        up_mat[((size_t)j * next + s) * (R + 1) + (i - lo)] = h_mont(v, m);
+        up_mat[((size_t)j * next + s) * (R + 1) + (i - lo)] = mont_up(v, m);
       }
     }
     for (u32 s = 0; s < next; s++) {
       u64 m = ext_mod(s), v = 1;
       for (u32 k = lo; k < hi; k++) v = h_mul(v, c->mod[k] % m, m);
-      up_mat[((size_t)j * next + s) * (R + 1) + R] = h_mont(v ? m - v : 0, m);
+      up_mat[((size_t)j * next + s) * (R + 1) + R] = mont_up(v ? m - v : 0, m);
     }
   }
   std::vector<ulonglong2> dn_inv(K), pinv(nlimbs);
@@ -249,13 +281,13 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
       u64 m = c->mod[i], v = 1;
       for (u32 r = 0; r < K; r++)
         if (r != k) v = h_mul(v, c->mod[c->nq + r] % m, m);
-      dn_mat[(size_t)i * (RK + 1) + k] = h_mont(v, m);
+      dn_mat[(size_t)i * (RK + 1) + k] = mont_dn(v, m);
     }
   }
   for (u32 i = 0; i < nlimbs; i++) {
     u64 m = c->mod[i], v = 1;
     for (u32 r = 0; r < K; r++) v = h_mul(v, c->mod[c->nq + r] % m, m);
-    dn_mat[(size_t)i * (RK + 1) + RK] = h_mont(v ? m - v : 0, m);
+    dn_mat[(size_t)i * (RK + 1) + RK] = mont_dn(v ? m - v : 0, m);
     u64 inv = h_inv(v, m);
     pinv[i] = ulonglong2{inv, h_shoup(inv, m)};
   }
@@ -305,8 +337,8 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
     rs_one[0] = ulonglong2{1, h_shoup(1, qL)};
     for (u32 i = 0; i + 1 < nlimbs; i++) {
       u64 m = c->mod[i], ql = qL % m, inv = h_inv(ql, m);
-      rs_mat[(size_t)i * 5 + 0] = h_mont(1, m);
-      rs_mat[(size_t)i * 5 + 4] = h_mont(ql ? m - ql : 0, m);
+      rs_mat[(size_t)i * 5 + 0] = mont_rs(1, m);
+      rs_mat[(size_t)i * 5 + 4] = mont_rs(ql ? m - ql : 0, m);
       rs_qinv[i] = ulonglong2{inv, h_shoup(inv, m)};
       rs_qinv16[i] = is_fp(m) ? as_fp(inv, m) : rs_qinv[i];
     }
@@ -494,22 +526,38 @@ KsLayout ks_layout(const ckks_ctx* c, u32 B, u32 nlimbs) {
 }
 
 // Base-conversion launches: two adjacent coefficients per lane up to 15 sources, one beyond (register budget).
-template <bool PRESCALED>
-void launch_modup(const ckks_ctx* c, const ModUpArgs& a, u32 beta, u32 B, hipStream_t st) {
+template <bool PRESCALED, bool NARROW>
+void launch_modup_n(const ckks_ctx* c, const ModUpArgs& a, u32 beta, u32 B, hipStream_t st) {
   dim3 block(BCONV_THREADS), g2(c->N / BCONV_THREADS / 2, beta, B), g1(c->N / BCONV_THREADS, beta, B);
-  if (c->alpha <= 4) hipLaunchKernelGGL((modup_kernel<4, PRESCALED, 2>), g2, block, 0, st, a);
-  else if (c->alpha <= 8) hipLaunchKernelGGL((modup_kernel<8, PRESCALED, 2>), g2, block, 0, st, a);
-  else if (c->alpha <= 15) hipLaunchKernelGGL((modup_kernel<15, PRESCALED, 2>), g2, block, 0, st, a);
-  else hipLaunchKernelGGL((modup_kernel<45, PRESCALED, 1>), g1, block, 0, st, a);
+#define LAUNCH_MODUP(LEN, EPT, GRID) \
+  hipLaunchKernelGGL((modup_kernel<LEN, PRESCALED, EPT, NARROW>), GRID, block, 0, st, a, a.dcoef, a.ext, a.mods, a.mat)
+  if (c->alpha <= 4) LAUNCH_MODUP(4, 2, g2);
+  else if (c->alpha <= 8) LAUNCH_MODUP(8, 2, g2);
+  else if (c->alpha <= 15) LAUNCH_MODUP(15, 2, g2);
+  else LAUNCH_MODUP(45, 1, g1);
+#undef LAUNCH_MODUP
 }
 template <bool PRESCALED>
-void launch_moddown(const ckks_ctx* c, const ModDownArgs& a, u32 B2, hipStream_t st) {
+void launch_modup(const ckks_ctx* c, const ModUpArgs& a, u32 beta, u32 B, bool narrow, hipStream_t st) {
+  if (narrow) launch_modup_n<PRESCALED, true>(c, a, beta, B, st);
+  else launch_modup_n<PRESCALED, false>(c, a, beta, B, st);
+}
+template <bool PRESCALED, bool NARROW>
+void launch_moddown_n(const ckks_ctx* c, const ModDownArgs& a, u32 B2, hipStream_t st) {
   dim3 block(BCONV_THREADS), g2(c->N / BCONV_THREADS / 2, B2), g1(c->N / BCONV_THREADS, B2);
   const u32 K = a.K;
-  if (K <= 4) hipLaunchKernelGGL((moddown_kernel<4, PRESCALED, 2>), g2, block, 0, st, a);
-  else if (K <= 8) hipLaunchKernelGGL((moddown_kernel<8, PRESCALED, 2>), g2, block, 0, st, a);
-  else if (K <= 15) hipLaunchKernelGGL((moddown_kernel<15, PRESCALED, 2>), g2, block, 0, st, a);
-  else hipLaunchKernelGGL((moddown_kernel<45, PRESCALED, 1>), g1, block, 0, st, a);
+#define LAUNCH_MODDOWN(LEN, EPT, GRID) \
+  hipLaunchKernelGGL((moddown_kernel<LEN, PRESCALED, EPT, NARROW>), GRID, block, 0, st, a, a.acc, a.tq, a.mods, a.mat)
+  if (K <= 4) LAUNCH_MODDOWN(4, 2, g2);
+  else if (K <= 8) LAUNCH_MODDOWN(8, 2, g2);
+  else if (K <= 15) LAUNCH_MODDOWN(15, 2, g2);
+  else LAUNCH_MODDOWN(45, 1, g1);
+#undef LAUNCH_MODDOWN
+}
+template <bool PRESCALED>
+void launch_moddown(const ckks_ctx* c, const ModDownArgs& a, u32 B2, bool narrow, hipStream_t st) {
+  if (narrow) launch_moddown_n<PRESCALED, true>(c, a, B2, st);
+  else launch_moddown_n<PRESCALED, false>(c, a, B2, st);
 }
 
 // What a key switch reads and how its result is assembled.
@@ -545,7 +593,7 @@ int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 n
   {
     ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
     ProfScope ps(c, PK_MODDOWN, st);
-    launch_moddown<true>(c, a, B * 2, st);
+    launch_moddown<true>(c, a, B * 2, lt->narrow_dn, st);
     HIP_TRY(hipGetLastError());
   }
   if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st, o2))) return rc;
@@ -594,7 +642,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
     ProfScope ps(c, PK_MODUP, st);
-    launch_modup<true>(c, a, beta, B, st);
+    launch_modup<true>(c, a, beta, B, lt->narrow_up, st);
     HIP_TRY(hipGetLastError());
   }
   NttOpts o2;
@@ -710,7 +758,7 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
     ProfScope ps(c, PK_MODUP, st);
-    launch_modup<true>(c, a, beta, B, st);
+    launch_modup<true>(c, a, beta, B, lt->narrow_up, st);
     HIP_TRY(hipGetLastError());
   }
   NttOpts of;
@@ -778,7 +826,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
     ProfScope ps(c, PK_MODUP, st);
-    launch_modup<false>(c, a, beta, B, st);
+    launch_modup<false>(c, a, beta, B, lt->narrow_up, st);
     HIP_TRY(hipGetLastError());
   }
   // 3. forward transform of the converted slots
@@ -800,7 +848,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   {
     ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
     ProfScope ps(c, PK_MODDOWN, st);
-    launch_moddown<false>(c, a, B * 2, st);
+    launch_moddown<false>(c, a, B * 2, lt->narrow_dn, st);
     HIP_TRY(hipGetLastError());
   }
   // 7. its forward transform, 8. subtract, scale by P^-1, assemble
@@ -1321,7 +1369,7 @@ int ckks_rescale(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t 
   {
     ModDownArgs a{last, tq, c->d_mods, lt->rs_one, lt->rs_mat, c->logN, nl1, c->nq, 1, 1, 0, nl1};
     ProfScope ps(c, PK_MODDOWN, st);
-    launch_moddown<true>(c, a, B * 2, st);
+    launch_moddown<true>(c, a, B * 2, lt->narrow_rs, st);
     HIP_TRY(hipGetLastError());
   }
   // 3. back to the evaluation domain, subtract, divide by q_last

@@ -133,12 +133,34 @@ __global__ void __launch_bounds__(256) automorph_kernel(AutoArgs a) {
 #define BCONV_THREADS 256
 #define M30 0x3FFFFFFFu
 
-// Sum over up to MAXLEN sources (+ the nneg term) for target column `col` of a constant matrix with row pitch
-// `pitch`; row `nneg_row` holds [-C]. Returns the canonical residue.
-template <int MAXLEN>
+// Sum over up to MAXLEN sources (+ the nneg term) for one output, whose MAXLEN + 1 constants are contiguous at
+// `crow` (rows beyond the source count are zero, row MAXLEN holds [-C]). Returns the canonical residue.
+// NARROW: three-sum accumulation with the base-2^30 reduction (constants carry 2^90); otherwise four sums, a
+// 128-bit value and one 2^-64 Montgomery reduction (constants carry 2^64).
+template <int MAXLEN, bool NARROW>
 __device__ __forceinline__ u64 bconv_dot(const u32 (&y0)[MAXLEN], const u32 (&y1)[MAXLEN], u32 nneg,
                                          const u64* __restrict__ crow, const ModInfo& mi) {
-  // crow: the MAXLEN + 1 constants of this output, contiguous; rows beyond the source count are zero.
+  if (NARROW) {
+    u64 r = 0;
+#pragma unroll
+    for (int i0 = 0; i0 < MAXLEN; i0 += 15) {
+      Dot30N dd;
+      dot30n_init(dd);
+#pragma unroll
+      for (int i = i0; i < i0 + 15 && i < MAXLEN; i++) {
+        const u64 c = crow[i];
+        dot30n_mac(dd, y0[i], y1[i], (u32)c & M30, (u32)(c >> 30));
+      }
+      if (i0 == 0) {
+        const u64 c = crow[MAXLEN];
+        dd.a += (u64)nneg * ((u32)c & M30);
+        dd.b += (u64)nneg * (u32)(c >> 30);
+      }
+      r += dot30n_redc90(dd, mi.m, mi.minv);   // each part < m + 2^34
+    }
+    if (MAXLEN > 15) r = csub(r, 2 * mi.m);   // three chunks: r < 4m
+    return csub(r, mi.m);
+  }
   Acc128 V = {0, 0};
 #pragma unroll
   for (int i0 = 0; i0 < MAXLEN; i0 += 15) {
@@ -181,13 +203,18 @@ struct ModUpArgs {
 // PRESCALED: the input already holds y_i (the inverse transform folded (Q_j/q_i)^-1 into its 1/N scaling).
 // EPT: adjacent coefficients per lane (16-byte accesses for EPT = 2); the constants of an output are fetched once
 // per lane through scalar loads and reused for all of them.
-template <int MAXLEN, bool PRESCALED, int EPT>
-__global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a) {
+// The tables and buffers are also passed as separate no-alias parameters: only then can the compiler see that the
+// stores never touch the constants and fetch those through wave-uniform scalar loads (splitting them on the
+// scalar unit as well).
+template <int MAXLEN, bool PRESCALED, int EPT, bool NARROW>
+__global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a, const u64* __restrict__ dcoef,
+                                                              u64* __restrict__ ext, const ModInfo* __restrict__ mods,
+                                                              const u64* __restrict__ matrix) {
   const u32 N = 1u << a.logN;
   const u32 n = (blockIdx.x * BCONV_THREADS + threadIdx.x) * EPT;
   const u32 j = blockIdx.y, b = blockIdx.z;
   const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs), len = hi - lo;
-  const u64* d = a.dcoef + ((size_t)b * a.nlimbs + lo) * N + n;
+  const u64* d = dcoef + ((size_t)b * a.nlimbs + lo) * N + n;
   u32 y0[EPT][MAXLEN], y1[EPT][MAXLEN], nneg[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; e++) nneg[e] = 0;
@@ -196,7 +223,7 @@ __global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a) {
 #pragma unroll
     for (int e = 0; e < EPT; e++) y0[e][i] = y1[e][i] = 0;
     if ((u32)i < len) {
-      const u64 m = a.mods[lo + i].m;
+      const u64 m = mods[lo + i].m;
       u64 yv[EPT];
       if (EPT == 2) {
         const ulonglong2 v = *(const ulonglong2*)(d + (size_t)i * N);
@@ -218,15 +245,15 @@ __global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a) {
       }
     }
   }
-  const u64* mat = a.mat + (size_t)j * a.next * (MAXLEN + 1);
-  u64* out = a.ext + (((size_t)b * a.beta + j) * a.next) * N + n;
+  const u64* mat = matrix + (size_t)j * a.next * (MAXLEN + 1);
+  u64* out = ext + (((size_t)b * a.beta + j) * a.next) * N + n;
   for (u32 t = 0; t < a.next; t++) {
     if (t >= lo && t < hi) continue;
     const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
-    const ModInfo mi = a.mods[id];
+    const ModInfo mi = mods[id];
     u64 r[EPT];
 #pragma unroll
-    for (int e = 0; e < EPT; e++) r[e] = bconv_dot<MAXLEN>(y0[e], y1[e], nneg[e], mat + (size_t)t * (MAXLEN + 1), mi);
+    for (int e = 0; e < EPT; e++) r[e] = bconv_dot<MAXLEN, NARROW>(y0[e], y1[e], nneg[e], mat + (size_t)t * (MAXLEN + 1), mi);
     if (EPT == 2) *(ulonglong2*)(out + (size_t)t * N) = ulonglong2{r[0], r[EPT - 1]};
     else out[(size_t)t * N] = r[0];
   }
@@ -273,12 +300,14 @@ struct ModDownArgs {
   u32 src_slot;           // slot of the first source limb inside a row of `acc` (nlimbs for a key switch)
   u32 src_id0;            // modulus id of the first source limb (nq for a key switch)
 };
-template <int MAXLEN, bool PRESCALED, int EPT>
-__global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
+template <int MAXLEN, bool PRESCALED, int EPT, bool NARROW>
+__global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a, const u64* __restrict__ acc,
+                                                                u64* __restrict__ tq, const ModInfo* __restrict__ mods,
+                                                                const u64* __restrict__ matrix) {
   const u32 N = 1u << a.logN;
   const u32 n = (blockIdx.x * BCONV_THREADS + threadIdx.x) * EPT;
   const u32 bc = blockIdx.y;
-  const u64* x = a.acc + ((size_t)bc * a.next + a.src_slot) * N + n;
+  const u64* x = acc + ((size_t)bc * a.next + a.src_slot) * N + n;
   u32 y0[EPT][MAXLEN], y1[EPT][MAXLEN], nneg[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; e++) nneg[e] = 0;
@@ -287,7 +316,7 @@ __global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
 #pragma unroll
     for (int e = 0; e < EPT; e++) y0[e][k] = y1[e][k] = 0;
     if ((u32)k < a.K) {
-      const u64 m = a.mods[a.src_id0 + k].m;
+      const u64 m = mods[a.src_id0 + k].m;
       u64 yv[EPT];
       if (EPT == 2) {
         const ulonglong2 v = *(const ulonglong2*)(x + (size_t)k * N);
@@ -309,12 +338,12 @@ __global__ void __launch_bounds__(BCONV_THREADS) moddown_kernel(ModDownArgs a) {
       }
     }
   }
-  u64* out = a.tq + (size_t)bc * a.nlimbs * N + n;
+  u64* out = tq + (size_t)bc * a.nlimbs * N + n;
   for (u32 i = 0; i < a.nlimbs; i++) {
-    const ModInfo mi = a.mods[i];
+    const ModInfo mi = mods[i];
     u64 r[EPT];
 #pragma unroll
-    for (int e = 0; e < EPT; e++) r[e] = bconv_dot<MAXLEN>(y0[e], y1[e], nneg[e], a.mat + (size_t)i * (MAXLEN + 1), mi);
+    for (int e = 0; e < EPT; e++) r[e] = bconv_dot<MAXLEN, NARROW>(y0[e], y1[e], nneg[e], matrix + (size_t)i * (MAXLEN + 1), mi);
     if (EPT == 2) *(ulonglong2*)(out + (size_t)i * N) = ulonglong2{r[0], r[EPT - 1]};
     else out[(size_t)i * N] = r[0];
   }

@@ -117,6 +117,36 @@ __device__ __forceinline__ Acc128 dot30_value(const Dot30& d) {
   v.lo = lo2;
   return v;
 }
+// The same dot product with three sums (the two middle ones share an accumulator) and a word-by-word Montgomery
+// reduction in base 2^30: V = a + b * 2^30 + c * 2^60 -> V * 2^-90 mod m in [0, m + 2^34), 22 instructions instead
+// of assembling a 128-bit value and reducing that. Valid when no sum can pass 2^64, which the host checks from the
+// bit sizes of the two bases and the number of terms (bconv_narrow_ok); constants then carry a factor 2^90.
+struct Dot30N {
+  u64 a, b, c;
+};
+__device__ __forceinline__ void dot30n_init(Dot30N& d) { d.a = d.b = d.c = 0; }
+__device__ __forceinline__ void dot30n_mac(Dot30N& d, u32 y0, u32 y1, u32 c0, u32 c1) {
+  d.a += (u64)y0 * c0;
+  d.b += (u64)y0 * c1;
+  d.b += (u64)y1 * c0;
+  d.c += (u64)y1 * c1;
+}
+// minv = -m^-1 mod 2^64 (its low 30 bits are -m^-1 mod 2^30).
+__device__ __forceinline__ u64 dot30n_redc90(const Dot30N& d, u64 m, u64 minv) {
+  const u32 q0 = (u32)m & 0x3FFFFFFFu, q1 = (u32)(m >> 30), qi = (u32)minv & 0x3FFFFFFFu;
+  u64 a = d.a, b = d.b, c = d.c;
+  u32 u = ((u32)a * qi) & 0x3FFFFFFFu;
+  a += (u64)u * q0;              // now a multiple of 2^30
+  b += a >> 30;
+  b += (u64)u * q1;
+  u = ((u32)b * qi) & 0x3FFFFFFFu;
+  b += (u64)u * q0;
+  c += b >> 30;
+  c += (u64)u * q1;
+  u = ((u32)c * qi) & 0x3FFFFFFFu;
+  c += (u64)u * q0;
+  return (c >> 30) + (u64)u * q1;
+}
 // Montgomery reduction: V * 2^-64 mod m, in [0, V/2^64 + m). minv = -m^-1 mod 2^64.
 __device__ __forceinline__ u64 redc(Acc128 v, u64 m, u64 minv) {
   u64 u = v.lo * minv;

@@ -89,6 +89,9 @@ KS_SHAPES = [
     ((12, 5, 50, 5, 60, 1), 5, 2),     # dnum = 1
     ((12, 7, 50, 3, 60, 3), 7, 2),     # ragged at the top level: digits 3,3,1
     ((13, 4, 50, 2, 60, 2), 4, 2),     # two-pass transform
+    ((12, 8, 60, 8, 60, 1), 8, 2),     # 60-bit sources and targets, 8 terms: the general 128-bit reduction
+    ((12, 6, 60, 3, 60, 2), 6, 2),     # 60-bit both sides but only 3 terms: the three-sum reduction still fits
+    ((12, 16, 50, 16, 60, 1), 16, 1),  # 16 sources: two chunks of the dot product
 ]
 
 
@@ -105,6 +108,27 @@ def test_keyswitch(gpu, shape, nlimbs, B):
     out = torch.empty((B, 2, nlimbs, p.N), dtype=torch.int64, device="cuda")
     gpu.ckks_keyswitch(gc, out, to_dev(d), B, nlimbs, to_dev(evk), 0, p.dnum, ws)
     assert_same(to_host(out), want, "keyswitch")
+
+
+@pytest.mark.parametrize("shape,nlimbs,B", [((12, 6, 50, 3, 60, 2), 6, 2), ((16, 4, 50, 2, 60, 2), 4, 2)])
+def test_keyswitch_general_reduction(gpu, shape, nlimbs, B):
+    """Base conversions forced onto the general four-sum / 128-bit reduction where the three-sum form would do."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = shape_params(shape)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    gpu.ckks_tune_set(gc, 5, 1)
+    d = uniform_residues(13, p.q[:nlimbs], (B,), p.N)
+    evk = uniform_residues(14, p.moduli, (p.dnum, 2), p.N)
+    want = rc.keyswitch(d, evk)
+    out = torch.empty((B, 2, nlimbs, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_keyswitch(gc, out, to_dev(d), B, nlimbs, to_dev(evk), 0, p.dnum, gc.workspace(gpu.OP_KEYSWITCH, B, nlimbs))
+    assert_same(to_host(out), want, "keyswitch, general reduction")
+    ct = uniform_residues(15, p.q[:nlimbs], (B, 2), p.N)
+    out2 = torch.empty((B, 2, nlimbs - 1, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_rescale(gc, out2, to_dev(ct), B, nlimbs, gc.workspace(gpu.OP_RESCALE, B, nlimbs))
+    assert_same(to_host(out2), rc.rescale(ct), "rescale, general reduction")
+    gc.close()
 
 
 def test_hrot_tiny_config_batch(gpu):
