@@ -3,9 +3,11 @@
 
 Workload ("keyswitch_micro"): N = 2^16, 24 main primes of 50 bits, 8 special primes of 60
 bits, dnum = 3; 64 ciphertexts with uniform residues and seeded uniform evaluation keys.
-One step = HRot of all 64 ciphertexts (in `--groups` groups, each group with its own Galois
-element and key, one library call per group) followed by HMult+relinearize of 32 ciphertext
-pairs (one call): 96 key switches. Inputs are resident in HBM before the timed region.
+One step = HRot of all 64 ciphertexts, each by its own seeded Galois element with its own
+key (`--groups 64`, one batched ckks_hrot_multi call; `--groups G --hrot-call grouped` shares
+an element and key inside each of G groups and makes one ckks_hrot call per group), followed
+by HMult+relinearize of 32 ciphertext pairs (one call): 96 key switches. Inputs are resident
+in HBM before the timed region.
 
 Prints ONE JSON line: whole-job key switches per second, the roofline figures of the kernel
 kind that dominates the timed region (HIP-event durations of every launch, taken by the
@@ -249,7 +251,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--groups", type=int, default=8, help="distinct (Galois element, key) groups among the 64 HRots")
+    ap.add_argument("--groups", type=int, default=64, help="distinct (Galois element, key) groups among the 64 HRots")
+    ap.add_argument("--hrot-call", default="multi", choices=["grouped", "multi"],
+                    help="grouped: one ckks_hrot per group; multi: one ckks_hrot_multi over all 64 ciphertexts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--map-mode", type=int, default=None, help="experiment: workgroup mapping mode of the 2^16 transforms")
     ap.add_argument("--int-only", action="store_true", help="experiment: integer bodies for every modulus")
@@ -312,14 +316,19 @@ def main():
     # the streams (default priority), each stream with its own workspace, so one call's tail overlaps another's start
     nstreams = max(1, args.streams)
     streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(nstreams - 1)]
-    wss = [ctx.workspace(ck.OP_HROT, max(Bg, B // 2), nl) for _ in range(nstreams)]
+    multi = args.hrot_call == "multi"
+    wss = [ctx.workspace(ck.OP_HROT, B if multi else max(Bg, B // 2), nl) for _ in range(nstreams)]
     ws = wss[0]
+    gal_pc = [gal[b // Bg] for b in range(B)]
+    evk_pc = [evks[b // Bg] for b in range(B)]
 
     def step():
         if nstreams > 1:
             for s_ in streams[1:]:
                 s_.wait_stream(streams[0])
-        for g in range(G):
+        if multi:   # all 64 rotations in one call, each ciphertext with its group's element and key
+            ck.ckks_hrot_multi(ctx, out_rot, ct, B, nl, gal_pc, evk_pc, ws)
+        for g in range(0 if multi else G):
             with torch.cuda.stream(streams[g % nstreams]):
                 ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g],
                              wss[g % nstreams])
@@ -397,6 +406,12 @@ def main():
       t_rot1 = timed(lambda: ck.ckks_hrot(ctx, out_rot, ct, B, nl, gal[0], evks[0],
                                           ctx.workspace(ck.OP_HROT, B, nl)), 3)
       t_mul = timed(lambda: ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws), 3)
+      # every ciphertext with its own element and key (64 keys, 6 GiB), one batched call
+      ws_b = ctx.workspace(ck.OP_HROT, B, nl)
+      evk64 = evks + [uniform((p.dnum, 2), p.moduli) for _ in range(B - G)]
+      gal64 = [galois_element(r, p.logN) for r in seeded_rotation_steps(8, B, 1, N // 2 - 1)]
+      t_rot64 = timed(lambda: ck.ckks_hrot_multi(ctx, out_rot, ct, B, nl, gal64, evk64, ws_b), 3)
+      del evk64
       # the step after a product: Rescale (and the PMult / Add building blocks), same batch
       ws_rs = ctx.workspace(ck.OP_RESCALE, B, nl)
       out_rs = torch.empty((B, 2, nl - 1, N), dtype=torch.int64, device=dev)
@@ -406,6 +421,7 @@ def main():
       t_ad = timed(lambda: ck.ckks_add(ctx, out_rot, ct, out_rot, B * 2, nl), 3)
       extra = dict(ntt_limbs_per_s=round(B * 2 * nl / t_ntt), intt_limbs_per_s=round(B * 2 * nl / t_intt),
                    hrot_per_s=round(B / t_rot, 1), hrot_per_s_one_group=round(B / t_rot1, 1),
+                   hrot_per_s_own_key_each=round(B / t_rot64, 1),
                    hmult_relin_per_s=round(B / 2 / t_mul, 1),
                  rescale_per_s=round(B / t_rs, 1),
                  rescale_hbm_frac=round(B * 2 * (4 + 3 * (nl - 1) + 4 * (nl - 1)) * 8 * N / t_rs / 1e9 / PEAK_HBM_GBS, 4),
@@ -436,12 +452,18 @@ def main():
         cpu = dict(value=round((ns + ns // 2) / cpu_sec, 3), unit="key-switches/s", cores=threads, kind="oracle",
                    sample="%d HRot + %d HMult+relin of the same workload (N=2^16, 24 limbs, dnum=3), %.1f s" % (ns, ns // 2, cpu_sec))
         # the sample doubles as an end-of-run parity check of the timed configuration
-        ck.ckks_hrot(ctx, out_rot[:Bg], ct[:Bg], Bg, nl, gal[0], evks[0], ws)
+        chk = torch.empty_like(ct[:ns])
+        ck.ckks_hrot(ctx, chk, ct[:ns].contiguous(), ns, nl, gal[0], evks[0], ctx.workspace(ck.OP_HROT, ns, nl))
         ck.ckks_hmult_relin(ctx, out_mul, ct_a, ct_b, B // 2, nl, evk_mult, ws)
         torch.cuda.synchronize()
-        nchk = min(ns, Bg)
-        ok = bool((out_rot[:nchk].cpu().numpy().view(np.uint64) == r1[:nchk]).all() and
+        ok = bool((chk.cpu().numpy().view(np.uint64) == r1).all() and
                   (out_mul[:ns // 2].cpu().numpy().view(np.uint64) == r2).all())
+        if multi:   # the batched call as timed: one ciphertext of another group against the oracle
+            b1 = B - 1
+            ck.ckks_hrot_multi(ctx, out_rot, ct, B, nl, gal_pc, evk_pc, ws)
+            torch.cuda.synchronize()
+            r3 = rctx.hrot(ct[b1:b1 + 1].cpu().numpy().view(np.uint64), gal_pc[b1], evk_pc[b1].cpu().numpy().view(np.uint64))
+            ok = ok and bool((out_rot[b1:b1 + 1].cpu().numpy().view(np.uint64) == r3).all())
         cpu["gpu_matches_oracle_on_sample"] = ok
         if not ok:
             print("bench.py: GPU output differs from the oracle on the sample", file=sys.stderr)
@@ -452,7 +474,7 @@ def main():
         "value": round(value, 2), "unit": "key-switches/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(1e3 * sec / args.steps, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "keyswitch_micro: N=2^16, 24x50-bit + 8x60-bit primes, dnum=3, 64 cts, %d HRot groups, 32 HMult pairs" % G,
+        "config": {"workload": "keyswitch_micro: N=2^16, 24x50-bit + 8x60-bit primes, dnum=3, 64 cts, %d HRot groups (%s), 32 HMult pairs" % (G, "one batched call" if multi else "one call per group"),
                    "global_batch": B, "parallelism": "single-gpu"},
         "roofline": roofline, "cpu_baseline": cpu, "phases": phases, "extra": extra,
     }

@@ -131,6 +131,17 @@ int ckks_hrot(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B
               uint32_t galois_elt, const uint64_t* evk_rot, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * HRot with a Galois element and a rotation key per ciphertext (the batch of the key-switch micro-benchmark is
+ * rotated "by seeded Galois elements"; same definition as ckks_hrot, Sec. 2.1 Rot): ct_out[b] =
+ * HRot_{galois_elts[b]}(ct_in[b]) with evks[b], i.e. exactly what B calls of ckks_hrot with B = 1 return, but
+ * in one launch sequence over the whole batch. galois_elts: HOST array of B odd elements < 2N; evks: HOST array
+ * of B device pointers, each laid out like evk_rot of ckks_hrot (pointers may repeat). Buffers, workspace
+ * (CKKS_OP_HROT for this B), stream and error behaviour as for ckks_hrot.
+ */
+int ckks_hrot_multi(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                    const uint32_t* galois_elts, const uint64_t* const* evks, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * HMult + relinearize (paper Sec. 2.1: CMult, Relin): with ct_a = (a0,a1), ct_b = (b0,b1):
  * d0 = a0*b0, d1 = a0*b1 + a1*b0, d2 = a1*b1 (pointwise per limb), ks = keyswitch(d2,
  * evk_mult), ct_out = (d0 + ks.b, d1 + ks.a). No rescale: the output scale is the product

@@ -17,7 +17,7 @@ _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_work
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
             "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
-            "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted"]
+            "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi"]
 
 
 class CkksError(RuntimeError):
@@ -36,7 +36,7 @@ def exported_symbols():
 
 def _load():
     if not os.path.exists(_LIB_PATH):
-        raise ImportError("libckks_mi355.so is not built: run `python -m paper_2604_03425_amd.build` "
+        raise ImportError("libckks_mi355.so is not built: run `python paper_2604_03425_amd/build.py` "
                           "(there is no CPU fallback)")
     lib = C.CDLL(_LIB_PATH)
     u64p, u32p, vp = C.c_void_p, C.POINTER(C.c_uint32), C.c_void_p
@@ -57,6 +57,7 @@ def _load():
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_hrot_hoisted.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), C.c_uint32, vp,
                                       C.c_size_t, vp]
+    lib.ckks_hrot_multi.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs_hoisted.argtypes = lib.ckks_pcmm_bsgs.argtypes
     lib.ckks_rescale.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, vp, C.c_size_t, vp]
     lib.ckks_pmult.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
@@ -195,6 +196,15 @@ def ckks_hrot_hoisted(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
     keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk").value for k in evks])
     _check(_lib.ckks_hrot_hoisted(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys, R,
                                   _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_hrot_multi(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
+    if len(galois_elts) != B or len(evks) != B:
+        raise ValueError("need one Galois element and one key per ciphertext")
+    gs, _ = _ids(galois_elts)
+    keys = (C.c_void_p * max(1, B))(*[_ptr(k, "evk").value for k in evks])
+    _check(_lib.ckks_hrot_multi(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys,
+                                _ptr(ws, "ws"), ws.numel() * 8, _stream()))
 
 
 def ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws, hoisted=False):

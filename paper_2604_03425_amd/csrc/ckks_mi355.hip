@@ -395,6 +395,7 @@ inline int host_class(const ckks_ctx* c, u64 m) {
 
 struct NttOpts {
   u32 galois = 0;                     // N = 2^16 inverse only: read src through the eval-domain Galois map
+  const u32* galois_pc = nullptr;     // same, one element per polynomial (host array, npoly <= KS_MULTI_MAX entries)
   const ulonglong2* scale = nullptr;  // N = 2^16 inverse only: per-slot constants (from slot0) replacing N^-1
   bool rows_only = false;             // N = 2^16 forward only: stop after the row pass (a fused kernel does the rest)
   bool blocks_only = false;           // N = 2^16 forward only: only the block pass, in place on dst
@@ -422,6 +423,11 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     for (u32 i = 0; i < 128; i++) a.id[i] = ids_from_slot0.id[i];
     a.map_mode = c->tune[0];
     a.galois = opt.galois;
+    if (opt.galois_pc) {
+      if (npoly > KS_MULTI_MAX) return fail(CKKS_ESHAPE, "internal: per-polynomial Galois elements for too many polynomials");
+      a.multi = 1;
+      for (u32 i = 0; i < npoly; i++) a.galois_pc[i] = opt.galois_pc[i];
+    }
     a.scale = opt.scale;
     a.raw_out = opt.raw_out ? 1 : 0;
     Ntt16Args b = a;  // second pass: in place on dst
@@ -569,6 +575,9 @@ struct KsIo {
   u32 mode[2];           // per component: 0 out = ks; 1 out += ks; 2 out = ks + sigma_g(add_src) (N = 2^16 path only)
   const u64* add_src;    // [B][2][nlimbs][N]
   u32 add_galois;
+  // N = 2^16 path, B <= KS_MULTI_MAX: ciphertext b uses galois_pc[b] (for d and add_src) and the key evk_pc[b]
+  const u32* galois_pc = nullptr;
+  const u64* const* evk_pc = nullptr;
 };
 
 // Second half of a key switch on the N = 2^16 path: from the accumulators (acc, all slots) to the assembled output.
@@ -613,6 +622,10 @@ int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 n
     a.mode0 = io.mode[0];
     a.mode1 = io.mode[1];
     a.galois = io.add_galois;
+    if (io.galois_pc) {
+      a.multi = 1;
+      for (u32 i = 0; i < B; i++) a.galois_pc[i] = io.galois_pc[i];
+    }
     a.map_mode = c->tune[0];
     auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
     LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
@@ -635,8 +648,10 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   u64* ext = (u64*)(ws + L.ext);
   u64* acc = (u64*)(ws + L.acc);
   const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
+  if (io.galois_pc && B > KS_MULTI_MAX) return fail(CKKS_ESHAPE, "internal: per-ciphertext keys for too many ciphertexts");
   NttOpts o1;
   o1.galois = io.d_galois;
+  o1.galois_pc = io.galois_pc;
   o1.scale = lt->up_scale;
   if ((rc = launch_ntt(c, true, io.d, io.d_stride, dcoef, (u64)nlimbs * N, B, 0, nlimbs, qmap, 0, 0, st, o1))) return rc;
   {
@@ -688,6 +703,10 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   ia.map_mode = c->tune[0];
   ia.galois = io.d_galois;
   ia.ext_galois = 0;
+  if (io.galois_pc) {
+    ia.multi = 1;
+    for (u32 i = 0; i < B; i++) ia.galois_pc[i] = io.galois_pc[i], ia.evk_pc[i] = io.evk_pc[i];
+  }
   if (unfused_fp && any_fp) {
     NttOpts o = o2;
     o.only_class = 0;
@@ -1189,6 +1208,41 @@ static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   if ((rc = launch_automorph(c, d, polyN, (const u64*)ct_in + polyN, 2 * polyN, B, nlimbs, qmap, g, true, st))) return rc;
   KsIo io{d, polyN, 0, (u64*)ct_out, {1, 0}, nullptr, 0};
   return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
+}
+
+int ckks_hrot_multi(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                    const uint32_t* galois_elts, const uint64_t* const* evks, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!ct_out || !ct_in || !galois_elts || !evks) return fail(CKKS_EINVAL, "null argument");
+  for (u32 b = 0; b < B; b++) {
+    if (!evks[b]) return fail(CKKS_EINVAL, "null key");
+    if (!(galois_elts[b] & 1) || galois_elts[b] >= 2 * c->N) return fail(CKKS_EINVAL, "galois_elt must be odd and < 2N");
+  }
+  if ((rc = check_ws(c, CKKS_OP_HROT, B, nlimbs, 0, ws, ws_bytes))) return rc;
+  const size_t polyN = (size_t)nlimbs * c->N, ct_bytes = (size_t)B * 2 * polyN * 8;
+  if (overlap(ct_out, ct_bytes, ct_in, ct_bytes)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
+  if (c->logN != 16) {
+    // other ring sizes: one rotation at a time through the general path
+    for (u32 b = 0; b < B; b++)
+      if ((rc = hrot_impl(c, ct_out + b * 2 * polyN, ct_in + b * 2 * polyN, 1, nlimbs, galois_elts[b], evks[b], ws, ws_bytes,
+                          stream, false)))
+        return rc;
+    return CKKS_OK;
+  }
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  // the kernels carry the per-ciphertext elements and key pointers in their arguments, KS_MULTI_MAX at a time
+  for (u32 b0 = 0; b0 < B; b0 += KS_MULTI_MAX) {
+    const u32 nb = std::min<u32>(KS_MULTI_MAX, B - b0);
+    const u64* in = (const u64*)ct_in + (size_t)b0 * 2 * polyN;
+    KsIo io{in + polyN, 2 * polyN, 0, (u64*)ct_out + (size_t)b0 * 2 * polyN, {2u, 0u}, in, 0};
+    io.galois_pc = galois_elts + b0;
+    io.evk_pc = (const u64* const*)evks + b0;
+    if ((rc = keyswitch_impl(c, io, nb, nlimbs, nullptr, (char*)ws, st))) return rc;
+  }
+  return CKKS_OK;
 }
 
 int ckks_hmult_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_a, const uint64_t* ct_b, uint32_t B,

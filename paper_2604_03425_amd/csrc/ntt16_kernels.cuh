@@ -8,6 +8,10 @@
 #include "ntt16fp.cuh"
 
 // ---- standalone passes: grid = (polynomials, 16 tiles, limb slots) ----
+// A batched rotation may give every ciphertext its own Galois element and key: the kernels then take both from
+// small per-ciphertext tables carried in the kernel arguments (at most this many ciphertexts per launch sequence).
+#define KS_MULTI_MAX 64
+
 struct Ntt16Args {
   const u64* src;
   u64* dst;
@@ -19,6 +23,8 @@ struct Ntt16Args {
   u32 map_mode;                          // workgroup -> (poly, tile, slot) mapping, see ntt16_map
   u32 raw_out;                           // forward last pass, double-precision class only: != 0 leaves reduced doubles
   u32 galois;                            // inverse first pass only: != 0 reads src through the eval-domain Galois map
+  u32 multi = 0;                         // != 0: polynomial p is read through galois_pc[p] instead (p < KS_MULTI_MAX)
+  u32 galois_pc[KS_MULTI_MAX];
   const ulonglong2* scale;               // inverse second pass only: per-slot constant replacing N^-1 (NULL = N^-1);
                                          // a double2 (c, c/q) for double-precision moduli, a Shoup pair otherwise
   unsigned char id[128];                 // slot -> modulus id
@@ -81,9 +87,10 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_inv_blocks_kernel(Ntt16Ar
   NTT16_PROLOGUE
   const u32 t = threadIdx.x, j0 = t & 15, h = tile * 16 + (t >> 4);
   u64 x[16];
-  if (a.galois) {
+  const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(poly)] : a.galois;
+  if (g) {
 #pragma unroll
-    for (int i = 0; i < 16; i++) x[i] = src[galois_src_index16(h * 256 + i * 16 + j0, a.galois)];
+    for (int i = 0; i < 16; i++) x[i] = src[galois_src_index16(h * 256 + i * 16 + j0, g)];
   } else {
 #pragma unroll
     for (int i = 0; i < 16; i++) x[i] = src[(size_t)h * 256 + i * 16 + j0];
@@ -149,18 +156,31 @@ struct FwdInnerArgs {
   u32 ext_galois;            // streaming kernels only: != 0 reads ext through the Galois map too (hoisted digits:
                              // ext holds the transform of the un-rotated polynomial, shared by many rotations)
   unsigned char slots[128];  // grid.z index -> extended slot (one modulus class per launch)
+  u32 multi = 0;             // != 0: ciphertext b uses galois_pc[b] and evk_pc[b] instead of galois and evk
+  u32 galois_pc[KS_MULTI_MAX];
+  const u64* evk_pc[KS_MULTI_MAX];
 };
+// b is the same for the whole workgroup; saying so keeps the table look-ups on the scalar unit and their results
+// in scalar registers.
+__device__ __forceinline__ u32 fwd_inner_galois(const FwdInnerArgs& a, u32 b) {
+  return a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(b)] : a.galois;
+}
+__device__ __forceinline__ const u64* fwd_inner_evk(const FwdInnerArgs& a, u32 b) {
+  const u64 v = (u64)(a.multi ? a.evk_pc[__builtin_amdgcn_readfirstlane(b)] : a.evk);
+  const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
+  return (const u64*)(((u64)hi << 32) | lo);
+}
 
 // Raw 64-bit words of the tile that digit j contributes to slot t: the digit's own limb read from d (through the
 // Galois map if asked), else the row-pass output in ext. Lane (hb, j0) gets positions i*16 + j0 of block h.
 __device__ __forceinline__ void fwd_inner_load(u64 (&raw)[16], const FwdInnerArgs& a, u32 b, u32 t, u32 j, bool own, u32 h,
-                                               u32 j0) {
+                                               u32 j0, u32 g) {
   const size_t N = 65536;
   if (own) {
     const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
-    if (a.galois) {
+    if (g) {
 #pragma unroll
-      for (int i = 0; i < 16; i++) raw[i] = src[galois_src_index16(h * 256 + i * 16 + j0, a.galois)];
+      for (int i = 0; i < 16; i++) raw[i] = src[galois_src_index16(h * 256 + i * 16 + j0, g)];
     } else {
 #pragma unroll
       for (int i = 0; i < 16; i++) raw[i] = src[(size_t)h * 256 + i * 16 + j0];
@@ -189,19 +209,21 @@ __device__ __forceinline__ void fwd_inner_body(const FwdInnerArgs& a, u32 b, u32
   u64 acc0[16], acc1[16], x[16], xn[16];
 #pragma unroll
   for (int i = 0; i < 16; i++) acc0[i] = acc1[i] = 0;
+  const u64* evk = fwd_inner_evk(a, b);
+  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
   bool own = fwd_inner_owns(a, t, 0);
-  fwd_inner_load(xn, a, b, t, 0, own, h, j0);
+  fwd_inner_load(xn, a, b, t, 0, own, h, j0, g);
   for (u32 j = 0; j < a.beta; j++) {
 #pragma unroll
     for (int i = 0; i < 16; i++) x[i] = xn[i];
-    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
+    const u64* kb = evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
     const u64* ka = kb + (size_t)a.nm * N;
     if (!own) {
       if (j) wave_lds_sync();  // the previous digit's transposes (inside 16-lane groups) are done with the LDS tile
       ntt16_fwd_blocks_loaded<BIG, false>(x, tw, q, mi.mu64, tile, sm);
     }
     const bool own_next = j + 1 < a.beta && fwd_inner_owns(a, t, j + 1);
-    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0);
+    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0, g);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 16; i++) {
@@ -235,20 +257,22 @@ __device__ __forceinline__ void fwd_inner_body_fp(const FwdInnerArgs& a, u32 b, 
   u64 xn[16];
 #pragma unroll
   for (int i = 0; i < 16; i++) acc0[i] = acc1[i] = 0.0;
+  const u64* evk = fwd_inner_evk(a, b);
+  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
   bool own = fwd_inner_owns(a, t, 0);
-  fwd_inner_load(xn, a, b, t, 0, own, h, j0);
+  fwd_inner_load(xn, a, b, t, 0, own, h, j0, g);
   for (u32 j = 0; j < a.beta; j++) {
     // own limbs arrive as canonical residues, converted digits as the reduced doubles the row pass left
 #pragma unroll
     for (int i = 0; i < 16; i++) x[i] = own ? u2d(xn[i]) : __longlong_as_double((long long)xn[i]);
-    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
+    const u64* kb = evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
     const u64* ka = kb + (size_t)a.nm * N;
     if (!own) {
       if (j) wave_lds_sync();
       ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm);
     }
     const bool own_next = j + 1 < a.beta && fwd_inner_owns(a, t, j + 1);
-    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0);
+    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0, g);
     __builtin_amdgcn_sched_barrier(0);
     // each product is below 0.9 q in magnitude; bring the sums back before they can reach 2^53
     const bool fold = (j & 3) == 3;
@@ -306,6 +330,8 @@ struct FwdFinalArgs {
   const ulonglong2* pinv;  // [nlimbs]
   u32 nlimbs, next, mode0, mode1, galois, map_mode;
   unsigned char slots[128];  // grid.z index -> limb (one modulus class per launch)
+  u32 multi = 0;             // != 0: ciphertext b = bc / 2 reads add_src through galois_pc[b]
+  u32 galois_pc[KS_MULTI_MAX];
 };
 template <bool BIG>
 __device__ __forceinline__ void fwd_final_body(const FwdFinalArgs& a, u32 bc, u32 tile, u32 i_limb, const ModInfo& mi, u64* sm) {
@@ -319,11 +345,12 @@ __device__ __forceinline__ void fwd_final_body(const FwdFinalArgs& a, u32 bc, u3
   u64* o = a.out + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
   const u32 mode = (bc & 1) ? a.mode1 : a.mode0;
   const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
+  const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(bc >> 1)] : a.galois;
 #pragma unroll
   for (int i = 0; i < 16; i++) {
     u64 r = shoup(ac[i * 16] + q2 - x[i], pv.x, pv.y, q);
     if (mode & 1) r = addmod(r, o[i * 16], q);
-    if (mode & 2) r = addmod(r, as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)], q);
+    if (mode & 2) r = addmod(r, as[galois_src_index16(h * 256 + i * 16 + j0, g)], q);
     o[i * 16] = r;
   }
 }
@@ -340,13 +367,14 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
   u64* o = a.out + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
   const u32 mode = (bc & 1) ? a.mode1 : a.mode0;
   const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
+  const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(bc >> 1)] : a.galois;
   u64 ad[16];
   if (mode == 1) {
 #pragma unroll
     for (int i = 0; i < 16; i++) ad[i] = o[i * 16];
   } else if (mode == 2) {
 #pragma unroll
-    for (int i = 0; i < 16; i++) ad[i] = as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)];
+    for (int i = 0; i < 16; i++) ad[i] = as[galois_src_index16(h * 256 + i * 16 + j0, g)];
   }
   ntt16_fwd_blocks_fp(x, (const double*)(a.tq + ((size_t)bc * a.nlimbs + i_limb) * N), a.twfp + (size_t)i_limb * N, q, qinv,
                       tile, sm);
@@ -355,7 +383,7 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
   for (int i = 0; i < 16; i++) {
     double r = fp_mulmod_const(u2d(av[i]) - x[i], pv.x, pv.y, q);  // |r| <= 0.9 q
     if (mode == 1 || mode == 2) r += u2d(ad[i]);
-    if (mode == 3) r += u2d(o[i * 16]) + u2d(as[galois_src_index16(h * 256 + i * 16 + j0, a.galois)]);
+    if (mode == 3) r += u2d(o[i * 16]) + u2d(as[galois_src_index16(h * 256 + i * 16 + j0, g)]);
     if (mode == 3) r = r >= q ? r - q : r;  // two addends: bring the sum back below 2q first
     o[i * 16] = d2u_canon(r, q);
   }
@@ -388,13 +416,15 @@ __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
   const double q = mi.qd, qinv = mi.qinv;
   const u32 n = (blk * 256 + threadIdx.x) * 2;
   double s0[2] = {0.0, 0.0}, s1[2] = {0.0, 0.0};
+  const u32 g_own = fwd_inner_galois(a, b);
+  const u64* evk = fwd_inner_evk(a, b);
   for (u32 j = 0; j < a.beta; j++) {
     double x[2];
     if (fwd_inner_owns(a, t, j)) {
       const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
-      if (a.galois) {
-        x[0] = u2d(src[galois_src_index16(n, a.galois)]);
-        x[1] = u2d(src[galois_src_index16(n + 1, a.galois)]);
+      if (g_own) {
+        x[0] = u2d(src[galois_src_index16(n, g_own)]);
+        x[1] = u2d(src[galois_src_index16(n + 1, g_own)]);
       } else {
         const ulonglong2 v = *(const ulonglong2*)(src + n);
         x[0] = u2d(v.x);
@@ -411,7 +441,7 @@ __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
         x[1] = v.y;
       }
     }
-    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
+    const u64* kb = evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
     const ulonglong2 eb = *(const ulonglong2*)kb;
     const ulonglong2 ea = *(const ulonglong2*)(kb + (size_t)a.nm * N);
     s0[0] += fp_mulmod_var(x[0], u2d(eb.x), qinv, q);
@@ -444,11 +474,13 @@ __global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
   const u64 q = mi.m, q2 = 2 * mi.m;
   const u32 n = (blk * 256 + threadIdx.x) * 2;
   u64 s0[2] = {0, 0}, s1[2] = {0, 0};
+  const u32 g_own = fwd_inner_galois(a, b);
+  const u64* evk = fwd_inner_evk(a, b);
   for (u32 j = 0; j < a.beta; j++) {
     const bool own = fwd_inner_owns(a, t, j);
     const u64* src = own ? a.d + (size_t)b * a.d_poly_stride + (size_t)t * N
                          : a.ext + (((size_t)b * a.beta + j) * a.next + t) * N;
-    const u32 g = own ? a.galois : a.ext_galois;
+    const u32 g = own ? g_own : a.ext_galois;
     u64 x[2];
     if (g) {
       x[0] = src[galois_src_index16(n, g)];
@@ -458,7 +490,7 @@ __global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
       x[0] = v.x;
       x[1] = v.y;
     }
-    const u64* kb = a.evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
+    const u64* kb = evk + (((size_t)j * 2 + 0) * a.nm + id) * N + n;
     const ulonglong2 eb = *(const ulonglong2*)kb;
     const ulonglong2 ea = *(const ulonglong2*)(kb + (size_t)a.nm * N);
     const u64 e0[2] = {eb.x, eb.y}, e1[2] = {ea.x, ea.y};

@@ -234,3 +234,28 @@ def test_attention_av_unit(gpu, name, nl, B, hd):
                   [to_dev(k) for k in sum_keys], to_dev(mask), [to_dev(k) for k in rep_keys], hd)
     assert got.shape == (B, 2, nl - 2, p.N)
     assert_same(to_host(got), want, "attention A x V unit")
+
+
+@pytest.mark.parametrize("name,nl,B", [("tiny_hrot", 4, 8), ("keyswitch_micro", 24, 3)])
+def test_hrot_multi_matches_single_rotations(gpu, name, nl, B):
+    """One Galois element and key per ciphertext in one call = the oracle's HRot of each ciphertext on its own
+    (the tiny configuration's "each rotated by a seeded step"; the micro-benchmark's seeded Galois elements)."""
+    import torch
+    from ckks_inputs import seeded_rotation_steps
+    from gpu_util import to_dev, to_host, assert_same
+    p = config_params(name)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    ct = uniform_residues(400, p.q[:nl], (B, 2), p.N)
+    steps = seeded_rotation_steps(401, B, 1, p.N // 2 - 1)
+    gs = [galois_element(k, p.logN) for k in steps]
+    nkeys = max(2, B - 1)                     # the last ciphertext shares the first one's key: pointers may repeat
+    keys = [uniform_residues(410 + i, p.moduli, (p.dnum, 2), p.N) for i in range(nkeys)]
+    kidx = [i % nkeys for i in range(B)]
+    ref.set_threads(4)
+    want = np.concatenate([rc.hrot(ct[b:b + 1], gs[b], keys[kidx[b]]) for b in range(B)])
+    ref.set_threads(1)
+    dkeys = [to_dev(k) for k in keys]
+    out = torch.empty((B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_hrot_multi(gc, out, to_dev(ct), B, nl, gs, [dkeys[i] for i in kidx], gc.workspace(gpu.OP_HROT, B, nl))
+    assert_same(to_host(out), want, "hrot_multi")
+    gc.close()
