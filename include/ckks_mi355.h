@@ -213,8 +213,9 @@ int ckks_add(ckks_ctx* ctx, uint64_t* out, const uint64_t* a, const uint64_t* b,
 int ckks_prof_enable(ckks_ctx* ctx, int on);
 /* Tuning knobs for experiments: knob 0 = workgroup-to-tile mapping of the N = 2^16 transforms (0..4);
  * knob 1 != 0 turns the double-precision bodies for primes < 2^50 off (integer bodies everywhere);
- * knob 2 != 0 selects the 3-waves-per-SIMD build of the fused inner-product kernel; knob 3 == 0 uses the fused
- * inner product on double-precision moduli too; knob 4 == 0 lets a key switch fork its two independent kernel
+ * knob 2 != 0 selects the 3-waves-per-SIMD build of the fused inner-product kernel; knob 3 picks the inner product
+ * on double-precision moduli: 0 = block pass fused with both key components (two accumulator tiles), 1 = plain
+ * block pass followed by a streaming product, 2 (default) = block pass fused with one key component per workgroup; knob 4 == 0 lets a key switch fork its two independent kernel
  * chains (double-precision slots / special-prime slots) onto a second internal stream and join them before the
  * result is assembled (default 1: everything on the caller's stream); knob 5 != 0 makes every base conversion
  * use the general four-sum accumulation with a 128-bit Montgomery reduction, also where the bit sizes of the

@@ -124,7 +124,7 @@ enum ProfKind {
   // N = 2^16 kernels: three consecutive kinds each, one per modulus class (the kernel's template argument)
   PK_FWD_ROWS, PK_FWD_BLOCKS = PK_FWD_ROWS + 3, PK_INV_BLOCKS = PK_FWD_BLOCKS + 3, PK_INV_ROWS = PK_INV_BLOCKS + 3,
   PK_FWD_INNER = PK_INV_ROWS + 3, PK_FWD_FINAL = PK_FWD_INNER + 3,
-  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
+  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
   PK_COPY, PK_COUNT
 };
 static const char* const kProfNames[PK_COUNT] = {
@@ -135,7 +135,7 @@ static const char* const kProfNames[PK_COUNT] = {
     "ntt16_inv_rows_kernel<0>", "ntt16_inv_rows_kernel<1>", "ntt16_inv_rows_kernel<2>",
     "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
     "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
-    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
+    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
     "pmacc_kernel", "addto_kernel", "copy"};
 struct ProfRec {
   int kind;
@@ -143,7 +143,9 @@ struct ProfRec {
 };
 
 struct ckks_ctx {
-  int tune[8] = {4, 0, 0, 1, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 transforms; 3: unfused FP inner product;
+  int tune[8] = {4, 0, 0, 2, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 transforms; 3: inner product on
+                                         // double-precision moduli (0 fused, two accumulators; 1 plain block pass +
+                                         // streaming product; 2 fused, one key component per workgroup);
                                          // 4: 1 = one stream only (0 forks the two chains of a key switch);
                                          // 5: 1 = base conversions always take the general (128-bit) reduction
   bool prof_on = false;
@@ -712,17 +714,21 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     o.only_class = 0;
     if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
       return rc;
-    o = NttOpts();
-    o.blocks_only = true;
-    o.raw_out = true;
-    o.only_class = 0;
-    if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
-      return rc;
     FwdInnerArgs a = ia;
     u32 cnt = 0;
     for (u32 s_ = 0; s_ < next; s_++)
       if (host_class(c, c->mod[emap.id[s_]]) == 0) a.slots[cnt++] = (unsigned char)s_;
-    {
+    if (c->tune[3] == 2) {
+      // block pass fused with the product, one key component per workgroup
+      ProfScope ps(c, PK_INNER_C, sb);
+      hipLaunchKernelGGL(ntt16_fwd_blocks_inner_c_kernel, dim3(B * 2, 16, cnt), dim3(NTT16_THREADS), 0, sb, a);
+    } else {
+      o = NttOpts();
+      o.blocks_only = true;
+      o.raw_out = true;
+      o.only_class = 0;
+      if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
+        return rc;
       ProfScope ps(c, PK_INNER16, sb);
       hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, sb, a);
     }

@@ -296,6 +296,78 @@ __device__ __forceinline__ void fwd_inner_body_fp(const FwdInnerArgs& a, u32 b, 
   }
 }
 
+// Double-precision moduli, one key component per workgroup: grid.x = 2B, polynomial index bc = 2b + c. Each of the
+// two workgroups of a ciphertext transforms the digit tiles itself (the arithmetic is cheap next to the traffic and
+// the second reader finds the tile in its XCD's L2, the pair being adjacent in the launch order) and multiplies by
+// its own half of the key: one accumulator tile instead of two, so the kernel keeps 3 waves per SIMD and, unlike
+// the two-accumulator form above, stays memory-bound. The key tile of a digit is requested before the transform.
+__device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 bc, u32 tile, u32 t, u32 id, const ModInfo& mi,
+                                                    double* sm) {
+  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
+  const u32 b = bc >> 1, c = bc & 1;
+  const size_t N = 65536;
+  const double q = mi.qd, qinv = mi.qinv;
+  const double* tw = a.twfp + (size_t)id * N;
+  const u64* evk = fwd_inner_evk(a, b) + ((size_t)c * a.nm + id) * N + (size_t)h * 256 + j0;
+  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
+  double acc[16], x[16];
+  u64 e[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) acc[i] = 0.0;
+#pragma nounroll
+  for (u32 j = 0; j < a.beta; j++) {
+    const bool own = fwd_inner_owns(a, t, j);
+    // the gather indices do not depend on the digit, but holding 16 of them across the loop costs a wave of
+    // occupancy: hide the element so that they are recomputed where they are used
+    u32 gj = g;
+    asm volatile("" : "+s"(gj));
+    const u64* k = evk + (size_t)j * 2 * a.nm * N;
+    if (own) {
+      const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+#pragma unroll
+      for (int i = 0; i < 16; i++) e[i] = k[i * 16];
+      if (gj) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) x[i] = u2d(src[galois_src_index16(h * 256 + i * 16 + j0, gj)]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; i++) x[i] = u2d(src[(size_t)h * 256 + i * 16 + j0]);
+      }
+    } else {
+      const double* src = (const double*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N) + (size_t)h * 256 + j0;
+#pragma unroll
+      for (int i = 0; i < 16; i++) x[i] = src[i * 16];
+      wave_lds_sync();  // the previous digit's transposes (inside 16-lane groups) are done with the LDS tile
+      // the key tile is requested between the two rounds of the transform, when the registers of the first
+      // round's twiddles are free again
+      ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm, [&] {
+#pragma unroll
+        for (int i = 0; i < 16; i++) e[i] = k[i * 16];
+      });
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const bool fold = (j & 3) == 3;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      acc[i] += fp_mulmod_var(x[i], u2d(e[i]), qinv, q);
+      if (fold) acc[i] = fp_reduce(acc[i], qinv, q);
+    }
+  }
+  u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + (size_t)h * 256 + j0;
+#pragma unroll
+  for (int i = 0; i < 16; i++) o[i * 16] = d2u_canon(fp_reduce(acc[i], qinv, q), q);
+}
+__global__ void __launch_bounds__(NTT16_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
+ntt16_fwd_blocks_inner_c_kernel(FwdInnerArgs a) {
+  __shared__ u64 sm[NTT16_LDS_BYTES / 8];
+  u32 bc, tile, zi;
+  ntt16_map(a.map_mode, bc, tile, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  fwd_inner_c_body_fp(a, bc, tile, t, id, mi, (double*)sm);
+}
+
 // Two builds of the same kernel: the default register allocation (2 waves per SIMD), and one held to 3 waves per
 // SIMD at the price of a few spilled accumulators; the host picks one (tuning knob 2).
 #define DEFINE_FWD_INNER_KERNEL(NAME, ATTR)                                                      \

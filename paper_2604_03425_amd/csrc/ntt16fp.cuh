@@ -82,8 +82,11 @@ __device__ __forceinline__ void ntt16_fwd_rows_fp(const u64* __restrict__ src, d
 
 // Forward, stages 8..15 on reduced doubles. Leaves x (|x| <= q/2) in the i-layout of ntt16_fwd_blocks.
 // `x` must already hold the tile in the i-layout (lane (hb, j0) holds positions i*16 + j0 of block h).
+// `between` runs after the first round (its twiddles are dead by then), e.g. to request data the caller needs
+// after the transform.
+template <class BETWEEN>
 __device__ __forceinline__ void ntt16_fwd_blocks_fp_loaded(double (&x)[16], const double* __restrict__ tw, double q,
-                                                           double qinv, u32 tile, double* sm) {
+                                                           double qinv, u32 tile, double* sm, BETWEEN between) {
   const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
   const u32 i0 = j0;
   // the second round's 15 twiddles are requested up front so they arrive during the first round
@@ -95,6 +98,7 @@ __device__ __forceinline__ void ntt16_fwd_blocks_fp_loaded(double (&x)[16], cons
   radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[hb * 272 + i * 17 + j0] = x[i];
+  between();
   wave_lds_sync();
 #pragma unroll
   for (int j = 0; j < 16; j++) x[j] = sm[hb * 272 + i0 * 17 + j];
@@ -105,6 +109,10 @@ __device__ __forceinline__ void ntt16_fwd_blocks_fp_loaded(double (&x)[16], cons
   wave_lds_sync();
 #pragma unroll
   for (int i = 0; i < 16; i++) x[i] = sm[hb * 272 + i * 17 + j0];
+}
+__device__ __forceinline__ void ntt16_fwd_blocks_fp_loaded(double (&x)[16], const double* __restrict__ tw, double q,
+                                                           double qinv, u32 tile, double* sm) {
+  ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm, [] {});
 }
 
 // Inverse, stages 15..8. In: x = canonical residues as doubles, i-layout. Out: reduced doubles, i-layout.
