@@ -303,13 +303,19 @@ __device__ __forceinline__ void fwd_inner_body_fp(const FwdInnerArgs& a, u32 b, 
 // the two-accumulator form above, stays memory-bound. The key tile of a digit is requested before the transform.
 __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 bc, u32 tile, u32 t, u32 id, const ModInfo& mi,
                                                     double* sm) {
-  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
   const u32 b = bc >> 1, c = bc & 1;
   const size_t N = 65536;
   const double q = mi.qd, qinv = mi.qinv;
   const double* tw = a.twfp + (size_t)id * N;
-  const u64* evk = fwd_inner_evk(a, b) + ((size_t)c * a.nm + id) * N + (size_t)h * 256 + j0;
+  const u64* evk = fwd_inner_evk(a, b) + ((size_t)c * a.nm + id) * N;
   const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
+  // Every address below is rebuilt from the lane index where it is used (a few integer instructions) instead of
+  // being kept in registers across the digit loop: the kernel is held to 168 registers.
+  auto lane_pos = [&]() {
+    u32 tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    return (tile * 16 + (tid >> 4)) * 256 + (tid & 15);   // position of element 0 of this lane in the limb
+  };
   double acc[16], x[16];
   u64 e[16];
 #pragma unroll
@@ -321,20 +327,21 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
     // occupancy: hide the element so that they are recomputed where they are used
     u32 gj = g;
     asm volatile("" : "+s"(gj));
-    const u64* k = evk + (size_t)j * 2 * a.nm * N;
+    const u32 pos = lane_pos();
+    const u64* k = evk + (size_t)j * 2 * a.nm * N + pos;
     if (own) {
       const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
 #pragma unroll
       for (int i = 0; i < 16; i++) e[i] = k[i * 16];
       if (gj) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) x[i] = u2d(src[galois_src_index16(h * 256 + i * 16 + j0, gj)]);
+        for (int i = 0; i < 16; i++) x[i] = u2d(src[galois_src_index16(pos + i * 16, gj)]);
       } else {
 #pragma unroll
-        for (int i = 0; i < 16; i++) x[i] = u2d(src[(size_t)h * 256 + i * 16 + j0]);
+        for (int i = 0; i < 16; i++) x[i] = u2d(src[pos + i * 16]);
       }
     } else {
-      const double* src = (const double*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N) + (size_t)h * 256 + j0;
+      const double* src = (const double*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N) + pos;
 #pragma unroll
       for (int i = 0; i < 16; i++) x[i] = src[i * 16];
       wave_lds_sync();  // the previous digit's transposes (inside 16-lane groups) are done with the LDS tile
@@ -353,7 +360,7 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
       if (fold) acc[i] = fp_reduce(acc[i], qinv, q);
     }
   }
-  u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + (size_t)h * 256 + j0;
+  u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + lane_pos();
 #pragma unroll
   for (int i = 0; i < 16; i++) o[i * 16] = d2u_canon(fp_reduce(acc[i], qinv, q), q);
 }
