@@ -38,16 +38,16 @@ OPS_BUTTERFLY_FP, OPS_MULRED_FP, OPS_SHOUP_FP = 9.5, 7, 6
 OPS_DOT30, OPS_REDUCE90 = 4, 27
 
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload (bytes, average
-# over the launches of a step, fetch scaled by the copy-kernel calibration); see profiles/keyswitch_micro_hbm_traffic.md.
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload in its default
+# configuration (bytes, average over the two launches of a step: 64 rotations, 32 products; fetch scaled by the
+# copy-kernel calibration); see profiles/keyswitch_micro_hbm_traffic.md.
 MEASURED_TRAFFIC = {
-    "ntt16_inv_blocks_kernel<0>": 281151296, "ntt16_inv_rows_kernel<0>": 269048650,
-    "ntt16_inv_blocks_kernel<2>": 187583914, "ntt16_inv_rows_kernel<2>": 179521159,
-    "modup_kernel": 537268760, "moddown_kernel": 358057340,
-    "ntt16_fwd_rows_kernel<0>": 537455765, "ntt16_fwd_rows_kernel<2>": 268969112,
-    "ntt16_fwd_blocks_kernel<0>": 549574400, "inner16_fp_kernel": 746709269,
-    "ntt16_fwd_blocks_inner_kernel<2>": 260386936, "ntt16_fwd_blocks_final_kernel<0>": 997051317,
-    "tensor_kernel": 2818660832,
+    "moddown_kernel": 1610732339, "modup_kernel": 2416127181,
+    "ntt16_fwd_blocks_final_kernel<0>": 4442038272, "ntt16_fwd_blocks_inner_c_kernel": 5500419686,
+    "ntt16_fwd_blocks_inner_kernel<2>": 1837678182, "ntt16_fwd_rows_kernel<0>": 2416511590,
+    "ntt16_fwd_rows_kernel<2>": 1208484045, "ntt16_inv_blocks_kernel<0>": 1220690534,
+    "ntt16_inv_blocks_kernel<2>": 813935411, "ntt16_inv_rows_kernel<0>": 1208559002,
+    "ntt16_inv_rows_kernel<2>": 805880013, "tensor_kernel": 2818657075,
 }
 
 
@@ -381,16 +381,18 @@ def main():
                             avg_launch_us=round(1e3 * ms / n, 2),
                             GBps=round(mdl["bytes"] / per_step_ms / 1e6, 1) if per_step_ms else None,
                             Tops=round(mdl["ops"] / per_step_ms / 1e9, 2) if per_step_ms else None)
+    # the counter runs were made in the default configuration only
+    default_cfg = (G == 64 and multi and not args.tune and not args.int_only and args.map_mode is None and nstreams == 1)
     dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
     d = phases[dom]
     hbm_frac = (d["GBps"] or 0) / PEAK_HBM_GBS
     alu_frac = (d["Tops"] or 0) / PEAK_ALU_TOPS
     if alu_frac >= hbm_frac:
         roofline = dict(bound="alu", kernel=dom, achieved=d["Tops"], peak=round(PEAK_ALU_TOPS, 1), unit="Tlane-op/s",
-                        frac=round(alu_frac, 4), traffic=MEASURED_TRAFFIC.get(dom), avg_launch_us=d["avg_launch_us"])
+                        frac=round(alu_frac, 4), traffic=MEASURED_TRAFFIC.get(dom) if default_cfg else None, avg_launch_us=d["avg_launch_us"])
     else:
         roofline = dict(bound="hbm", kernel=dom, achieved=d["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(hbm_frac, 4), traffic=MEASURED_TRAFFIC.get(dom), avg_launch_us=d["avg_launch_us"])
+                        frac=round(hbm_frac, 4), traffic=MEASURED_TRAFFIC.get(dom) if default_cfg else None, avg_launch_us=d["avg_launch_us"])
     total_bytes = sum(v["bytes"] for v in model.values())
     total_ops = sum(v["ops"] for v in model.values())
     # compulsory traffic of a step: read every input ciphertext and key once, write every output once

@@ -94,7 +94,7 @@ struct Pass {
 };
 
 // Number of source rows the base-conversion kernels are instantiated for (the smallest that covers n).
-inline u32 bconv_rows(u32 n) { return n <= 4 ? 4 : n <= 8 ? 8 : n <= 15 ? 15 : 45; }
+inline u32 bconv_rows(u32 n) { return n <= 4 ? 4 : n <= 8 ? 8 : n <= 15 ? 15 : n <= 24 ? 24 : n <= 36 ? 36 : 45; }
 
 // Base-conversion constants for ciphertexts at one limb count.
 struct LevelTables {
@@ -533,7 +533,7 @@ KsLayout ks_layout(const ckks_ctx* c, u32 B, u32 nlimbs) {
   return L;
 }
 
-// Base-conversion launches: two adjacent coefficients per lane up to 15 sources, one beyond (register budget).
+// Base-conversion launches: two adjacent coefficients per lane up to 24 sources, one beyond (register budget).
 template <bool PRESCALED, bool NARROW>
 void launch_modup_n(const ckks_ctx* c, const ModUpArgs& a, u32 beta, u32 B, hipStream_t st) {
   dim3 block(BCONV_THREADS), g2(c->N / BCONV_THREADS / 2, beta, B), g1(c->N / BCONV_THREADS, beta, B);
@@ -542,6 +542,8 @@ void launch_modup_n(const ckks_ctx* c, const ModUpArgs& a, u32 beta, u32 B, hipS
   if (c->alpha <= 4) LAUNCH_MODUP(4, 2, g2);
   else if (c->alpha <= 8) LAUNCH_MODUP(8, 2, g2);
   else if (c->alpha <= 15) LAUNCH_MODUP(15, 2, g2);
+  else if (c->alpha <= 24) LAUNCH_MODUP(24, 2, g2);
+  else if (c->alpha <= 36) LAUNCH_MODUP(36, 1, g1);
   else LAUNCH_MODUP(45, 1, g1);
 #undef LAUNCH_MODUP
 }
@@ -559,6 +561,8 @@ void launch_moddown_n(const ckks_ctx* c, const ModDownArgs& a, u32 B2, hipStream
   if (K <= 4) LAUNCH_MODDOWN(4, 2, g2);
   else if (K <= 8) LAUNCH_MODDOWN(8, 2, g2);
   else if (K <= 15) LAUNCH_MODDOWN(15, 2, g2);
+  else if (K <= 24) LAUNCH_MODDOWN(24, 2, g2);
+  else if (K <= 36) LAUNCH_MODDOWN(36, 1, g1);
   else LAUNCH_MODDOWN(45, 1, g1);
 #undef LAUNCH_MODDOWN
 }

@@ -92,6 +92,7 @@ KS_SHAPES = [
     ((12, 8, 60, 8, 60, 1), 8, 2),     # 60-bit sources and targets, 8 terms: the general 128-bit reduction
     ((12, 6, 60, 3, 60, 2), 6, 2),     # 60-bit both sides but only 3 terms: the three-sum reduction still fits
     ((12, 16, 50, 16, 60, 1), 16, 1),  # 16 sources: two chunks of the dot product
+    ((12, 40, 45, 40, 55, 1), 40, 1),  # 40 sources: three chunks, the widest instantiation
 ]
 
 
