@@ -245,6 +245,45 @@ def test_full_size_hrot_and_hmult_sampled(gpu):
     ref.set_threads(1)
 
 
+def test_full_batch_against_oracle_digests(gpu):
+    """The whole micro-benchmark batch (64 rotations with their own elements and keys in one call, 32 products):
+    SHA-256 of every output ciphertext equals the digest the oracle wrote (tests/golden/, made by
+    make_keyswitch_micro_digests.py from the same seeded inputs)."""
+    import hashlib
+    import os
+    import torch
+    from gpu_util import to_dev, to_host
+    p = config_params("keyswitch_micro")
+    gc = gpu.Context(p)
+    B, nl = 64, 24
+    want = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "keyswitch_micro_digests.txt")) as f:
+        for line in f:
+            if not line.startswith("#"):
+                parts = line.split()
+                want[(parts[0], int(parts[1]))] = parts[-1]
+    assert len(want) == B + B // 2
+    ct = uniform_residues(0xC0FFEE, p.q, (B, 2), p.N)
+    steps = seeded_rotation_steps(7, B, 1, p.N // 2 - 1)
+    keys = [to_dev(uniform_residues(1000 + b, p.moduli, (p.dnum, 2), p.N)) for b in range(B)]
+    d_ct = to_dev(ct)
+    out = torch.empty_like(d_ct)
+    ws = gc.workspace(gpu.OP_HROT, B, nl)
+    gpu.ckks_hrot_multi(gc, out, d_ct, B, nl, [galois_element(k, p.logN) for k in steps], keys, ws)
+    got = to_host(out)
+    bad = [b for b in range(B) if hashlib.sha256(np.ascontiguousarray(got[b]).tobytes()).hexdigest() != want[("hrot", b)]]
+    assert not bad, "rotations differ from the oracle's digests: %s" % bad
+    del keys
+    relin = to_dev(uniform_residues(999, p.moduli, (p.dnum, 2), p.N))
+    prod = torch.empty((B // 2, 2, nl, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_hmult_relin(gc, prod, d_ct[0::2].contiguous(), d_ct[1::2].contiguous(), B // 2, nl, relin, ws)
+    got = to_host(prod)
+    bad = [i for i in range(B // 2)
+           if hashlib.sha256(np.ascontiguousarray(got[i]).tobytes()).hexdigest() != want[("hmult", i)]]
+    assert not bad, "products differ from the oracle's digests: %s" % bad
+    gc.close()
+
+
 def test_argument_errors(gpu):
     import torch
     from gpu_util import to_dev
