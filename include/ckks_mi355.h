@@ -219,7 +219,10 @@ int ckks_prof_enable(ckks_ctx* ctx, int on);
  * chains (double-precision slots / special-prime slots) onto a second internal stream and join them before the
  * result is assembled (default 1: everything on the caller's stream); knob 5 != 0 makes every base conversion
  * use the general four-sum accumulation with a 128-bit Montgomery reduction, also where the bit sizes of the
- * bases would allow the shorter three-sum form (set before the first call at a given limb count). */
+ * bases would allow the shorter three-sum form (set before the first call at a given limb count); knob 6 != 0
+ * computes the inner sums of ckks_pcmm_bsgs with the integer kernel on every limb (default: double precision on
+ * primes < 2^50), knob 7 > 0 caps the number of giant steps whose inner sums one pass over the baby-step
+ * ciphertexts computes (default and maximum 24). */
 int ckks_tune_set(ckks_ctx* ctx, int knob, int value);
 int ckks_prof_num_kinds(void);
 const char* ckks_prof_kind_name(int kind);

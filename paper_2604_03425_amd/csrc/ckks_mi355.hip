@@ -147,7 +147,9 @@ struct ckks_ctx {
                                          // double-precision moduli (0 fused, two accumulators; 1 plain block pass +
                                          // streaming product; 2 fused, one key component per workgroup);
                                          // 4: 1 = one stream only (0 forks the two chains of a key switch);
-                                         // 5: 1 = base conversions always take the general (128-bit) reduction
+                                         // 5: 1 = base conversions always take the general (128-bit) reduction;
+                                         // 6: 1 = PCMM inner sums with the integer kernel on every limb;
+                                         // 7: > 0 caps the giant steps per pass of the PCMM inner sums
   bool prof_on = false;
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
@@ -1114,8 +1116,8 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlim
       return nlimbs < 2 ? 0 : align256((size_t)B * 2 * c->N * 8) + align256((size_t)B * 2 * (nlimbs - 1) * c->N * 8);
     case CKKS_OP_PCMM_BSGS:
       if (n1 == 0) return 0;
-      // baby steps 1..n1-1, PMACC_GT inner sums, rotated inner sum, HRot workspace
-      return (size_t)(n1 - 1) * 2 * poly + (size_t)PMACC_GT * 2 * poly + 2 * poly + ks + poly;
+      // baby steps 1..n1-1, PMACC_TILE inner sums, rotated inner sum, HRot workspace
+      return (size_t)(n1 - 1) * 2 * poly + (size_t)PMACC_TILE * 2 * poly + 2 * poly + ks + poly;
     default: return 0;
   }
 }
@@ -1339,7 +1341,7 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   const size_t ct_al = 2 * align256((size_t)B * polyN * 8);
   char* w = (char*)ws;
   u64* baby = (u64*)w;                  w += (size_t)(n1 - 1) * ct_al;
-  u64* inner = (u64*)w;                 w += (size_t)PMACC_GT * ct_al;   // inner sums of one tile of giant steps
+  u64* inner = (u64*)w;                 w += (size_t)PMACC_TILE * ct_al;   // inner sums of one tile of giant steps
   u64* rot = (u64*)w;                   w += ct_al;
   char* hws = w;
   const size_t hws_bytes = ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0);
@@ -1365,26 +1367,68 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
       if (rc) return rc;
     }
   }
-  for (u32 g0 = 0; g0 < n2; g0 += PMACC_GT) {
-    const u32 ng = std::min<u32>(PMACC_GT, n2 - g0);
+  // limbs by arithmetic kind: the double-precision kernel computes up to 6 giant steps x 8 polynomials per pass
+  // over the baby-step ciphertexts, the integer kernel PMACC_GT giant steps of one polynomial
+  PmaccArgs fa, ia;
+  u32 nfp = 0, nint = 0;
+  for (u32 i = 0; i < nlimbs; i++) {
+    if (host_class(c, c->mod[i]) == 0 && c->tune[6] == 0) fa.limbs[nfp++] = (unsigned char)i;
+    else ia.limbs[nint++] = (unsigned char)i;
+  }
+  const u32 tile_max = c->tune[7] > 0 ? std::min<u32>(PMACC_TILE, (u32)c->tune[7]) : PMACC_TILE;
+  for (u32 g0 = 0; g0 < n2;) {
+    const u32 ng = std::min<u32>(tile_max, n2 - g0);
     // giant step 0 needs no rotation: its inner sum is written straight into the output
-    PmaccArgs a{(const u64*)ct_in, baby, (const u64*)pt, g0 == 0 ? (u64*)ct_out : inner, inner + ct_elems, c->d_mods,
-                c->logN, nlimbs, n1, B, g0, ng};
-    {
+    auto fill = [&](PmaccArgs& a, u32 first, u32 count) {
+      a.ct_in = (const u64*)ct_in;
+      a.baby = baby;
+      a.pt = (const u64*)pt;
+      a.out0 = first == 0 ? (u64*)ct_out : inner + (size_t)(first - g0) * ct_elems;
+      a.out_rest = inner + (size_t)(first - g0 + 1) * ct_elems;
+      a.mods = c->d_mods;
+      a.logN = c->logN;
+      a.nlimbs = nlimbs;
+      a.n1 = n1;
+      a.B = B;
+      a.g0 = first;
+      a.ng = count;
+    };
+    for (u32 h0 = g0; nfp && h0 < g0 + ng;) {
+      static const u32 kSizes[] = {6, 4, 3, 2, 1};
+      u32 cnt = 1;
+      for (u32 sz : kSizes)
+        if (sz <= g0 + ng - h0) {
+          cnt = sz;
+          break;
+        }
+      const u32 ngt = (g0 + ng - h0) / cnt;   // as many whole tiles of this size as remain, in one launch
+      fill(fa, h0, cnt);
+      fa.ngt = ngt;
       ProfScope ps(c, PK_PMACC, st);
-      dim3 grid(2 * B, N / 512, nlimbs), block(256);
-      switch (ng) {
-        case 8: hipLaunchKernelGGL(pmacc_kernel<8>, grid, block, 0, st, a); break;
-        case 7: hipLaunchKernelGGL(pmacc_kernel<7>, grid, block, 0, st, a); break;
-        case 6: hipLaunchKernelGGL(pmacc_kernel<6>, grid, block, 0, st, a); break;
-        case 5: hipLaunchKernelGGL(pmacc_kernel<5>, grid, block, 0, st, a); break;
-        case 4: hipLaunchKernelGGL(pmacc_kernel<4>, grid, block, 0, st, a); break;
-        case 3: hipLaunchKernelGGL(pmacc_kernel<3>, grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL(pmacc_kernel<2>, grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL(pmacc_kernel<1>, grid, block, 0, st, a); break;
+      dim3 grid((2 * B + PMACC_FP_P - 1) / PMACC_FP_P * ngt, N / 256, nfp), block(256);
+      switch (cnt) {
+        case 6: hipLaunchKernelGGL(pmacc_fp_kernel<6>, grid, block, 0, st, fa); break;
+        case 4: hipLaunchKernelGGL(pmacc_fp_kernel<4>, grid, block, 0, st, fa); break;
+        case 3: hipLaunchKernelGGL(pmacc_fp_kernel<3>, grid, block, 0, st, fa); break;
+        case 2: hipLaunchKernelGGL(pmacc_fp_kernel<2>, grid, block, 0, st, fa); break;
+        default: hipLaunchKernelGGL(pmacc_fp_kernel<1>, grid, block, 0, st, fa); break;
       }
+      HIP_TRY(hipGetLastError());
+      h0 += cnt * ngt;
     }
-    HIP_TRY(hipGetLastError());
+    for (u32 h0 = g0; nint && h0 < g0 + ng; h0 += PMACC_GT) {
+      const u32 cnt = std::min<u32>(PMACC_GT, g0 + ng - h0);
+      fill(ia, h0, cnt);
+      ProfScope ps(c, PK_PMACC, st);
+      dim3 grid(2 * B, N / 512, nint), block(256);
+      switch (cnt) {
+        case 4: hipLaunchKernelGGL(pmacc_kernel<4>, grid, block, 0, st, ia); break;
+        case 3: hipLaunchKernelGGL(pmacc_kernel<3>, grid, block, 0, st, ia); break;
+        case 2: hipLaunchKernelGGL(pmacc_kernel<2>, grid, block, 0, st, ia); break;
+        default: hipLaunchKernelGGL(pmacc_kernel<1>, grid, block, 0, st, ia); break;
+      }
+      HIP_TRY(hipGetLastError());
+    }
     for (u32 k = 0; k < ng; k++) {
       const u32 g = g0 + k;
       if (g == 0) continue;
@@ -1403,6 +1447,7 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
         HIP_TRY(hipGetLastError());
       }
     }
+    g0 += ng;
   }
   return CKKS_OK;
 }

@@ -406,8 +406,11 @@ struct PmaccArgs {
   u64* out_rest;      // [GT-1][B][2][nlimbs][N]: destinations of giant steps g0+1 .. g0+GT-1
   const ModInfo* mods;
   u32 logN, nlimbs, n1, B, g0, ng;  // ng <= GT giant steps are computed
+  u32 ngt;                          // pmacc_fp_kernel: the launch covers ngt consecutive tiles of NG giant steps
+  unsigned char limbs[128];         // grid.z index -> limb (the launch covers the limbs of one arithmetic kind)
 };
-#define PMACC_GT 4
+#define PMACC_GT 4        // giant steps per pass of the integer kernel
+#define PMACC_TILE 24     // giant steps whose inner sums are held in the workspace at once
 template <int NG>
 __global__ void __launch_bounds__(256) pmacc_kernel(PmaccArgs a) {
   const u32 N = 1u << a.logN;
@@ -424,7 +427,7 @@ __global__ void __launch_bounds__(256) pmacc_kernel(PmaccArgs a) {
     bc = lin % gridDim.x;
     group = lin / gridDim.x;
   }
-  const u32 nb = group % gridDim.y, i = group / gridDim.y;
+  const u32 nb = group % gridDim.y, i = a.limbs[group / gridDim.y];
   const u32 n = (nb * 256 + threadIdx.x) * 2;
   const ModInfo mi = a.mods[i];
   const size_t ct_sz = (size_t)a.B * 2 * a.nlimbs * N;
@@ -476,6 +479,79 @@ __global__ void __launch_bounds__(256) pmacc_kernel(PmaccArgs a) {
   for (int g = 0; g < NG; g++) {
     u64* dst = g == 0 ? a.out0 + o : a.out_rest + (size_t)(g - 1) * ct_sz + o;
     *(ulonglong2*)dst = ulonglong2{run[g][0], run[g][1]};
+  }
+}
+
+// The same inner sums on double-precision moduli (q < 2^50), register-tiled like a small matrix product: a lane owns
+// one coefficient position and keeps the running sums of PMACC_FP_P polynomials x NG giant steps (one double each:
+// every product is reduced on the spot with 5 FP64 instructions), so per baby step it loads P ciphertext words and
+// NG plaintext words for P * NG multiply-adds: 8/P + 8/NG bytes per multiply-add instead of 16. grid =
+// (ceil(2B / P) * ngt, N / 256, limbs of the class): polynomial groups innermost, then the ngt tiles of NG giant
+// steps, so the workgroups that share a plaintext tile or a set of baby-step words run together on one XCD and
+// find each other's fetches in its L2 (the HBM read counter equals one pass over the plaintexts and the baby steps).
+#define PMACC_FP_P 8
+template <int NG>
+__global__ void __launch_bounds__(256) pmacc_fp_kernel(PmaccArgs a) {
+  constexpr int P = PMACC_FP_P;
+  const u32 N = 1u << a.logN;
+  const u32 lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  u32 xi, group;
+  if (((gridDim.y * gridDim.z) & 7) == 0) {   // same placement as pmacc_kernel
+    const u32 rest = lin >> 3;
+    xi = rest % gridDim.x;
+    group = (lin & 7) + 8 * (rest / gridDim.x);
+  } else {
+    xi = lin % gridDim.x;
+    group = lin / gridDim.x;
+  }
+  const u32 npg = gridDim.x / a.ngt, pg = xi % npg, gt = xi / npg;
+  const u32 nb = group % gridDim.y, i = a.limbs[group / gridDim.y];
+  const u32 n = nb * 256 + threadIdx.x;
+  const ModInfo mi = a.mods[i];
+  const double q = mi.qd, qinv = mi.qinv;
+  const u32 npoly = 2 * a.B;
+  const size_t ct_sz = (size_t)npoly * a.nlimbs * N;
+  const size_t pt_g = (size_t)a.n1 * a.nlimbs * N;
+  size_t o[P];   // the last group may be short: its surplus lanes recompute the last polynomial and store nothing
+#pragma unroll
+  for (int p = 0; p < P; p++) o[p] = ((size_t)min(pg * P + p, npoly - 1) * a.nlimbs + i) * N + n;
+  double s[P][NG];
+#pragma unroll
+  for (int p = 0; p < P; p++)
+#pragma unroll
+    for (int g = 0; g < NG; g++) s[p][g] = 0.0;
+  for (u32 k = 0; k < a.n1; k++) {
+    const u64* src = k == 0 ? a.ct_in : a.baby + (size_t)(k - 1) * ct_sz;
+    const u64* w = a.pt + (size_t)(a.g0 + gt * NG) * pt_g + ((size_t)k * a.nlimbs + i) * N + n;
+    u64 xr[P], cr[NG];
+#pragma unroll
+    for (int p = 0; p < P; p++) xr[p] = src[o[p]];
+#pragma unroll
+    for (int g = 0; g < NG; g++) cr[g] = w[(size_t)g * pt_g];
+    double c[NG];
+#pragma unroll
+    for (int g = 0; g < NG; g++) c[g] = u2d(cr[g]);
+    // each product is below 0.75 q in magnitude: four of them and a folded sum stay below 2^52
+    const bool fold = (k & 3) == 3;
+#pragma unroll
+    for (int p = 0; p < P; p++) {
+      const double x = u2d(xr[p]);
+#pragma unroll
+      for (int g = 0; g < NG; g++) {
+        s[p][g] += fp_mulmod_var(x, c[g], qinv, q);
+        if (fold) s[p][g] = fp_reduce(s[p][g], qinv, q);
+      }
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < P; p++) {
+    if (pg * P + p >= npoly) break;
+#pragma unroll
+    for (int g = 0; g < NG; g++) {
+      const u32 rel = gt * NG + g;   // giant step relative to the launch's first one
+      u64* dst = (rel == 0 ? a.out0 : a.out_rest + (size_t)(rel - 1) * ct_sz) + o[p];
+      *dst = d2u_canon(fp_reduce(s[p][g], qinv, q), q);
+    }
   }
 }
 

@@ -190,13 +190,30 @@ def test_hmult_relin(gpu, shape, nlimbs, B):
     assert_same(to_host(out), rc.hmult_relin(a, b, evk), "hmult_relin")
 
 
-@pytest.mark.parametrize("n1,n2,stride", [(3, 2, 1), (1, 3, 2), (4, 1, 1), (9, 2, 1)])
-def test_pcmm_bsgs(gpu, n1, n2, stride):
+PCMM_CASES = [
+    # n1 n2 stride, shape, tuning knobs
+    (3, 2, 1, (12, 4, 40, 2, 50, 2), {}),
+    (1, 3, 2, (12, 4, 40, 2, 50, 2), {}),
+    (4, 1, 1, (12, 4, 40, 2, 50, 2), {}),
+    (9, 2, 1, (12, 4, 40, 2, 50, 2), {}),
+    (5, 7, 1, (12, 4, 40, 2, 50, 2), {}),          # 7 giant steps = passes of 6 and 1
+    (17, 13, 1, (12, 4, 40, 2, 50, 2), {7: 12}),   # more than 16 terms per sum; passes of 12 and 1
+    (5, 7, 1, (12, 4, 40, 2, 50, 2), {6: 1}),      # integer kernel on every limb: passes of 4 and 3
+    (3, 5, 1, (12, 4, 60, 2, 60, 2), {}),          # 60-bit primes: integer kernel by necessity
+]
+
+
+@pytest.mark.parametrize("n1,n2,stride,shape,knobs", PCMM_CASES)
+def test_pcmm_bsgs(gpu, n1, n2, stride, shape, knobs):
     import torch
     from gpu_util import to_dev, to_host, assert_same
-    shape = (12, 4, 40, 2, 50, 2)
     p = shape_params(shape)
-    rc, gc = contexts(gpu, shape, p)
+    if knobs:
+        rc, gc = ref.RefContext(p), gpu.Context(p)
+        for k, v in knobs.items():
+            gpu.ckks_tune_set(gc, k, v)
+    else:
+        rc, gc = contexts(gpu, shape, p)
     B, nl = 2, 4
     ct = uniform_residues(41, p.q, (B, 2), p.N)
     pt = uniform_residues(42, p.q, (n2, n1), p.N)
