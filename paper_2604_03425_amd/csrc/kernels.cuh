@@ -531,16 +531,19 @@ __global__ void __launch_bounds__(256) pmacc_fp_kernel(PmaccArgs a) {
     double c[NG];
 #pragma unroll
     for (int g = 0; g < NG; g++) c[g] = u2d(cr[g]);
-    // each product is below 0.75 q in magnitude: four of them and a folded sum stay below 2^52
-    const bool fold = (k & 3) == 3;
 #pragma unroll
     for (int p = 0; p < P; p++) {
       const double x = u2d(xr[p]);
 #pragma unroll
-      for (int g = 0; g < NG; g++) {
-        s[p][g] += fp_mulmod_var(x, c[g], qinv, q);
-        if (fold) s[p][g] = fp_reduce(s[p][g], qinv, q);
-      }
+      for (int g = 0; g < NG; g++) s[p][g] += fp_mulmod_var(x, c[g], qinv, q);
+    }
+    // each product is below 0.75 q in magnitude: four of them and a folded sum stay below 2^52. A separate
+    // (wave-uniform) branch, so that the reduction is not computed and discarded on the other three steps.
+    if ((k & 3) == 3) {
+#pragma unroll
+      for (int p = 0; p < P; p++)
+#pragma unroll
+        for (int g = 0; g < NG; g++) s[p][g] = fp_reduce(s[p][g], qinv, q);
     }
   }
 #pragma unroll

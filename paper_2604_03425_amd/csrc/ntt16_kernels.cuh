@@ -275,12 +275,14 @@ __device__ __forceinline__ void fwd_inner_body_fp(const FwdInnerArgs& a, u32 b, 
     if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0, g);
     __builtin_amdgcn_sched_barrier(0);
     // each product is below 0.9 q in magnitude; bring the sums back before they can reach 2^53
-    const bool fold = (j & 3) == 3;
 #pragma unroll
     for (int i = 0; i < 16; i++) {
       acc0[i] += fp_mulmod_var(x[i], u2d(kb[i * 16]), qinv, q);
       acc1[i] += fp_mulmod_var(x[i], u2d(ka[i * 16]), qinv, q);
-      if (fold) {
+    }
+    if ((j & 3) == 3) {
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
         acc0[i] = fp_reduce(acc0[i], qinv, q);
         acc1[i] = fp_reduce(acc1[i], qinv, q);
       }
@@ -353,11 +355,11 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
       });
     }
     __builtin_amdgcn_sched_barrier(0);
-    const bool fold = (j & 3) == 3;
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-      acc[i] += fp_mulmod_var(x[i], u2d(e[i]), qinv, q);
-      if (fold) acc[i] = fp_reduce(acc[i], qinv, q);
+    for (int i = 0; i < 16; i++) acc[i] += fp_mulmod_var(x[i], u2d(e[i]), qinv, q);
+    if ((j & 3) == 3) {   // each product is below 0.75 q: fold before the sum can reach 2^53 (own uniform branch)
+#pragma unroll
+      for (int i = 0; i < 16; i++) acc[i] = fp_reduce(acc[i], qinv, q);
     }
   }
   u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + lane_pos();
