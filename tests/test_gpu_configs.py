@@ -236,19 +236,20 @@ def test_attention_av_unit(gpu, name, nl, B, hd):
     assert_same(to_host(got), want, "attention A x V unit")
 
 
-@pytest.mark.parametrize("name,nl,B", [("tiny_hrot", 4, 8), ("keyswitch_micro", 24, 3)])
+@pytest.mark.parametrize("name,nl,B", [("tiny_hrot", 4, 8), ("keyswitch_micro", 24, 3),
+                                       ((16, 2, 50, 1, 60, 2), 2, 67)])   # more than 64: two launch sequences
 def test_hrot_multi_matches_single_rotations(gpu, name, nl, B):
     """One Galois element and key per ciphertext in one call = the oracle's HRot of each ciphertext on its own
     (the tiny configuration's "each rotated by a seeded step"; the micro-benchmark's seeded Galois elements)."""
     import torch
     from ckks_inputs import seeded_rotation_steps
     from gpu_util import to_dev, to_host, assert_same
-    p = config_params(name)
+    p = config_params(name) if isinstance(name, str) else make_params(*name)
     rc, gc = ref.RefContext(p), gpu.Context(p)
     ct = uniform_residues(400, p.q[:nl], (B, 2), p.N)
     steps = seeded_rotation_steps(401, B, 1, p.N // 2 - 1)
     gs = [galois_element(k, p.logN) for k in steps]
-    nkeys = max(2, B - 1)                     # the last ciphertext shares the first one's key: pointers may repeat
+    nkeys = min(9, max(2, B - 1))             # fewer keys than ciphertexts: pointers repeat
     keys = [uniform_residues(410 + i, p.moduli, (p.dnum, 2), p.N) for i in range(nkeys)]
     kidx = [i % nkeys for i in range(B)]
     ref.set_threads(4)

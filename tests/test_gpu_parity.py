@@ -329,6 +329,14 @@ def test_argument_errors(gpu):
     with pytest.raises(gpu.CkksError) as e:
         gpu.ckks_keyswitch(gc, out, x[:, 0].contiguous(), 1, 4, evk, 0, 3, ws)   # wrong dnum
     assert e.value.code == -2
+    with pytest.raises(gpu.CkksError) as e:
+        gpu.ckks_hrot_multi(gc, out, x, 1, 4, [6], [evk], ws)   # even Galois element in the per-ciphertext list
+    assert e.value.code == -1
+    with pytest.raises(ValueError):
+        gpu.ckks_hrot_multi(gc, out, x, 1, 4, [5, 25], [evk], ws)   # list lengths must equal the batch
+    with pytest.raises(gpu.CkksError) as e:
+        gpu.ckks_rescale(gc, out, x, 1, 1, ws)                  # nothing to drop
+    assert e.value.code == -2
     bad = make_params(12, 2, 40, 1, 50, 1)
     bad.q[0] += 2
     with pytest.raises(gpu.CkksError):
