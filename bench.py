@@ -430,6 +430,10 @@ def main():
       out_rs = torch.empty((B, 2, nl - 1, N), dtype=torch.int64, device=dev)
       t_rs = timed(lambda: ck.ckks_rescale(ctx, out_rs, ct, B, nl, ws_rs), 3)
       pt1 = ct[0, 0].contiguous()
+      # the Galois automorphism as a call of its own (inside HRot it is a gather fused into the loads)
+      g_auto = galois_element(4321, p.logN)
+      t_au = timed(lambda: ck.ckks_automorph(ctx, out_rot, ct, B * 2, ids, g_auto, True), 3)
+      t_auc = timed(lambda: ck.ckks_automorph(ctx, out_rot, ct, B * 2, ids, g_auto, False), 3)
       t_pm = timed(lambda: ck.ckks_pmult(ctx, out_rot, ct, pt1, B, nl), 3)
       t_ad = timed(lambda: ck.ckks_add(ctx, out_rot, ct, out_rot, B * 2, nl), 3)
       extra = dict(ntt_limbs_per_s=round(B * 2 * nl / t_ntt), intt_limbs_per_s=round(B * 2 * nl / t_intt),
@@ -438,6 +442,8 @@ def main():
                    hmult_relin_per_s=round(B / 2 / t_mul, 1),
                  rescale_per_s=round(B / t_rs, 1),
                  rescale_hbm_frac=round(B * 2 * (4 + 3 * (nl - 1) + 4 * (nl - 1)) * 8 * N / t_rs / 1e9 / PEAK_HBM_GBS, 4),
+                 automorph_eval_GBps=round(B * 2 * nl * 2 * 8 * N / t_au / 1e9, 1),
+                 automorph_coeff_GBps=round(B * 2 * nl * 2 * 8 * N / t_auc / 1e9, 1),
                  pmult_hbm_frac=round(B * 2 * nl * 2 * 8 * N / t_pm / 1e9 / PEAK_HBM_GBS, 4),
                  add_hbm_frac=round(B * 2 * nl * 3 * 8 * N / t_ad / 1e9 / PEAK_HBM_GBS, 4),
                    ntt_int32_equiv_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
