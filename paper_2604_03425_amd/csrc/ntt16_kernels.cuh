@@ -450,7 +450,7 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
   const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
   const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(bc >> 1)] : a.galois;
   u64 ad[16];
-  if (mode == 1) {
+  if (mode & 1) {
 #pragma unroll
     for (int i = 0; i < 16; i++) ad[i] = o[i * 16];
   } else if (mode == 2) {
@@ -463,9 +463,11 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
 #pragma unroll
   for (int i = 0; i < 16; i++) {
     double r = fp_mulmod_const(u2d(av[i]) - x[i], pv.x, pv.y, q);  // |r| <= 0.9 q
-    if (mode == 1 || mode == 2) r += u2d(ad[i]);
-    if (mode == 3) r += u2d(o[i * 16]) + u2d(as[galois_src_index16(h * 256 + i * 16 + j0, g)]);
-    if (mode == 3) r = r >= q ? r - q : r;  // two addends: bring the sum back below 2q first
+    if (mode) r += u2d(ad[i]);
+    if (mode == 3) {   // two addends: the gathered one is fetched here; bring the sum back below 2q first
+      r += u2d(as[galois_src_index16(h * 256 + i * 16 + j0, g)]);
+      r = r >= q ? r - q : r;
+    }
     o[i * 16] = d2u_canon(r, q);
   }
 }
