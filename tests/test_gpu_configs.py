@@ -260,3 +260,72 @@ def test_hrot_multi_matches_single_rotations(gpu, name, nl, B):
     gpu.ckks_hrot_multi(gc, out, to_dev(ct), B, nl, gs, [dkeys[i] for i in kidx], gc.workspace(gpu.OP_HROT, B, nl))
     assert_same(to_host(out), want, "hrot_multi")
     gc.close()
+
+
+@pytest.mark.parametrize("shape", [(16, 4, 50, 2, 60, 2), (12, 4, 40, 2, 50, 2), (16, 3, 60, 2, 60, 2)])
+def test_extreme_residues(gpu, shape):
+    """Inputs at the ends of the residue range (every residue q-1, and 0 / q-1 alternating), keys and plaintexts at
+    m-1: the lazy ranges of the kernels (double-precision sums, 30-bit partial products, Harvey butterflies) are
+    argued from these maxima."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(*shape)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    nl, B = len(p.q), 2
+    top = np.array(p.q, dtype=np.uint64)[None, None, :, None] - np.uint64(1)
+    ct = np.broadcast_to(top, (B, 2, nl, p.N)).copy()
+    ct[1, :, :, ::2] = 0
+    mtop = np.array(p.moduli, dtype=np.uint64)[None, None, :, None] - np.uint64(1)
+    evk = np.broadcast_to(mtop, (p.dnum, 2, len(p.moduli), p.N)).copy()
+    g = galois_element(5, p.logN)
+    ws = gc.workspace(gpu.OP_HROT, B, nl)
+    d_ct, d_evk = to_dev(ct), to_dev(evk)
+    out = torch.empty_like(d_ct)
+    ref.set_threads(2)
+    gpu.ckks_hrot(gc, out, d_ct, B, nl, g, d_evk, ws)
+    assert_same(to_host(out), rc.hrot(ct, g, evk), "hrot at the maxima")
+    gpu.ckks_hmult_relin(gc, out, d_ct, d_ct.flip(0).contiguous(), B, nl, d_evk, ws)
+    assert_same(to_host(out), rc.hmult_relin(ct, ct[::-1].copy(), evk), "hmult at the maxima")
+    rs = torch.empty((B, 2, nl - 1, p.N), dtype=torch.int64, device="cuda")
+    gpu.ckks_rescale(gc, rs, d_ct, B, nl, gc.workspace(gpu.OP_RESCALE, B, nl))
+    assert_same(to_host(rs), rc.rescale(ct), "rescale at the maxima")
+    n1, n2 = 9, 2
+    pt = np.broadcast_to(top[0], (n2, n1, nl, p.N)).copy()
+    keys = [evk] * (n1 - 1 + n2 - 1)
+    want = rc.pcmm_bsgs(ct, pt, n1, n2, 1, keys[:n1 - 1], keys[n1 - 1:])
+    ref.set_threads(1)
+    gpu.ckks_pcmm_bsgs(gc, out, d_ct, B, nl, to_dev(pt), n1, n2, 1, [d_evk] * (n1 - 1), [d_evk] * (n2 - 1),
+                       gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
+    assert_same(to_host(out), want, "pcmm at the maxima")
+    gc.close()
+
+
+def test_tuning_knobs_do_not_change_results(gpu):
+    """Every alternative code path selectable with ckks_tune_set gives the oracle's bits: workgroup mappings,
+    the three forms of the inner product on double-precision moduli, the 3-wave build of the fused kernel, and the
+    two-stream fork/join of a key switch."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(16, 5, 50, 3, 60, 2)
+    rc = ref.RefContext(p)
+    B, nl = 3, 5
+    ct = uniform_residues(500, p.q, (B, 2), p.N)
+    evk = uniform_residues(501, p.moduli, (p.dnum, 2), p.N)
+    g = galois_element(77, p.logN)
+    ref.set_threads(3)
+    want_rot = rc.hrot(ct, g, evk)
+    want_mul = rc.hmult_relin(ct, ct[::-1].copy(), evk)
+    ref.set_threads(1)
+    d_ct, d_evk = to_dev(ct), to_dev(evk)
+    d_rev = d_ct.flip(0).contiguous()
+    for knobs in ({0: 0}, {0: 1}, {0: 2}, {0: 3}, {3: 0}, {3: 0, 2: 1}, {3: 1}, {3: 1, 4: 0}, {3: 2, 4: 0}, {1: 1, 3: 0}):
+        gc = gpu.Context(p)
+        for k, v in knobs.items():
+            gpu.ckks_tune_set(gc, k, v)
+        ws = gc.workspace(gpu.OP_HROT, B, nl)
+        out = torch.empty_like(d_ct)
+        gpu.ckks_hrot(gc, out, d_ct, B, nl, g, d_evk, ws)
+        assert_same(to_host(out), want_rot, "hrot with knobs %s" % knobs)
+        gpu.ckks_hmult_relin(gc, out, d_ct, d_rev, B, nl, d_evk, ws)
+        assert_same(to_host(out), want_mul, "hmult with knobs %s" % knobs)
+        gc.close()
