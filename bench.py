@@ -187,11 +187,10 @@ def other_workloads(args):
 
         def units():
             ck.ckks_hmult_relin(ctx, acc, qa, kb, B, nl, relin, ws)
-            cur = acc
-            for i in range(6):
-                ck.ckks_hrot(ctx, tmp, cur, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
-                s = cur + tmp                                  # harness-side modular add of the rotate-and-sum
-                cur = torch.where(s >= mods, s - mods, s)
+            cur, nxt = acc, tmp
+            for i in range(6):   # rotate-and-sum: next = cur + HRot(cur)
+                ck.ckks_hrot_add(ctx, nxt, cur, cur, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
+                cur, nxt = nxt, cur
         dt = _time(torch, units, 2)
         print(json.dumps({"workload": "attention_qk_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
                           "key_switches_per_s": round(7 * B / dt, 1),
@@ -215,16 +214,18 @@ def other_workloads(args):
 
         def units():
             ck.ckks_hmult_relin(ctx, d, qa, kb, B, nl, relin, ws)
+            cur, nxt = d, tmp
             for i in range(6):
-                ck.ckks_hrot(ctx, tmp, d, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
-                ck.ckks_add(ctx, d, d, tmp, B * 2, nl)
-            ck.ckks_rescale(ctx, d1, d, B, nl, ws)
+                ck.ckks_hrot_add(ctx, nxt, cur, cur, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
+                cur, nxt = nxt, cur
+            ck.ckks_rescale(ctx, d1, cur, B, nl, ws)
             ck.ckks_pmult(ctx, m1, d1, mask, B, nl - 1)
             ck.ckks_rescale(ctx, m, m1, B, nl - 1, ws)
+            cur, nxt = m, tmp2
             for i in range(6):
-                ck.ckks_hrot(ctx, tmp2, m, B, nl - 2, galois_element(-(1 << i), p.logN), rot[6 + i], ws)
-                ck.ckks_add(ctx, m, m, tmp2, B * 2, nl - 2)
-            ck.ckks_hmult_relin(ctx, out, m, vb, B, nl - 2, relin, ws)
+                ck.ckks_hrot_add(ctx, nxt, cur, cur, B, nl - 2, galois_element(-(1 << i), p.logN), rot[6 + i], ws)
+                cur, nxt = nxt, cur
+            ck.ckks_hmult_relin(ctx, out, cur, vb, B, nl - 2, relin, ws)
         dt = _time(torch, units, 2)
         print(json.dumps({"workload": "attention_av_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
                           "key_switches_per_s": round(14 * B / dt, 1),

@@ -131,6 +131,16 @@ int ckks_hrot(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B
               uint32_t galois_elt, const uint64_t* evk_rot, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Rotate-and-add (the step of the rotate-and-sum reductions and of the rotate-multiply-accumulate loops of the
+ * attention and linear layers, paper Sec. 4.2-4.3): ct_out = ct_add + HRot_{galois_elt}(ct_in), with the addition
+ * done where the rotation's result is assembled instead of in a pass of its own. ct_add is a device ciphertext
+ * batch like ct_in; it may be ct_in (rotate-and-sum) or, at N = 2^16, ct_out itself (accumulate in place);
+ * otherwise it must not overlap ct_out. Everything else as for ckks_hrot.
+ */
+int ckks_hrot_add(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, const uint64_t* ct_add, uint32_t B,
+                  uint32_t nlimbs, uint32_t galois_elt, const uint64_t* evk_rot, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * HRot with a Galois element and a rotation key per ciphertext (the batch of the key-switch micro-benchmark is
  * rotated "by seeded Galois elements"; same definition as ckks_hrot, Sec. 2.1 Rot): ct_out[b] =
  * HRot_{galois_elts[b]}(ct_in[b]) with evks[b], i.e. exactly what B calls of ckks_hrot with B = 1 return, but

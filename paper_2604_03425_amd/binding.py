@@ -17,7 +17,7 @@ _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_work
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
             "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
-            "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi"]
+            "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi", "ckks_hrot_add"]
 
 
 class CkksError(RuntimeError):
@@ -57,6 +57,7 @@ def _load():
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_hrot_hoisted.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), C.c_uint32, vp,
                                       C.c_size_t, vp]
+    lib.ckks_hrot_add.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_hrot_multi.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs_hoisted.argtypes = lib.ckks_pcmm_bsgs.argtypes
     lib.ckks_rescale.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, vp, C.c_size_t, vp]
@@ -196,6 +197,11 @@ def ckks_hrot_hoisted(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
     keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk").value for k in evks])
     _check(_lib.ckks_hrot_hoisted(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys, R,
                                   _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_hrot_add(ctx, ct_out, ct_in, ct_add, B, nlimbs, galois_elt, evk_rot, ws):
+    _check(_lib.ckks_hrot_add(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), _ptr(ct_add, "ct_add"), B, nlimbs,
+                              galois_elt, _ptr(evk_rot, "evk_rot"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
 
 
 def ckks_hrot_multi(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):

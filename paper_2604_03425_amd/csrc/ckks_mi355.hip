@@ -580,12 +580,13 @@ struct KsIo {
   u64 d_stride;
   u32 d_galois;          // != 0: d is read through the eval-domain Galois map (HRot's sigma(c1)); N = 2^16 path only
   u64* out;              // [B][2][nlimbs][N]
-  u32 mode[2];           // per component: 0 out = ks; 1 out += ks; 2 out = ks + sigma_g(add_src) (N = 2^16 path only)
+  u32 mode[2];           // per component: bit 0: + add2 (out itself when null); bit 1: + sigma_g(add_src) (N = 2^16 path only)
   const u64* add_src;    // [B][2][nlimbs][N]
   u32 add_galois;
   // N = 2^16 path, B <= KS_MULTI_MAX: ciphertext b uses galois_pc[b] (for d and add_src) and the key evk_pc[b]
   const u32* galois_pc = nullptr;
   const u64* const* evk_pc = nullptr;
+  const u64* add2 = nullptr;   // [B][2][nlimbs][N] plain addend of mode bit 0 (N = 2^16 path); null = out, in place
 };
 
 // Second half of a key switch on the N = 2^16 path: from the accumulators (acc, all slots) to the assembled output.
@@ -621,6 +622,7 @@ int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 n
     a.acc = acc;
     a.out = io.out;
     a.add_src = io.add_src;
+    a.add2 = io.add2 ? io.add2 : io.out;
     a.tw = c->d_tw_fwd;
     a.twfp = c->d_twfp_fwd;
     a.mods = c->d_mods;
@@ -1185,14 +1187,14 @@ int ckks_keyswitch(ckks_ctx* c, uint64_t* ks_out, const uint64_t* d, uint32_t B,
 }
 
 static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
-                     const uint64_t* evk, void* ws, size_t ws_bytes, void* stream, bool accumulate);
+                     const uint64_t* evk, void* ws, size_t ws_bytes, void* stream, const uint64_t* ct_add);
 int ckks_hrot(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
               const uint64_t* evk, void* ws, size_t ws_bytes, void* stream) {
-  return hrot_impl(c, ct_out, ct_in, B, nlimbs, g, evk, ws, ws_bytes, stream, false);
+  return hrot_impl(c, ct_out, ct_in, B, nlimbs, g, evk, ws, ws_bytes, stream, nullptr);
 }
-// accumulate (N = 2^16 path only): ct_out += HRot(ct_in) instead of ct_out = HRot(ct_in).
+// ct_add != null: ct_out = ct_add + HRot(ct_in); ct_add == ct_out accumulates in place (N = 2^16 path only).
 static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
-                     const uint64_t* evk, void* ws, size_t ws_bytes, void* stream, bool accumulate) {
+                     const uint64_t* evk, void* ws, size_t ws_bytes, void* stream, const uint64_t* ct_add) {
   int rc = check_common(c, B, nlimbs);
   if (rc) return rc;
   if (!ct_out || !ct_in || !evk) return fail(CKKS_EINVAL, "null argument");
@@ -1200,17 +1202,20 @@ static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   if ((rc = check_ws(c, CKKS_OP_HROT, B, nlimbs, 0, ws, ws_bytes))) return rc;
   const size_t polyN = (size_t)nlimbs * c->N, ct_bytes = (size_t)B * 2 * polyN * 8;
   if (overlap(ct_out, ct_bytes, ct_in, ct_bytes)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
+  if (ct_add && ct_add != ct_out && overlap(ct_out, ct_bytes, ct_add, ct_bytes))
+    return fail(CKKS_EINVAL, "ct_add must be ct_out itself or not overlap it");
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
   hipStream_t st = (hipStream_t)stream;
   if (c->logN == 16) {
     // the permutation is applied where the ciphertext is read: by the first inverse pass and the fused inner product
-    // (sigma(c1)) and by the final assembly (sigma(c0))
-    KsIo io{(const u64*)ct_in + polyN, 2 * polyN, g, (u64*)ct_out, {accumulate ? 3u : 2u, accumulate ? 1u : 0u},
+    // (sigma(c1)) and by the final assembly (sigma(c0)), which also adds ct_add
+    KsIo io{(const u64*)ct_in + polyN, 2 * polyN, g, (u64*)ct_out, {ct_add ? 3u : 2u, ct_add ? 1u : 0u},
             (const u64*)ct_in, g};
+    io.add2 = (const u64*)ct_add;
     return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
   }
-  if (accumulate) return fail(CKKS_EINVAL, "internal: accumulating HRot needs the N = 2^16 path");
+  if (ct_add && ct_add == ct_out) return fail(CKKS_EINVAL, "internal: accumulating in place needs the N = 2^16 path");
   const size_t ks = ks_layout(c, B, nlimbs).total;
   u64* d = (u64*)((char*)ws + ks);
   const LimbMap qmap = identity_map(nlimbs);
@@ -1219,7 +1224,21 @@ static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
     return rc;
   if ((rc = launch_automorph(c, d, polyN, (const u64*)ct_in + polyN, 2 * polyN, B, nlimbs, qmap, g, true, st))) return rc;
   KsIo io{d, polyN, 0, (u64*)ct_out, {1, 0}, nullptr, 0};
-  return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
+  if ((rc = keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st))) return rc;
+  if (ct_add) {
+    AddArgs ad{(u64*)ct_out, (const u64*)ct_add, c->d_mods, c->logN, nlimbs};
+    ProfScope ps(c, PK_ADD, st);
+    hipLaunchKernelGGL(addto_kernel, dim3(c->N / 256, nlimbs, 2 * B), dim3(256), 0, st, ad);
+    HIP_TRY(hipGetLastError());
+  }
+  return CKKS_OK;
+}
+
+int ckks_hrot_add(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, const uint64_t* ct_add, uint32_t B, uint32_t nlimbs,
+                  uint32_t g, const uint64_t* evk, void* ws, size_t ws_bytes, void* stream) {
+  if (!ct_add) return fail(CKKS_EINVAL, "null argument");
+  if (c && c->logN != 16 && ct_add == ct_out) return fail(CKKS_EINVAL, "ct_add == ct_out needs N = 2^16");
+  return hrot_impl(c, ct_out, ct_in, B, nlimbs, g, evk, ws, ws_bytes, stream, ct_add);
 }
 
 int ckks_hrot_multi(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
@@ -1238,7 +1257,7 @@ int ckks_hrot_multi(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32
     // other ring sizes: one rotation at a time through the general path
     for (u32 b = 0; b < B; b++)
       if ((rc = hrot_impl(c, ct_out + b * 2 * polyN, ct_in + b * 2 * polyN, 1, nlimbs, galois_elts[b], evks[b], ws, ws_bytes,
-                          stream, false)))
+                          stream, nullptr)))
         return rc;
     return CKKS_OK;
   }
@@ -1435,7 +1454,7 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
       const u64* src = inner + (size_t)k * ct_elems;
       if (c->logN == 16) {
         rc = hrot_impl(c, ct_out, (const uint64_t*)src, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws,
-                       hws_bytes, stream, /*accumulate=*/true);
+                       hws_bytes, stream, /*ct_add=*/ct_out);
         if (rc) return rc;
       } else {
         rc = ckks_hrot(c, (uint64_t*)rot, (const uint64_t*)src, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws,
@@ -1492,6 +1511,7 @@ int ckks_rescale(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t 
     a.acc = (const u64*)ct_in;
     a.out = (u64*)ct_out;
     a.add_src = nullptr;
+    a.add2 = nullptr;
     a.tw = c->d_tw_fwd;
     a.twfp = c->d_twfp_fwd;
     a.mods = c->d_mods;

@@ -398,13 +398,14 @@ DEFINE_FWD_INNER_KERNEL(ntt16_fwd_blocks_inner_occ3_kernel, __attribute__((amdgp
 // ---- fused: last forward pass of the ModDown correction + final assembly ----
 // out[bc][i] = (acc[bc][i] - NTT(tq[bc][i])) * pinv[i]  (+ addend). On integer-class moduli acc and tq carry the
 // factor 2^-64 and pinv = 2^64/P; on double-precision moduli they are plain and pinv = (1/P, (1/P)/q).
-// addend modes per component c = bc & 1: 0 none; 1 the value already in out (in place); 2 add_src read through
-// the Galois map g (HRot's sigma(c0)); 3 both (an HRot accumulated into out).
+// addend modes per component c = bc & 1: 0 none; 1 the plain addend add2 (== out: in place); 2 add_src read
+// through the Galois map g (HRot's sigma(c0)); 3 both (an HRot added to another ciphertext or accumulated into out).
 struct FwdFinalArgs {
   const u64* tq;      // [B*2][nlimbs][N], after the row pass
   const u64* acc;     // [B*2][next][N]
   u64* out;           // [B*2][nlimbs][N]
-  const u64* add_src; // [B][2][nlimbs][N] (mode 2)
+  const u64* add2;    // [B*2][nlimbs][N] (mode bit 1); may be out itself
+  const u64* add_src; // [B][2][nlimbs][N] (mode bit 2)
   const ulonglong2* tw;
   const double* twfp; 
   const ModInfo* mods;
@@ -426,11 +427,12 @@ __device__ __forceinline__ void fwd_final_body(const FwdFinalArgs& a, u32 bc, u3
   u64* o = a.out + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
   const u32 mode = (bc & 1) ? a.mode1 : a.mode0;
   const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
+  const u64* a2 = a.add2 + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
   const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(bc >> 1)] : a.galois;
 #pragma unroll
   for (int i = 0; i < 16; i++) {
     u64 r = shoup(ac[i * 16] + q2 - x[i], pv.x, pv.y, q);
-    if (mode & 1) r = addmod(r, o[i * 16], q);
+    if (mode & 1) r = addmod(r, a2[i * 16], q);
     if (mode & 2) r = addmod(r, as[galois_src_index16(h * 256 + i * 16 + j0, g)], q);
     o[i * 16] = r;
   }
@@ -451,8 +453,9 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
   const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(bc >> 1)] : a.galois;
   u64 ad[16];
   if (mode & 1) {
+    const u64* a2 = a.add2 + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
 #pragma unroll
-    for (int i = 0; i < 16; i++) ad[i] = o[i * 16];
+    for (int i = 0; i < 16; i++) ad[i] = a2[i * 16];
   } else if (mode == 2) {
 #pragma unroll
     for (int i = 0; i < 16; i++) ad[i] = as[galois_src_index16(h * 256 + i * 16 + j0, g)];

@@ -26,6 +26,10 @@ class RefOps:
     def add(self, a, b):
         return self.c.pointwise(a, b, list(range(a.shape[2])), "add")
 
+    def hrot_add(self, a, add, g, key):
+        """add + HRot_g(a): by definition the rotation followed by the addition."""
+        return self.add(add, self.c.hrot(a, g, key))
+
     def rescale(self, a):
         return self.c.rescale(a)
 
@@ -63,6 +67,11 @@ class GpuOps:
         self.m.ckks_add(self.c, out, a, b, a.shape[0] * 2, a.shape[2])
         return out
 
+    def hrot_add(self, a, add, g, key):
+        out = self._new(a)
+        self.m.ckks_hrot_add(self.c, out, a, add, a.shape[0], a.shape[2], g, key, self.ws)
+        return out
+
     def rescale(self, a):
         out = self._new(a, a.shape[2] - 1)
         self.m.ckks_rescale(self.c, out, a, a.shape[0], a.shape[2], self.ws)
@@ -82,7 +91,7 @@ def score_diagonal(ops, logN, q_ct, k_rot, relin, sum_keys, hd):
     <q_t, k_{t+r}> (scale Delta^2); the other slots hold partial sums."""
     d = ops.hmult(q_ct, k_rot, relin)
     for i in range(hd.bit_length() - 1):
-        d = ops.add(d, ops.hrot(d, galois_element(1 << i, logN), sum_keys[i]))
+        d = ops.hrot_add(d, d, galois_element(1 << i, logN), sum_keys[i])
     return d
 
 
@@ -91,7 +100,7 @@ def mask_and_pack(ops, logN, d, mask_pt, rep_keys, hd):
     slots by rotations to the right by 1, 2, 4, ...; mask_pt is at one limb fewer than d."""
     m = ops.rescale(ops.pmult(ops.rescale(d), mask_pt))
     for i in range(hd.bit_length() - 1):
-        m = ops.add(m, ops.hrot(m, galois_element(-(1 << i), logN), rep_keys[i]))
+        m = ops.hrot_add(m, m, galois_element(-(1 << i), logN), rep_keys[i])
     return m
 
 

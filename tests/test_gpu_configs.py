@@ -329,3 +329,36 @@ def test_tuning_knobs_do_not_change_results(gpu):
         gpu.ckks_hmult_relin(gc, out, d_ct, d_rev, B, nl, d_evk, ws)
         assert_same(to_host(out), want_mul, "hmult with knobs %s" % knobs)
         gc.close()
+
+
+@pytest.mark.parametrize("shape,nl,B", [((12, 4, 40, 2, 50, 2), 4, 3), ((16, 5, 50, 3, 60, 2), 5, 2), ((16, 3, 60, 2, 60, 2), 3, 2)])
+def test_hrot_add(gpu, shape, nl, B):
+    """ct_add + HRot(ct_in) in one call: with a third ciphertext, with ct_add = ct_in (rotate-and-sum) and, at
+    N = 2^16, accumulated into ct_out in place."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(*shape)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    ct = uniform_residues(600, p.q[:nl], (B, 2), p.N)
+    other = uniform_residues(601, p.q[:nl], (B, 2), p.N)
+    evk = uniform_residues(602, p.moduli, (p.dnum, 2), p.N)
+    g = galois_element(321, p.logN)
+    ids = list(range(nl))
+    ref.set_threads(2)
+    rot = rc.hrot(ct, g, evk)
+    ref.set_threads(1)
+    ws = gc.workspace(gpu.OP_HROT, B, nl)
+    d_ct, d_other, d_evk = to_dev(ct), to_dev(other), to_dev(evk)
+    out = torch.empty_like(d_ct)
+    gpu.ckks_hrot_add(gc, out, d_ct, d_other, B, nl, g, d_evk, ws)
+    assert_same(to_host(out), rc.pointwise(other, rot, ids, "add"), "hrot_add, third ciphertext")
+    gpu.ckks_hrot_add(gc, out, d_ct, d_ct, B, nl, g, d_evk, ws)
+    assert_same(to_host(out), rc.pointwise(ct, rot, ids, "add"), "hrot_add, rotate-and-sum")
+    if p.logN == 16:
+        acc = d_other.clone()
+        gpu.ckks_hrot_add(gc, acc, d_ct, acc, B, nl, g, d_evk, ws)
+        assert_same(to_host(acc), rc.pointwise(other, rot, ids, "add"), "hrot_add, in place")
+    else:
+        with pytest.raises(gpu.CkksError):
+            gpu.ckks_hrot_add(gc, out, d_ct, out, B, nl, g, d_evk, ws)
+    gc.close()
