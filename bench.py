@@ -276,7 +276,7 @@ def main():
     ap.add_argument("--streams", type=int, default=1, help="HIP streams the independent calls of a step are spread over")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate NTT / HRot / HMult timings (profiling runs)")
     ap.add_argument("--workload", default="keyswitch_micro", choices=["keyswitch_micro", "pcmm", "attention", "attention_av", "sweep"])
-    ap.add_argument("--pcmm-batch", type=int, default=16)
+    ap.add_argument("--pcmm-batch", type=int, default=32)
     ap.add_argument("--pcmm-n1", type=int, default=32, help="baby steps (32 x 24 = the FFN share; 8 x 8 = a 64-slot block)")
     ap.add_argument("--pcmm-n2", type=int, default=24, help="giant steps")
     ap.add_argument("--att-batch", type=int, default=32)
