@@ -672,10 +672,12 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   }
   NttOpts o2;
   o2.rows_only = true;
-  // Double-precision slots take the plain block pass + streaming inner product (memory-bound); integer-class slots
-  // (the special primes) take the fused block pass + inner product and then feed ModDown (ALU-bound). The two
-  // chains touch disjoint slots, so they run side by side on two streams and join before the result is assembled.
-  const bool unfused_fp = c->tune[3] != 0;
+  // Double-precision slots take their own kernels for the block pass and the inner product (knob 3: fused with one
+  // key component per workgroup, or a plain block pass + streaming product; memory-bound either way); integer-class
+  // slots (the special primes) take the block pass fused with both key components and then feed ModDown
+  // (ALU-bound). The two chains touch disjoint slots, so with knob 4 == 0 they run side by side on two streams and
+  // join before the result is assembled.
+  const bool unfused_fp = c->tune[3] != 0;   // class-0 slots are not handled by the two-accumulator fused kernel
   bool any_fp = false, any_int = false, special_fp = false;
   for (u32 s_ = 0; s_ < next; s_++) {
     const bool fp = host_class(c, c->mod[emap.id[s_]]) == 0;

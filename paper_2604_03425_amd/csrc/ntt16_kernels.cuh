@@ -487,7 +487,8 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_final_kernel(F
   else fwd_final_body<false>(a, bc, tile, i_limb, mi, sm);
 }
 
-// ---- streaming inner product for double-precision moduli (the unfused alternative to the kernel above) ----
+// ---- streaming inner product for double-precision moduli (hoisted rotations, and the unfused alternative of a
+// plain key switch) ----
 // acc[b][c][t][n] = sum_j D_j[n] * evk[j][c][id(t)][n] with D_j = ext[b][j][t] (reduced doubles, evaluation domain)
 // or d[b][t] (canonical residues, read through the Galois map if asked). One lane per coefficient; grid =
 // (B, N/256, slots of the class), batch innermost so that consecutive workgroups share the key slice.
