@@ -124,7 +124,7 @@ enum ProfKind {
   // N = 2^16 kernels: three consecutive kinds each, one per modulus class (the kernel's template argument)
   PK_FWD_ROWS, PK_FWD_BLOCKS = PK_FWD_ROWS + 3, PK_INV_BLOCKS = PK_FWD_BLOCKS + 3, PK_INV_ROWS = PK_INV_BLOCKS + 3,
   PK_FWD_INNER = PK_INV_ROWS + 3, PK_FWD_FINAL = PK_FWD_INNER + 3,
-  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_ADD,
+  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_PMACC_FP, PK_ADD,
   PK_COPY, PK_COUNT
 };
 static const char* const kProfNames[PK_COUNT] = {
@@ -136,7 +136,7 @@ static const char* const kProfNames[PK_COUNT] = {
     "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
     "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
     "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
-    "pmacc_kernel", "addto_kernel", "copy"};
+    "pmacc_kernel", "pmacc_fp_kernel", "addto_kernel", "copy"};
 struct ProfRec {
   int kind;
   hipEvent_t start, stop;
@@ -1425,7 +1425,7 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
       const u32 ngt = (g0 + ng - h0) / cnt;   // as many whole tiles of this size as remain, in one launch
       fill(fa, h0, cnt);
       fa.ngt = ngt;
-      ProfScope ps(c, PK_PMACC, st);
+      ProfScope ps(c, PK_PMACC_FP, st);
       dim3 grid((2 * B + PMACC_FP_P - 1) / PMACC_FP_P * ngt, N / 256, nfp), block(256);
       switch (cnt) {
         case 6: hipLaunchKernelGGL(pmacc_fp_kernel<6>, grid, block, 0, st, fa); break;
