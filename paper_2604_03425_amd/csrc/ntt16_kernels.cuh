@@ -377,6 +377,93 @@ ntt16_fwd_blocks_inner_c_kernel(FwdInnerArgs a) {
   fwd_inner_c_body_fp(a, bc, tile, t, id, mi, (double*)sm);
 }
 
+// Double-precision moduli, both key components in one workgroup, 8 values per lane: a workgroup of 256 lanes takes
+// 8 of the 256-element blocks of a (ciphertext, slot) (grid.y = 32 tiles), each block transformed by 32 lanes
+// (ntt256_fwd_blocks_fp8). With half as many values per lane the two accumulator tiles, both key tiles of a digit
+// (requested between the first two rounds of the transform) and the transform itself fit in 3 waves per SIMD, so
+// every digit tile is read and transformed once. After the transform a lane holds 8 consecutive coefficients:
+// key words, own-digit words and the accumulators move as 16-byte accesses. Measured equal to the kernel above
+// (2.6 against 2.5 ms per step): kept as an alternative (tuning knob 3 = 3).
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+ntt16_fwd_blocks_inner2_kernel(FwdInnerArgs a) {
+  __shared__ double sm[8 * NTT8_BLOCK_LDS];
+  u32 b, tile, zi;
+  ntt16_map(a.map_mode, b, tile, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const size_t N = 65536;
+  const double q = mi.qd, qinv = mi.qinv;
+  const double* tw = a.twfp + (size_t)id * N;
+  const u32 tid = threadIdx.x, l = tid & 31, hb = tid >> 5, h = tile * 8 + hb;
+  double* smb = sm + hb * NTT8_BLOCK_LDS;
+  const u64* evk = fwd_inner_evk(a, b) + (size_t)id * N;
+  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
+  const u32 posA = h * 256 + l;                              // element 0 of the lane before the transform
+  const u32 posC = h * 256 + (l >> 2) * 32 + (l & 3) * 8;    // first of its 8 consecutive elements after it
+  double acc0[8], acc1[8], x[8];
+  ulonglong2 e0[4], e1[4];
+#pragma unroll
+  for (int c = 0; c < 8; c++) acc0[c] = acc1[c] = 0.0;
+#pragma nounroll
+  for (u32 j = 0; j < a.beta; j++) {
+    const u64* kb = evk + (size_t)j * 2 * a.nm * N + posC;
+    const u64* ka = kb + (size_t)a.nm * N;
+    auto request_key = [&]() {
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        e0[v] = *(const ulonglong2*)(kb + 2 * v);
+        e1[v] = *(const ulonglong2*)(ka + 2 * v);
+      }
+    };
+    if (fwd_inner_owns(a, t, j)) {
+      const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+      request_key();
+      if (g) {
+#pragma unroll
+        for (int c = 0; c < 8; c++) x[c] = u2d(src[galois_src_index16(posC + c, g)]);
+      } else {
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+          const ulonglong2 w = *(const ulonglong2*)(src + posC + 2 * v);
+          x[2 * v] = u2d(w.x);
+          x[2 * v + 1] = u2d(w.y);
+        }
+      }
+    } else {
+      const double* src = (const double*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N) + posA;
+#pragma unroll
+      for (int i = 0; i < 8; i++) x[i] = src[i * 32];
+      wave_lds_sync();  // the previous digit's exchanges are done with the block's LDS rows
+      ntt256_fwd_blocks_fp8(x, tw, q, qinv, h, l, smb, request_key);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+      acc0[2 * v] += fp_mulmod_var(x[2 * v], u2d(e0[v].x), qinv, q);
+      acc0[2 * v + 1] += fp_mulmod_var(x[2 * v + 1], u2d(e0[v].y), qinv, q);
+      acc1[2 * v] += fp_mulmod_var(x[2 * v], u2d(e1[v].x), qinv, q);
+      acc1[2 * v + 1] += fp_mulmod_var(x[2 * v + 1], u2d(e1[v].y), qinv, q);
+    }
+    if ((j & 3) == 3) {   // each product is below 0.75 q: fold before the sums can reach 2^53
+#pragma unroll
+      for (int c = 0; c < 8; c++) {
+        acc0[c] = fp_reduce(acc0[c], qinv, q);
+        acc1[c] = fp_reduce(acc1[c], qinv, q);
+      }
+    }
+  }
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + posC;
+  u64* o1 = o0 + (size_t)a.next * N;
+#pragma unroll
+  for (int v = 0; v < 4; v++) {
+    *(ulonglong2*)(o0 + 2 * v) = ulonglong2{d2u_canon(fp_reduce(acc0[2 * v], qinv, q), q),
+                                           d2u_canon(fp_reduce(acc0[2 * v + 1], qinv, q), q)};
+    *(ulonglong2*)(o1 + 2 * v) = ulonglong2{d2u_canon(fp_reduce(acc1[2 * v], qinv, q), q),
+                                           d2u_canon(fp_reduce(acc1[2 * v + 1], qinv, q), q)};
+  }
+}
+
 // Two builds of the same kernel: the default register allocation (2 waves per SIMD), and one held to 3 waves per
 // SIMD at the price of a few spilled accumulators; the host picks one (tuning knob 2).
 #define DEFINE_FWD_INNER_KERNEL(NAME, ATTR)                                                      \

@@ -169,3 +169,84 @@ __device__ __forceinline__ void ntt16_fwd_blocks_fp(double (&x)[16], const doubl
   for (int i = 0; i < 16; i++) x[i] = blk[i * 16 + j0];
   ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm);
 }
+
+// ---- block pass with 8 values per lane (used where a kernel needs the registers for something else) ----
+// One 256-element block is transformed by 32 adjacent lanes: radix-8 on stages 8..10, exchange, radix-8 on stages
+// 11..13, exchange, radix-4 on stages 14..15; the exchanges go through the block's own LDS rows (pitch 35 doubles per
+// 32 elements: near conflict-free for all three access patterns) and stay inside the half-wave, so no workgroup
+// barrier. In: x[i] = element i*32 + l of block h (l = lane & 31), |x| <= q/2. Out: x[c] = element
+// (l >> 2)*32 + (l & 3)*8 + c, i.e. 8 consecutive elements per lane, |x| <= q/2. Ranges: reduced after the first
+// round; the following five stages take |x| <= 0.5 q to at most 7.7 q < 2^53 / q.
+#define NTT8_PITCH 35
+#define NTT8_BLOCK_LDS (8 * NTT8_PITCH)
+
+template <class TW>
+__device__ __forceinline__ void radix8_fwd_fp(double (&x)[8], double q, double qinv, TW tw) {
+#pragma unroll
+  for (int s = 0; s < 3; s++) {
+    const int half = 4 >> s;
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      const double w = tw(s, g);
+#pragma unroll
+      for (int p = 0; p < half; p++) {
+        double& X = x[g * 2 * half + p];
+        double& Y = x[g * 2 * half + p + half];
+        const double T = fp_mulmod_var(Y, w, qinv, q);
+        Y = X - T;
+        X = X + T;
+      }
+    }
+  }
+}
+
+template <class BETWEEN>
+__device__ __forceinline__ void ntt256_fwd_blocks_fp8(double (&x)[8], const double* __restrict__ tw, double q, double qinv,
+                                                      u32 h, u32 l, double* smb, BETWEEN between) {
+  const u32 a = l >> 2, b = l & 3;
+  // the twiddles of the second and third round are requested up front so they arrive during the first
+  double t2[7], t3[6];
+#pragma unroll
+  for (int s = 0; s < 3; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) t2[(1 << s) - 1 + g] = tw[(2048 << s) + (h << (3 + s)) + (a << s) + g];
+#pragma unroll
+  for (int u = 0; u < 2; u++) t3[u] = tw[16384 + (h << 6) + (a << 3) + (b << 1) + u];
+#pragma unroll
+  for (int k = 0; k < 4; k++) t3[2 + k] = tw[32768 + (h << 7) + (a << 4) + (b << 2) + k];
+  radix8_fwd_fp(x, q, qinv, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
+#pragma unroll
+  for (int i = 0; i < 8; i++) smb[i * NTT8_PITCH + l] = fp_reduce(x[i], qinv, q);
+  between();
+  wave_lds_sync();
+#pragma unroll
+  for (int r = 0; r < 8; r++) x[r] = smb[a * NTT8_PITCH + r * 4 + b];
+  radix8_fwd_fp(x, q, qinv, [&](int s, int g) { return t2[(1 << s) - 1 + g]; });
+  wave_lds_sync();
+#pragma unroll
+  for (int r = 0; r < 8; r++) smb[a * NTT8_PITCH + r * 4 + b] = x[r];
+  wave_lds_sync();
+#pragma unroll
+  for (int c = 0; c < 8; c++) x[c] = smb[a * NTT8_PITCH + b * 8 + c];
+  // stage 14: pairs (c, c + 2) inside each half; stage 15: pairs (2k, 2k + 1)
+#pragma unroll
+  for (int u = 0; u < 2; u++)
+#pragma unroll
+    for (int p = 0; p < 2; p++) {
+      double& X = x[u * 4 + p];
+      double& Y = x[u * 4 + p + 2];
+      const double T = fp_mulmod_var(Y, t3[u], qinv, q);
+      Y = X - T;
+      X = X + T;
+    }
+#pragma unroll
+  for (int k = 0; k < 4; k++) {
+    double& X = x[2 * k];
+    double& Y = x[2 * k + 1];
+    const double T = fp_mulmod_var(Y, t3[2 + k], qinv, q);
+    Y = X - T;
+    X = X + T;
+  }
+#pragma unroll
+  for (int c = 0; c < 8; c++) x[c] = fp_reduce(x[c], qinv, q);
+}
