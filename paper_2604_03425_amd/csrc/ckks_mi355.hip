@@ -143,7 +143,7 @@ struct ProfRec {
 };
 
 struct ckks_ctx {
-  int tune[8] = {4, 0, 0, 2, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 transforms; 3: inner product on
+  int tune[8] = {-1, 0, 0, 2, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 kernels (-1: per kernel); 3: inner product on
                                          // double-precision moduli (0 fused, two accumulators; 1 plain block pass +
                                          // streaming product; 2 fused, one key component per workgroup);
                                          // 4: 1 = one stream only (0 forks the two chains of a key switch);
@@ -383,6 +383,15 @@ inline int host_class(const ckks_ctx* c, u64 m) {
   if (c->tune[1] == 0 && (m >> 50) == 0) return 0;
   return (m >> 52) == 0 ? 1 : 2;
 }
+// Workgroup-to-tile mapping of the N = 2^16 kernels (ntt16_map). Knob 0 >= 0 forces one mode everywhere; by default
+// the transform passes and the final assembly, which share nothing but twiddles across polynomials, take the
+// XCD-swizzled tile-major order (measured best for them), and the kernels that read the key take the
+// group-per-XCD order when the batch shares one key (its slices then stay in that XCD's L2) and the plain
+// tile-major order when every ciphertext has its own.
+inline u32 map_mode_pass(const ckks_ctx* c) { return c->tune[0] >= 0 ? (u32)c->tune[0] : 3u; }
+inline u32 map_mode_inner(const ckks_ctx* c, bool shared_key) {
+  return c->tune[0] >= 0 ? (u32)c->tune[0] : shared_key ? 4u : 2u;
+}
 // Launch KERNEL<cls> once per modulus class present among `nslots` slots, with ARGS.slots listing that class's slots.
 #define LAUNCH_BY_CLASS(CTX, PKBASE, KERNEL, ARGS, NX, NSLOTS, CLASS_OF_SLOT, STREAM)                      \
   for (int cls_ = 0; cls_ < 3; cls_++) {                                                                    \
@@ -425,7 +434,7 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     a.skip_alpha = c->alpha;
     a.skip_nq = skip_nq;
     for (u32 i = 0; i < 128; i++) a.id[i] = ids_from_slot0.id[i];
-    a.map_mode = c->tune[0];
+    a.map_mode = map_mode_pass(c);
     a.galois = opt.galois;
     if (opt.galois_pc) {
       if (npoly > KS_MULTI_MAX) return fail(CKKS_ESHAPE, "internal: per-polynomial Galois elements for too many polynomials");
@@ -636,7 +645,7 @@ int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 n
       a.multi = 1;
       for (u32 i = 0; i < B; i++) a.galois_pc[i] = io.galois_pc[i];
     }
-    a.map_mode = c->tune[0];
+    a.map_mode = map_mode_pass(c);
     auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
     LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
     HIP_TRY(hipGetLastError());
@@ -712,7 +721,7 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   ia.alpha = c->alpha;
   ia.beta = beta;
   ia.next = next;
-  ia.map_mode = c->tune[0];
+  ia.map_mode = map_mode_inner(c, io.galois_pc == nullptr);
   ia.galois = io.d_galois;
   ia.ext_galois = 0;
   if (io.galois_pc) {
@@ -818,7 +827,7 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
   ia.alpha = c->alpha;
   ia.beta = beta;
   ia.next = next;
-  ia.map_mode = c->tune[0];
+  ia.map_mode = map_mode_inner(c, true);
   for (u32 r = 0; r < R; r++) {
     ia.evk = evks[r];
     ia.galois = galois[r];
@@ -1526,7 +1535,7 @@ int ckks_rescale(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t 
     a.next = nlimbs;
     a.mode0 = a.mode1 = 0;
     a.galois = 0;
-    a.map_mode = c->tune[0];
+    a.map_mode = map_mode_pass(c);
     auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
     LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nl1, cls_of, st)
     HIP_TRY(hipGetLastError());
