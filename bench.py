@@ -42,12 +42,12 @@ OPS_DOT30, OPS_REDUCE90 = 4, 27
 # configuration (bytes, average over the two launches of a step: 64 rotations, 32 products; fetch scaled by the
 # copy-kernel calibration); see profiles/keyswitch_micro_hbm_traffic.md.
 MEASURED_TRAFFIC = {
-    "moddown_kernel": 1610740429, "modup_kernel": 2416128614,
-    "ntt16_fwd_blocks_final_kernel<0>": 4442011853, "ntt16_fwd_blocks_inner_c_kernel": 5502187110,
-    "ntt16_fwd_blocks_inner_kernel<2>": 1837135258, "ntt16_fwd_rows_kernel<0>": 2416511590,
-    "ntt16_fwd_rows_kernel<2>": 1208492442, "ntt16_inv_blocks_kernel<0>": 1220688691,
-    "ntt16_inv_blocks_kernel<2>": 813934182, "ntt16_inv_rows_kernel<0>": 1208567398,
-    "ntt16_inv_rows_kernel<2>": 805865267, "tensor_kernel": 2818659123,
+    "moddown_kernel": 1610747699, "modup_kernel": 2416127488,
+    "ntt16_fwd_blocks_final_kernel<0>": 4565286707, "ntt16_fwd_blocks_inner_c_kernel": 5508665344,
+    "ntt16_fwd_blocks_inner_kernel<2>": 1839728845, "ntt16_fwd_rows_kernel<0>": 2416117350,
+    "ntt16_fwd_rows_kernel<2>": 1208250163, "ntt16_inv_blocks_kernel<0>": 1222682829,
+    "ntt16_inv_blocks_kernel<2>": 815734579, "ntt16_inv_rows_kernel<0>": 1208186880,
+    "ntt16_inv_rows_kernel<2>": 805642650, "tensor_kernel": 2818663219,
 }
 
 
