@@ -501,7 +501,9 @@ def main():
         "ms_per_step": round(1e3 * sec / args.steps, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": "keyswitch_micro: N=2^16, 24x50-bit + 8x60-bit primes, dnum=3, 64 cts, %d HRot groups (%s), 32 HMult pairs" % (G, "one batched call" if multi else "one call per group"),
-                   "global_batch": B, "parallelism": "single-gpu"},
+                   "global_batch": B, "parallelism": "single-gpu",
+                   "arithmetic": "64-bit residues; the 50-bit limbs are computed exactly on the FP64 units, the 60-bit ones on "
+                                 "the integer units"},
         "roofline": roofline, "cpu_baseline": cpu, "phases": phases, "extra": extra,
     }
     print(json.dumps(line))
