@@ -124,7 +124,7 @@ enum ProfKind {
   // N = 2^16 kernels: three consecutive kinds each, one per modulus class (the kernel's template argument)
   PK_FWD_ROWS, PK_FWD_BLOCKS = PK_FWD_ROWS + 3, PK_INV_BLOCKS = PK_FWD_BLOCKS + 3, PK_INV_ROWS = PK_INV_BLOCKS + 3,
   PK_FWD_INNER = PK_INV_ROWS + 3, PK_FWD_FINAL = PK_FWD_INNER + 3,
-  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_INNER2, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_PMACC_FP, PK_ADD,
+  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_INNER2, PK_INNER8, PK_INNER8_BIG, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_PMACC_FP, PK_ADD,
   PK_COPY, PK_COUNT
 };
 static const char* const kProfNames[PK_COUNT] = {
@@ -135,7 +135,7 @@ static const char* const kProfNames[PK_COUNT] = {
     "ntt16_inv_rows_kernel<0>", "ntt16_inv_rows_kernel<1>", "ntt16_inv_rows_kernel<2>",
     "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
     "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
-    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "ntt16_fwd_blocks_inner2_kernel", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
+    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "ntt16_fwd_blocks_inner2_kernel", "ntt16_fwd_blocks_inner8_kernel<1>", "ntt16_fwd_blocks_inner8_kernel<2>", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
     "pmacc_kernel", "pmacc_fp_kernel", "addto_kernel", "copy"};
 struct ProfRec {
   int kind;
@@ -769,7 +769,18 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
       int k = host_class(c, c->mod[emap.id[s]]);
       return (unfused_fp && k == 0) ? -1 : k;
     };
-    if (c->tune[2]) {
+    if (c->tune[2] == 2 && unfused_fp) {
+      // integer classes with 8 values per lane (grid.y = 32 tiles of 8 blocks)
+      for (int cls = 1; cls <= 2; cls++) {
+        u32 cnt = 0;
+        for (u32 s_ = 0; s_ < next; s_++)
+          if (cls_of(s_) == cls) a.slots[cnt++] = (unsigned char)s_;
+        if (!cnt) continue;
+        ProfScope ps(c, PK_INNER8 + cls - 1, st);
+        if (cls == 1) hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<1>, dim3(B, 32, cnt), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<2>, dim3(B, 32, cnt), dim3(256), 0, st, a);
+      }
+    } else if (c->tune[2] == 1) {
       LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_occ3_kernel, a, B, next, cls_of, st)
     } else {
       LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_kernel, a, B, next, cls_of, st)

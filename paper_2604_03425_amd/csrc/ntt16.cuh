@@ -129,6 +129,59 @@ __device__ __forceinline__ void ntt16_fwd_blocks(u64 (&x)[16], const u64* __rest
   ntt16_fwd_blocks_loaded<BIG, CANON>(x, tw, q, mu, tile, sm);
 }
 
+// Forward, stages 8..15 of one 256-element block by 32 adjacent lanes with 8 values each (the layout of
+// ntt256_fwd_blocks_fp8: radix-8, exchange, radix-8, exchange, radix-4; LDS rows of pitch 35 words per 32 elements,
+// all exchanges inside the half-wave). In: x[i] = element i*32 + l, lazy (BIG: < 4q). Out: x[c] = element
+// (l >> 2)*32 + (l & 3)*8 + c, below 2q. `between` runs after the first exchange has been written.
+#define NTT8_PITCH_I 35
+#define NTT8_BLOCK_LDS_I (8 * NTT8_PITCH_I)
+template <bool BIG, class TW>
+__device__ __forceinline__ void radix8_fwd(u64 (&x)[8], u64 q, u64 q2, TW tw) {
+#pragma unroll
+  for (int s = 0; s < 3; s++) {
+    const int half = 4 >> s;
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      const ulonglong2 w = tw(s, g);
+#pragma unroll
+      for (int p = 0; p < half; p++) bf_fwd<BIG>(x[g * 2 * half + p], x[g * 2 * half + p + half], w, q, q2);
+    }
+  }
+}
+template <bool BIG, class BETWEEN>
+__device__ __forceinline__ void ntt256_fwd_blocks_int8(u64 (&x)[8], const ulonglong2* __restrict__ tw, u64 q, u64 mu, u32 h,
+                                                       u32 l, u64* smb, BETWEEN between) {
+  const u32 a = l >> 2, b = l & 3;
+  const u64 q2 = 2 * q;
+  radix8_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
+#pragma unroll
+  for (int i = 0; i < 8; i++) smb[i * NTT8_PITCH_I + l] = x[i];
+  between();
+  wave_lds_sync();
+#pragma unroll
+  for (int r = 0; r < 8; r++) x[r] = smb[a * NTT8_PITCH_I + r * 4 + b];
+  radix8_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(2048 << s) + (h << (3 + s)) + (a << s) + g]; });
+  wave_lds_sync();
+#pragma unroll
+  for (int r = 0; r < 8; r++) smb[a * NTT8_PITCH_I + r * 4 + b] = x[r];
+  wave_lds_sync();
+#pragma unroll
+  for (int c = 0; c < 8; c++) x[c] = smb[a * NTT8_PITCH_I + b * 8 + c];
+#pragma unroll
+  for (int u = 0; u < 2; u++) {   // stage 14: pairs (c, c + 2) inside each half
+    const ulonglong2 w = tw[16384 + (h << 6) + (a << 3) + (b << 1) + u];
+#pragma unroll
+    for (int p = 0; p < 2; p++) bf_fwd<BIG>(x[u * 4 + p], x[u * 4 + p + 2], w, q, q2);
+  }
+#pragma unroll
+  for (int k = 0; k < 4; k++) {   // stage 15: pairs (2k, 2k + 1)
+    const ulonglong2 w = tw[32768 + (h << 7) + (a << 4) + (b << 2) + k];
+    bf_fwd<BIG>(x[2 * k], x[2 * k + 1], w, q, q2);
+  }
+#pragma unroll
+  for (int c = 0; c < 8; c++) x[c] = BIG ? csub(x[c], q2) : barrett_lazy(x[c], mu, q);
+}
+
 // Inverse, stages 15..8 on contiguous blocks. In: x holds, for lane (hb, j0), the values at positions i*16 + j0
 // of block h (any value < 2q). Out: < 2q, same lane layout, ready for a coalesced store.
 template <bool BIG>

@@ -464,6 +464,89 @@ ntt16_fwd_blocks_inner2_kernel(FwdInnerArgs a) {
   }
 }
 
+// The same for integer-class moduli (the special primes): both key components per workgroup, 8 values per lane, so
+// that the kernel runs at 3-4 waves per SIMD instead of the 2 the 16-values-per-lane form is held to. Products go
+// through a Montgomery reduction (acc carries the factor 2^-64), as in fwd_inner_body.
+template <int CLS>
+__global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerArgs a) {
+  constexpr bool BIG = CLS == 2;
+  __shared__ u64 sm[8 * NTT8_BLOCK_LDS_I];
+  u32 b, tile, zi;
+  ntt16_map(a.map_mode, b, tile, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const size_t N = 65536;
+  const u64 q = mi.m, q2 = 2 * mi.m;
+  const ulonglong2* tw = a.tw + (size_t)id * N;
+  const u32 tid = threadIdx.x, l = tid & 31, hb = tid >> 5, h = tile * 8 + hb;
+  u64* smb = sm + hb * NTT8_BLOCK_LDS_I;
+  const u64* evk = fwd_inner_evk(a, b) + (size_t)id * N;
+  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
+  const u32 posA = h * 256 + l;
+  const u32 posC = h * 256 + (l >> 2) * 32 + (l & 3) * 8;
+  u64 acc0[8], acc1[8], x[8];
+  ulonglong2 e0[4], e1[4];
+#pragma unroll
+  for (int c = 0; c < 8; c++) acc0[c] = acc1[c] = 0;
+#pragma nounroll
+  for (u32 j = 0; j < a.beta; j++) {
+    const u64* kb = evk + (size_t)j * 2 * a.nm * N + posC;
+    const u64* ka = kb + (size_t)a.nm * N;
+    auto request_key = [&]() {
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        e0[v] = *(const ulonglong2*)(kb + 2 * v);
+        e1[v] = *(const ulonglong2*)(ka + 2 * v);
+      }
+    };
+    if (fwd_inner_owns(a, t, j)) {
+      const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+      request_key();
+      if (g) {
+#pragma unroll
+        for (int c = 0; c < 8; c++) x[c] = src[galois_src_index16(posC + c, g)];
+      } else {
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+          const ulonglong2 w = *(const ulonglong2*)(src + posC + 2 * v);
+          x[2 * v] = w.x;
+          x[2 * v + 1] = w.y;
+        }
+      }
+    } else {
+      const u64* src = a.ext + (((size_t)b * a.beta + j) * a.next + t) * N + posA;
+#pragma unroll
+      for (int i = 0; i < 8; i++) x[i] = src[i * 32];
+      wave_lds_sync();  // the previous digit's exchanges are done with the block's LDS rows
+      ntt256_fwd_blocks_int8<BIG>(x, tw, q, mi.mu64, h, l, smb, request_key);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+      const u64 eb[2] = {e0[v].x, e0[v].y}, ea[2] = {e1[v].x, e1[v].y};
+#pragma unroll
+      for (int k = 0; k < 2; k++) {
+        const u64 xv = x[2 * v + k];
+        Acc128 p0, p1;
+        p0.lo = xv * eb[k];
+        p0.hi = mul_hi64(xv, eb[k]);
+        p1.lo = xv * ea[k];
+        p1.hi = mul_hi64(xv, ea[k]);
+        acc0[2 * v + k] = csub(acc0[2 * v + k] + redc(p0, q, mi.minv), q2);
+        acc1[2 * v + k] = csub(acc1[2 * v + k] + redc(p1, q, mi.minv), q2);
+      }
+    }
+  }
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + posC;
+  u64* o1 = o0 + (size_t)a.next * N;
+#pragma unroll
+  for (int v = 0; v < 4; v++) {
+    *(ulonglong2*)(o0 + 2 * v) = ulonglong2{csub(acc0[2 * v], q), csub(acc0[2 * v + 1], q)};
+    *(ulonglong2*)(o1 + 2 * v) = ulonglong2{csub(acc1[2 * v], q), csub(acc1[2 * v + 1], q)};
+  }
+}
+
 // Two builds of the same kernel: the default register allocation (2 waves per SIMD), and one held to 3 waves per
 // SIMD at the price of a few spilled accumulators; the host picks one (tuning knob 2).
 #define DEFINE_FWD_INNER_KERNEL(NAME, ATTR)                                                      \
