@@ -51,7 +51,7 @@ MEASURED_TRAFFIC = {
 }
 
 
-def keyswitch_model(p, B, nl, hrot, hmult, fp_inner=2):
+def keyswitch_model(p, B, nl, hrot, hmult, fp_inner=2, int_inner=2):
     """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B (N = 2^16 path:
     double-precision bodies on primes < 2^50, with their inner product as a separate streaming kernel)."""
     N, K, alpha = p.N, len(p.p), p.alpha
@@ -98,7 +98,7 @@ def keyswitch_model(p, B, nl, hrot, hmult, fp_inner=2):
         put("ntt16_fwd_blocks_kernel", 0, B * new_fp * 2 * limb, B * new_fp * bf_pass_fp)
         put("inner16_fp_kernel", None, (B * (new_fp + own_fp + 2 * n_fp) + 2 * beta * n_fp) * limb,
             B * N * n_fp * beta * 2 * OPS_MULRED_FP)
-    put("ntt16_fwd_blocks_inner_kernel", 2, (B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
+    put("ntt16_fwd_blocks_inner8_kernel" if int_inner == 2 else "ntt16_fwd_blocks_inner_kernel", 2, (B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
         B * (new_int * bf_pass + N * n_int * beta * 2 * mul_redc))
     put("moddown_kernel", None, 2 * B * (K + nl) * limb, 2 * B * N * nl * ((K + 1) * OPS_DOT30 + OPS_REDUCE90))
     addend = 1 if hrot else 2 if hmult else 0
@@ -306,12 +306,14 @@ def main():
         ck.ckks_tune_set(ctx, 0, args.map_mode)
     if args.int_only:
         ck.ckks_tune_set(ctx, 1, 1)
-    fp_inner = 2   # library default of knob 3
+    fp_inner, int_inner = 2, 2   # library defaults of knobs 3 and 2
     for kv in filter(None, args.tune.split(",")):
         k, v = kv.split("=")
         ck.ckks_tune_set(ctx, int(k), int(v))
         if int(k) == 3:
             fp_inner = int(v)
+        if int(k) == 2:
+            int_inner = int(v)
     gen = torch.Generator(device=dev).manual_seed(0xC0FFEE)
 
     def uniform(prefix, moduli):
@@ -376,7 +378,7 @@ def main():
     # --- per-kind roofline figures from the event durations of the timed region ---
     model = {}
     for (b, hrot, hmult, calls) in ((Bg, True, False, G), (B // 2, False, True, 1)):
-        for kind, v in keyswitch_model(p, b, nl, hrot, hmult, fp_inner).items():
+        for kind, v in keyswitch_model(p, b, nl, hrot, hmult, fp_inner, int_inner).items():
             acc = model.setdefault(kind, dict(bytes=0.0, ops=0.0))
             acc["bytes"] += v["bytes"] * calls
             acc["ops"] += v["ops"] * calls

@@ -224,7 +224,7 @@ int ckks_prof_enable(ckks_ctx* ctx, int on);
 /* Tuning knobs for experiments: knob 0 = workgroup-to-tile mapping of the N = 2^16 kernels (0..4 forces one
  * mapping everywhere; default -1 chooses per kernel);
  * knob 1 != 0 turns the double-precision bodies for primes < 2^50 off (integer bodies everywhere);
- * knob 2 != 0 selects the 3-waves-per-SIMD build of the fused inner-product kernel; knob 3 picks the inner product
+ * knob 2 picks the fused inner product on integer-class moduli: 2 (default) = 8 values per lane, 0 = 16; knob 3 picks the inner product
  * on double-precision moduli: 0 = block pass fused with both key components (two accumulator tiles), 1 = plain
  * block pass followed by a streaming product, 2 (default) = block pass fused with one key component per workgroup,
  * 3 = block pass with 8 values per lane fused with both key components; knob 4 == 0 lets a key switch fork its two independent kernel

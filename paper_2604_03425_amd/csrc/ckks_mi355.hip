@@ -143,7 +143,8 @@ struct ProfRec {
 };
 
 struct ckks_ctx {
-  int tune[8] = {-1, 0, 0, 2, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 kernels (-1: per kernel); 3: inner product on
+  int tune[8] = {-1, 0, 2, 2, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 kernels (-1: per kernel); 2: fused inner product
+                                         // on integer-class moduli (2: 8 values per lane, 0: 16); 3: inner product on
                                          // double-precision moduli (0 fused, two accumulators; 1 plain block pass +
                                          // streaming product; 2 fused, one key component per workgroup);
                                          // 4: 1 = one stream only (0 forks the two chains of a key switch);
@@ -780,8 +781,6 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
         if (cls == 1) hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<1>, dim3(B, 32, cnt), dim3(256), 0, st, a);
         else hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<2>, dim3(B, 32, cnt), dim3(256), 0, st, a);
       }
-    } else if (c->tune[2] == 1) {
-      LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_occ3_kernel, a, B, next, cls_of, st)
     } else {
       LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_kernel, a, B, next, cls_of, st)
     }

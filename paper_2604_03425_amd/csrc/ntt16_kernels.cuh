@@ -547,23 +547,20 @@ __global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerAr
   }
 }
 
-// Two builds of the same kernel: the default register allocation (2 waves per SIMD), and one held to 3 waves per
-// SIMD at the price of a few spilled accumulators; the host picks one (tuning knob 2).
-#define DEFINE_FWD_INNER_KERNEL(NAME, ATTR)                                                      \
-  template <int CLS>                                                                             \
-  __global__ void __launch_bounds__(NTT16_THREADS) ATTR NAME(FwdInnerArgs a) {                   \
-    __shared__ u64 sm[NTT16_LDS_BYTES / 8];                                                      \
-    u32 b, tile, zi;                                                                             \
-    ntt16_map(a.map_mode, b, tile, zi);                                                          \
-    const u32 t = a.slots[zi];                                                                   \
-    const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;                                       \
-    const ModInfo mi = a.mods[id];                                                               \
-    if (CLS == 0) fwd_inner_body_fp(a, b, tile, t, id, mi, (double*)sm);                         \
-    else if (CLS == 2) fwd_inner_body<true>(a, b, tile, t, id, mi, sm);                          \
-    else fwd_inner_body<false>(a, b, tile, t, id, mi, sm);                                       \
-  }
-DEFINE_FWD_INNER_KERNEL(ntt16_fwd_blocks_inner_kernel, )
-DEFINE_FWD_INNER_KERNEL(ntt16_fwd_blocks_inner_occ3_kernel, __attribute__((amdgpu_waves_per_eu(3, 3))))
+// The 16-values-per-lane form of the kernels above (both key components, 240-248 registers, 2 waves per SIMD):
+// the first version of this fusion, kept selectable (tuning knobs 2 = 0 / 3 = 0).
+template <int CLS>
+__global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_inner_kernel(FwdInnerArgs a) {
+  __shared__ u64 sm[NTT16_LDS_BYTES / 8];
+  u32 b, tile, zi;
+  ntt16_map(a.map_mode, b, tile, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  if (CLS == 0) fwd_inner_body_fp(a, b, tile, t, id, mi, (double*)sm);
+  else if (CLS == 2) fwd_inner_body<true>(a, b, tile, t, id, mi, sm);
+  else fwd_inner_body<false>(a, b, tile, t, id, mi, sm);
+}
 
 // ---- fused: last forward pass of the ModDown correction + final assembly ----
 // out[bc][i] = (acc[bc][i] - NTT(tq[bc][i])) * pinv[i]  (+ addend). On integer-class moduli acc and tq carry the
