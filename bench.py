@@ -42,12 +42,12 @@ OPS_DOT30, OPS_REDUCE90 = 4, 27
 # configuration (bytes, average over the two launches of a step: 64 rotations, 32 products; fetch scaled by the
 # copy-kernel calibration); see profiles/keyswitch_micro_hbm_traffic.md.
 MEASURED_TRAFFIC = {
-    "moddown_kernel": 1610747699, "modup_kernel": 2416127488,
-    "ntt16_fwd_blocks_final_kernel<0>": 4565286707, "ntt16_fwd_blocks_inner_c_kernel": 5508665344,
-    "ntt16_fwd_blocks_inner_kernel<2>": 1839728845, "ntt16_fwd_rows_kernel<0>": 2416117350,
-    "ntt16_fwd_rows_kernel<2>": 1208250163, "ntt16_inv_blocks_kernel<0>": 1222682829,
-    "ntt16_inv_blocks_kernel<2>": 815734579, "ntt16_inv_rows_kernel<0>": 1208186880,
-    "ntt16_inv_rows_kernel<2>": 805642650, "tensor_kernel": 2818663219,
+    "moddown_kernel": 1610744934, "modup_kernel": 2416124006,
+    "ntt16_fwd_blocks_final_kernel<0>": 4565991014, "ntt16_fwd_blocks_inner8_kernel<2>": 1834122445,
+    "ntt16_fwd_blocks_inner_c_kernel": 5507694387, "ntt16_fwd_rows_kernel<0>": 2416117350,
+    "ntt16_fwd_rows_kernel<2>": 1208248115, "ntt16_inv_blocks_kernel<0>": 1222694707,
+    "ntt16_inv_blocks_kernel<2>": 815880192, "ntt16_inv_rows_kernel<0>": 1208182374,
+    "ntt16_inv_rows_kernel<2>": 805633434, "tensor_kernel": 2818658918,
 }
 
 
