@@ -81,8 +81,12 @@ class RefContext:
                                     C.c_uint32(self.np_), C.c_uint32(params.dnum), psip))
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().ref_ctx_destroy(self._h)
+        # at interpreter shutdown the module globals may already be gone; the process is ending anyway
+        if getattr(self, "_h", None) and lib is not None:
+            try:
+                lib().ref_ctx_destroy(self._h)
+            except Exception:
+                pass
             self._h = None
 
     # ---- transforms (return new arrays) ----
