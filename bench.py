@@ -280,7 +280,7 @@ def main():
     ap.add_argument("--pcmm-n1", type=int, default=32, help="baby steps (32 x 24 = the FFN share; 8 x 8 = a 64-slot block)")
     ap.add_argument("--pcmm-n2", type=int, default=24, help="giant steps")
     ap.add_argument("--att-batch", type=int, default=32)
-    ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
+    ap.add_argument("--cpu-sample", type=int, default=32, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the work; --gpus %d is not supported (use --gpus 1)" % args.gpus,
