@@ -185,6 +185,29 @@ class RefContext:
         _check(lib().ref_hmult_relin(self._h, out.ctypes.data_as(u64p), ap, bp, C.c_uint32(B), C.c_uint32(nl), ep))
         return out
 
+    def tensor_acc(self, ct_a, ct_b, d_acc=None):
+        """Un-relinearised product [B][3][nl][N], added to d_acc when given (late relinearisation, Sec. 5.2)."""
+        ct_a, ap = _u64(ct_a)
+        ct_b, bp = _u64(ct_b)
+        B, two, nl, _ = ct_a.shape
+        assert ct_b.shape == ct_a.shape and two == 2
+        out = np.empty((B, 3, nl, self.N), dtype=np.uint64)
+        ep = None
+        if d_acc is not None:
+            d_acc, ep = _u64(d_acc)
+            assert d_acc.shape == out.shape
+        _check(lib().ref_tensor_acc(self._h, out.ctypes.data_as(u64p), ap, bp, ep, C.c_uint32(B), C.c_uint32(nl)))
+        return out
+
+    def relin(self, d, evk):
+        d, dp = _u64(d)
+        evk, ep = _u64(evk)
+        B, three, nl, _ = d.shape
+        assert three == 3 and evk.shape == (self.params.dnum, 2, self.nm, self.N)
+        out = np.empty((B, 2, nl, self.N), dtype=np.uint64)
+        _check(lib().ref_relin(self._h, out.ctypes.data_as(u64p), dp, C.c_uint32(B), C.c_uint32(nl), ep))
+        return out
+
     def pcmm_bsgs(self, ct, pt, n1, n2, stride, evk_baby, evk_giant):
         ct, cp = _u64(ct)
         pt, pp = _u64(pt)

@@ -589,6 +589,60 @@ int ref_hmult_relin(const RefCtx* c, u64* ct_out, const u64* ct_a, const u64* ct
   return 0;
 }
 
+// Late relinearisation (Sec. 5.2): products are kept as three components and summed; one key switch follows the sum.
+// d_out[b] = (c0 c0', c0 c1' + c1 c0', c1 c1') (+ d_acc[b] when d_acc is given), each [3][nlimbs][N].
+int ref_tensor_acc(const RefCtx* c, u64* d_out, const u64* ct_a, const u64* ct_b, const u64* d_acc, uint32_t B,
+                   uint32_t nlimbs) {
+  if (nlimbs == 0 || nlimbs > (uint32_t)c->nq) return fail("bad limb count");
+  const size_t N = c->N, pl = (size_t)nlimbs * N;
+  parallel_for(B, [&](size_t b) {
+    const u64 *a0 = ct_a + b * 2 * pl, *a1 = a0 + pl, *b0 = ct_b + b * 2 * pl, *b1 = b0 + pl;
+    u64* d = d_out + b * 3 * pl;
+    const u64* e = d_acc ? d_acc + b * 3 * pl : nullptr;
+    for (uint32_t i = 0; i < nlimbs; i++) {
+      u64 m = c->mod[i];
+      for (size_t n = 0; n < N; n++) {
+        size_t k = (size_t)i * N + n;
+        u64 t0 = mulm(a0[k] % m, b0[k] % m, m);
+        u64 t1 = addm(mulm(a0[k] % m, b1[k] % m, m), mulm(a1[k] % m, b0[k] % m, m), m);
+        u64 t2 = mulm(a1[k] % m, b1[k] % m, m);
+        if (e) {
+          t0 = addm(t0, e[k] % m, m);
+          t1 = addm(t1, e[pl + k] % m, m);
+          t2 = addm(t2, e[2 * pl + k] % m, m);
+        }
+        d[k] = t0;
+        d[pl + k] = t1;
+        d[2 * pl + k] = t2;
+      }
+    }
+  });
+  return 0;
+}
+
+// Relinearisation of a three-component ciphertext: out = (d0 + ks.b, d1 + ks.a), ks = KS(d2) under the key for s^2.
+int ref_relin(const RefCtx* c, u64* ct_out, const u64* d_in, uint32_t B, uint32_t nlimbs, const u64* evk) {
+  if (nlimbs == 0 || nlimbs > (uint32_t)c->nq) return fail("bad limb count");
+  const size_t N = c->N, pl = (size_t)nlimbs * N;
+  parallel_for(B, [&](size_t b) {
+    const u64* d = d_in + b * 3 * pl;
+    std::vector<u64> d2(pl), ks(2 * pl);
+    for (uint32_t i = 0; i < nlimbs; i++)
+      for (size_t n = 0; n < N; n++) d2[(size_t)i * N + n] = d[2 * pl + (size_t)i * N + n] % c->mod[i];
+    keyswitch_one(c, ks.data(), d2.data(), nlimbs, evk);
+    u64* o = ct_out + b * 2 * pl;
+    for (uint32_t i = 0; i < nlimbs; i++) {
+      u64 m = c->mod[i];
+      for (size_t n = 0; n < N; n++) {
+        size_t k = (size_t)i * N + n;
+        o[k] = addm(d[k] % m, ks[k], m);
+        o[pl + k] = addm(d[pl + k] % m, ks[pl + k], m);
+      }
+    }
+  });
+  return 0;
+}
+
 // y = sum_{g<n2} rot_{g*n1*stride}( sum_{b<n1} pt[g][b] (.) rot_{b*stride}(x) ); rotation by 0 is the identity (no
 // key switch). evk_baby[b-1] switches 5^(b*stride), evk_giant[g-1] switches 5^(g*n1*stride). pt: [n2][n1][nlimbs][N].
 int ref_pcmm_bsgs(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, uint32_t nlimbs, const u64* pt,

@@ -140,6 +140,53 @@ def test_hmult_relin_multiplies_slots():
     assert err3 < 2.0**-16
 
 
+def test_late_relinearisation():
+    """Sum of three-component products, one key switch at the end (Sec. 5.2). The three components are pinned by
+    the exact identity d0 + d1 s + d2 s^2 = sum_i (a_i0 + a_i1 s)(b_i0 + b_i1 s) in every limb, built here from
+    pointwise products of the phases; the relinearised sum is pinned through decryption."""
+    p = make_params(10, 4, 40, 2, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 77)
+    ids = [0, 1, 2, 3]
+    pairs = []
+    want_slots = 0
+    for i in range(3):
+        z1 = normal_slots(10 + i, p.N // 2, 0.1)
+        z2 = normal_slots(20 + i, p.N // 2, 0.1)
+        pairs.append((keys.encrypt_slots(z1, 2.0**30, 4), keys.encrypt_slots(z2, 2.0**30, 4)))
+        want_slots = want_slots + z1 * z2
+    acc = None
+    for a, b in pairs:
+        acc = c.tensor_acc(a[None], b[None], acc)
+    s1 = c.ntt(c.signed_to_rns(keys.s, ids)[None], ids)
+    s2 = c.pointwise(s1, s1, ids, "mul")
+    phase = lambda ct: c.pointwise(ct[0:1], c.pointwise(ct[1:2], s1, ids, "mul"), ids, "add")
+    want = None
+    for a, b in pairs:
+        t = c.pointwise(phase(a), phase(b), ids, "mul")
+        want = t if want is None else c.pointwise(want, t, ids, "add")
+    got = c.pointwise(c.pointwise(acc[0, 0:1], c.pointwise(acc[0, 1:2], s1, ids, "mul"), ids, "add"),
+                      c.pointwise(acc[0, 2:3], s2, ids, "mul"), ids, "add")
+    assert np.array_equal(got, want)
+    # the components are not interchangeable: a swapped pair breaks the identity
+    swapped = acc[0, [2, 1, 0]]
+    bad = c.pointwise(c.pointwise(swapped[0:1], c.pointwise(swapped[1:2], s1, ids, "mul"), ids, "add"),
+                      c.pointwise(swapped[2:3], s2, ids, "mul"), ids, "add")
+    assert not np.array_equal(bad, want)
+    # one product, relinearised late, is HMult+relin
+    rk = keys.relin_key()
+    a, b = pairs[0]
+    assert np.array_equal(c.relin(c.tensor_acc(a[None], b[None]), rk), c.hmult_relin(a[None], b[None], rk))
+    # the relinearised sum decrypts to the sum of the slot products, and stays close to the three-component phase
+    out = c.relin(acc, rk)[0]
+    err = np.max(np.abs(keys.decrypt_slots(out, 2.0**60) - want_slots))
+    assert err < 2.0**-20, err         # measured 2^-24
+    m3 = c.decrypt_centred(acc[0], keys.s)
+    m2 = c.decrypt_centred(out, keys.s)
+    noise = max(abs(int(x) - int(y)) for x, y in zip(m2, m3))
+    assert noise < 2**10, noise        # key-switch noise only (measured about 2^4), against a 2^60 scale
+
+
 def test_pcmm_bsgs_is_a_matrix_product():
     """Diagonal BSGS with n1*n2 = d diagonals on vectors x||x packed in d2-slot segments: y = x W."""
     p = make_params(8, 4, 40, 2, 50, 2)
