@@ -225,12 +225,28 @@ def other_workloads(args):
             for i in range(6):
                 ck.ckks_hrot_add(ctx, nxt, cur, cur, B, nl - 2, galois_element(-(1 << i), p.logN), rot[6 + i], ws)
                 cur, nxt = nxt, cur
-            ck.ckks_hmult_relin(ctx, out, cur, vb, B, nl - 2, relin, ws)
+            if late[0]:
+                ck.ckks_tensor_acc(ctx, acc3, cur, vb, acc3, B, nl - 2)
+            else:
+                ck.ckks_hmult_relin(ctx, out, cur, vb, B, nl - 2, relin, ws)
+        late = [False]
+        acc3 = torch.zeros((B, 3, nl - 2, N), dtype=torch.int64, device=dev)
         dt = _time(torch, units, 2)
+        # late relinearisation (Sec. 5.2): the products with V of a block's 64 diagonals stay in three components
+        # and share one key switch, timed here as 64 calls of the unit followed by one ckks_relin
+        late[0] = True
+
+        def block():
+            for _ in range(64):
+                units()
+            ck.ckks_relin(ctx, out, acc3, B, nl - 2, relin, ws)
+        dt_late = _time(torch, block, 1) / 64
         print(json.dumps({"workload": "attention_av_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
                           "key_switches_per_s": round(14 * B / dt, 1),
+                          "units_per_s_late_relin": round(B / dt_late, 1),
                           "note": "unit = score diagonal (HMult+relin + 6 HRot) + mask-and-pack (2 Rescale, PMult, "
-                                  "6 HRot) + HMult+relin with V, 20 -> 18 limbs, dnum=4, K=5"}))
+                                  "6 HRot) + HMult+relin with V, 20 -> 18 limbs, dnum=4, K=5; late_relin: the "
+                                  "product with V accumulated in three components, one key switch per 64 units"}))
     elif args.workload == "sweep":
         B = 32
         for limbs in (4, 8, 12, 16, 20, 24, 28, 32, 36):

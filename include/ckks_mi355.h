@@ -161,6 +161,26 @@ int ckks_hmult_relin(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_a, cons
                      uint32_t nlimbs, const uint64_t* evk_mult, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Late relinearisation (paper Sec. 5.2, an optimisation applied to every system compared there): products are kept
+ * as three components, summed, and key-switched once. ckks_tensor_acc computes, pointwise per limb,
+ *   d_out[b] = (a0*b0, a0*b1 + a1*b0, a1*b1) + d_acc[b]      (d_acc == NULL: no addend)
+ * d_out, d_acc: device [B][3][nlimbs][N], canonical residues; d_acc may be d_out itself (accumulate in place) but
+ * may not overlap it otherwise; d_out may overlap neither input ciphertext. No workspace. Errors as for ckks_add.
+ */
+int ckks_tensor_acc(ckks_ctx* ctx, uint64_t* d_out, const uint64_t* ct_a, const uint64_t* ct_b, const uint64_t* d_acc,
+                    uint32_t B, uint32_t nlimbs, void* stream);
+
+/*
+ * Relinearisation of three-component ciphertexts (paper Sec. 2.1: Relin; Sec. 5.2: late relinearisation):
+ *   ks = keyswitch(d2, evk_mult), ct_out[b] = (d0 + ks.b, d1 + ks.a).
+ * ckks_relin(ckks_tensor_acc(a, b, NULL)) returns exactly what ckks_hmult_relin(a, b) returns. d_in: device
+ * [B][3][nlimbs][N]; ct_out: device [B][2][nlimbs][N], may not overlap d_in. Workspace: CKKS_OP_KEYSWITCH for
+ * this B and nlimbs. Key layout, stream and error behaviour as for ckks_hmult_relin.
+ */
+int ckks_relin(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* d_in, uint32_t B, uint32_t nlimbs,
+               const uint64_t* evk_mult, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Diagonal baby-step/giant-step ciphertext-plaintext matmul, one rotation at a time, no
  * hoisting (paper Sec. 5.1 "Implementation"; Sec. 3.2.2 BSGS matmul):
  *   ct_out = sum_{g<n2} rot_{g*n1*stride}( sum_{b<n1} pt_diag[g][b] (.) rot_{b*stride}(ct_in) )

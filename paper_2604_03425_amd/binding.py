@@ -17,7 +17,8 @@ _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_work
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
             "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
-            "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi", "ckks_hrot_add"]
+            "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi", "ckks_hrot_add", "ckks_tensor_acc",
+            "ckks_relin"]
 
 
 class CkksError(RuntimeError):
@@ -53,6 +54,8 @@ def _load():
                                    C.c_size_t, vp]
     lib.ckks_hrot.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_hmult_relin.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
+    lib.ckks_tensor_acc.argtypes = [vp, u64p, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
+    lib.ckks_relin.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_hrot_hoisted.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), C.c_uint32, vp,
@@ -187,6 +190,16 @@ def ckks_hrot(ctx, ct_out, ct_in, B, nlimbs, galois_elt, evk_rot, ws):
 def ckks_hmult_relin(ctx, ct_out, ct_a, ct_b, B, nlimbs, evk_mult, ws):
     _check(_lib.ckks_hmult_relin(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_a, "ct_a"), _ptr(ct_b, "ct_b"), B, nlimbs,
                                  _ptr(evk_mult, "evk_mult"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_tensor_acc(ctx, d_out, ct_a, ct_b, d_acc, B, nlimbs):
+    _check(_lib.ckks_tensor_acc(ctx.handle, _ptr(d_out, "d_out"), _ptr(ct_a, "ct_a"), _ptr(ct_b, "ct_b"),
+                                None if d_acc is None else _ptr(d_acc, "d_acc"), B, nlimbs, _stream()))
+
+
+def ckks_relin(ctx, ct_out, d_in, B, nlimbs, evk_mult, ws):
+    _check(_lib.ckks_relin(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(d_in, "d_in"), B, nlimbs, _ptr(evk_mult, "evk_mult"),
+                           _ptr(ws, "ws"), ws.numel() * 8, _stream()))
 
 
 def ckks_hrot_hoisted(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):

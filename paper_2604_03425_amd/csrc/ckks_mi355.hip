@@ -597,6 +597,7 @@ struct KsIo {
   const u32* galois_pc = nullptr;
   const u64* const* evk_pc = nullptr;
   const u64* add2 = nullptr;   // [B][2][nlimbs][N] plain addend of mode bit 0 (N = 2^16 path); null = out, in place
+  bool add2_three = false;     // add2 is [B][3][nlimbs][N]; its first two components are the addends
 };
 
 // Second half of a key switch on the N = 2^16 path: from the accumulators (acc, all slots) to the assembled output.
@@ -633,6 +634,7 @@ int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 n
     a.out = io.out;
     a.add_src = io.add_src;
     a.add2 = io.add2 ? io.add2 : io.out;
+    a.add2_three = io.add2 && io.add2_three ? 1u : 0u;
     a.tw = c->d_tw_fwd;
     a.twfp = c->d_twfp_fwd;
     a.mods = c->d_mods;
@@ -865,8 +867,8 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   int rc = get_level(c, nlimbs, &lt);
   if (rc) return rc;
   if (c->logN == 16) return keyswitch_fused16(c, lt, io, B, nlimbs, evk, ws, st);
-  if (io.d_galois || io.mode[0] >= 2 || io.mode[1] >= 2 || io.d_stride != (u64)nlimbs * c->N)
-    return fail(CKKS_EINVAL, "internal: gather modes need the N = 2^16 path");
+  if (io.d_galois || io.mode[0] >= 2 || io.mode[1] >= 2 || io.add2)
+    return fail(CKKS_EINVAL, "internal: gather modes and separate addends need the N = 2^16 path");
   const u64* d = io.d;
   u64* out = io.out;
   const u32 add_mask = (io.mode[0] ? 1u : 0u) | (io.mode[1] ? 2u : 0u);
@@ -879,7 +881,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
 
   // 1. coefficient form of d
-  if ((rc = launch_ntt(c, true, d, (u64)nlimbs * N, dcoef, (u64)nlimbs * N, B, 0, nlimbs, qmap, 0, 0, st))) return rc;
+  if ((rc = launch_ntt(c, true, d, io.d_stride, dcoef, (u64)nlimbs * N, B, 0, nlimbs, qmap, 0, 0, st))) return rc;
   // 2. ModUp every digit to the slots it does not own
   {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
@@ -891,7 +893,7 @@ int keyswitch_impl(ckks_ctx* c, const KsIo& io, u32 B, u32 nlimbs, const u64* ev
   if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st))) return rc;
   // 4. inner product with the key
   {
-    InnerArgs a{d, ext, evk, acc, c->d_mods, c->logN, nlimbs, c->nq, c->nm, c->alpha, beta, next};
+    InnerArgs a{d, ext, evk, acc, c->d_mods, c->logN, nlimbs, c->nq, c->nm, c->alpha, beta, next, io.d_stride};
     ProfScope ps(c, PK_INNER, st);
     hipLaunchKernelGGL(inner_kernel, dim3(B, N / 256, next), dim3(256), 0, st, a);
     HIP_TRY(hipGetLastError());
@@ -1322,6 +1324,57 @@ int ckks_hmult_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_a, const 
   }
   HIP_TRY(hipGetLastError());
   KsIo io{d2, (u64)nlimbs * c->N, 0, (u64*)ct_out, {1, 1}, nullptr, 0};
+  return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
+}
+
+int ckks_tensor_acc(ckks_ctx* c, uint64_t* d_out, const uint64_t* ct_a, const uint64_t* ct_b, const uint64_t* d_acc,
+                    uint32_t B, uint32_t nlimbs, void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!d_out || !ct_a || !ct_b) return fail(CKKS_EINVAL, "null argument");
+  const size_t ct_bytes = (size_t)B * 2 * nlimbs * c->N * 8, d_bytes = ct_bytes / 2 * 3;
+  if (overlap(d_out, d_bytes, ct_a, ct_bytes) || overlap(d_out, d_bytes, ct_b, ct_bytes))
+    return fail(CKKS_EINVAL, "d_out overlaps an input ciphertext");
+  if (d_acc && d_acc != d_out && overlap(d_out, d_bytes, d_acc, d_bytes))
+    return fail(CKKS_EINVAL, "d_acc overlaps d_out without being d_out");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  TensorAccArgs a{(const u64*)ct_a, (const u64*)ct_b, (const u64*)d_acc, (u64*)d_out, c->d_mods, c->logN, nlimbs};
+  {
+    ProfScope ps(c, PK_TENSOR, st);
+    hipLaunchKernelGGL(tensor_acc_kernel, dim3(c->N / 256, nlimbs, B), dim3(256), 0, st, a);
+  }
+  HIP_TRY(hipGetLastError());
+  return CKKS_OK;
+}
+
+int ckks_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* d_in, uint32_t B, uint32_t nlimbs, const uint64_t* evk,
+               void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (!ct_out || !d_in || !evk) return fail(CKKS_EINVAL, "null argument");
+  if ((rc = check_ws(c, CKKS_OP_KEYSWITCH, B, nlimbs, 0, ws, ws_bytes))) return rc;
+  const size_t polyN = (size_t)nlimbs * c->N;
+  if (overlap(ct_out, (size_t)B * 2 * polyN * 8, d_in, (size_t)B * 3 * polyN * 8))
+    return fail(CKKS_EINVAL, "ct_out overlaps d_in");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  const u64* d = (const u64*)d_in;
+  KsIo io{d + 2 * polyN, 3 * (u64)polyN, 0, (u64*)ct_out, {1, 1}, nullptr, 0};
+  if (c->logN == 16) {
+    // the last kernel of the key switch reads d0 and d1 in place
+    io.add2 = d;
+    io.add2_three = true;
+  } else {
+    // general path: d0, d1 are copied into ct_out and the key switch adds to them in place
+    const size_t pl2 = polyN / 2;
+    ProfScope ps(c, PK_ADD, st);
+    hipLaunchKernelGGL(first_two_components_kernel, dim3((unsigned)((2 * pl2 + 255) / 256), B), dim3(256), 0, st,
+                       (const ulonglong2*)d, (ulonglong2*)ct_out, pl2);
+    HIP_TRY(hipGetLastError());
+  }
   return keyswitch_impl(c, io, B, nlimbs, (const u64*)evk, (char*)ws, st);
 }
 

@@ -262,12 +262,13 @@ __global__ void __launch_bounds__(BCONV_THREADS) modup_kernel(ModUpArgs a, const
 // Inner product with the evaluation key over the extended basis, eval domain:
 // acc[b][c][t][n] = sum_j D_j[t][n] * evk[j][c][id(t)][n], D_j[t] = d[b][t] on digit j's own limbs, ext[b][j][t] else.
 struct InnerArgs {
-  const u64* d;     // [B][nlimbs][N] eval
+  const u64* d;     // [B][nlimbs][N] eval, polynomial b at d + b*d_stride
   const u64* ext;   // [B][beta][next][N] eval
   const u64* evk;   // [dnum][2][nm][N]
   u64* acc;         // [B][2][next][N]
   const ModInfo* mods;
   u32 logN, nlimbs, nq, nm, alpha, beta, next;
+  u64 d_stride;
 };
 __global__ void __launch_bounds__(256) inner_kernel(InnerArgs a) {
   const u32 N = 1u << a.logN;
@@ -279,7 +280,7 @@ __global__ void __launch_bounds__(256) inner_kernel(InnerArgs a) {
   Acc128 sb = {0, 0}, sa = {0, 0};
   for (u32 j = 0; j < a.beta; j++) {
     const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs);
-    u64 x = (t >= lo && t < hi) ? a.d[((size_t)b * a.nlimbs + t) * N + n]
+    u64 x = (t >= lo && t < hi) ? a.d[(size_t)b * a.d_stride + (size_t)t * N + n]
                                 : a.ext[(((size_t)b * a.beta + j) * a.next + t) * N + n];
     mac128(sb, x, a.evk[(((size_t)j * 2 + 0) * a.nm + id) * N + n]);
     mac128(sa, x, a.evk[(((size_t)j * 2 + 1) * a.nm + id) * N + n]);
@@ -392,6 +393,48 @@ __global__ void __launch_bounds__(256) tensor_kernel(TensorArgs a) {
   mac128(s, a1, b0);
   a.out[o1] = reduce128(s, mi);
   a.d2[((size_t)b * a.nlimbs + i) * N + n] = mulmod(a1, b1, mi);
+}
+
+// Three-component product kept for a later relinearisation: out[b] = (a0 b0, a0 b1 + a1 b0, a1 b1) (+ acc[b]).
+// acc may be out itself: every lane reads its own words before it writes them.
+struct TensorAccArgs {
+  const u64 *cta, *ctb, *acc;  // [B][2][nlimbs][N], [B][2][nlimbs][N], null or [B][3][nlimbs][N]
+  u64* out;                    // [B][3][nlimbs][N]
+  const ModInfo* mods;
+  u32 logN, nlimbs;
+};
+__global__ void __launch_bounds__(256) tensor_acc_kernel(TensorAccArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = blockIdx.x * 256 + threadIdx.x;
+  const u32 i = blockIdx.y, b = blockIdx.z;
+  const ModInfo mi = a.mods[i];
+  const size_t pl = (size_t)a.nlimbs * N;
+  const size_t i0 = (size_t)b * 2 * pl + (size_t)i * N + n, i1 = i0 + pl;
+  const size_t o0 = (size_t)b * 3 * pl + (size_t)i * N + n;
+  u64 a0 = a.cta[i0], a1 = a.cta[i1], b0 = a.ctb[i0], b1 = a.ctb[i1];
+  u64 t0 = mulmod(a0, b0, mi);
+  Acc128 s = {0, 0};
+  mac128(s, a0, b1);
+  mac128(s, a1, b0);
+  u64 t1 = reduce128(s, mi);
+  u64 t2 = mulmod(a1, b1, mi);
+  if (a.acc) {
+    t0 = addmod(t0, a.acc[o0], mi.m);
+    t1 = addmod(t1, a.acc[o0 + pl], mi.m);
+    t2 = addmod(t2, a.acc[o0 + 2 * pl], mi.m);
+  }
+  a.out[o0] = t0;
+  a.out[o0 + pl] = t1;
+  a.out[o0 + 2 * pl] = t2;
+}
+
+// out[b][c] = in[b][c] for c < 2, in holding three components per ciphertext (two adjacent words per lane).
+__global__ void __launch_bounds__(256) first_two_components_kernel(const ulonglong2* __restrict__ in,
+                                                                   ulonglong2* __restrict__ out, size_t pl2) {
+  const size_t k = (size_t)blockIdx.x * 256 + threadIdx.x;   // < 2 * pl2: both kept components of one ciphertext
+  if (k >= 2 * pl2) return;
+  const size_t b = blockIdx.y;
+  out[b * 2 * pl2 + k] = in[b * 3 * pl2 + k];
 }
 
 // BSGS inner sums for GT consecutive giant steps at once:

@@ -581,7 +581,12 @@ struct FwdFinalArgs {
   unsigned char slots[128];  // grid.z index -> limb (one modulus class per launch)
   u32 multi = 0;             // != 0: ciphertext b = bc / 2 reads add_src through galois_pc[b]
   u32 galois_pc[KS_MULTI_MAX];
+  u32 add2_three = 0;        // != 0: add2 holds three components per ciphertext ([B][3][nlimbs][N]); the first two are added
 };
+// polynomial index of component bc & 1 of ciphertext bc / 2 inside add2
+__device__ __forceinline__ size_t final_add2_poly(const FwdFinalArgs& a, u32 bc) {
+  return a.add2_three ? (size_t)(bc >> 1) * 3 + (bc & 1) : (size_t)bc;
+}
 template <bool BIG>
 __device__ __forceinline__ void fwd_final_body(const FwdFinalArgs& a, u32 bc, u32 tile, u32 i_limb, const ModInfo& mi, u64* sm) {
   const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
@@ -594,7 +599,7 @@ __device__ __forceinline__ void fwd_final_body(const FwdFinalArgs& a, u32 bc, u3
   u64* o = a.out + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
   const u32 mode = (bc & 1) ? a.mode1 : a.mode0;
   const u64* as = a.add_src + ((size_t)bc * a.nlimbs + i_limb) * N;
-  const u64* a2 = a.add2 + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
+  const u64* a2 = a.add2 + (final_add2_poly(a, bc) * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
   const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(bc >> 1)] : a.galois;
 #pragma unroll
   for (int i = 0; i < 16; i++) {
@@ -620,7 +625,7 @@ __device__ __forceinline__ void fwd_final_body_fp(const FwdFinalArgs& a, u32 bc,
   const u32 g = a.multi ? a.galois_pc[__builtin_amdgcn_readfirstlane(bc >> 1)] : a.galois;
   u64 ad[16];
   if (mode & 1) {
-    const u64* a2 = a.add2 + ((size_t)bc * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
+    const u64* a2 = a.add2 + (final_add2_poly(a, bc) * a.nlimbs + i_limb) * N + (size_t)h * 256 + j0;
 #pragma unroll
     for (int i = 0; i < 16; i++) ad[i] = a2[i * 16];
   } else if (mode == 2) {

@@ -30,6 +30,12 @@ class RefOps:
         """add + HRot_g(a): by definition the rotation followed by the addition."""
         return self.add(add, self.c.hrot(a, g, key))
 
+    def tensor_acc(self, a, b, acc):
+        return self.c.tensor_acc(a, b, acc)
+
+    def relin(self, d, relin):
+        return self.c.relin(d, relin)
+
     def rescale(self, a):
         return self.c.rescale(a)
 
@@ -72,6 +78,21 @@ class GpuOps:
         self.m.ckks_hrot_add(self.c, out, a, add, a.shape[0], a.shape[2], g, key, self.ws)
         return out
 
+    def tensor_acc(self, a, b, acc):
+        """Accumulates in place when acc is given."""
+        import torch
+        B, _, n, N = a.shape
+        out = acc if acc is not None else torch.empty((B, 3, n, N), dtype=a.dtype, device=a.device)
+        self.m.ckks_tensor_acc(self.c, out, a, b, acc, B, n)
+        return out
+
+    def relin(self, d, relin):
+        import torch
+        B, _, n, N = d.shape
+        out = torch.empty((B, 2, n, N), dtype=d.dtype, device=d.device)
+        self.m.ckks_relin(self.c, out, d, B, n, relin, self.ws)
+        return out
+
     def rescale(self, a):
         out = self._new(a, a.shape[2] - 1)
         self.m.ckks_rescale(self.c, out, a, a.shape[0], a.shape[2], self.ws)
@@ -110,3 +131,10 @@ def av_unit(ops, logN, q_ct, k_rot, v_rot, relin, sum_keys, mask_pt, rep_keys, h
     than q_ct."""
     a = mask_and_pack(ops, logN, score_diagonal(ops, logN, q_ct, k_rot, relin, sum_keys, hd), mask_pt, rep_keys, hd)
     return ops.hmult(a, v_rot, relin)
+
+
+def av_unit_late(ops, logN, q_ct, k_rot, v_rot, relin, sum_keys, mask_pt, rep_keys, hd, acc):
+    """av_unit with late relinearisation (Sec. 5.2): the product with V stays in three components and is added to
+    acc (None for the first unit); one ops.relin after the last unit of the block replaces a key switch per unit."""
+    a = mask_and_pack(ops, logN, score_diagonal(ops, logN, q_ct, k_rot, relin, sum_keys, hd), mask_pt, rep_keys, hd)
+    return ops.tensor_acc(a, v_rot, acc)

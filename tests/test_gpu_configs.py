@@ -234,6 +234,20 @@ def test_attention_av_unit(gpu, name, nl, B, hd):
                   [to_dev(k) for k in sum_keys], to_dev(mask), [to_dev(k) for k in rep_keys], hd)
     assert got.shape == (B, 2, nl - 2, p.N)
     assert_same(to_host(got), want, "attention A x V unit")
+    # late relinearisation: two units accumulated in three components (here the same unit twice), one key switch
+    from flows import av_unit_late
+    rops, gops = RefOps(rc), GpuOps(gpu, gc, B, nl)
+    dev = (to_dev(q_ct), to_dev(k_ct), to_dev(v_ct), to_dev(relin), [to_dev(k) for k in sum_keys], to_dev(mask),
+           [to_dev(k) for k in rep_keys])
+    ref.set_threads(4)
+    w = g = None
+    for _ in range(2):
+        w = av_unit_late(rops, p.logN, q_ct, k_ct, v_ct, relin, sum_keys, mask, rep_keys, hd, w)
+        g = av_unit_late(gops, p.logN, *dev, hd, g)
+    want_late = rops.relin(w, relin)
+    ref.set_threads(1)
+    assert_same(to_host(g), w, "A x V units in three components")
+    assert_same(to_host(gops.relin(g, dev[3])), want_late, "A x V block relinearised late")
 
 
 @pytest.mark.parametrize("name,nl,B", [("tiny_hrot", 4, 8), ("keyswitch_micro", 24, 3),
@@ -362,4 +376,54 @@ def test_hrot_add(gpu, shape, nl, B):
     else:
         with pytest.raises(gpu.CkksError):
             gpu.ckks_hrot_add(gc, out, d_ct, out, B, nl, g, d_evk, ws)
+    gc.close()
+
+
+@pytest.mark.parametrize("shape,nl,B", [((12, 4, 40, 2, 50, 2), 4, 3), ((12, 5, 50, 3, 60, 2), 3, 2),
+                                        ((16, 5, 50, 3, 60, 2), 5, 2), ((16, 4, 60, 2, 60, 2), 3, 2)])
+def test_late_relinearisation(gpu, shape, nl, B):
+    """Three-component products accumulated over three pairs (first call without addend, then in place and into
+    a second buffer), relinearised once; and relin(tensor(a, b)) against HMult+relin of the library itself."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(*shape)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    pairs = [(uniform_residues(700 + 2 * i, p.q[:nl], (B, 2), p.N), uniform_residues(701 + 2 * i, p.q[:nl], (B, 2), p.N))
+             for i in range(3)]
+    evk = uniform_residues(710, p.moduli, (p.dnum, 2), p.N)
+    ref.set_threads(2)
+    want = None
+    for a, b in pairs:
+        want = rc.tensor_acc(a, b, want)
+    want_ct = rc.relin(want, evk)
+    ref.set_threads(1)
+    d_evk = to_dev(evk)
+    dp = [(to_dev(a), to_dev(b)) for a, b in pairs]
+    acc = torch.empty((B, 3, nl, p.N), dtype=dp[0][0].dtype, device=dp[0][0].device)
+    gpu.ckks_tensor_acc(gc, acc, dp[0][0], dp[0][1], None, B, nl)
+    assert_same(to_host(acc), rc.tensor_acc(*pairs[0]), "tensor, no addend")
+    gpu.ckks_tensor_acc(gc, acc, dp[1][0], dp[1][1], acc, B, nl)          # in place
+    acc2 = torch.empty_like(acc)
+    gpu.ckks_tensor_acc(gc, acc2, dp[2][0], dp[2][1], acc, B, nl)         # into another buffer
+    assert_same(to_host(acc2), want, "tensor, accumulated")
+    ws = gc.workspace(gpu.OP_KEYSWITCH, B, nl)
+    out = torch.empty((B, 2, nl, p.N), dtype=acc.dtype, device=acc.device)
+    gpu.ckks_relin(gc, out, acc2, B, nl, d_evk, ws)
+    assert_same(to_host(out), want_ct, "relin of the sum")
+    assert_same(to_host(acc2), want, "relin leaves its input alone")
+    # one product: relin(tensor) is HMult+relin
+    one = torch.empty_like(acc)
+    gpu.ckks_tensor_acc(gc, one, dp[0][0], dp[0][1], None, B, nl)
+    gpu.ckks_relin(gc, out, one, B, nl, d_evk, ws)
+    ws2 = gc.workspace(gpu.OP_HMULT_RELIN, B, nl)
+    hm = torch.empty_like(out)
+    gpu.ckks_hmult_relin(gc, hm, dp[0][0], dp[0][1], B, nl, d_evk, ws2)
+    assert torch.equal(out, hm)
+    # error paths: overlap of output and input, partial overlap of addend and output
+    with pytest.raises(gpu.CkksError):
+        gpu.ckks_relin(gc, acc2.view(-1)[:out.numel()].view_as(out), acc2, B, nl, d_evk, ws)
+    pl, part = nl * p.N, (B - 1) * 3 * nl * p.N
+    shifted = acc.view(-1)[pl:pl + part].view(B - 1, 3, nl, p.N)     # one component further on: overlaps acc[:B-1]
+    with pytest.raises(gpu.CkksError):
+        gpu.ckks_tensor_acc(gc, shifted, dp[0][0][1:], dp[0][1][1:], acc[:B - 1], B - 1, nl)
     gc.close()

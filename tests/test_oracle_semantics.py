@@ -281,7 +281,7 @@ def test_attention_av_block():
     aggregation with V is local): summing the units over all cyclic diagonals r gives (Q K^T) V. hd = 8 slots per
     token, 64 tokens per ciphertext, Delta = 2^40 with 40-bit primes so that each Rescale keeps the scale near
     Delta; max |err| < 2^-20."""
-    from flows import RefOps, av_unit
+    from flows import RefOps, av_unit, av_unit_late
     p = make_params(10, 5, 40, 3, 50, 2)
     c = ref.RefContext(p)
     keys = Keys(p, c, 71)
@@ -302,16 +302,21 @@ def test_attention_av_block():
     rep_keys = [rk(-(1 << i)) for i in range(3)]
     g_tok, tok_key = galois_element(hd, p.logN), rk(hd)
     ops = RefOps(c)
-    out = None
+    out = late = None
     for r in range(T):
         if r:
             ck = c.hrot(ck, g_tok, tok_key)
             cv = c.hrot(cv, g_tok, tok_key)
         u = av_unit(ops, p.logN, cq, ck, cv, relin, sum_keys, mask_pt, rep_keys, hd)
         out = u if out is None else ops.add(out, u)
+        late = av_unit_late(ops, p.logN, cq, ck, cv, relin, sum_keys, mask_pt, rep_keys, hd, late)
     assert out.shape == (1, 2, 3, p.N)
     scale = D**4 / (p.q[4] * p.q[3])
     got = keys.decrypt_slots(out[0], scale).real.reshape(T, hd)
     want = (Q @ Kmat.T) @ V
     err = np.max(np.abs(got - want))
     assert err < 2.0**-20, err
+    # late relinearisation: one key switch for the block instead of one per diagonal, same result up to noise
+    got_late = keys.decrypt_slots(ops.relin(late, relin)[0], scale).real.reshape(T, hd)
+    err_late = np.max(np.abs(got_late - want))
+    assert err_late < 2.0**-20, err_late
