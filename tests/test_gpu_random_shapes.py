@@ -58,6 +58,13 @@ def test_random_parameter_sets(seed):
         same(out, multi, "hrot_multi")
         gpu.ckks_hmult_relin(gc, out, d_ct, d_ct2, B, nl, d_evk, ws)
         same(out, rc.hmult_relin(ct, ct2, evk), "hmult_relin")
+        d3 = torch.empty((B, 3, nl, p.N), dtype=torch.int64, device="cuda")
+        gpu.ckks_tensor_acc(gc, d3, d_ct, d_ct2, None, B, nl)
+        gpu.ckks_tensor_acc(gc, d3, d_ct2, d_ct2, d3, B, nl)
+        want3 = rc.tensor_acc(ct2, ct2, rc.tensor_acc(ct, ct2))
+        same(d3, want3, "tensor_acc")
+        gpu.ckks_relin(gc, out, d3, B, nl, d_evk2, ws)
+        same(out, rc.relin(want3, evk2), "relin")
         if nl >= 2:
             rs = torch.empty((B, 2, nl - 1, p.N), dtype=torch.int64, device="cuda")
             gpu.ckks_rescale(gc, rs, d_ct, B, nl, gc.workspace(gpu.OP_RESCALE, B, nl))
