@@ -185,6 +185,23 @@ class RefContext:
         _check(lib().ref_hmult_relin(self._h, out.ctypes.data_as(u64p), ap, bp, C.c_uint32(B), C.c_uint32(nl), ep))
         return out
 
+    def pcmm_bsgs_double_hoisted(self, ct, pt_ext, n1, n2, stride, evk_baby, evk_giant):
+        """BSGS matmul with the baby steps kept in the extended basis; pt_ext [n2][n1][nlimbs + K][N]."""
+        ct, cp = _u64(ct)
+        pt_ext, pp = _u64(pt_ext)
+        B, two, nl, _ = ct.shape
+        assert pt_ext.shape == (n2, n1, nl + self.np_, self.N)
+        assert len(evk_baby) == n1 - 1 and len(evk_giant) == n2 - 1
+        keep = [_u64(k) for k in list(evk_baby) + list(evk_giant)]
+        PA = u64p * max(1, n1 - 1)
+        PG = u64p * max(1, n2 - 1)
+        baby = PA(*[k[1] for k in keep[:n1 - 1]])
+        giant = PG(*[k[1] for k in keep[n1 - 1:]])
+        out = np.empty_like(ct)
+        _check(lib().ref_pcmm_bsgs_double_hoisted(self._h, out.ctypes.data_as(u64p), cp, C.c_uint32(B), C.c_uint32(nl),
+                                                  pp, C.c_uint32(n1), C.c_uint32(n2), C.c_uint32(stride), baby, giant))
+        return out
+
     def tensor_acc(self, ct_a, ct_b, d_acc=None):
         """Un-relinearised product [B][3][nl][N], added to d_acc when given (late relinearisation, Sec. 5.2)."""
         ct_a, ap = _u64(ct_a)

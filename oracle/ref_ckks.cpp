@@ -274,8 +274,10 @@ bool check_ids(const RefCtx* c, const uint32_t* ids, uint32_t n) {
   return true;
 }
 
-// Hybrid key switch of ONE polynomial d (eval domain, nlimbs limbs) with evk; writes ks (2 x nlimbs x N).
-void keyswitch_one(const RefCtx* c, u64* ks, const u64* d, int nlimbs, const u64* evk) {
+// First half of the hybrid key switch of ONE polynomial d (eval domain, nlimbs limbs): digit decomposition, ModUp of
+// every digit to the extended basis q_0..q_{nlimbs-1}, p_0..p_{K-1}, and the inner product with evk. Returns the two
+// accumulators in the evaluation domain, [2][nlimbs + K][N].
+std::vector<u64> keyswitch_accumulate(const RefCtx* c, const u64* d, int nlimbs, const u64* evk) {
   const size_t N = c->N;
   const int K = c->np, nm = c->nq + c->np, alpha = c->alpha;
   const int beta = (nlimbs + alpha - 1) / alpha;
@@ -321,7 +323,17 @@ void keyswitch_one(const RefCtx* c, u64* ks, const u64* d, int nlimbs, const u64
       }
     }
   }
-  // ModDown of each accumulator: x_c = INTT(x); t = BConv_{P->Q_l}(x_c|P); ks_i = NTT((x_c,i - t_i) * P^-1).
+  return acc;
+}
+
+// Second half: ModDown of both accumulators (evaluation domain, [2][nlimbs + K][N], overwritten):
+// x_c = INTT(x); t = BConv_{P->Q_l}(x_c|P); ks_i = NTT((x_c,i - t_i) * P^-1). Writes ks (2 x nlimbs x N).
+void moddown_pair(const RefCtx* c, u64* ks, std::vector<u64>& acc, int nlimbs) {
+  const size_t N = c->N;
+  const int K = c->np, next = nlimbs + K;
+  std::vector<int> ext_id(next);
+  for (int t = 0; t < nlimbs; t++) ext_id[t] = t;
+  for (int k = 0; k < K; k++) ext_id[nlimbs + k] = c->nq + k;
   std::vector<u64> psrc, qdst;
   for (int k = 0; k < K; k++) psrc.push_back(c->mod[c->nq + k]);
   for (int i = 0; i < nlimbs; i++) qdst.push_back(c->mod[i]);
@@ -345,6 +357,12 @@ void keyswitch_one(const RefCtx* c, u64* ks, const u64* d, int nlimbs, const u64
       ntt_fast(c, o, i);
     }
   }
+}
+
+// Hybrid key switch of ONE polynomial d (eval domain, nlimbs limbs) with evk; writes ks (2 x nlimbs x N).
+void keyswitch_one(const RefCtx* c, u64* ks, const u64* d, int nlimbs, const u64* evk) {
+  std::vector<u64> acc = keyswitch_accumulate(c, d, nlimbs, evk);
+  moddown_pair(c, ks, acc, nlimbs);
 }
 
 void automorph_eval(const RefCtx* c, u64* out, const u64* in, int id, u64 g) {
@@ -669,6 +687,88 @@ int ref_pcmm_bsgs(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, ui
             }
           }
       }
+      const u64* add = inner.data();
+      if (g > 0) {
+        hrot_one(c, rot.data(), inner.data(), nlimbs, powm(5, (u64)g * n1 * stride, twoN), evk_giant[g - 1]);
+        add = rot.data();
+      }
+      for (int comp = 0; comp < 2; comp++)
+        for (uint32_t i = 0; i < nlimbs; i++) {
+          u64 m = c->mod[i];
+          for (size_t n = 0; n < N; n++) {
+            size_t k = (size_t)comp * pl + (size_t)i * N + n;
+            y[k] = addm(y[k], add[k], m);
+          }
+        }
+    }
+    std::copy(y.begin(), y.end(), ct_out + bi * sz);
+  });
+  return 0;
+}
+
+// BSGS matmul with the baby steps kept in the extended basis ("double hoisting": the hoisting the paper discusses
+// in Sec. 5.1 taken one step further; not the paper's own schedule, which rotates one at a time). With
+// P = p_0 ... p_{K-1} and the basis q_0..q_{nlimbs-1}, p_0..p_{K-1}:
+//   A_0 = (P c0, P c1) on the q-limbs, 0 on the p-limbs;
+//   A_r = accumulators of the key switch of sigma_r(c1) under evk_baby[r-1] (before ModDown), with P sigma_r(c0)
+//         added to the first one on the q-limbs                                  (r = 1..n1-1, sigma_r = 5^(r*stride));
+//   S_g = sum_r pt_ext[g][r] (.) A_r  (both components, every limb of the extended basis);
+//   y   = sum_g rot_{g*n1*stride}( ModDown(S_g) ), the giant-step rotations being ordinary HRots.
+// ModDown(x + P z) = z + ModDown(x) exactly, so the c0 terms come out as in the plain schedule; what differs is that
+// the rounding of ModDown is applied once per giant step, after the sum over baby steps. pt_ext: [n2][n1][nlimbs+K][N],
+// the plaintext's residues for q_0..q_{nlimbs-1} and then p_0..p_{K-1}, evaluation domain.
+int ref_pcmm_bsgs_double_hoisted(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, uint32_t nlimbs,
+                                 const u64* pt_ext, uint32_t n1, uint32_t n2, uint32_t stride,
+                                 const u64* const* evk_baby, const u64* const* evk_giant) {
+  if (nlimbs == 0 || nlimbs > (uint32_t)c->nq || n1 == 0 || n2 == 0) return fail("bad shape");
+  const size_t N = c->N, pl = (size_t)nlimbs * N, sz = 2 * pl;
+  const int K = c->np, next = (int)nlimbs + K;
+  const size_t el = (size_t)next * N;   // one component in the extended basis
+  const u64 twoN = 2 * N;
+  auto ext_mod = [&](int t) { return c->mod[t < (int)nlimbs ? t : c->nq + (t - (int)nlimbs)]; };
+  std::vector<u64> pmod(nlimbs);        // P mod q_i
+  for (uint32_t i = 0; i < nlimbs; i++) {
+    u64 m = c->mod[i], v = 1;
+    for (int k = 0; k < K; k++) v = mulm(v, c->mod[c->nq + k] % m, m);
+    pmod[i] = v;
+  }
+  parallel_for(B, [&](size_t bi) {
+    const u64* x = ct_in + bi * sz;
+    std::vector<std::vector<u64>> A(n1);
+    A[0].assign(2 * el, 0);
+    for (int comp = 0; comp < 2; comp++)
+      for (uint32_t i = 0; i < nlimbs; i++)
+        for (size_t n = 0; n < N; n++)
+          A[0][(size_t)comp * el + (size_t)i * N + n] = mulm(x[(size_t)comp * pl + (size_t)i * N + n] % c->mod[i], pmod[i], c->mod[i]);
+    std::vector<u64> r0(pl), r1(pl);
+    for (uint32_t r = 1; r < n1; r++) {
+      const u64 g = powm(5, (u64)r * stride, twoN);
+      for (uint32_t i = 0; i < nlimbs; i++) {
+        automorph_eval(c, &r0[(size_t)i * N], x + (size_t)i * N, i, g);
+        automorph_eval(c, &r1[(size_t)i * N], x + pl + (size_t)i * N, i, g);
+      }
+      A[r] = keyswitch_accumulate(c, r1.data(), nlimbs, evk_baby[r - 1]);
+      for (uint32_t i = 0; i < nlimbs; i++)
+        for (size_t n = 0; n < N; n++) {
+          u64& a = A[r][(size_t)i * N + n];
+          a = addm(a, mulm(r0[(size_t)i * N + n], pmod[i], c->mod[i]), c->mod[i]);
+        }
+    }
+    std::vector<u64> y(sz, 0), S(2 * el), inner(sz), rot(sz);
+    for (uint32_t g = 0; g < n2; g++) {
+      std::fill(S.begin(), S.end(), 0);
+      for (uint32_t r = 0; r < n1; r++) {
+        const u64* w = pt_ext + ((size_t)g * n1 + r) * el;
+        for (int comp = 0; comp < 2; comp++)
+          for (int t = 0; t < next; t++) {
+            u64 m = ext_mod(t);
+            for (size_t n = 0; n < N; n++) {
+              size_t k = (size_t)comp * el + (size_t)t * N + n;
+              S[k] = addm(S[k], mulm(A[r][k], w[(size_t)t * N + n] % m, m), m);
+            }
+          }
+      }
+      moddown_pair(c, inner.data(), S, nlimbs);
       const u64* add = inner.data();
       if (g > 0) {
         hrot_one(c, rot.data(), inner.data(), nlimbs, powm(5, (u64)g * n1 * stride, twoN), evk_giant[g - 1]);

@@ -43,3 +43,10 @@ def encode_plain_eval(ctx, z, scale, nlimbs):
     msg = ref.encode(z, ctx.N, scale)
     ids = list(range(nlimbs))
     return ctx.ntt(ctx.signed_to_rns(msg, ids)[None], ids)[0]
+
+
+def encode_plain_eval_ext(ctx, z, scale, nlimbs):
+    """The same plaintext in the extended basis q_0..q_{nlimbs-1}, p_0..p_{K-1}: [nlimbs + K][N]."""
+    msg = ref.encode(z, ctx.N, scale)
+    ids = list(range(nlimbs)) + [len(ctx.params.q) + k for k in range(len(ctx.params.p))]
+    return ctx.ntt(ctx.signed_to_rns(msg, ids)[None], ids)[0]

@@ -8,7 +8,7 @@ import pytest
 
 from ckks_inputs import config_params, galois_element, make_params, uniform_slots, normal_slots, uniform_residues
 from oracle import ref
-from harness import Keys, encode_plain_eval
+from harness import Keys, encode_plain_eval, encode_plain_eval_ext
 
 
 def test_encode_decode_against_slot_definition():
@@ -221,6 +221,59 @@ def test_pcmm_bsgs_is_a_matrix_product():
     Y = X @ W
     for t in range(ntok):
         assert np.max(np.abs(y[t * seg:t * seg + dim] - Y[t])) < 2.0**-14
+
+
+def test_pcmm_double_hoisted():
+    """BSGS with the baby steps kept in the extended basis (one ModDown per giant step). Pins: (1) the same matrix
+    product after decryption, and a phase that differs from the plain schedule's by rounding noise only; (2) with
+    n1 = 1 no key switch happens before the sum, ModDown(P x) = x exactly, so the result is bit-identical to the plain
+    schedule; (3) with the all-ones plaintext, n1 = 2, n2 = 1: ModDown(P c + A_1) = c + ModDown(A_1) exactly, so the
+    result is ct + HRot(ct), bit for bit."""
+    p = make_params(8, 4, 40, 2, 50, 2)
+    c = ref.RefContext(p)
+    keys = Keys(p, c, 43)
+    S = p.N // 2
+    dim, seg, n1, n2 = 6, 16, 3, 2
+    ntok = S // seg
+    rng = np.random.default_rng(1)
+    X = rng.uniform(-1, 1, (ntok, dim))
+    W = rng.normal(0, 0.5, (dim, dim))
+    z = np.zeros(S)
+    for t in range(ntok):
+        z[t * seg:t * seg + dim] = X[t]
+        z[t * seg + dim:t * seg + 2 * dim] = X[t]
+    ct = keys.encrypt_slots(z, 2.0**30, 4)
+    pts = np.empty((n2, n1, 6, p.N), dtype=np.uint64)
+    for g in range(n2):
+        for b in range(n1):
+            dvec = np.zeros(S)
+            for t in range(ntok):
+                for j in range(dim):
+                    jp = j + g * n1
+                    dvec[t * seg + jp] = W[(jp + b) % dim][j]
+            pts[g, b] = encode_plain_eval_ext(c, dvec, 2.0**30, 4)
+    baby = [keys.rotation_key(galois_element(b, p.logN)) for b in range(1, n1)]
+    giant = [keys.rotation_key(galois_element(g * n1, p.logN)) for g in range(1, n2)]
+    out = c.pcmm_bsgs_double_hoisted(ct[None], pts, n1, n2, 1, baby, giant)[0]
+    y = keys.decrypt_slots(out, 2.0**60).real
+    Y = X @ W
+    for t in range(ntok):
+        assert np.max(np.abs(y[t * seg:t * seg + dim] - Y[t])) < 2.0**-14
+    plain = c.pcmm_bsgs(ct[None], np.ascontiguousarray(pts[:, :, :4]), n1, n2, 1, baby, giant)[0]
+    assert not np.array_equal(out, plain)                       # the rounding really is placed differently
+    ma, mb = c.decrypt_centred(out, keys.s), c.decrypt_centred(plain, keys.s)
+    noise = max(abs(int(a) - int(b)) for a, b in zip(ma, mb))
+    assert noise < 2**36, noise             # plaintext (2^30) x ModDown rounding: measured 2^32.4, against 2^60
+    # (2) n1 = 1
+    giant1 = [keys.rotation_key(galois_element(g, p.logN)) for g in range(1, n2)]
+    one = np.ascontiguousarray(pts[:, :1])
+    assert np.array_equal(c.pcmm_bsgs_double_hoisted(ct[None], one, 1, n2, 1, [], giant1),
+                          c.pcmm_bsgs(ct[None], np.ascontiguousarray(one[:, :, :4]), 1, n2, 1, [], giant1))
+    # (3) all-ones plaintext (the constant polynomial 1 in the evaluation domain), one baby step, no giant step
+    ones = np.ones((1, 2, 6, p.N), dtype=np.uint64)
+    g1 = galois_element(1, p.logN)
+    got = c.pcmm_bsgs_double_hoisted(ct[None], ones, 2, 1, 1, baby[:1], [])
+    assert np.array_equal(got, c.pointwise(ct[None], c.hrot(ct[None], g1, baby[0]), [0, 1, 2, 3], "add"))
 
 
 def test_hrot_rotates_slots_at_full_size():
