@@ -61,6 +61,7 @@ extern "C" {
 #define CKKS_OP_HMULT_RELIN 3
 #define CKKS_OP_PCMM_BSGS 4
 #define CKKS_OP_RESCALE 5
+#define CKKS_OP_PCMM_BSGS_DH 6
 
 typedef struct ckks_ctx ckks_ctx;
 
@@ -212,6 +213,26 @@ int ckks_pcmm_bsgs_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_i
                            const uint64_t* pt_diag, uint32_t n1, uint32_t n2, uint32_t stride,
                            const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws, size_t ws_bytes,
                            void* stream);
+
+/*
+ * BSGS matmul with the baby steps kept in the extended basis ("double hoisting"): hoisting as discussed in the
+ * paper's Sec. 5.1, taken one step further; not the paper's own schedule and NOT bit-identical to ckks_pcmm_bsgs.
+ * With P the product of the special primes:
+ *   A_0 = (P*c0, P*c1) on the main primes, 0 on the special primes;
+ *   A_r = the key-switch accumulators of sigma_r(c1) under evk_baby[r-1] before ModDown, plus P*sigma_r(c0) on the
+ *         main primes of the first one (r = 1..n1-1, sigma_r = 5^(r*stride));
+ *   S_g = sum_r pt_ext[g][r] (.) A_r over all nlimbs + K limbs;   ct_out = sum_g rot_{g*n1*stride}(ModDown(S_g)).
+ * ModDown(x + P*z) = z + ModDown(x) exactly, so only the placement of ModDown's rounding differs from the plain
+ * schedule: once per giant step, after the sum (n2 ModDowns of baby-step data instead of n1 - 1 per ciphertext).
+ *   pt_ext  device [n2][n1][nlimbs + K][N]: the plaintexts' residues for q_0..q_{nlimbs-1}, then p_0..p_{K-1},
+ *           evaluation domain
+ * N = 2^16 only (CKKS_ESHAPE otherwise). Workspace: CKKS_OP_PCMM_BSGS_DH with n1 (n1 + 24 ciphertexts in the
+ * extended basis). Other arguments, overlap rules and errors as for ckks_pcmm_bsgs.
+ */
+int ckks_pcmm_bsgs_double_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                                  const uint64_t* pt_ext, uint32_t n1, uint32_t n2, uint32_t stride,
+                                  const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws,
+                                  size_t ws_bytes, void* stream);
 
 /*
  * Rescale (paper Sec. 2.1: "divides by the last modulus q_L to reduce scale and remove one prime"): for

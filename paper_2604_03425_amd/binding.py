@@ -11,14 +11,14 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libckks_mi355.so")
 
-OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS, OP_RESCALE = 1, 2, 3, 4, 5
+OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS, OP_RESCALE, OP_PCMM_BSGS_DH = 1, 2, 3, 4, 5, 6
 
 _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
             "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
             "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi", "ckks_hrot_add", "ckks_tensor_acc",
-            "ckks_relin"]
+            "ckks_relin", "ckks_pcmm_bsgs_double_hoisted"]
 
 
 class CkksError(RuntimeError):
@@ -63,6 +63,7 @@ def _load():
     lib.ckks_hrot_add.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_hrot_multi.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs_hoisted.argtypes = lib.ckks_pcmm_bsgs.argtypes
+    lib.ckks_pcmm_bsgs_double_hoisted.argtypes = lib.ckks_pcmm_bsgs.argtypes
     lib.ckks_rescale.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, vp, C.c_size_t, vp]
     lib.ckks_pmult.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
     lib.ckks_add.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
@@ -231,7 +232,7 @@ def ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_b
     giant = (C.c_void_p * max(1, n2 - 1))(*[_ptr(k, "evk_giant").value for k in evk_giant])
     if len(evk_baby) != n1 - 1 or len(evk_giant) != n2 - 1:
         raise ValueError("need n1-1 baby-step keys and n2-1 giant-step keys")
-    fn = _lib.ckks_pcmm_bsgs_hoisted if hoisted else _lib.ckks_pcmm_bsgs
+    fn = {False: _lib.ckks_pcmm_bsgs, True: _lib.ckks_pcmm_bsgs_hoisted, "double": _lib.ckks_pcmm_bsgs_double_hoisted}[hoisted]
     _check(fn(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs,
                                _ptr(pt_diag, "pt_diag"), n1, n2, stride, baby, giant, _ptr(ws, "ws"), ws.numel() * 8,
                                _stream()))
@@ -252,3 +253,7 @@ def ckks_add(ctx, out, a, b, npoly, nlimbs):
 
 def ckks_pcmm_bsgs_hoisted(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws):
     ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws, hoisted=True)
+
+
+def ckks_pcmm_bsgs_double_hoisted(ctx, ct_out, ct_in, B, nlimbs, pt_ext, n1, n2, stride, evk_baby, evk_giant, ws):
+    ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_ext, n1, n2, stride, evk_baby, evk_giant, ws, hoisted="double")

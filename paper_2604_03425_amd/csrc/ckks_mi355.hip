@@ -603,11 +603,12 @@ struct KsIo {
 // Second half of a key switch on the N = 2^16 path: from the accumulators (acc, all slots) to the assembled output.
 // wait_before_assembly: event the stream must wait for before the last kernel reads the main-prime accumulators.
 int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, char* ws, hipStream_t st,
-                hipEvent_t wait_before_assembly) {
+                hipEvent_t wait_before_assembly, u64* acc_in = nullptr) {
   int rc;
   const u32 N = c->N, next = lt->next, K = c->np;
   KsLayout L = ks_layout(c, B, nlimbs);
-  u64* acc = (u64*)(ws + L.acc);
+  // acc_in: accumulators held outside the workspace ([B][2][next][N]; their special-prime slots are overwritten)
+  u64* acc = acc_in ? acc_in : (u64*)(ws + L.acc);
   u64* tq = (u64*)(ws + L.tq);
   const LimbMap qmap = identity_map(nlimbs);
   NttOpts o2;
@@ -799,8 +800,10 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
 // centred base conversion (it permutes coefficients up to sign, and the conversion is odd), so INTT, ModUp and the
 // forward transform of c1 are done once on the un-rotated polynomial; each rotation then reads the transformed
 // digits through its own index map in the streaming inner product and finishes as usual.
+// acc_base != null: rotation r stops before ModDown and leaves its accumulators, with P * sigma(c0) added to the
+// first one, at acc_base + r * acc_stride (rotations kept in the extended basis); out_base is not used then.
 int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in, u32 B, u32 nlimbs, const u32* galois,
-                   const u64* const* evks, u32 R, char* ws, hipStream_t st) {
+                   const u64* const* evks, u32 R, char* ws, hipStream_t st, u64* acc_base = nullptr, u64 acc_stride = 0) {
   const LevelTables* lt;
   int rc = get_level(c, nlimbs, &lt);
   if (rc) return rc;
@@ -840,10 +843,15 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
   ia.beta = beta;
   ia.next = next;
   ia.map_mode = map_mode_inner(c, true);
+  if (acc_base) {
+    ia.c0 = ct_in;
+    ia.c0_poly_stride = 2 * polyN;
+  }
   for (u32 r = 0; r < R; r++) {
     ia.evk = evks[r];
     ia.galois = galois[r];
     ia.ext_galois = galois[r];
+    if (acc_base) ia.acc = acc_base + (size_t)r * acc_stride;
     for (int fp = 1; fp >= 0; fp--) {
       FwdInnerArgs a = ia;
       u32 cnt = 0;
@@ -855,6 +863,7 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
       else hipLaunchKernelGGL(inner16_int_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
     }
     HIP_TRY(hipGetLastError());
+    if (acc_base) continue;
     KsIo io{c1, 2 * polyN, galois[r], out_base + (size_t)r * out_stride, {2, 0}, ct_in, galois[r]};
     if ((rc = ks16_finish(c, lt, io, B, nlimbs, ws, st, nullptr))) return rc;
   }
@@ -1021,7 +1030,11 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
       u64 x = 1;  // Newton iteration for m^-1 mod 2^64 (m odd)
       for (int it = 0; it < 6; it++) x *= 2 - m * x;
       mi.minv = (u64)0 - x;
-      mi.pad = 0;
+      mi.pmod = 0;
+      if (i < c->nq) {
+        mi.pmod = 1;
+        for (u32 k = 0; k < c->np; k++) mi.pmod = h_mul(mi.pmod, c->mod[c->nq + k] % m, m);
+      }
     }
     mi.qd = (double)m;
     mi.qinv = 1.0 / (double)m;
@@ -1147,6 +1160,12 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlim
       if (n1 == 0) return 0;
       // baby steps 1..n1-1, PMACC_TILE inner sums, rotated inner sum, HRot workspace
       return (size_t)(n1 - 1) * 2 * poly + (size_t)PMACC_TILE * 2 * poly + 2 * poly + ks + poly;
+    case CKKS_OP_PCMM_BSGS_DH: {
+      if (n1 == 0) return 0;
+      // n1 baby steps and PMACC_TILE inner sums in the extended basis, one inner sum after ModDown, HRot workspace
+      const size_t ext_poly = align256((size_t)B * (nlimbs + c->np) * c->N * 8);
+      return (size_t)(n1 + PMACC_TILE) * 2 * ext_poly + 2 * poly + ks + poly;
+    }
     default: return 0;
   }
 }
@@ -1380,17 +1399,24 @@ int ckks_relin(ckks_ctx* c, uint64_t* ct_out, const uint64_t* d_in, uint32_t B, 
 
 static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                      const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
-                     const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream, bool hoisted);
+                     const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream, int mode);
 int ckks_pcmm_bsgs(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                    const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
                    const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream) {
-  return pcmm_impl(c, ct_out, ct_in, B, nlimbs, pt, n1, n2, stride, evk_baby, evk_giant, ws, ws_bytes, stream, false);
+  return pcmm_impl(c, ct_out, ct_in, B, nlimbs, pt, n1, n2, stride, evk_baby, evk_giant, ws, ws_bytes, stream, 0);
 }
 int ckks_pcmm_bsgs_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                            const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride,
                            const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws, size_t ws_bytes,
                            void* stream) {
-  return pcmm_impl(c, ct_out, ct_in, B, nlimbs, pt, n1, n2, stride, evk_baby, evk_giant, ws, ws_bytes, stream, true);
+  return pcmm_impl(c, ct_out, ct_in, B, nlimbs, pt, n1, n2, stride, evk_baby, evk_giant, ws, ws_bytes, stream, 1);
+}
+int ckks_pcmm_bsgs_double_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                                  const uint64_t* pt_ext, uint32_t n1, uint32_t n2, uint32_t stride,
+                                  const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws,
+                                  size_t ws_bytes, void* stream) {
+  if (c && c->logN != 16) return fail(CKKS_ESHAPE, "the double-hoisted schedule is built for N = 2^16 only");
+  return pcmm_impl(c, ct_out, ct_in, B, nlimbs, pt_ext, n1, n2, stride, evk_baby, evk_giant, ws, ws_bytes, stream, 2);
 }
 int ckks_hrot_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                       const uint32_t* galois_elts, const uint64_t* const* evks, uint32_t R, void* ws, size_t ws_bytes,
@@ -1418,7 +1444,10 @@ int ckks_hrot_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint
 }
 static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                      const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
-                     const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream, bool hoisted) {
+                     const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream, int mode) {
+  // mode 0: one rotation at a time; 1: hoisted baby steps; 2: baby steps kept in the extended basis (pt holds the
+  // plaintexts in that basis), one ModDown per giant step
+  const bool hoisted = mode == 1, dh = mode == 2;
   int rc = check_common(c, B, nlimbs);
   if (rc) return rc;
   if (!ct_out || !ct_in || !pt) return fail(CKKS_EINVAL, "null argument");
@@ -1429,16 +1458,21 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   for (u32 g = 1; g < n2; g++)
     if (!evk_giant[g - 1]) return fail(CKKS_EINVAL, "null giant-step key");
   if (2 * B > 65535) return fail(CKKS_ESHAPE, "batch too large for one call");
-  if ((rc = check_ws(c, CKKS_OP_PCMM_BSGS, B, nlimbs, n1, ws, ws_bytes))) return rc;
+  if ((rc = check_ws(c, dh ? CKKS_OP_PCMM_BSGS_DH : CKKS_OP_PCMM_BSGS, B, nlimbs, n1, ws, ws_bytes))) return rc;
   const size_t N = c->N, polyN = (size_t)nlimbs * N, ct_bytes = (size_t)B * 2 * polyN * 8;
   if (overlap(ct_out, ct_bytes, ct_in, ct_bytes)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
   hipStream_t st = (hipStream_t)stream;
   const size_t ct_al = 2 * align256((size_t)B * polyN * 8);
+  // polynomials the inner sums work on: nlimbs limbs, or the nlimbs + K slots of the extended basis
+  const u32 pl_limbs = dh ? nlimbs + c->np : nlimbs;
+  const size_t sum_al = dh ? 2 * align256((size_t)B * pl_limbs * N * 8) : ct_al;
   char* w = (char*)ws;
-  u64* baby = (u64*)w;                  w += (size_t)(n1 - 1) * ct_al;
-  u64* inner = (u64*)w;                 w += (size_t)PMACC_TILE * ct_al;   // inner sums of one tile of giant steps
+  u64* first = nullptr;                 // double-hoisted: (P c0, P c1), the term of baby step 0
+  if (dh) { first = (u64*)w;            w += sum_al; }
+  u64* baby = (u64*)w;                  w += (size_t)(n1 - 1) * sum_al;
+  u64* inner = (u64*)w;                 w += (size_t)PMACC_TILE * sum_al;   // inner sums of one tile of giant steps
   u64* rot = (u64*)w;                   w += ct_al;
   char* hws = w;
   const size_t hws_bytes = ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0);
@@ -1452,7 +1486,25 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
     return (u32)g;
   };
   const size_t ct_elems = ct_al / 8;  // == B*2*nlimbs*N: a limb-vector is a multiple of 256 bytes
-  if (hoisted && n1 > 1) {
+  const size_t sum_elems = sum_al / 8;
+  const LevelTables* lt = nullptr;
+  if (dh) {
+    if ((rc = get_level(c, nlimbs, &lt))) return rc;
+    LiftArgs la{(const u64*)ct_in, first, c->d_mods, c->logN, nlimbs, pl_limbs, {}};
+    for (u32 i = 0; i < nlimbs; i++) la.fp[i] = host_class(c, c->mod[i]) == 0 ? 1 : 0;
+    {
+      ProfScope ps(c, PK_ADD, st);
+      hipLaunchKernelGGL(lift_qp_kernel, dim3(N / 512, pl_limbs, 2 * B), dim3(256), 0, st, la);
+    }
+    HIP_TRY(hipGetLastError());
+    if (n1 > 1) {
+      std::vector<u32> gs(n1 - 1);
+      for (u32 b = 1; b < n1; b++) gs[b - 1] = galois((u64)b * stride);
+      if ((rc = hrot_hoisted16(c, nullptr, 0, (const u64*)ct_in, B, nlimbs, gs.data(), (const u64* const*)evk_baby, n1 - 1,
+                               hws, st, baby, sum_elems)))
+        return rc;
+    }
+  } else if (hoisted && n1 > 1) {
     std::vector<u32> gs(n1 - 1);
     for (u32 b = 1; b < n1; b++) gs[b - 1] = galois((u64)b * stride);
     if ((rc = ckks_hrot_hoisted(c, (uint64_t*)baby, ct_in, B, nlimbs, gs.data(), evk_baby, n1 - 1, hws, hws_bytes, stream)))
@@ -1468,26 +1520,32 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   // over the baby-step ciphertexts, the integer kernel PMACC_GT giant steps of one polynomial
   PmaccArgs fa, ia;
   u32 nfp = 0, nint = 0;
-  for (u32 i = 0; i < nlimbs; i++) {
-    if (host_class(c, c->mod[i]) == 0 && c->tune[6] == 0) fa.limbs[nfp++] = (unsigned char)i;
-    else ia.limbs[nint++] = (unsigned char)i;
+  for (u32 i = 0; i < pl_limbs; i++) {
+    const u32 id = i < nlimbs ? i : c->nq + (i - nlimbs);
+    if (host_class(c, c->mod[id]) == 0 && c->tune[6] == 0) {
+      fa.mod_ids[nfp] = (unsigned char)id;
+      fa.limbs[nfp++] = (unsigned char)i;
+    } else {
+      ia.mod_ids[nint] = (unsigned char)id;
+      ia.limbs[nint++] = (unsigned char)i;
+    }
   }
   const u32 tile_max = c->tune[7] > 0 ? std::min<u32>(PMACC_TILE, (u32)c->tune[7]) : PMACC_TILE;
   for (u32 g0 = 0; g0 < n2;) {
     const u32 ng = std::min<u32>(tile_max, n2 - g0);
     // giant step 0 needs no rotation: its inner sum is written straight into the output
-    auto fill = [&](PmaccArgs& a, u32 first, u32 count) {
-      a.ct_in = (const u64*)ct_in;
+    auto fill = [&](PmaccArgs& a, u32 first_g, u32 count) {
+      a.ct_in = dh ? first : (const u64*)ct_in;
       a.baby = baby;
       a.pt = (const u64*)pt;
-      a.out0 = first == 0 ? (u64*)ct_out : inner + (size_t)(first - g0) * ct_elems;
-      a.out_rest = inner + (size_t)(first - g0 + 1) * ct_elems;
+      a.out0 = first_g == 0 && !dh ? (u64*)ct_out : inner + (size_t)(first_g - g0) * sum_elems;
+      a.out_rest = inner + (size_t)(first_g - g0 + 1) * sum_elems;
       a.mods = c->d_mods;
       a.logN = c->logN;
-      a.nlimbs = nlimbs;
+      a.nlimbs = pl_limbs;
       a.n1 = n1;
       a.B = B;
-      a.g0 = first;
+      a.g0 = first_g;
       a.ng = count;
     };
     for (u32 h0 = g0; nfp && h0 < g0 + ng;) {
@@ -1528,6 +1586,16 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
     }
     for (u32 k = 0; k < ng; k++) {
       const u32 g = g0 + k;
+      if (dh) {
+        // ModDown of the inner sum: giant step 0 lands in the output, the others in `rot` and are then rotated
+        KsIo io{nullptr, 0, 0, g == 0 ? (u64*)ct_out : rot, {0, 0}, nullptr, 0};
+        if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, inner + (size_t)k * sum_elems))) return rc;
+        if (g == 0) continue;
+        rc = hrot_impl(c, ct_out, (const uint64_t*)rot, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws,
+                       hws_bytes, stream, /*ct_add=*/ct_out);
+        if (rc) return rc;
+        continue;
+      }
       if (g == 0) continue;
       const u64* src = inner + (size_t)k * ct_elems;
       if (c->logN == 16) {

@@ -437,6 +437,33 @@ __global__ void __launch_bounds__(256) first_two_components_kernel(const ulonglo
   out[b * 2 * pl2 + k] = in[b * 3 * pl2 + k];
 }
 
+// A ciphertext lifted to the extended basis as (P c0, P c1): out[bc][t] = P * in[bc][t] on the main-prime slots
+// t < nlimbs (with the factor 2^-64 on integer-class moduli, the form the key-switch accumulators have there), 0 on
+// the special-prime slots. grid = (N/512, next, 2B), two adjacent coefficients per lane.
+struct LiftArgs {
+  const u64* in;   // [2B][nlimbs][N]
+  u64* out;        // [2B][next][N]
+  const ModInfo* mods;
+  u32 logN, nlimbs, next;
+  unsigned char fp[128];   // per main-prime slot: 1 = double-precision class (plain residues)
+};
+__global__ void __launch_bounds__(256) lift_qp_kernel(LiftArgs a) {
+  const u32 N = 1u << a.logN;
+  const u32 n = (blockIdx.x * 256 + threadIdx.x) * 2, t = blockIdx.y, bc = blockIdx.z;
+  ulonglong2 r = {0, 0};
+  if (t < a.nlimbs) {
+    const ModInfo mi = a.mods[t];
+    const ulonglong2 v = *(const ulonglong2*)(a.in + ((size_t)bc * a.nlimbs + t) * N + n);
+    if (a.fp[t]) {
+      r = ulonglong2{mulmod(v.x, mi.pmod, mi), mulmod(v.y, mi.pmod, mi)};
+    } else {
+      Acc128 p0 = {v.x * mi.pmod, mul_hi64(v.x, mi.pmod)}, p1 = {v.y * mi.pmod, mul_hi64(v.y, mi.pmod)};
+      r = ulonglong2{csub(redc(p0, mi.m, mi.minv), mi.m), csub(redc(p1, mi.m, mi.minv), mi.m)};
+    }
+  }
+  *(ulonglong2*)(a.out + ((size_t)bc * a.next + t) * N + n) = r;
+}
+
 // BSGS inner sums for GT consecutive giant steps at once:
 //   out_g[b][c][i][n] = sum_{s<n1} src_s[b][c][i][n] * pt[g][s][i][n],  src_0 = ct_in, src_s = baby[s-1],
 // so every baby ciphertext word is read once per GT giant steps instead of once per giant step. Two adjacent
@@ -451,6 +478,8 @@ struct PmaccArgs {
   u32 logN, nlimbs, n1, B, g0, ng;  // ng <= GT giant steps are computed
   u32 ngt;                          // pmacc_fp_kernel: the launch covers ngt consecutive tiles of NG giant steps
   unsigned char limbs[128];         // grid.z index -> limb (the launch covers the limbs of one arithmetic kind)
+  unsigned char mod_ids[128];       // grid.z index -> modulus of that limb (differs from the limb index when the
+                                    // polynomials are in an extended basis: main primes first, then special ones)
 };
 #define PMACC_GT 4        // giant steps per pass of the integer kernel
 #define PMACC_TILE 24     // giant steps whose inner sums are held in the workspace at once
@@ -472,7 +501,7 @@ __global__ void __launch_bounds__(256) pmacc_kernel(PmaccArgs a) {
   }
   const u32 nb = group % gridDim.y, i = a.limbs[group / gridDim.y];
   const u32 n = (nb * 256 + threadIdx.x) * 2;
-  const ModInfo mi = a.mods[i];
+  const ModInfo mi = a.mods[a.mod_ids[group / gridDim.y]];
   const size_t ct_sz = (size_t)a.B * 2 * a.nlimbs * N;
   const size_t o = ((size_t)bc * a.nlimbs + i) * N + n;
   const size_t pt_g = (size_t)a.n1 * a.nlimbs * N;
@@ -550,7 +579,7 @@ __global__ void __launch_bounds__(256) pmacc_fp_kernel(PmaccArgs a) {
   const u32 npg = gridDim.x / a.ngt, pg = xi % npg, gt = xi / npg;
   const u32 nb = group % gridDim.y, i = a.limbs[group / gridDim.y];
   const u32 n = nb * 256 + threadIdx.x;
-  const ModInfo mi = a.mods[i];
+  const ModInfo mi = a.mods[a.mod_ids[group / gridDim.y]];
   const double q = mi.qd, qinv = mi.qinv;
   const u32 npoly = 2 * a.B;
   const size_t ct_sz = (size_t)npoly * a.nlimbs * N;

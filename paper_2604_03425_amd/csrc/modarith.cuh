@@ -16,7 +16,7 @@ struct ModInfo {
   u64 ninv;   // N^-1 mod m
   u64 ninvs;  // floor(ninv * 2^64 / m)
   u64 minv;   // -m^-1 mod 2^64 (Montgomery)
-  u64 pad;
+  u64 pmod;   // main primes: (p_0 ... p_{K-1}) mod m, the product of all special primes; 0 on special primes
   // double-precision view, used for primes < 2^50 (every residue and every lazy value below 2^53 is exact)
   double qd;     // m
   double qinv;   // 1/m rounded

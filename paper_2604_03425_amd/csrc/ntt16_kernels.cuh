@@ -159,6 +159,10 @@ struct FwdInnerArgs {
   u32 multi = 0;             // != 0: ciphertext b uses galois_pc[b] and evk_pc[b] instead of galois and evk
   u32 galois_pc[KS_MULTI_MAX];
   const u64* evk_pc[KS_MULTI_MAX];
+  // streaming kernels only: != null adds P * sigma_g(c0[b][t]) to the first accumulator on the main-prime slots
+  // (rotations kept in the extended basis: ModDown of the sum then returns sigma_g(c0) + ModDown(accumulator))
+  const u64* c0 = nullptr;   // limb-vector (b, t) at c0 + b*c0_poly_stride + t*N, canonical residues, eval domain
+  u64 c0_poly_stride = 0;
 };
 // b is the same for the whole workgroup; saying so keeps the table look-ups on the scalar unit and their results
 // in scalar registers.
@@ -715,6 +719,12 @@ __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
       }
     }
   }
+  if (a.c0 && t < a.nlimbs) {   // at most three products are pending here, a fourth keeps the sum below 2^52
+    const u64* src = a.c0 + (size_t)b * a.c0_poly_stride + (size_t)t * N;
+    const double pm = u2d(mi.pmod);
+    s0[0] += fp_mulmod_var(u2d(src[galois_src_index16(n, g_own)]), pm, qinv, q);
+    s0[1] += fp_mulmod_var(u2d(src[galois_src_index16(n + 1, g_own)]), pm, qinv, q);
+  }
   u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
   *(ulonglong2*)o0 = ulonglong2{d2u_canon(fp_reduce(s0[0], qinv, q), q), d2u_canon(fp_reduce(s0[1], qinv, q), q)};
   *(ulonglong2*)(o0 + (size_t)a.next * N) =
@@ -762,6 +772,17 @@ __global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
       p1.hi = mul_hi64(x[e], e1[e]);
       s0[e] = csub(s0[e] + redc(p0, q, mi.minv), q2);
       s1[e] = csub(s1[e] + redc(p1, q, mi.minv), q2);
+    }
+  }
+  if (a.c0 && t < a.nlimbs) {   // P * c0 with the same factor 2^-64 as the products above
+    const u64* src = a.c0 + (size_t)b * a.c0_poly_stride + (size_t)t * N;
+#pragma unroll
+    for (int e = 0; e < 2; e++) {
+      const u64 v = src[galois_src_index16(n + e, g_own)];
+      Acc128 p0;
+      p0.lo = v * mi.pmod;
+      p0.hi = mul_hi64(v, mi.pmod);
+      s0[e] = csub(s0[e] + redc(p0, q, mi.minv), q2);
     }
   }
   u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;

@@ -427,3 +427,55 @@ def test_late_relinearisation(gpu, shape, nl, B):
     with pytest.raises(gpu.CkksError):
         gpu.ckks_tensor_acc(gc, shifted, dp[0][0][1:], dp[0][1][1:], acc[:B - 1], B - 1, nl)
     gc.close()
+
+
+@pytest.mark.parametrize("shape,nl,B,n1,n2,stride", [
+    ((16, 5, 50, 3, 60, 2), 5, 2, 3, 2, 1),     # double-precision main primes, integer-class special primes
+    ((16, 5, 50, 3, 60, 2), 3, 1, 4, 1, 2),     # lower level, no giant step
+    ((16, 4, 60, 2, 60, 2), 3, 2, 2, 3, 1),     # integer-class moduli everywhere
+    ((16, 4, 45, 2, 50, 2), 4, 1, 1, 3, 1),     # double-precision special primes too; n1 = 1
+    ((16, 6, 50, 2, 60, 3), 6, 1, 9, 2, 1),     # three digits, more baby steps than one fold of the inner sums
+])
+def test_pcmm_double_hoisted(gpu, shape, nl, B, n1, n2, stride):
+    """Baby steps kept in the extended basis, one ModDown per giant step: bit-exact against the oracle's statement
+    of that schedule; with n1 = 1 also against the plain schedule of the library itself."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(*shape)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    K = len(p.p)
+    ct = uniform_residues(800, p.q[:nl], (B, 2), p.N)
+    pt = uniform_residues(801, list(p.q[:nl]) + list(p.p), (n2, n1), p.N)
+    baby = [uniform_residues(810 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n1 - 1)]
+    giant = [uniform_residues(830 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n2 - 1)]
+    ref.set_threads(4)
+    want = rc.pcmm_bsgs_double_hoisted(ct, pt, n1, n2, stride, baby, giant)
+    ref.set_threads(1)
+    d_ct, d_pt = to_dev(ct), to_dev(pt)
+    d_baby, d_giant = [to_dev(k) for k in baby], [to_dev(k) for k in giant]
+    out = torch.empty_like(d_ct)
+    ws = gc.workspace(gpu.OP_PCMM_BSGS_DH, B, nl, n1)
+    gpu.ckks_pcmm_bsgs_double_hoisted(gc, out, d_ct, B, nl, d_pt, n1, n2, stride, d_baby, d_giant, ws)
+    assert_same(to_host(out), want, "double-hoisted PCMM")
+    if n1 == 1:
+        plain = torch.empty_like(d_ct)
+        gpu.ckks_pcmm_bsgs(gc, plain, d_ct, B, nl, d_pt[:, :, :nl].contiguous(), n1, n2, stride, d_baby, d_giant,
+                           gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
+        assert torch.equal(out, plain)
+    with pytest.raises(gpu.CkksError):     # workspace of the plain schedule is too small here
+        small = gc.workspace(gpu.OP_HROT, B, nl)
+        gpu.ckks_pcmm_bsgs_double_hoisted(gc, out, d_ct, B, nl, d_pt, n1, n2, stride, d_baby, d_giant, small)
+    gc.close()
+
+
+def test_pcmm_double_hoisted_needs_full_ring(gpu):
+    import torch
+    from gpu_util import to_dev
+    p = make_params(12, 4, 40, 2, 50, 2)
+    gc = gpu.Context(p)
+    ct = to_dev(uniform_residues(1, p.q, (1, 2), p.N))
+    pt = to_dev(uniform_residues(2, p.moduli, (1, 1), p.N))
+    ws = gc.workspace(gpu.OP_PCMM_BSGS, 1, 4, 1)
+    with pytest.raises(gpu.CkksError):
+        gpu.ckks_pcmm_bsgs_double_hoisted(gc, torch.empty_like(ct), ct, 1, 4, pt, 1, 1, 1, [], [], ws)
+    gc.close()
