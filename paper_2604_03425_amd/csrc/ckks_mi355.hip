@@ -136,7 +136,7 @@ static const char* const kProfNames[PK_COUNT] = {
     "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
     "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
     "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "ntt16_fwd_blocks_inner2_kernel", "ntt16_fwd_blocks_inner8_kernel<1>", "ntt16_fwd_blocks_inner8_kernel<2>", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
-    "pmacc_kernel", "pmacc_fp_kernel", "addto_kernel", "copy"};
+    "pmacc_int_kernel", "pmacc_fp_kernel", "addto_kernel", "copy"};
 struct ProfRec {
   int kind;
   hipEvent_t start, stop;
@@ -1517,7 +1517,7 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
     }
   }
   // limbs by arithmetic kind: the double-precision kernel computes up to 6 giant steps x 8 polynomials per pass
-  // over the baby-step ciphertexts, the integer kernel PMACC_GT giant steps of one polynomial
+  // over the baby-step ciphertexts, the integer kernel up to 3 giant steps x 4 polynomials
   PmaccArgs fa, ia;
   u32 nfp = 0, nint = 0;
   for (u32 i = 0; i < pl_limbs; i++) {
@@ -1571,18 +1571,26 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
       HIP_TRY(hipGetLastError());
       h0 += cnt * ngt;
     }
-    for (u32 h0 = g0; nint && h0 < g0 + ng; h0 += PMACC_GT) {
-      const u32 cnt = std::min<u32>(PMACC_GT, g0 + ng - h0);
+    for (u32 h0 = g0; nint && h0 < g0 + ng;) {
+      static const u32 kSizes[] = {3, 2, 1};
+      u32 cnt = 1;
+      for (u32 sz : kSizes)
+        if (sz <= g0 + ng - h0) {
+          cnt = sz;
+          break;
+        }
+      const u32 ngt = (g0 + ng - h0) / cnt;
       fill(ia, h0, cnt);
+      ia.ngt = ngt;
       ProfScope ps(c, PK_PMACC, st);
-      dim3 grid(2 * B, N / 512, nint), block(256);
+      dim3 grid((2 * B + PMACC_INT_P - 1) / PMACC_INT_P * ngt, N / 256, nint), block(256);
       switch (cnt) {
-        case 4: hipLaunchKernelGGL(pmacc_kernel<4>, grid, block, 0, st, ia); break;
-        case 3: hipLaunchKernelGGL(pmacc_kernel<3>, grid, block, 0, st, ia); break;
-        case 2: hipLaunchKernelGGL(pmacc_kernel<2>, grid, block, 0, st, ia); break;
-        default: hipLaunchKernelGGL(pmacc_kernel<1>, grid, block, 0, st, ia); break;
+        case 3: hipLaunchKernelGGL(pmacc_int_kernel<3>, grid, block, 0, st, ia); break;
+        case 2: hipLaunchKernelGGL(pmacc_int_kernel<2>, grid, block, 0, st, ia); break;
+        default: hipLaunchKernelGGL(pmacc_int_kernel<1>, grid, block, 0, st, ia); break;
       }
       HIP_TRY(hipGetLastError());
+      h0 += cnt * ngt;
     }
     for (u32 k = 0; k < ng; k++) {
       const u32 g = g0 + k;

@@ -464,10 +464,9 @@ __global__ void __launch_bounds__(256) lift_qp_kernel(LiftArgs a) {
   *(ulonglong2*)(a.out + ((size_t)bc * a.next + t) * N + n) = r;
 }
 
-// BSGS inner sums for GT consecutive giant steps at once:
-//   out_g[b][c][i][n] = sum_{s<n1} src_s[b][c][i][n] * pt[g][s][i][n],  src_0 = ct_in, src_s = baby[s-1],
-// so every baby ciphertext word is read once per GT giant steps instead of once per giant step. Two adjacent
-// coefficients per lane (16-byte accesses); one lazy 128-bit sum per output, folded every 8 terms.
+// BSGS inner sums for several giant steps and polynomials at once:
+//   out_g[b][c][i][n] = sum_{s<n1} src_s[b][c][i][n] * pt[g][s][i][n],  src_0 = ct_in, src_s = baby[s-1].
+// One launch covers the limbs of one arithmetic kind (pmacc_fp_kernel, pmacc_int_kernel below).
 struct PmaccArgs {
   const u64* ct_in;   // [B][2][nlimbs][N]
   const u64* baby;    // [n1-1][B][2][nlimbs][N]
@@ -481,80 +480,9 @@ struct PmaccArgs {
   unsigned char mod_ids[128];       // grid.z index -> modulus of that limb (differs from the limb index when the
                                     // polynomials are in an extended basis: main primes first, then special ones)
 };
-#define PMACC_GT 4        // giant steps per pass of the integer kernel
 #define PMACC_TILE 24     // giant steps whose inner sums are held in the workspace at once
-template <int NG>
-__global__ void __launch_bounds__(256) pmacc_kernel(PmaccArgs a) {
-  const u32 N = 1u << a.logN;
-  // grid = (2B, N/512, nlimbs): the polynomial index is innermost so that the workgroups sharing a plaintext tile
-  // run together; when the number of (block, limb) groups allows, a whole group is placed on one XCD (whose L2
-  // then serves the tile to all of them) and eight consecutive groups run side by side.
-  const u32 lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-  u32 bc, group;
-  if (((gridDim.y * gridDim.z) & 7) == 0) {
-    const u32 rest = lin >> 3;
-    bc = rest % gridDim.x;
-    group = (lin & 7) + 8 * (rest / gridDim.x);
-  } else {
-    bc = lin % gridDim.x;
-    group = lin / gridDim.x;
-  }
-  const u32 nb = group % gridDim.y, i = a.limbs[group / gridDim.y];
-  const u32 n = (nb * 256 + threadIdx.x) * 2;
-  const ModInfo mi = a.mods[a.mod_ids[group / gridDim.y]];
-  const size_t ct_sz = (size_t)a.B * 2 * a.nlimbs * N;
-  const size_t o = ((size_t)bc * a.nlimbs + i) * N + n;
-  const size_t pt_g = (size_t)a.n1 * a.nlimbs * N;
-  // per output: four carry-free sums of 30-bit partial products (at most 15 terms), folded into a canonical
-  // running sum
-  Dot30 dd[NG][2];
-  u64 run[NG][2];
-#pragma unroll
-  for (int g = 0; g < NG; g++)
-#pragma unroll
-    for (int e = 0; e < 2; e++) {
-      dot30_init(dd[g][e]);
-      run[g][e] = 0;
-    }
-  // baby steps in chunks of 8 with all loads of a chunk issued together (memory-level parallelism), one fold per chunk
-  auto term = [&](u32 k) {
-    const ulonglong2 x = *(const ulonglong2*)(k == 0 ? a.ct_in + o : a.baby + (size_t)(k - 1) * ct_sz + o);
-    const u64* w = a.pt + (size_t)a.g0 * pt_g + ((size_t)k * a.nlimbs + i) * N + n;
-    const u32 x0[2] = {(u32)x.x & M30, (u32)x.y & M30}, x1[2] = {(u32)(x.x >> 30), (u32)(x.y >> 30)};
-#pragma unroll
-    for (int g = 0; g < NG; g++) {
-      const ulonglong2 c = *(const ulonglong2*)(w + (size_t)g * pt_g);
-      dot30_mac(dd[g][0], x0[0], x1[0], (u32)c.x & M30, (u32)(c.x >> 30));
-      dot30_mac(dd[g][1], x0[1], x1[1], (u32)c.y & M30, (u32)(c.y >> 30));
-    }
-  };
-  auto fold = [&]() {
-#pragma unroll
-    for (int g = 0; g < NG; g++)
-#pragma unroll
-      for (int e = 0; e < 2; e++) {
-        run[g][e] = addmod(run[g][e], reduce128(dot30_value(dd[g][e]), mi), mi.m);
-        dot30_init(dd[g][e]);
-      }
-  };
-  u32 k = 0;
-  for (; k + 8 <= a.n1; k += 8) {
-#pragma unroll
-    for (int kk = 0; kk < 8; kk++) term(k + kk);
-    fold();
-  }
-  if (k < a.n1) {
-    for (; k < a.n1; k++) term(k);
-    fold();
-  }
-#pragma unroll
-  for (int g = 0; g < NG; g++) {
-    u64* dst = g == 0 ? a.out0 + o : a.out_rest + (size_t)(g - 1) * ct_sz + o;
-    *(ulonglong2*)dst = ulonglong2{run[g][0], run[g][1]};
-  }
-}
 
-// The same inner sums on double-precision moduli (q < 2^50), register-tiled like a small matrix product: a lane owns
+// Inner sums on double-precision moduli (q < 2^50), register-tiled like a small matrix product: a lane owns
 // one coefficient position and keeps the running sums of PMACC_FP_P polynomials x NG giant steps (one double each:
 // every product is reduced on the spot with 5 FP64 instructions), so per baby step it loads P ciphertext words and
 // NG plaintext words for P * NG multiply-adds: 8/P + 8/NG bytes per multiply-add instead of 16. grid =
@@ -568,7 +496,9 @@ __global__ void __launch_bounds__(256) pmacc_fp_kernel(PmaccArgs a) {
   const u32 N = 1u << a.logN;
   const u32 lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
   u32 xi, group;
-  if (((gridDim.y * gridDim.z) & 7) == 0) {   // same placement as pmacc_kernel
+  // when the number of (block, limb) groups allows, a whole group is placed on one XCD (whose L2 then serves the
+  // shared words to all of its workgroups) and eight consecutive groups run side by side
+  if (((gridDim.y * gridDim.z) & 7) == 0) {
     const u32 rest = lin >> 3;
     xi = rest % gridDim.x;
     group = (lin & 7) + 8 * (rest / gridDim.x);
@@ -626,6 +556,85 @@ __global__ void __launch_bounds__(256) pmacc_fp_kernel(PmaccArgs a) {
       const u32 rel = gt * NG + g;   // giant step relative to the launch's first one
       u64* dst = (rel == 0 ? a.out0 : a.out_rest + (size_t)(rel - 1) * ct_sz) + o[p];
       *dst = d2u_canon(fp_reduce(s[p][g], qinv, q), q);
+    }
+  }
+}
+
+// The register-tiled form for integer-class moduli (q < 2^60): a lane owns one coefficient position of
+// PMACC_INT_P polynomials x NG giant steps, each running sum held as four carry-free sums of 30-bit partial products
+// (folded to a canonical residue every 15 baby steps and re-seeded with it: 15 products below 2^60 plus the seed
+// stay below 2^64). Per baby step P ciphertext words and NG plaintext words are loaded for P * NG multiply-adds. Grid and
+// placement as for pmacc_fp_kernel.
+#define PMACC_INT_P 4
+template <int NG>
+__global__ void __launch_bounds__(256) pmacc_int_kernel(PmaccArgs a) {
+  constexpr int P = PMACC_INT_P;
+  const u32 N = 1u << a.logN;
+  const u32 lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  u32 xi, group;
+  if (((gridDim.y * gridDim.z) & 7) == 0) {
+    const u32 rest = lin >> 3;
+    xi = rest % gridDim.x;
+    group = (lin & 7) + 8 * (rest / gridDim.x);
+  } else {
+    xi = lin % gridDim.x;
+    group = lin / gridDim.x;
+  }
+  const u32 npg = gridDim.x / a.ngt, pg = xi % npg, gt = xi / npg;
+  const u32 nb = group % gridDim.y, i = a.limbs[group / gridDim.y];
+  const u32 n = nb * 256 + threadIdx.x;
+  const ModInfo mi = a.mods[a.mod_ids[group / gridDim.y]];
+  const u32 npoly = 2 * a.B;
+  const size_t ct_sz = (size_t)npoly * a.nlimbs * N;
+  const size_t pt_g = (size_t)a.n1 * a.nlimbs * N;
+  size_t o[P];   // a short last group recomputes the last polynomial in its surplus lanes and stores nothing for them
+#pragma unroll
+  for (int p = 0; p < P; p++) o[p] = ((size_t)min(pg * P + p, npoly - 1) * a.nlimbs + i) * N + n;
+  Dot30 dd[P][NG];
+#pragma unroll
+  for (int p = 0; p < P; p++)
+#pragma unroll
+    for (int g = 0; g < NG; g++) dot30_init(dd[p][g]);
+  for (u32 k = 0, pending = 0; k < a.n1; k++) {
+    const u64* src = k == 0 ? a.ct_in : a.baby + (size_t)(k - 1) * ct_sz;
+    const u64* w = a.pt + (size_t)(a.g0 + gt * NG) * pt_g + ((size_t)k * a.nlimbs + i) * N + n;
+    u64 xr[P], cr[NG];
+#pragma unroll
+    for (int p = 0; p < P; p++) xr[p] = src[o[p]];
+#pragma unroll
+    for (int g = 0; g < NG; g++) cr[g] = w[(size_t)g * pt_g];
+    u32 c0[NG], c1[NG];
+#pragma unroll
+    for (int g = 0; g < NG; g++) {
+      c0[g] = (u32)cr[g] & M30;
+      c1[g] = (u32)(cr[g] >> 30);
+    }
+#pragma unroll
+    for (int p = 0; p < P; p++) {
+      const u32 x0 = (u32)xr[p] & M30, x1 = (u32)(xr[p] >> 30);
+#pragma unroll
+      for (int g = 0; g < NG; g++) dot30_mac(dd[p][g], x0, x1, c0[g], c1[g]);
+    }
+    if (++pending == 15) {   // wave-uniform branch
+      pending = 0;
+#pragma unroll
+      for (int p = 0; p < P; p++)
+#pragma unroll
+        for (int g = 0; g < NG; g++) {
+          const u64 r = reduce128(dot30_value(dd[p][g]), mi);
+          dot30_init(dd[p][g]);
+          dd[p][g].s00 = r;
+        }
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < P; p++) {
+    if (pg * P + p >= npoly) break;
+#pragma unroll
+    for (int g = 0; g < NG; g++) {
+      const u32 rel = gt * NG + g;
+      u64* dst = (rel == 0 ? a.out0 : a.out_rest + (size_t)(rel - 1) * ct_sz) + o[p];
+      *dst = reduce128(dot30_value(dd[p][g]), mi);
     }
   }
 }

@@ -303,7 +303,7 @@ def test_extreme_residues(gpu, shape):
     rs = torch.empty((B, 2, nl - 1, p.N), dtype=torch.int64, device="cuda")
     gpu.ckks_rescale(gc, rs, d_ct, B, nl, gc.workspace(gpu.OP_RESCALE, B, nl))
     assert_same(to_host(rs), rc.rescale(ct), "rescale at the maxima")
-    n1, n2 = 9, 2
+    n1, n2 = 17, 2     # more baby steps than one fold of the integer inner sums (15)
     pt = np.broadcast_to(top[0], (n2, n1, nl, p.N)).copy()
     keys = [evk] * (n1 - 1 + n2 - 1)
     want = rc.pcmm_bsgs(ct, pt, n1, n2, 1, keys[:n1 - 1], keys[n1 - 1:])
