@@ -713,10 +713,13 @@ int ref_pcmm_bsgs(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, ui
 //   A_r = accumulators of the key switch of sigma_r(c1) under evk_baby[r-1] (before ModDown), with P sigma_r(c0)
 //         added to the first one on the q-limbs                                  (r = 1..n1-1, sigma_r = 5^(r*stride));
 //   S_g = sum_r pt_ext[g][r] (.) A_r  (both components, every limb of the extended basis);
-//   y   = sum_g rot_{g*n1*stride}( ModDown(S_g) ), the giant-step rotations being ordinary HRots.
-// ModDown(x + P z) = z + ModDown(x) exactly, so the c0 terms come out as in the plain schedule; what differs is that
-// the rounding of ModDown is applied once per giant step, after the sum over baby steps. pt_ext: [n2][n1][nlimbs+K][N],
-// the plaintext's residues for q_0..q_{nlimbs-1} and then p_0..p_{K-1}, evaluation domain.
+//   u_g = ModDown(S_g) for g >= 1 (an ordinary ciphertext), rotated by sigma'_g = 5^(g*n1*stride) without leaving
+//         the extended basis: G_g = accumulators of the key switch of sigma'_g(u_g.c1) under evk_giant[g-1], with
+//         P sigma'_g(u_g.c0) added to the first one on the q-limbs;
+//   y   = ModDown( S_0 + sum_{g>=1} G_g ).
+// ModDown(x + P z) = z + ModDown(x) exactly, so the c0 terms come out as in the plain schedule; what differs is where
+// ModDown rounds: once per giant step on the sum over baby steps, and once at the end on the sum over giant steps.
+// pt_ext: [n2][n1][nlimbs+K][N], the plaintext's residues for q_0..q_{nlimbs-1} and then p_0..p_{K-1}, eval domain.
 int ref_pcmm_bsgs_double_hoisted(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, uint32_t nlimbs,
                                  const u64* pt_ext, uint32_t n1, uint32_t n2, uint32_t stride,
                                  const u64* const* evk_baby, const u64* const* evk_giant) {
@@ -754,7 +757,7 @@ int ref_pcmm_bsgs_double_hoisted(const RefCtx* c, u64* ct_out, const u64* ct_in,
           a = addm(a, mulm(r0[(size_t)i * N + n], pmod[i], c->mod[i]), c->mod[i]);
         }
     }
-    std::vector<u64> y(sz, 0), S(2 * el), inner(sz), rot(sz);
+    std::vector<u64> T(2 * el, 0), S(2 * el), u(sz);
     for (uint32_t g = 0; g < n2; g++) {
       std::fill(S.begin(), S.end(), 0);
       for (uint32_t r = 0; r < n1; r++) {
@@ -768,22 +771,30 @@ int ref_pcmm_bsgs_double_hoisted(const RefCtx* c, u64* ct_out, const u64* ct_in,
             }
           }
       }
-      moddown_pair(c, inner.data(), S, nlimbs);
-      const u64* add = inner.data();
       if (g > 0) {
-        hrot_one(c, rot.data(), inner.data(), nlimbs, powm(5, (u64)g * n1 * stride, twoN), evk_giant[g - 1]);
-        add = rot.data();
+        moddown_pair(c, u.data(), S, nlimbs);
+        const u64 gg = powm(5, (u64)g * n1 * stride, twoN);
+        for (uint32_t i = 0; i < nlimbs; i++) {
+          automorph_eval(c, &r0[(size_t)i * N], &u[(size_t)i * N], i, gg);
+          automorph_eval(c, &r1[(size_t)i * N], &u[pl + (size_t)i * N], i, gg);
+        }
+        S = keyswitch_accumulate(c, r1.data(), nlimbs, evk_giant[g - 1]);
+        for (uint32_t i = 0; i < nlimbs; i++)
+          for (size_t n = 0; n < N; n++) {
+            u64& a = S[(size_t)i * N + n];
+            a = addm(a, mulm(r0[(size_t)i * N + n], pmod[i], c->mod[i]), c->mod[i]);
+          }
       }
       for (int comp = 0; comp < 2; comp++)
-        for (uint32_t i = 0; i < nlimbs; i++) {
-          u64 m = c->mod[i];
+        for (int t = 0; t < next; t++) {
+          u64 m = ext_mod(t);
           for (size_t n = 0; n < N; n++) {
-            size_t k = (size_t)comp * pl + (size_t)i * N + n;
-            y[k] = addm(y[k], add[k], m);
+            size_t k = (size_t)comp * el + (size_t)t * N + n;
+            T[k] = addm(T[k], S[k], m);
           }
         }
     }
-    std::copy(y.begin(), y.end(), ct_out + bi * sz);
+    moddown_pair(c, ct_out + bi * sz, T, nlimbs);
   });
   return 0;
 }

@@ -224,11 +224,12 @@ def test_pcmm_bsgs_is_a_matrix_product():
 
 
 def test_pcmm_double_hoisted():
-    """BSGS with the baby steps kept in the extended basis (one ModDown per giant step). Pins: (1) the same matrix
-    product after decryption, and a phase that differs from the plain schedule's by rounding noise only; (2) with
-    n1 = 1 no key switch happens before the sum, ModDown(P x) = x exactly, so the result is bit-identical to the plain
-    schedule; (3) with the all-ones plaintext, n1 = 2, n2 = 1: ModDown(P c + A_1) = c + ModDown(A_1) exactly, so the
-    result is ct + HRot(ct), bit for bit."""
+    """BSGS with baby and giant steps kept in the extended basis (one ModDown per giant step on the sum over baby
+    steps, one at the end on the sum over giant steps). Pins: (1) the same matrix product after decryption, and a
+    phase that differs from the plain schedule's by rounding noise only; (2) with n1 = 1 the inner sums are P times
+    an ordinary ciphertext, ModDown(P x + A) = x + ModDown(A) exactly, and one giant step's key switch is the only
+    rounding, so the result is bit-identical to the plain schedule; (3) with the all-ones plaintext, n1 = 2, n2 = 1:
+    ModDown(P c + A_1) = c + ModDown(A_1) exactly, so the result is ct + HRot(ct), bit for bit."""
     p = make_params(8, 4, 40, 2, 50, 2)
     c = ref.RefContext(p)
     keys = Keys(p, c, 43)
