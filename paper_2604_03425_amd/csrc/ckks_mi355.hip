@@ -801,9 +801,11 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
 // forward transform of c1 are done once on the un-rotated polynomial; each rotation then reads the transformed
 // digits through its own index map in the streaming inner product and finishes as usual.
 // acc_base != null: rotation r stops before ModDown and leaves its accumulators, with P * sigma(c0) added to the
-// first one, at acc_base + r * acc_stride (rotations kept in the extended basis); out_base is not used then.
+// first one, at acc_base + r * acc_stride (rotations kept in the extended basis), or adds them to what is there
+// (acc_add); out_base is not used then.
 int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in, u32 B, u32 nlimbs, const u32* galois,
-                   const u64* const* evks, u32 R, char* ws, hipStream_t st, u64* acc_base = nullptr, u64 acc_stride = 0) {
+                   const u64* const* evks, u32 R, char* ws, hipStream_t st, u64* acc_base = nullptr, u64 acc_stride = 0,
+                   bool acc_add = false) {
   const LevelTables* lt;
   int rc = get_level(c, nlimbs, &lt);
   if (rc) return rc;
@@ -846,6 +848,7 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
   if (acc_base) {
     ia.c0 = ct_in;
     ia.c0_poly_stride = 2 * polyN;
+    ia.accumulate = acc_add ? 1u : 0u;
   }
   for (u32 r = 0; r < R; r++) {
     ia.evk = evks[r];
@@ -1162,9 +1165,10 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlim
       return (size_t)(n1 - 1) * 2 * poly + (size_t)PMACC_TILE * 2 * poly + 2 * poly + ks + poly;
     case CKKS_OP_PCMM_BSGS_DH: {
       if (n1 == 0) return 0;
-      // n1 baby steps and PMACC_TILE inner sums in the extended basis, one inner sum after ModDown, HRot workspace
+      // n1 baby steps, PMACC_TILE inner sums and the sum over giant steps in the extended basis, one inner sum
+      // after ModDown, HRot workspace
       const size_t ext_poly = align256((size_t)B * (nlimbs + c->np) * c->N * 8);
-      return (size_t)(n1 + PMACC_TILE) * 2 * ext_poly + 2 * poly + ks + poly;
+      return (size_t)(n1 + PMACC_TILE + 1) * 2 * ext_poly + 2 * poly + ks + poly;
     }
     default: return 0;
   }
@@ -1470,7 +1474,9 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   const size_t sum_al = dh ? 2 * align256((size_t)B * pl_limbs * N * 8) : ct_al;
   char* w = (char*)ws;
   u64* first = nullptr;                 // double-hoisted: (P c0, P c1), the term of baby step 0
+  u64* total = nullptr;                 // double-hoisted: sum over giant steps, extended basis
   if (dh) { first = (u64*)w;            w += sum_al; }
+  if (dh) { total = (u64*)w;            w += sum_al; }
   u64* baby = (u64*)w;                  w += (size_t)(n1 - 1) * sum_al;
   u64* inner = (u64*)w;                 w += (size_t)PMACC_TILE * sum_al;   // inner sums of one tile of giant steps
   u64* rot = (u64*)w;                   w += ct_al;
@@ -1538,7 +1544,7 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
       a.ct_in = dh ? first : (const u64*)ct_in;
       a.baby = baby;
       a.pt = (const u64*)pt;
-      a.out0 = first_g == 0 && !dh ? (u64*)ct_out : inner + (size_t)(first_g - g0) * sum_elems;
+      a.out0 = first_g == 0 ? (dh ? total : (u64*)ct_out) : inner + (size_t)(first_g - g0) * sum_elems;
       a.out_rest = inner + (size_t)(first_g - g0 + 1) * sum_elems;
       a.mods = c->d_mods;
       a.logN = c->logN;
@@ -1595,13 +1601,14 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
     for (u32 k = 0; k < ng; k++) {
       const u32 g = g0 + k;
       if (dh) {
-        // ModDown of the inner sum: giant step 0 lands in the output, the others in `rot` and are then rotated
-        KsIo io{nullptr, 0, 0, g == 0 ? (u64*)ct_out : rot, {0, 0}, nullptr, 0};
-        if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, inner + (size_t)k * sum_elems))) return rc;
+        // giant step 0 is already in `total`; the others: ModDown of the inner sum into `rot`, then its rotation
+        // (one hoisted rotation that stops before ModDown) added to `total`
         if (g == 0) continue;
-        rc = hrot_impl(c, ct_out, (const uint64_t*)rot, B, nlimbs, galois((u64)g * n1 * stride), evk_giant[g - 1], hws,
-                       hws_bytes, stream, /*ct_add=*/ct_out);
-        if (rc) return rc;
+        KsIo io{nullptr, 0, 0, rot, {0, 0}, nullptr, 0};
+        if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, inner + (size_t)k * sum_elems))) return rc;
+        const u32 gg = galois((u64)g * n1 * stride);
+        const u64* key = (const u64*)evk_giant[g - 1];
+        if ((rc = hrot_hoisted16(c, nullptr, 0, rot, B, nlimbs, &gg, &key, 1, hws, st, total, 0, /*acc_add=*/true))) return rc;
         continue;
       }
       if (g == 0) continue;
@@ -1621,6 +1628,10 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
       }
     }
     g0 += ng;
+  }
+  if (dh) {   // one ModDown of the sum over giant steps
+    KsIo io{nullptr, 0, 0, (u64*)ct_out, {0, 0}, nullptr, 0};
+    if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, total))) return rc;
   }
   return CKKS_OK;
 }

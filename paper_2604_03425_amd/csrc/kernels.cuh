@@ -580,7 +580,7 @@ __global__ void __launch_bounds__(256) pmacc_int_kernel(PmaccArgs a) {
     xi = lin % gridDim.x;
     group = lin / gridDim.x;
   }
-  const u32 npg = gridDim.x / a.ngt, gt = xi % a.ngt, pg = xi / a.ngt;
+  const u32 gt = xi % a.ngt, pg = xi / a.ngt;   // the giant tiles of one polynomial group are adjacent
   const u32 nb = group % gridDim.y, i = a.limbs[group / gridDim.y];
   const u32 n = nb * 256 + threadIdx.x;
   const ModInfo mi = a.mods[a.mod_ids[group / gridDim.y]];

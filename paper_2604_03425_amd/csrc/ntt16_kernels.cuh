@@ -163,6 +163,7 @@ struct FwdInnerArgs {
   // (rotations kept in the extended basis: ModDown of the sum then returns sigma_g(c0) + ModDown(accumulator))
   const u64* c0 = nullptr;   // limb-vector (b, t) at c0 + b*c0_poly_stride + t*N, canonical residues, eval domain
   u64 c0_poly_stride = 0;
+  u32 accumulate = 0;        // streaming kernels only: != 0 adds the result to what acc holds instead of overwriting it
 };
 // b is the same for the whole workgroup; saying so keeps the table look-ups on the scalar unit and their results
 // in scalar registers.
@@ -726,6 +727,13 @@ __global__ void __launch_bounds__(256) inner16_fp_kernel(FwdInnerArgs a) {
     s0[1] += fp_mulmod_var(u2d(src[galois_src_index16(n + 1, g_own)]), pm, qinv, q);
   }
   u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
+  if (a.accumulate) {   // fold first (|.| <= q/2), then the old canonical values fit under the same bound
+    const ulonglong2 p0 = *(const ulonglong2*)o0, p1 = *(const ulonglong2*)(o0 + (size_t)a.next * N);
+    s0[0] = fp_reduce(s0[0], qinv, q) + u2d(p0.x);
+    s0[1] = fp_reduce(s0[1], qinv, q) + u2d(p0.y);
+    s1[0] = fp_reduce(s1[0], qinv, q) + u2d(p1.x);
+    s1[1] = fp_reduce(s1[1], qinv, q) + u2d(p1.y);
+  }
   *(ulonglong2*)o0 = ulonglong2{d2u_canon(fp_reduce(s0[0], qinv, q), q), d2u_canon(fp_reduce(s0[1], qinv, q), q)};
   *(ulonglong2*)(o0 + (size_t)a.next * N) =
       ulonglong2{d2u_canon(fp_reduce(s1[0], qinv, q), q), d2u_canon(fp_reduce(s1[1], qinv, q), q)};
@@ -786,6 +794,13 @@ __global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
     }
   }
   u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
+  if (a.accumulate) {   // old values are canonical: a sum below 3q comes back below 2q
+    const ulonglong2 p0 = *(const ulonglong2*)o0, p1 = *(const ulonglong2*)(o0 + (size_t)a.next * N);
+    s0[0] = csub(s0[0] + p0.x, q2);
+    s0[1] = csub(s0[1] + p0.y, q2);
+    s1[0] = csub(s1[0] + p1.x, q2);
+    s1[1] = csub(s1[1] + p1.y, q2);
+  }
   *(ulonglong2*)o0 = ulonglong2{csub(s0[0], q), csub(s0[1], q)};
   *(ulonglong2*)(o0 + (size_t)a.next * N) = ulonglong2{csub(s1[0], q), csub(s1[1], q)};
 }

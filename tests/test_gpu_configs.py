@@ -434,11 +434,12 @@ def test_late_relinearisation(gpu, shape, nl, B):
     ((16, 5, 50, 3, 60, 2), 3, 1, 4, 1, 2),     # lower level, no giant step
     ((16, 4, 60, 2, 60, 2), 3, 2, 2, 3, 1),     # integer-class moduli everywhere
     ((16, 4, 45, 2, 50, 2), 4, 1, 1, 3, 1),     # double-precision special primes too; n1 = 1
+    ((16, 4, 45, 2, 50, 2), 3, 2, 1, 2, 3),     # n1 = 1 and one giant step: the plain schedule's bits
     ((16, 6, 50, 2, 60, 3), 6, 1, 9, 2, 1),     # three digits, more baby steps than one fold of the inner sums
 ])
 def test_pcmm_double_hoisted(gpu, shape, nl, B, n1, n2, stride):
-    """Baby steps kept in the extended basis, one ModDown per giant step: bit-exact against the oracle's statement
-    of that schedule; with n1 = 1 also against the plain schedule of the library itself."""
+    """Baby and giant steps kept in the extended basis: bit-exact against the oracle's statement of that schedule;
+    with n1 = 1 and a single giant rotation also against the plain schedule of the library itself."""
     import torch
     from gpu_util import to_dev, to_host, assert_same
     p = make_params(*shape)
@@ -457,7 +458,7 @@ def test_pcmm_double_hoisted(gpu, shape, nl, B, n1, n2, stride):
     ws = gc.workspace(gpu.OP_PCMM_BSGS_DH, B, nl, n1)
     gpu.ckks_pcmm_bsgs_double_hoisted(gc, out, d_ct, B, nl, d_pt, n1, n2, stride, d_baby, d_giant, ws)
     assert_same(to_host(out), want, "double-hoisted PCMM")
-    if n1 == 1:
+    if n1 == 1 and n2 <= 2:
         plain = torch.empty_like(d_ct)
         gpu.ckks_pcmm_bsgs(gc, plain, d_ct, B, nl, d_pt[:, :, :nl].contiguous(), n1, n2, stride, d_baby, d_giant,
                            gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
