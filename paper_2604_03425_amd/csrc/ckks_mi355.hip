@@ -850,6 +850,34 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
     ia.c0_poly_stride = 2 * polyN;
     ia.accumulate = acc_add ? 1u : 0u;
   }
+  if (acc_base && !acc_add && beta <= INNER16_ROT_MAX_BETA) {
+    // rotations kept in the extended basis: up to KS_MULTI_MAX of them per pass over the digits
+    for (u32 r0 = 0; r0 < R; r0 += KS_MULTI_MAX) {
+      const u32 nr = std::min<u32>(KS_MULTI_MAX, R - r0);
+      ia.acc = acc_base + (size_t)r0 * acc_stride;
+      ia.acc_rot_stride = acc_stride;
+      ia.nrot = nr;
+      for (u32 r = 0; r < nr; r++) {
+        ia.galois_pc[r] = inv_mod_pow2(galois[r0 + r], c->logN + 1);
+        ia.evk_pc[r] = evks[r0 + r];
+      }
+      for (int fp = 1; fp >= 0; fp--) {
+        FwdInnerArgs a = ia;
+        u32 cnt = 0;
+        for (u32 s_ = 0; s_ < next; s_++)
+          if ((host_class(c, c->mod[emap.id[s_]]) == 0) == (fp == 1)) a.slots[cnt++] = (unsigned char)s_;
+        if (!cnt) continue;
+        ProfScope ps(c, fp ? PK_INNER16 : PK_INNER16_INT, st);
+        const dim3 grid((B + INNER16_ROT_CB - 1) / INNER16_ROT_CB, 256, cnt);
+        if (fp && beta <= 4) hipLaunchKernelGGL(inner16_rot_fp_kernel<4>, grid, dim3(256), 0, st, a, B);
+        else if (fp) hipLaunchKernelGGL(inner16_rot_fp_kernel<INNER16_ROT_MAX_BETA>, grid, dim3(256), 0, st, a, B);
+        else if (beta <= 4) hipLaunchKernelGGL(inner16_rot_int_kernel<4>, grid, dim3(256), 0, st, a, B);
+        else hipLaunchKernelGGL(inner16_rot_int_kernel<INNER16_ROT_MAX_BETA>, grid, dim3(256), 0, st, a, B);
+      }
+      HIP_TRY(hipGetLastError());
+    }
+    return CKKS_OK;
+  }
   for (u32 r = 0; r < R; r++) {
     ia.evk = evks[r];
     ia.galois = galois[r];

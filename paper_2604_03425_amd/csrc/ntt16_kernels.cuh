@@ -164,6 +164,10 @@ struct FwdInnerArgs {
   const u64* c0 = nullptr;   // limb-vector (b, t) at c0 + b*c0_poly_stride + t*N, canonical residues, eval domain
   u64 c0_poly_stride = 0;
   u32 accumulate = 0;        // streaming kernels only: != 0 adds the result to what acc holds instead of overwriting it
+  // many-rotation kernels (inner16_rot_*): rotation r < nrot of every ciphertext uses the key evk_pc[r], writes to
+  // acc + r * acc_rot_stride, and galois_pc[r] holds the INVERSE of its Galois element modulo 2N
+  u32 nrot = 0;
+  u64 acc_rot_stride = 0;
 };
 // b is the same for the whole workgroup; saying so keeps the table look-ups on the scalar unit and their results
 // in scalar registers.
@@ -803,4 +807,157 @@ __global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
   }
   *(ulonglong2*)o0 = ulonglong2{csub(s0[0], q), csub(s0[1], q)};
   *(ulonglong2*)(o0 + (size_t)a.next * N) = ulonglong2{csub(s1[0], q), csub(s1[1], q)};
+}
+
+// ---- many rotations of the same hoisted digits in one pass (rotations kept in the extended basis) ----
+// acc_r[b][c][t][m] = sum_j D_j[pi_r(m)] * evk_r[j][c][id(t)][m]  (+ P * c0[b][t][pi_r(m)] for c = 0 on main primes),
+// pi_r the evaluation-domain index map of rotation r. A lane keeps, for one position n and INNER16_ROT_CB ciphertexts,
+// the beta digit values and the c0 term in registers and walks over the rotations: for each one it reads the 2 beta
+// key words at m = pi_r^-1(n) once for all its ciphertexts and stores the sums there. The map sends aligned
+// 16-element segments onto aligned 16-element segments, so a wave's gathered key reads and scattered stores still
+// move whole 128-byte lines; the digits, c1 and c0 are read once for all rotations instead of once per rotation, and a
+// key word once per INNER16_ROT_CB ciphertexts. grid = (ceil(B / CB), N / 256, slots of the class), mapped like the
+// one-rotation kernels. MAXB bounds beta (the host picks 4 or 8).
+#define INNER16_ROT_MAX_BETA 8
+#define INNER16_ROT_CB 4
+__device__ __forceinline__ const u64* uniform_ptr(const u64* p) {
+  const u64 v = (u64)p;
+  const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
+  return (const u64*)(((u64)hi << 32) | lo);
+}
+template <int MAXB>
+__global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32 B) {
+  constexpr int CB = INNER16_ROT_CB;
+  const size_t N = 65536;
+  u32 bg, blk, zi;
+  ntt16_map(a.map_mode, bg, blk, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const double q = mi.qd, qinv = mi.qinv;
+  const u32 n = blk * 256 + threadIdx.x;
+  u32 bb[CB];   // a short last group recomputes its last ciphertext in the surplus slots and stores nothing for them
+#pragma unroll
+  for (int k = 0; k < CB; k++) bb[k] = min(bg * CB + k, B - 1);
+  double x[MAXB][CB], pc0[CB];
+#pragma unroll
+  for (int j = 0; j < MAXB; j++)
+#pragma unroll
+    for (int k = 0; k < CB; k++) {
+      x[j][k] = 0.0;
+      if ((u32)j < a.beta) {
+        if (fwd_inner_owns(a, t, j)) x[j][k] = u2d(a.d[(size_t)bb[k] * a.d_poly_stride + (size_t)t * N + n]);
+        else x[j][k] = __longlong_as_double((long long)a.ext[(((size_t)bb[k] * a.beta + j) * a.next + t) * N + n]);
+      }
+    }
+#pragma unroll
+  for (int k = 0; k < CB; k++) {   // P * c0, reduced, the same for every rotation
+    pc0[k] = 0.0;
+    if (t < a.nlimbs)
+      pc0[k] = fp_reduce(fp_mulmod_var(u2d(a.c0[(size_t)bb[k] * a.c0_poly_stride + (size_t)t * N + n]), u2d(mi.pmod), qinv, q),
+                         qinv, q);
+  }
+  for (u32 r = 0; r < a.nrot; r++) {
+    const u32 m = galois_src_index16(n, a.galois_pc[r]);
+    const u64* evk = uniform_ptr(a.evk_pc[r]) + (size_t)id * N + m;
+    double s0[CB], s1[CB];
+#pragma unroll
+    for (int k = 0; k < CB; k++) {
+      s0[k] = pc0[k];
+      s1[k] = 0.0;
+    }
+#pragma unroll
+    for (int j = 0; j < MAXB; j++) {
+      if ((u32)j < a.beta) {
+        const double kb = u2d(evk[((size_t)j * 2 + 0) * a.nm * N]), ka = u2d(evk[((size_t)j * 2 + 1) * a.nm * N]);
+#pragma unroll
+        for (int k = 0; k < CB; k++) {
+          s0[k] += fp_mulmod_var(x[j][k], kb, qinv, q);
+          s1[k] += fp_mulmod_var(x[j][k], ka, qinv, q);
+        }
+        if (j == 2 || j == 5) {   // P*c0 (|.| <= q/2) and three products stay below 2^52; then fold
+#pragma unroll
+          for (int k = 0; k < CB; k++) {
+            s0[k] = fp_reduce(s0[k], qinv, q);
+            s1[k] = fp_reduce(s1[k], qinv, q);
+          }
+        }
+      }
+    }
+    u64* o = a.acc + (size_t)r * a.acc_rot_stride + (size_t)t * N + m;
+#pragma unroll
+    for (int k = 0; k < CB; k++) {
+      if (bg * CB + k >= B) break;
+      u64* o0 = o + ((size_t)bb[k] * 2 + 0) * a.next * N;
+      o0[0] = d2u_canon(fp_reduce(s0[k], qinv, q), q);
+      o0[(size_t)a.next * N] = d2u_canon(fp_reduce(s1[k], qinv, q), q);
+    }
+  }
+}
+
+// The same for integer-class moduli: products go through a Montgomery reduction (factor 2^-64, as in the
+// one-rotation kernel), P * c0 likewise.
+template <int MAXB>
+__global__ void __launch_bounds__(256) inner16_rot_int_kernel(FwdInnerArgs a, u32 B) {
+  constexpr int CB = INNER16_ROT_CB;
+  const size_t N = 65536;
+  u32 bg, blk, zi;
+  ntt16_map(a.map_mode, bg, blk, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const u64 q = mi.m, q2 = 2 * mi.m;
+  const u32 n = blk * 256 + threadIdx.x;
+  u32 bb[CB];
+#pragma unroll
+  for (int k = 0; k < CB; k++) bb[k] = min(bg * CB + k, B - 1);
+  u64 x[MAXB][CB], pc0[CB];
+#pragma unroll
+  for (int j = 0; j < MAXB; j++)
+#pragma unroll
+    for (int k = 0; k < CB; k++) {
+      x[j][k] = 0;
+      if ((u32)j < a.beta)
+        x[j][k] = fwd_inner_owns(a, t, j) ? a.d[(size_t)bb[k] * a.d_poly_stride + (size_t)t * N + n]
+                                          : a.ext[(((size_t)bb[k] * a.beta + j) * a.next + t) * N + n];
+    }
+#pragma unroll
+  for (int k = 0; k < CB; k++) {   // P * c0 * 2^-64, below 2q
+    pc0[k] = 0;
+    if (t < a.nlimbs) {
+      const u64 v = a.c0[(size_t)bb[k] * a.c0_poly_stride + (size_t)t * N + n];
+      Acc128 p0 = {v * mi.pmod, mul_hi64(v, mi.pmod)};
+      pc0[k] = redc(p0, q, mi.minv);
+    }
+  }
+  for (u32 r = 0; r < a.nrot; r++) {
+    const u32 m = galois_src_index16(n, a.galois_pc[r]);
+    const u64* evk = uniform_ptr(a.evk_pc[r]) + (size_t)id * N + m;
+    u64 s0[CB], s1[CB];
+#pragma unroll
+    for (int k = 0; k < CB; k++) {
+      s0[k] = pc0[k];
+      s1[k] = 0;
+    }
+#pragma unroll
+    for (int j = 0; j < MAXB; j++) {
+      if ((u32)j < a.beta) {
+        const u64 e0 = evk[((size_t)j * 2 + 0) * a.nm * N], e1 = evk[((size_t)j * 2 + 1) * a.nm * N];
+#pragma unroll
+        for (int k = 0; k < CB; k++) {
+          Acc128 p0 = {x[j][k] * e0, mul_hi64(x[j][k], e0)}, p1 = {x[j][k] * e1, mul_hi64(x[j][k], e1)};
+          s0[k] = csub(s0[k] + redc(p0, q, mi.minv), q2);
+          s1[k] = csub(s1[k] + redc(p1, q, mi.minv), q2);
+        }
+      }
+    }
+    u64* o = a.acc + (size_t)r * a.acc_rot_stride + (size_t)t * N + m;
+#pragma unroll
+    for (int k = 0; k < CB; k++) {
+      if (bg * CB + k >= B) break;
+      u64* o0 = o + ((size_t)bb[k] * 2 + 0) * a.next * N;
+      o0[0] = csub(s0[k], q);
+      o0[(size_t)a.next * N] = csub(s1[k], q);
+    }
+  }
 }
