@@ -869,8 +869,11 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
         if (!cnt) continue;
         ProfScope ps(c, fp ? PK_INNER16 : PK_INNER16_INT, st);
         const dim3 grid((B + INNER16_ROT_CB - 1) / INNER16_ROT_CB, 256, cnt);
-        if (fp && beta <= 4) hipLaunchKernelGGL(inner16_rot_fp_kernel<4>, grid, dim3(256), 0, st, a, B);
-        else if (fp) hipLaunchKernelGGL(inner16_rot_fp_kernel<INNER16_ROT_MAX_BETA>, grid, dim3(256), 0, st, a, B);
+        if (fp && beta == 1) hipLaunchKernelGGL((inner16_rot_fp_kernel<1, true>), grid, dim3(256), 0, st, a, B);
+        else if (fp && beta == 2) hipLaunchKernelGGL((inner16_rot_fp_kernel<2, true>), grid, dim3(256), 0, st, a, B);
+        else if (fp && beta == 3) hipLaunchKernelGGL((inner16_rot_fp_kernel<3, true>), grid, dim3(256), 0, st, a, B);
+        else if (fp && beta == 4) hipLaunchKernelGGL((inner16_rot_fp_kernel<4, true>), grid, dim3(256), 0, st, a, B);
+        else if (fp) hipLaunchKernelGGL((inner16_rot_fp_kernel<INNER16_ROT_MAX_BETA, false>), grid, dim3(256), 0, st, a, B);
         else if (beta <= 4) hipLaunchKernelGGL(inner16_rot_int_kernel<4>, grid, dim3(256), 0, st, a, B);
         else hipLaunchKernelGGL(inner16_rot_int_kernel<INNER16_ROT_MAX_BETA>, grid, dim3(256), 0, st, a, B);
       }

@@ -825,7 +825,7 @@ __device__ __forceinline__ const u64* uniform_ptr(const u64* p) {
   const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
   return (const u64*)(((u64)hi << 32) | lo);
 }
-template <int MAXB>
+template <int MAXB, bool EXACT>   // EXACT: beta == MAXB (no per-digit tests), else beta <= MAXB
 __global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32 B) {
   constexpr int CB = INNER16_ROT_CB;
   const size_t N = 65536;
@@ -845,7 +845,7 @@ __global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32
 #pragma unroll
     for (int k = 0; k < CB; k++) {
       x[j][k] = 0.0;
-      if ((u32)j < a.beta) {
+      if (EXACT || (u32)j < a.beta) {
         if (fwd_inner_owns(a, t, j)) x[j][k] = u2d(a.d[(size_t)bb[k] * a.d_poly_stride + (size_t)t * N + n]);
         else x[j][k] = __longlong_as_double((long long)a.ext[(((size_t)bb[k] * a.beta + j) * a.next + t) * N + n]);
       }
@@ -857,9 +857,34 @@ __global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32
       pc0[k] = fp_reduce(fp_mulmod_var(u2d(a.c0[(size_t)bb[k] * a.c0_poly_stride + (size_t)t * N + n]), u2d(mi.pmod), qinv, q),
                          qinv, q);
   }
+  // the key words of rotation r + 1 are requested before the sums of rotation r are formed
+  u64 kw[MAXB][2], kn[MAXB][2];
+  u32 m_next = galois_src_index16(n, a.galois_pc[0]);
+  const size_t comp_stride = (size_t)a.nm * N, id_off = (size_t)id * N;
+  auto load_keys = [&](u64 (&w)[MAXB][2], u32 r, u32 m) {
+    const u64* kp = uniform_ptr(a.evk_pc[r]) + id_off + m;
+#pragma unroll
+    for (int j = 0; j < MAXB; j++) {
+      w[j][0] = w[j][1] = 0;
+      if (EXACT || (u32)j < a.beta) {
+        w[j][0] = kp[0];
+        w[j][1] = kp[comp_stride];
+      }
+      kp += 2 * comp_stride;
+    }
+  };
+  load_keys(kn, 0, m_next);
   for (u32 r = 0; r < a.nrot; r++) {
-    const u32 m = galois_src_index16(n, a.galois_pc[r]);
-    const u64* evk = uniform_ptr(a.evk_pc[r]) + (size_t)id * N + m;
+    const u32 m = m_next;
+#pragma unroll
+    for (int j = 0; j < MAXB; j++) {
+      kw[j][0] = kn[j][0];
+      kw[j][1] = kn[j][1];
+    }
+    if (r + 1 < a.nrot) {
+      m_next = galois_src_index16(n, a.galois_pc[r + 1]);
+      load_keys(kn, r + 1, m_next);
+    }
     double s0[CB], s1[CB];
 #pragma unroll
     for (int k = 0; k < CB; k++) {
@@ -868,14 +893,15 @@ __global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32
     }
 #pragma unroll
     for (int j = 0; j < MAXB; j++) {
-      if ((u32)j < a.beta) {
-        const double kb = u2d(evk[((size_t)j * 2 + 0) * a.nm * N]), ka = u2d(evk[((size_t)j * 2 + 1) * a.nm * N]);
+      if (EXACT || (u32)j < a.beta) {
+        const double kb = u2d(kw[j][0]), ka = u2d(kw[j][1]);
 #pragma unroll
         for (int k = 0; k < CB; k++) {
           s0[k] += fp_mulmod_var(x[j][k], kb, qinv, q);
           s1[k] += fp_mulmod_var(x[j][k], ka, qinv, q);
         }
-        if (j == 2 || j == 5) {   // P*c0 (|.| <= q/2) and three products stay below 2^52; then fold
+        // P*c0 (|.| <= q/2) and three products stay below 2^52; fold before more are added
+        if ((j == 2 || j == 5) && (EXACT ? j + 1 < MAXB : true)) {
 #pragma unroll
           for (int k = 0; k < CB; k++) {
             s0[k] = fp_reduce(s0[k], qinv, q);
