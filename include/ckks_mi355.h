@@ -215,18 +215,21 @@ int ckks_pcmm_bsgs_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_i
                            void* stream);
 
 /*
- * BSGS matmul with the baby steps kept in the extended basis ("double hoisting"): hoisting as discussed in the
- * paper's Sec. 5.1, taken one step further; not the paper's own schedule and NOT bit-identical to ckks_pcmm_bsgs.
+ * BSGS matmul with baby and giant steps kept in the extended basis ("double hoisting"): hoisting as discussed in
+ * the paper's Sec. 5.1, taken further; not the paper's own schedule and NOT bit-identical to ckks_pcmm_bsgs.
  * With P the product of the special primes:
  *   A_0 = (P*c0, P*c1) on the main primes, 0 on the special primes;
  *   A_r = the key-switch accumulators of sigma_r(c1) under evk_baby[r-1] before ModDown, plus P*sigma_r(c0) on the
  *         main primes of the first one (r = 1..n1-1, sigma_r = 5^(r*stride));
- *   S_g = sum_r pt_ext[g][r] (.) A_r over all nlimbs + K limbs;   ct_out = sum_g rot_{g*n1*stride}(ModDown(S_g)).
+ *   S_g = sum_r pt_ext[g][r] (.) A_r over all nlimbs + K limbs;
+ *   u_g = ModDown(S_g) for g >= 1, and G_g = the accumulators of the key switch of sigma'_g(u_g.c1) under
+ *         evk_giant[g-1] plus P*sigma'_g(u_g.c0) as above (sigma'_g = 5^(g*n1*stride));
+ *   ct_out = ModDown(S_0 + sum_{g>=1} G_g).
  * ModDown(x + P*z) = z + ModDown(x) exactly, so only the placement of ModDown's rounding differs from the plain
- * schedule: once per giant step, after the sum (n2 ModDowns of baby-step data instead of n1 - 1 per ciphertext).
+ * schedule: n2 ModDowns per ciphertext instead of n1 + n2 - 2, and baby steps that cost one inner product each.
  *   pt_ext  device [n2][n1][nlimbs + K][N]: the plaintexts' residues for q_0..q_{nlimbs-1}, then p_0..p_{K-1},
  *           evaluation domain
- * N = 2^16 only (CKKS_ESHAPE otherwise). Workspace: CKKS_OP_PCMM_BSGS_DH with n1 (n1 + 24 ciphertexts in the
+ * N = 2^16 only (CKKS_ESHAPE otherwise). Workspace: CKKS_OP_PCMM_BSGS_DH with n1 (n1 + 25 ciphertexts in the
  * extended basis). Other arguments, overlap rules and errors as for ckks_pcmm_bsgs.
  */
 int ckks_pcmm_bsgs_double_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
