@@ -25,7 +25,7 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 PEAK_ALU_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
 
-# Algorithmic 32-bit lane-op counts (stated in the design doc): one 64-bit Shoup butterfly = 10 multiply-class
+# Algorithmic 32-bit lane-op counts: one 64-bit Shoup butterfly = 10 multiply-class
 # + 14 add/compare/select ops; one 64x64->128 multiply-accumulate = 4 multiplies + 4 adds; one 128->64
 # Montgomery reduction = 7 multiplies + 9 adds/selects; one Shoup constant multiply = 10 + 4.
 OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 16, 14, 4
@@ -40,7 +40,7 @@ OPS_DOT30, OPS_REDUCE90 = 4, 27
 
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload in its default
 # configuration (bytes, average over the two launches of a step: 64 rotations, 32 products; fetch scaled by the
-# copy-kernel calibration); see profiles/keyswitch_micro_hbm_traffic.md.
+# copy-kernel calibration); the counter summary is kept under profiles/.
 MEASURED_TRAFFIC = {
     "moddown_kernel": 1610744934, "modup_kernel": 2416124006,
     "ntt16_fwd_blocks_final_kernel<0>": 4565991014, "ntt16_fwd_blocks_inner8_kernel<2>": 1834122445,
