@@ -436,6 +436,7 @@ def test_late_relinearisation(gpu, shape, nl, B):
     ((16, 4, 45, 2, 50, 2), 4, 1, 1, 3, 1),     # double-precision special primes too; n1 = 1
     ((16, 4, 45, 2, 50, 2), 3, 2, 1, 2, 3),     # n1 = 1 and one giant step: the plain schedule's bits
     ((16, 6, 50, 2, 60, 3), 6, 1, 9, 2, 1),     # three digits, more baby steps than one fold of the inner sums
+    ((16, 4, 50, 2, 60, 2), 4, 5, 3, 5, 1),     # five ciphertexts (a short last group of 4); giant steps in tiles of 2
 ])
 def test_pcmm_double_hoisted(gpu, shape, nl, B, n1, n2, stride):
     """Baby and giant steps kept in the extended basis: bit-exact against the oracle's statement of that schedule;
@@ -456,6 +457,8 @@ def test_pcmm_double_hoisted(gpu, shape, nl, B, n1, n2, stride):
     d_baby, d_giant = [to_dev(k) for k in baby], [to_dev(k) for k in giant]
     out = torch.empty_like(d_ct)
     ws = gc.workspace(gpu.OP_PCMM_BSGS_DH, B, nl, n1)
+    if n2 == 5:
+        gpu.ckks_tune_set(gc, 7, 2)      # at most two giant steps' inner sums held at once: three tiles
     gpu.ckks_pcmm_bsgs_double_hoisted(gc, out, d_ct, B, nl, d_pt, n1, n2, stride, d_baby, d_giant, ws)
     assert_same(to_host(out), want, "double-hoisted PCMM")
     if n1 == 1 and n2 <= 2:
