@@ -802,10 +802,12 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
 // digits through its own index map in the streaming inner product and finishes as usual.
 // acc_base != null: rotation r stops before ModDown and leaves its accumulators, with P * sigma(c0) added to the
 // first one, at acc_base + r * acc_stride (rotations kept in the extended basis), or adds them to what is there
-// (acc_add); out_base is not used then.
+// (acc_add); out_base is not used then. scratch != null (ordinary rotations): room for the accumulators
+// ([B][2][next][N] each) of scratch_rots rotations, which are then computed that many at a time in one pass over the
+// digits before each is finished.
 int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in, u32 B, u32 nlimbs, const u32* galois,
                    const u64* const* evks, u32 R, char* ws, hipStream_t st, u64* acc_base = nullptr, u64 acc_stride = 0,
-                   bool acc_add = false) {
+                   bool acc_add = false, u64* scratch = nullptr, u32 scratch_rots = 0) {
   const LevelTables* lt;
   int rc = get_level(c, nlimbs, &lt);
   if (rc) return rc;
@@ -850,12 +852,11 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
     ia.c0_poly_stride = 2 * polyN;
     ia.accumulate = acc_add ? 1u : 0u;
   }
-  if (acc_base && !acc_add && beta <= INNER16_ROT_MAX_BETA) {
-    // rotations kept in the extended basis: up to KS_MULTI_MAX of them per pass over the digits
-    for (u32 r0 = 0; r0 < R; r0 += KS_MULTI_MAX) {
-      const u32 nr = std::min<u32>(KS_MULTI_MAX, R - r0);
-      ia.acc = acc_base + (size_t)r0 * acc_stride;
-      ia.acc_rot_stride = acc_stride;
+  // several rotations per pass over the digits (at most KS_MULTI_MAX): accumulators of rotations r0 .. r0+nr-1 to
+  // dst + k * stride
+  auto launch_rot = [&](u32 r0, u32 nr, u64* dst, u64 stride) -> int {
+      ia.acc = dst;
+      ia.acc_rot_stride = stride;
       ia.nrot = nr;
       for (u32 r = 0; r < nr; r++) {
         ia.galois_pc[r] = inv_mod_pow2(galois[r0 + r], c->logN + 1);
@@ -878,6 +879,26 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
         else hipLaunchKernelGGL(inner16_rot_int_kernel<INNER16_ROT_MAX_BETA>, grid, dim3(256), 0, st, a, B);
       }
       HIP_TRY(hipGetLastError());
+      return CKKS_OK;
+  };
+  if (acc_base && !acc_add && beta <= INNER16_ROT_MAX_BETA) {
+    for (u32 r0 = 0; r0 < R; r0 += KS_MULTI_MAX) {
+      const u32 nr = std::min<u32>(KS_MULTI_MAX, R - r0);
+      if ((rc = launch_rot(r0, nr, acc_base + (size_t)r0 * acc_stride, acc_stride))) return rc;
+    }
+    return CKKS_OK;
+  }
+  if (!acc_base && scratch && scratch_rots >= 2 && R >= 2 && beta <= INNER16_ROT_MAX_BETA) {
+    const u64 one = (u64)B * 2 * next * N;
+    const u32 per_pass = std::min<u32>(scratch_rots, KS_MULTI_MAX);
+    for (u32 r0 = 0; r0 < R; r0 += per_pass) {
+      const u32 nr = std::min<u32>(per_pass, R - r0);
+      if ((rc = launch_rot(r0, nr, scratch, one))) return rc;
+      for (u32 k = 0; k < nr; k++) {
+        const u32 r = r0 + k;
+        KsIo io{c1, 2 * polyN, galois[r], out_base + (size_t)r * out_stride, {2, 0}, ct_in, galois[r]};
+        if ((rc = ks16_finish(c, lt, io, B, nlimbs, ws, st, nullptr, scratch + (size_t)k * one))) return rc;
+      }
     }
     return CKKS_OK;
   }
@@ -1544,8 +1565,17 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   } else if (hoisted && n1 > 1) {
     std::vector<u32> gs(n1 - 1);
     for (u32 b = 1; b < n1; b++) gs[b - 1] = galois((u64)b * stride);
-    if ((rc = ckks_hrot_hoisted(c, (uint64_t*)baby, ct_in, B, nlimbs, gs.data(), evk_baby, n1 - 1, hws, hws_bytes, stream)))
-      return rc;
+    if (c->logN == 16) {
+      // the region of the inner sums is free until the baby steps are done: it holds the accumulators of as many
+      // rotations as fit, which then share one pass over the hoisted digits
+      const size_t one = (size_t)B * 2 * (nlimbs + c->np) * N * 8;
+      const u32 fit = (u32)std::min<size_t>((size_t)PMACC_TILE * ct_al / one, 1u << 20);
+      rc = hrot_hoisted16(c, baby, ct_elems, (const u64*)ct_in, B, nlimbs, gs.data(), (const u64* const*)evk_baby, n1 - 1,
+                          hws, st, nullptr, 0, false, inner, fit);
+    } else {
+      rc = ckks_hrot_hoisted(c, (uint64_t*)baby, ct_in, B, nlimbs, gs.data(), evk_baby, n1 - 1, hws, hws_bytes, stream);
+    }
+    if (rc) return rc;
   } else {
     for (u32 b = 1; b < n1; b++) {
       rc = ckks_hrot(c, (uint64_t*)(baby + (size_t)(b - 1) * ct_elems), ct_in, B, nlimbs, galois((u64)b * stride),

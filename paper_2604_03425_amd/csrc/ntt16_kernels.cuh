@@ -853,7 +853,7 @@ __global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32
 #pragma unroll
   for (int k = 0; k < CB; k++) {   // P * c0, reduced, the same for every rotation
     pc0[k] = 0.0;
-    if (t < a.nlimbs)
+    if (a.c0 && t < a.nlimbs)
       pc0[k] = fp_reduce(fp_mulmod_var(u2d(a.c0[(size_t)bb[k] * a.c0_poly_stride + (size_t)t * N + n]), u2d(mi.pmod), qinv, q),
                          qinv, q);
   }
@@ -950,7 +950,7 @@ __global__ void __launch_bounds__(256) inner16_rot_int_kernel(FwdInnerArgs a, u3
 #pragma unroll
   for (int k = 0; k < CB; k++) {   // P * c0 * 2^-64, below 2q
     pc0[k] = 0;
-    if (t < a.nlimbs) {
+    if (a.c0 && t < a.nlimbs) {
       const u64 v = a.c0[(size_t)bb[k] * a.c0_poly_stride + (size_t)t * N + n];
       Acc128 p0 = {v * mi.pmod, mul_hi64(v, mi.pmod)};
       pc0[k] = redc(p0, q, mi.minv);
