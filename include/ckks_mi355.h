@@ -204,7 +204,9 @@ int ckks_pcmm_bsgs(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint3
  * inverse transform, ModUp and forward transform of c1 among the rotations. ckks_pcmm_bsgs_hoisted is
  * ckks_pcmm_bsgs with its baby steps computed that way. Results are bit-identical to the one-at-a-time calls
  * (the Galois map commutes exactly with the centred base conversion); workspace sizes are those of
- * CKKS_OP_HROT and CKKS_OP_PCMM_BSGS.
+ * CKKS_OP_HROT and CKKS_OP_PCMM_BSGS. At N = 2^16 ckks_hrot_hoisted uses whatever the workspace holds beyond that
+ * size: every further B*2*(nlimbs+K)*N*8 bytes let one more rotation share a pass over the transformed digits
+ * (up to 64 per pass), which saves reading them once per rotation.
  */
 int ckks_hrot_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                       const uint32_t* galois_elts, const uint64_t* const* evks, uint32_t R, void* ws, size_t ws_bytes,

@@ -1490,9 +1490,14 @@ int ckks_hrot_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint
   if (overlap(ct_out, (size_t)R * ct_elems * 8, ct_in, ct_elems * 8)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
-  if (c->logN == 16)
+  if (c->logN == 16) {
+    // workspace beyond the required size holds accumulators of rotations that then share a pass over the digits
+    const size_t need = ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0);
+    const size_t one = (size_t)B * 2 * (nlimbs + c->np) * c->N * 8;
+    const u32 fit = (u32)std::min<size_t>((ws_bytes - need) / one, 1u << 20);
     return hrot_hoisted16(c, (u64*)ct_out, ct_elems, (const u64*)ct_in, B, nlimbs, galois_elts, (const u64* const*)evks, R,
-                          (char*)ws, (hipStream_t)stream);
+                          (char*)ws, (hipStream_t)stream, nullptr, 0, false, (u64*)((char*)ws + need), fit);
+  }
   for (u32 r = 0; r < R; r++)  // other ring degrees: the same result, one rotation at a time
     if ((rc = ckks_hrot(c, ct_out + (size_t)r * ct_elems, ct_in, B, nlimbs, galois_elts[r], evks[r], ws, ws_bytes, stream)))
       return rc;

@@ -183,6 +183,14 @@ def test_hoisted_rotations_are_bit_identical(gpu):
     for r in range(3):
         assert_same(got[r], rc.hrot(ct, gs[r], evks[r]), "hoisted rotation %d" % r)
     ref.set_threads(1)
+    # a workspace with room for two more accumulator pairs: rotations share passes over the digits, two at a time
+    # (one pass of two, one of one); same bits
+    need = gpu.ckks_workspace_bytes(gc, gpu.OP_HROT, B, nl, 0)
+    one = B * 2 * (nl + len(p.p)) * p.N * 8
+    big = torch.empty((need + 2 * one + 8) // 8, dtype=torch.int64, device="cuda")
+    out2 = torch.empty_like(out)
+    gpu.ckks_hrot_hoisted(gc, out2, to_dev(ct), B, nl, gs, [to_dev(k) for k in evks], big)
+    assert torch.equal(out2, out)
     gc.close()
 
 
