@@ -959,21 +959,18 @@ __global__ void __launch_bounds__(256) inner16_rot_int_kernel(FwdInnerArgs a, u3
   for (u32 r = 0; r < a.nrot; r++) {
     const u32 m = galois_src_index16(n, a.galois_pc[r]);
     const u64* evk = uniform_ptr(a.evk_pc[r]) + (size_t)id * N + m;
-    u64 s0[CB], s1[CB];
+    // up to 8 products below 2^120 summed in 128 bits, one Montgomery reduction per output (result below 2q)
+    Acc128 v0[CB], v1[CB];
 #pragma unroll
-    for (int k = 0; k < CB; k++) {
-      s0[k] = pc0[k];
-      s1[k] = 0;
-    }
+    for (int k = 0; k < CB; k++) v0[k] = v1[k] = Acc128{0, 0};
 #pragma unroll
     for (int j = 0; j < MAXB; j++) {
       if ((u32)j < a.beta) {
         const u64 e0 = evk[((size_t)j * 2 + 0) * a.nm * N], e1 = evk[((size_t)j * 2 + 1) * a.nm * N];
 #pragma unroll
         for (int k = 0; k < CB; k++) {
-          Acc128 p0 = {x[j][k] * e0, mul_hi64(x[j][k], e0)}, p1 = {x[j][k] * e1, mul_hi64(x[j][k], e1)};
-          s0[k] = csub(s0[k] + redc(p0, q, mi.minv), q2);
-          s1[k] = csub(s1[k] + redc(p1, q, mi.minv), q2);
+          mac128(v0[k], x[j][k], e0);
+          mac128(v1[k], x[j][k], e1);
         }
       }
     }
@@ -982,8 +979,8 @@ __global__ void __launch_bounds__(256) inner16_rot_int_kernel(FwdInnerArgs a, u3
     for (int k = 0; k < CB; k++) {
       if (bg * CB + k >= B) break;
       u64* o0 = o + ((size_t)bb[k] * 2 + 0) * a.next * N;
-      o0[0] = csub(s0[k], q);
-      o0[(size_t)a.next * N] = csub(s1[k], q);
+      o0[0] = csub(csub(redc(v0[k], q, mi.minv) + pc0[k], q2), q);
+      o0[(size_t)a.next * N] = csub(redc(v1[k], q, mi.minv), q);
     }
   }
 }
