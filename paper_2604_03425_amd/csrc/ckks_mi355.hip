@@ -662,8 +662,10 @@ int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 n
 //   INTT(d) with (Q_j/q_i)^-1/N folded in -> ModUp -> row pass -> [block pass + evk inner product] (x 2^-64)
 //   -> INTT of the special limbs with 2^64 (P/p_k)^-1/N folded in -> ModDown (x 2^-64) -> row pass
 //   -> [block pass + (acc - t) * 2^64/P + addend].
+// acc_add != null (knobs 2 and 3 at their defaults only): the sequence stops before ModDown and ADDS the two
+// accumulators, plus P * sigma(io.add_src component 0) on the main primes of the first, to acc_add ([B][2][next][N]).
 int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, const u64* evk, char* ws,
-                      hipStream_t st) {
+                      hipStream_t st, u64* acc_add = nullptr) {
   int rc;
   const u32 N = c->N, next = lt->next, beta = lt->beta;
   KsLayout L = ks_layout(c, B, nlimbs);
@@ -732,6 +734,13 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     ia.multi = 1;
     for (u32 i = 0; i < B; i++) ia.galois_pc[i] = io.galois_pc[i], ia.evk_pc[i] = io.evk_pc[i];
   }
+  if (acc_add) {
+    if (c->tune[3] != 2 || c->tune[2] != 2) return fail(CKKS_EINVAL, "internal: accumulation needs the default inner kernels");
+    ia.acc = acc_add;
+    ia.accumulate = 1;
+    ia.c0 = io.add_src;
+    ia.c0_poly_stride = 2 * (u64)nlimbs * N;
+  }
   if (unfused_fp && any_fp) {
     NttOpts o = o2;
     o.only_class = 0;
@@ -789,10 +798,11 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     }
     HIP_TRY(hipGetLastError());
   }
-  if (!joined && special_fp) {  // a special prime's accumulator came from the other chain
+  if (!joined && (special_fp || acc_add)) {  // a special prime's accumulator came from the other chain
     HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
     joined = true;
   }
+  if (acc_add) return CKKS_OK;
   return ks16_finish(c, lt, io, B, nlimbs, ws, st, joined ? nullptr : c->ev_join);
 }
 
@@ -1674,7 +1684,14 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
         if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, inner + (size_t)k * sum_elems))) return rc;
         const u32 gg = galois((u64)g * n1 * stride);
         const u64* key = (const u64*)evk_giant[g - 1];
-        if ((rc = hrot_hoisted16(c, nullptr, 0, rot, B, nlimbs, &gg, &key, 1, hws, st, total, 0, /*acc_add=*/true))) return rc;
+        if (c->tune[3] == 2 && c->tune[2] == 2) {
+          // the usual fused sequence of a rotation (c1 read through the Galois map), stopped before ModDown
+          KsIo gio{rot + polyN, 2 * (u64)polyN, gg, nullptr, {0, 0}, rot, gg};
+          rc = keyswitch_fused16(c, lt, gio, B, nlimbs, key, hws, st, total);
+        } else {
+          rc = hrot_hoisted16(c, nullptr, 0, rot, B, nlimbs, &gg, &key, 1, hws, st, total, 0, /*acc_add=*/true);
+        }
+        if (rc) return rc;
         continue;
       }
       if (g == 0) continue;

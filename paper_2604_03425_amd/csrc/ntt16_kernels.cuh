@@ -372,6 +372,17 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
     }
   }
   u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + lane_pos();
+  if (a.accumulate) {   // a rotation kept in the extended basis, added to what acc holds (wave-uniform branch)
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc[i] = fp_reduce(acc[i], qinv, q) + u2d(o[i * 16]);
+    if (c == 0 && a.c0 && t < a.nlimbs) {   // + P * sigma_g(c0) on the main primes
+      const u64* src = a.c0 + (size_t)b * a.c0_poly_stride + (size_t)t * N;
+      const double pm = u2d(mi.pmod);
+      const u32 pos = lane_pos();
+#pragma unroll
+      for (int i = 0; i < 16; i++) acc[i] += fp_mulmod_var(u2d(src[galois_src_index16(pos + i * 16, g)]), pm, qinv, q);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < 16; i++) o[i * 16] = d2u_canon(fp_reduce(acc[i], qinv, q), q);
 }
@@ -549,6 +560,25 @@ __global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerAr
   }
   u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + posC;
   u64* o1 = o0 + (size_t)a.next * N;
+  if (a.accumulate) {   // a rotation kept in the extended basis, added to what acc holds (wave-uniform branch)
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+      const ulonglong2 p0 = *(const ulonglong2*)(o0 + 2 * v), p1 = *(const ulonglong2*)(o1 + 2 * v);
+      acc0[2 * v] = csub(acc0[2 * v] + p0.x, q2);        // old values are canonical: below 3q, back below 2q
+      acc0[2 * v + 1] = csub(acc0[2 * v + 1] + p0.y, q2);
+      acc1[2 * v] = csub(acc1[2 * v] + p1.x, q2);
+      acc1[2 * v + 1] = csub(acc1[2 * v + 1] + p1.y, q2);
+    }
+    if (a.c0 && t < a.nlimbs) {   // + P * sigma_g(c0) * 2^-64 on the main primes
+      const u64* src = a.c0 + (size_t)b * a.c0_poly_stride + (size_t)t * N;
+#pragma unroll
+      for (int c = 0; c < 8; c++) {
+        const u64 v = src[galois_src_index16(posC + c, g)];
+        Acc128 p = {v * mi.pmod, mul_hi64(v, mi.pmod)};
+        acc0[c] = csub(acc0[c] + redc(p, q, mi.minv), q2);
+      }
+    }
+  }
 #pragma unroll
   for (int v = 0; v < 4; v++) {
     *(ulonglong2*)(o0 + 2 * v) = ulonglong2{csub(acc0[2 * v], q), csub(acc0[2 * v + 1], q)};

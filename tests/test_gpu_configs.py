@@ -469,6 +469,13 @@ def test_pcmm_double_hoisted(gpu, shape, nl, B, n1, n2, stride):
         gpu.ckks_tune_set(gc, 7, 2)      # at most two giant steps' inner sums held at once: three tiles
     gpu.ckks_pcmm_bsgs_double_hoisted(gc, out, d_ct, B, nl, d_pt, n1, n2, stride, d_baby, d_giant, ws)
     assert_same(to_host(out), want, "double-hoisted PCMM")
+    if n2 == 5:
+        # with another form of the inner product selected the giant steps take the streaming kernels: same bits
+        gpu.ckks_tune_set(gc, 3, 1)
+        again = torch.empty_like(d_ct)
+        gpu.ckks_pcmm_bsgs_double_hoisted(gc, again, d_ct, B, nl, d_pt, n1, n2, stride, d_baby, d_giant, ws)
+        assert torch.equal(again, out)
+        gpu.ckks_tune_set(gc, 3, 2)
     if n1 == 1 and n2 <= 2:
         plain = torch.empty_like(d_ct)
         gpu.ckks_pcmm_bsgs(gc, plain, d_ct, B, nl, d_pt[:, :, :nl].contiguous(), n1, n2, stride, d_baby, d_giant,
