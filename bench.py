@@ -143,6 +143,9 @@ def other_workloads(args):
         N, nl, n1, n2, total = p.N, len(p.q), args.pcmm_n1, args.pcmm_n2, 128
         Bc = args.pcmm_batch
         ctx = ck.Context(p, 0)
+        for kv in filter(None, args.tune.split(",")):
+            k, v = kv.split("=")
+            ck.ckks_tune_set(ctx, int(k), int(v))
         ct = _uniform(torch, gen, dev, (Bc, 2), p.q, N)
         pt = _uniform(torch, gen, dev, (n2, n1), p.q, N)
         baby = [_uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N) for _ in range(n1 - 1)]
