@@ -183,7 +183,17 @@ def other_workloads(args):
         ck.ckks_prof_enable(ctx, False)
         prof_d = {k: round(v[0], 2) for k, v in ck.ckks_prof_collect(ctx).items()}
         rots = Bc * (n1 - 1 + n2 - 1)
-        print(json.dumps({"workload": "pcmm_ffn_share", "ciphertexts_per_call": Bc, "seconds_per_call": round(dt, 4),
+        # inner sums on the double-precision limbs: 7 FP64 instructions per multiply-add (exact product in two
+        # parts, quotient, remainder, accumulate), against the chip's FP64 vector issue rate
+        nfp = sum(1 for m in p.q if m < (1 << 50))
+        macs = Bc * 2 * nfp * N * n1 * n2
+        pm_ms = prof.get("pmacc_fp_kernel", 0.0)
+        pm_roof = None
+        if pm_ms:
+            tops = macs * OPS_MULRED_FP / (pm_ms * 1e-3) / 1e12
+            pm_roof = {"bound": "alu", "kernel": "pmacc_fp_kernel", "achieved": round(tops, 2), "peak": round(PEAK_ALU_TOPS, 1),
+                       "unit": "T lane-instructions/s", "frac": round(tops / PEAK_ALU_TOPS, 3)}
+        print(json.dumps({"workload": "pcmm_ffn_share", "inner_sum_roofline": pm_roof, "ciphertexts_per_call": Bc, "seconds_per_call": round(dt, 4),
                           "seconds_for_128_ciphertexts": round(dt * total / Bc, 3), "hrot_per_s": round(rots / dt, 1),
                           "hoisted_seconds_per_call": round(dth, 4),
                           "hoisted_seconds_for_128_ciphertexts": round(dth * total / Bc, 3),
