@@ -498,3 +498,37 @@ def test_pcmm_double_hoisted_needs_full_ring(gpu):
     with pytest.raises(gpu.CkksError):
         gpu.ckks_pcmm_bsgs_double_hoisted(gc, torch.empty_like(ct), ct, 1, 4, pt, 1, 1, 1, [], [], ws)
     gc.close()
+
+
+def test_pcmm_schedules_under_knobs(gpu):
+    """The hoisted and the extended-basis schedule give the oracle's bits under every alternative code path that
+    ckks_tune_set selects (integer-only arithmetic, general base-conversion reduction, integer inner sums, workgroup
+    mappings, the other forms of the fused inner product, two streams)."""
+    import torch
+    from gpu_util import to_dev, to_host
+    p = make_params(16, 5, 50, 3, 60, 2)
+    nl, B, n1, n2 = 5, 3, 5, 3
+    rc = ref.RefContext(p)
+    ct = uniform_residues(1, p.q[:nl], (B, 2), p.N)
+    pte = uniform_residues(2, list(p.q[:nl]) + list(p.p), (n2, n1), p.N)
+    pt = np.ascontiguousarray(pte[:, :, :nl])
+    bk = [uniform_residues(10 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n1 - 1)]
+    gk = [uniform_residues(20 + i, p.moduli, (p.dnum, 2), p.N) for i in range(n2 - 1)]
+    ref.set_threads(4)
+    want_d = rc.pcmm_bsgs_double_hoisted(ct, pte, n1, n2, 1, bk, gk)
+    want_p = rc.pcmm_bsgs(ct, pt, n1, n2, 1, bk, gk)
+    ref.set_threads(1)
+    d_ct, d_pte, d_pt = to_dev(ct), to_dev(pte), to_dev(pt)
+    dbk, dgk = [to_dev(k) for k in bk], [to_dev(k) for k in gk]
+    for knobs in [{1: 1}, {5: 1}, {6: 1}, {0: 0}, {0: 2}, {3: 0}, {3: 3}, {2: 0}, {4: 0}, {1: 1, 5: 1, 6: 1}]:
+        gc = gpu.Context(p)
+        for k, v in knobs.items():
+            gpu.ckks_tune_set(gc, k, v)
+        out = torch.empty_like(d_ct)
+        gpu.ckks_pcmm_bsgs_double_hoisted(gc, out, d_ct, B, nl, d_pte, n1, n2, 1, dbk, dgk,
+                                          gc.workspace(gpu.OP_PCMM_BSGS_DH, B, nl, n1))
+        assert (to_host(out) == want_d).all(), "extended-basis schedule with knobs %s" % knobs
+        gpu.ckks_pcmm_bsgs_hoisted(gc, out, d_ct, B, nl, d_pt, n1, n2, 1, dbk, dgk,
+                                   gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
+        assert (to_host(out) == want_p).all(), "hoisted schedule with knobs %s" % knobs
+        gc.close()
