@@ -879,7 +879,8 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
           if ((host_class(c, c->mod[emap.id[s_]]) == 0) == (fp == 1)) a.slots[cnt++] = (unsigned char)s_;
         if (!cnt) continue;
         ProfScope ps(c, fp ? PK_INNER16 : PK_INNER16_INT, st);
-        const dim3 grid((B + INNER16_ROT_CB - 1) / INNER16_ROT_CB, 256, cnt);
+        const u32 cb = fp ? INNER16_ROT_CB_FP : INNER16_ROT_CB;
+        const dim3 grid((B + cb - 1) / cb, 256, cnt);
         if (fp && beta == 1) hipLaunchKernelGGL((inner16_rot_fp_kernel<1, true>), grid, dim3(256), 0, st, a, B);
         else if (fp && beta == 2) hipLaunchKernelGGL((inner16_rot_fp_kernel<2, true>), grid, dim3(256), 0, st, a, B);
         else if (fp && beta == 3) hipLaunchKernelGGL((inner16_rot_fp_kernel<3, true>), grid, dim3(256), 0, st, a, B);

@@ -841,15 +841,17 @@ __global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
 
 // ---- many rotations of the same hoisted digits in one pass (rotations kept in the extended basis) ----
 // acc_r[b][c][t][m] = sum_j D_j[pi_r(m)] * evk_r[j][c][id(t)][m]  (+ P * c0[b][t][pi_r(m)] for c = 0 on main primes),
-// pi_r the evaluation-domain index map of rotation r. A lane keeps, for one position n and INNER16_ROT_CB ciphertexts,
+// pi_r the evaluation-domain index map of rotation r. A lane keeps, for one position n and CB ciphertexts (8 on
+// double-precision moduli, 4 on integer-class ones),
 // the beta digit values and the c0 term in registers and walks over the rotations: for each one it reads the 2 beta
 // key words at m = pi_r^-1(n) once for all its ciphertexts and stores the sums there. The map sends aligned
 // 16-element segments onto aligned 16-element segments, so a wave's gathered key reads and scattered stores still
 // move whole 128-byte lines; the digits, c1 and c0 are read once for all rotations instead of once per rotation, and a
-// key word once per INNER16_ROT_CB ciphertexts. grid = (ceil(B / CB), N / 256, slots of the class), mapped like the
+// key word once per CB ciphertexts. grid = (ceil(B / CB), N / 256, slots of the class), mapped like the
 // one-rotation kernels. MAXB bounds beta (the host picks 4 or 8).
 #define INNER16_ROT_MAX_BETA 8
 #define INNER16_ROT_CB 4
+#define INNER16_ROT_CB_FP 8
 __device__ __forceinline__ const u64* uniform_ptr(const u64* p) {
   const u64 v = (u64)p;
   const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
@@ -857,7 +859,7 @@ __device__ __forceinline__ const u64* uniform_ptr(const u64* p) {
 }
 template <int MAXB, bool EXACT>   // EXACT: beta == MAXB (no per-digit tests), else beta <= MAXB
 __global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32 B) {
-  constexpr int CB = INNER16_ROT_CB;
+  constexpr int CB = INNER16_ROT_CB_FP;
   const size_t N = 65536;
   u32 bg, blk, zi;
   ntt16_map(a.map_mode, bg, blk, zi);
