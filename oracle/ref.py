@@ -202,6 +202,21 @@ class RefContext:
                                                   pp, C.c_uint32(n1), C.c_uint32(n2), C.c_uint32(stride), baby, giant))
         return out
 
+    def hrot_sum(self, ct, galois_elts, evks):
+        """ct + sum_r HRot_{g_r}(ct) with one ModDown for all rotations (hoisted rotate-and-sum)."""
+        ct, cp = _u64(ct)
+        B, two, nl, _ = ct.shape
+        R = len(galois_elts)
+        assert two == 2 and len(evks) == R
+        keep = [_u64(k) for k in evks]
+        PA = u64p * max(1, R)
+        keys = PA(*[k[1] for k in keep])
+        gs = (C.c_uint32 * max(1, R))(*[int(g) for g in galois_elts])
+        out = np.empty_like(ct)
+        _check(lib().ref_hrot_sum(self._h, out.ctypes.data_as(u64p), cp, C.c_uint32(B), C.c_uint32(nl), gs, keys,
+                                  C.c_uint32(R)))
+        return out
+
     def tensor_acc(self, ct_a, ct_b, d_acc=None):
         """Un-relinearised product [B][3][nl][N], added to d_acc when given (late relinearisation, Sec. 5.2)."""
         ct_a, ap = _u64(ct_a)

@@ -706,6 +706,58 @@ int ref_pcmm_bsgs(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, ui
   return 0;
 }
 
+// Sum of a ciphertext and R of its rotations with one rounding ("hoisted rotate-and-sum", our extension in the spirit
+// of the hoisting of Sec. 5.1): with P = p_0 ... p_{K-1},
+//   T = (P c0, P c1) on the q-limbs, 0 on the p-limbs
+//     + sum_r [ accumulators of the key switch of sigma_r(c1) under evks[r], plus P sigma_r(c0) on the q-limbs ],
+//   out = ModDown(T).
+// ModDown(x + P z) = z + ModDown(x) exactly, so out = ct + sum_r sigma_r(c0) + ModDown(sum of the accumulators): the
+// rotations' key switches share one ModDown (and, all acting on the same c1, one decomposition).
+int ref_hrot_sum(const RefCtx* c, u64* ct_out, const u64* ct_in, uint32_t B, uint32_t nlimbs, const uint32_t* galois,
+                 const u64* const* evks, uint32_t R) {
+  if (nlimbs == 0 || nlimbs > (uint32_t)c->nq) return fail("bad limb count");
+  const size_t N = c->N, pl = (size_t)nlimbs * N, sz = 2 * pl;
+  const int K = c->np, next = (int)nlimbs + K;
+  const size_t el = (size_t)next * N;
+  auto ext_mod = [&](int t) { return c->mod[t < (int)nlimbs ? t : c->nq + (t - (int)nlimbs)]; };
+  std::vector<u64> pmod(nlimbs);
+  for (uint32_t i = 0; i < nlimbs; i++) {
+    u64 m = c->mod[i], v = 1;
+    for (int k = 0; k < K; k++) v = mulm(v, c->mod[c->nq + k] % m, m);
+    pmod[i] = v;
+  }
+  parallel_for(B, [&](size_t bi) {
+    const u64* x = ct_in + bi * sz;
+    std::vector<u64> T(2 * el, 0), r0(pl), r1(pl);
+    for (int comp = 0; comp < 2; comp++)
+      for (uint32_t i = 0; i < nlimbs; i++)
+        for (size_t n = 0; n < N; n++)
+          T[(size_t)comp * el + (size_t)i * N + n] = mulm(x[(size_t)comp * pl + (size_t)i * N + n] % c->mod[i], pmod[i], c->mod[i]);
+    for (uint32_t r = 0; r < R; r++) {
+      for (uint32_t i = 0; i < nlimbs; i++) {
+        automorph_eval(c, &r0[(size_t)i * N], x + (size_t)i * N, i, galois[r]);
+        automorph_eval(c, &r1[(size_t)i * N], x + pl + (size_t)i * N, i, galois[r]);
+      }
+      std::vector<u64> A = keyswitch_accumulate(c, r1.data(), nlimbs, evks[r]);
+      for (uint32_t i = 0; i < nlimbs; i++)
+        for (size_t n = 0; n < N; n++) {
+          u64& a = A[(size_t)i * N + n];
+          a = addm(a, mulm(r0[(size_t)i * N + n], pmod[i], c->mod[i]), c->mod[i]);
+        }
+      for (int comp = 0; comp < 2; comp++)
+        for (int t = 0; t < next; t++) {
+          u64 m = ext_mod(t);
+          for (size_t n = 0; n < N; n++) {
+            size_t k = (size_t)comp * el + (size_t)t * N + n;
+            T[k] = addm(T[k], A[k], m);
+          }
+        }
+    }
+    moddown_pair(c, ct_out + bi * sz, T, nlimbs);
+  });
+  return 0;
+}
+
 // BSGS matmul with the baby steps kept in the extended basis ("double hoisting": the hoisting the paper discusses
 // in Sec. 5.1 taken one step further; not the paper's own schedule, which rotates one at a time). With
 // P = p_0 ... p_{K-1} and the basis q_0..q_{nlimbs-1}, p_0..p_{K-1}:
