@@ -62,6 +62,7 @@ extern "C" {
 #define CKKS_OP_PCMM_BSGS 4
 #define CKKS_OP_RESCALE 5
 #define CKKS_OP_PCMM_BSGS_DH 6
+#define CKKS_OP_HROT_SUM 7
 
 typedef struct ckks_ctx ckks_ctx;
 
@@ -238,6 +239,21 @@ int ckks_pcmm_bsgs_double_hoisted(ckks_ctx* ctx, uint64_t* ct_out, const uint64_
                                   const uint64_t* pt_ext, uint32_t n1, uint32_t n2, uint32_t stride,
                                   const uint64_t* const* evk_baby, const uint64_t* const* evk_giant, void* ws,
                                   size_t ws_bytes, void* stream);
+
+/*
+ * Hoisted rotate-and-sum (an extension in the spirit of the hoisting of the paper's Sec. 5.1; the rotate-and-sum of
+ * Sec. 4.3's score slices in fewer roundings): ct_out[b] = ct_in[b] + sum_{r<R} HRot_{galois_elts[r]}(ct_in[b]) with
+ * ONE ModDown for all rotations. With P the product of the special primes,
+ *   T = (P*c0, P*c1) + sum_r [ key-switch accumulators of sigma_r(c1) under evks[r], plus P*sigma_r(c0) ],
+ *   ct_out = ModDown(T).
+ * ModDown(x + P*z) = z + ModDown(x) exactly; for R = 1 the result is bit-identical to ct_in + ckks_hrot(ct_in), for
+ * R > 1 it differs from R separate rotations in the rounding only. All rotations share one decomposition of c1.
+ * galois_elts, evks: HOST arrays of R entries (R = 0 copies the input through ModDown(P*ct) = ct). ct_out may not
+ * overlap ct_in. N = 2^16 only (CKKS_ESHAPE otherwise). Workspace: CKKS_OP_HROT_SUM. Errors as for ckks_hrot.
+ */
+int ckks_hrot_sum(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                  const uint32_t* galois_elts, const uint64_t* const* evks, uint32_t R, void* ws, size_t ws_bytes,
+                  void* stream);
 
 /*
  * Rescale (paper Sec. 2.1: "divides by the last modulus q_L to reduce scale and remove one prime"): for

@@ -11,14 +11,14 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libckks_mi355.so")
 
-OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS, OP_RESCALE, OP_PCMM_BSGS_DH = 1, 2, 3, 4, 5, 6
+OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS, OP_RESCALE, OP_PCMM_BSGS_DH, OP_HROT_SUM = 1, 2, 3, 4, 5, 6, 7
 
 _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
             "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
             "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi", "ckks_hrot_add", "ckks_tensor_acc",
-            "ckks_relin", "ckks_pcmm_bsgs_double_hoisted"]
+            "ckks_relin", "ckks_pcmm_bsgs_double_hoisted", "ckks_hrot_sum"]
 
 
 class CkksError(RuntimeError):
@@ -60,6 +60,8 @@ def _load():
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_hrot_hoisted.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), C.c_uint32, vp,
                                       C.c_size_t, vp]
+    lib.ckks_hrot_sum.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), C.c_uint32, vp,
+                                  C.c_size_t, vp]
     lib.ckks_hrot_add.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_hrot_multi.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_void_p), vp, C.c_size_t, vp]
     lib.ckks_pcmm_bsgs_hoisted.argtypes = lib.ckks_pcmm_bsgs.argtypes
@@ -211,6 +213,16 @@ def ckks_hrot_hoisted(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
     keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk").value for k in evks])
     _check(_lib.ckks_hrot_hoisted(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys, R,
                                   _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+
+
+def ckks_hrot_sum(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
+    R = len(galois_elts)
+    if len(evks) != R:
+        raise ValueError("need one key per Galois element")
+    gs, _ = _ids(galois_elts)
+    keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk").value for k in evks])
+    _check(_lib.ckks_hrot_sum(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys, R,
+                              _ptr(ws, "ws"), ws.numel() * 8, _stream()))
 
 
 def ckks_hrot_add(ctx, ct_out, ct_in, ct_add, B, nlimbs, galois_elt, evk_rot, ws):

@@ -1226,6 +1226,9 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t B, uint32_t nlim
       if (n1 == 0) return 0;
       // baby steps 1..n1-1, PMACC_TILE inner sums, rotated inner sum, HRot workspace
       return (size_t)(n1 - 1) * 2 * poly + (size_t)PMACC_TILE * 2 * poly + 2 * poly + ks + poly;
+    case CKKS_OP_HROT_SUM:
+      // hoisted digits and ModDown scratch, plus the running sum in the extended basis
+      return ks + poly + 2 * align256((size_t)B * (nlimbs + c->np) * c->N * 8);
     case CKKS_OP_PCMM_BSGS_DH: {
       if (n1 == 0) return 0;
       // n1 baby steps, PMACC_TILE inner sums and the sum over giant steps in the extended basis, one inner sum
@@ -1514,6 +1517,43 @@ int ckks_hrot_hoisted(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint
       return rc;
   return CKKS_OK;
 }
+int ckks_hrot_sum(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                  const uint32_t* galois_elts, const uint64_t* const* evks, uint32_t R, void* ws, size_t ws_bytes,
+                  void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (c->logN != 16) return fail(CKKS_ESHAPE, "the hoisted rotate-and-sum is built for N = 2^16 only");
+  if (!ct_out || !ct_in || (R && (!galois_elts || !evks))) return fail(CKKS_EINVAL, "null argument");
+  if (2 * B > 65535) return fail(CKKS_ESHAPE, "batch too large for one call");
+  for (u32 r = 0; r < R; r++) {
+    if (!evks[r]) return fail(CKKS_EINVAL, "null key");
+    if (!(galois_elts[r] & 1) || galois_elts[r] >= 2 * c->N) return fail(CKKS_EINVAL, "galois_elt must be odd and < 2N");
+  }
+  if ((rc = check_ws(c, CKKS_OP_HROT_SUM, B, nlimbs, 0, ws, ws_bytes))) return rc;
+  const size_t N = c->N, ct_bytes = (size_t)B * 2 * nlimbs * N * 8;
+  if (overlap(ct_out, ct_bytes, ct_in, ct_bytes)) return fail(CKKS_EINVAL, "ct_out overlaps ct_in");
+  const LevelTables* lt;
+  if ((rc = get_level(c, nlimbs, &lt))) return rc;
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  hipStream_t st = (hipStream_t)stream;
+  const u32 next = nlimbs + c->np;
+  char* hws = (char*)ws;
+  u64* total = (u64*)(hws + ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0));
+  LiftArgs la{(const u64*)ct_in, total, c->d_mods, c->logN, nlimbs, next, {}};
+  for (u32 i = 0; i < nlimbs; i++) la.fp[i] = host_class(c, c->mod[i]) == 0 ? 1 : 0;
+  {
+    ProfScope ps(c, PK_ADD, st);
+    hipLaunchKernelGGL(lift_qp_kernel, dim3(N / 512, next, 2 * B), dim3(256), 0, st, la);
+  }
+  HIP_TRY(hipGetLastError());
+  if (R && (rc = hrot_hoisted16(c, nullptr, 0, (const u64*)ct_in, B, nlimbs, galois_elts, (const u64* const*)evks, R, hws,
+                                st, total, 0, /*acc_add=*/true)))
+    return rc;
+  KsIo io{nullptr, 0, 0, (u64*)ct_out, {0, 0}, nullptr, 0};
+  return ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, total);
+}
+
 static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
                      const uint64_t* pt, uint32_t n1, uint32_t n2, uint32_t stride, const uint64_t* const* evk_baby,
                      const uint64_t* const* evk_giant, void* ws, size_t ws_bytes, void* stream, int mode) {

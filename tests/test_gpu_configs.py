@@ -532,3 +532,51 @@ def test_pcmm_schedules_under_knobs(gpu):
                                    gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1))
         assert (to_host(out) == want_p).all(), "hoisted schedule with knobs %s" % knobs
         gc.close()
+
+
+@pytest.mark.parametrize("shape,nl,B,steps", [
+    ((16, 5, 50, 3, 60, 2), 5, 2, (1, 2, 3)),      # double-precision main primes, integer-class special primes
+    ((16, 4, 60, 2, 60, 2), 3, 3, (5,)),           # integer-class everywhere, one rotation
+    ((16, 4, 45, 2, 50, 2), 4, 1, ()),             # no rotation: the input comes back
+    ((16, 6, 50, 2, 60, 3), 4, 2, (8, 16, 24, 32, 40, 48, 56)),   # lower level, seven rotations (the outer sum of 64)
+])
+def test_hrot_sum(gpu, shape, nl, B, steps):
+    """ct + sum of rotations with one ModDown, bit-exact against the oracle; one rotation also equals the library's
+    own rotate-and-add, none returns the input."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(*shape)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    ct = uniform_residues(900, p.q[:nl], (B, 2), p.N)
+    gs = [galois_element(k, p.logN) for k in steps]
+    evks = [uniform_residues(910 + i, p.moduli, (p.dnum, 2), p.N) for i in range(len(steps))]
+    ref.set_threads(4)
+    want = rc.hrot_sum(ct, gs, evks)
+    ref.set_threads(1)
+    d_ct, d_evks = to_dev(ct), [to_dev(k) for k in evks]
+    out = torch.empty_like(d_ct)
+    ws = gc.workspace(gpu.OP_HROT_SUM, B, nl)
+    gpu.ckks_hrot_sum(gc, out, d_ct, B, nl, gs, d_evks, ws)
+    assert_same(to_host(out), want, "hrot_sum")
+    if len(steps) == 1:
+        ra = torch.empty_like(d_ct)
+        gpu.ckks_hrot_add(gc, ra, d_ct, d_ct, B, nl, gs[0], d_evks[0], gc.workspace(gpu.OP_HROT, B, nl))
+        assert torch.equal(out, ra)
+    if not steps:
+        assert torch.equal(out, d_ct)
+    with pytest.raises(gpu.CkksError):
+        gpu.ckks_hrot_sum(gc, d_ct, d_ct, B, nl, gs, d_evks, ws)                    # output overlaps input
+    with pytest.raises(gpu.CkksError):
+        gpu.ckks_hrot_sum(gc, out, d_ct, B, nl, gs, d_evks, gc.workspace(gpu.OP_HROT, B, nl))   # workspace too small
+    gc.close()
+
+
+def test_hrot_sum_needs_full_ring(gpu):
+    import torch
+    from gpu_util import to_dev
+    p = make_params(12, 4, 40, 2, 50, 2)
+    gc = gpu.Context(p)
+    ct = to_dev(uniform_residues(1, p.q, (1, 2), p.N))
+    with pytest.raises(gpu.CkksError):
+        gpu.ckks_hrot_sum(gc, torch.empty_like(ct), ct, 1, 4, [], [], gc.workspace(gpu.OP_HROT, 1, 4))
+    gc.close()
