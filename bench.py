@@ -227,7 +227,20 @@ def other_workloads(args):
                 ck.ckks_hrot_add(ctx, nxt, cur, cur, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
                 cur, nxt = nxt, cur
         dt = _time(torch, units, 2)
+        # the same slot sums as two hoisted sums (rotations by 1..7, then by 8, 16, .., 56): 2 decompositions and 2
+        # ModDowns instead of 6 key switches, 14 rotation keys instead of 6
+        rot14 = rot + [_uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N) for _ in range(8)]
+        ws_sum = ctx.workspace(ck.OP_HROT_SUM, B, nl)
+        g_in = [galois_element(k, p.logN) for k in range(1, 8)]
+        g_out = [galois_element(8 * j, p.logN) for j in range(1, 8)]
+
+        def units_hoisted():
+            ck.ckks_hmult_relin(ctx, acc, qa, kb, B, nl, relin, ws)
+            ck.ckks_hrot_sum(ctx, tmp, acc, B, nl, g_in, rot14[:7], ws_sum)
+            ck.ckks_hrot_sum(ctx, acc, tmp, B, nl, g_out, rot14[7:], ws_sum)
+        dth = _time(torch, units_hoisted, 2)
         print(json.dumps({"workload": "attention_qk_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
+                          "units_per_s_hoisted_sums": round(B / dth, 1),
                           "key_switches_per_s": round(7 * B / dt, 1),
                           "note": "unit = HMult+relin + 6 rotate-and-sum HRot at 20 limbs, dnum=4, K=5; "
                                   "1536 units per (head, block pair) x 3 heads scale linearly"}))

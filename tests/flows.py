@@ -33,6 +33,9 @@ class RefOps:
     def tensor_acc(self, a, b, acc):
         return self.c.tensor_acc(a, b, acc)
 
+    def hrot_sum(self, a, gs, keys):
+        return self.c.hrot_sum(a, gs, keys)
+
     def relin(self, d, relin):
         return self.c.relin(d, relin)
 
@@ -76,6 +79,12 @@ class GpuOps:
     def hrot_add(self, a, add, g, key):
         out = self._new(a)
         self.m.ckks_hrot_add(self.c, out, a, add, a.shape[0], a.shape[2], g, key, self.ws)
+        return out
+
+    def hrot_sum(self, a, gs, keys):
+        out = self._new(a)
+        B, n = a.shape[0], a.shape[2]
+        self.m.ckks_hrot_sum(self.c, out, a, B, n, gs, keys, self.c.workspace(self.m.OP_HROT_SUM, B, n))
         return out
 
     def tensor_acc(self, a, b, acc):
@@ -138,3 +147,20 @@ def av_unit_late(ops, logN, q_ct, k_rot, v_rot, relin, sum_keys, mask_pt, rep_ke
     acc (None for the first unit); one ops.relin after the last unit of the block replaces a key switch per unit."""
     a = mask_and_pack(ops, logN, score_diagonal(ops, logN, q_ct, k_rot, relin, sum_keys, hd), mask_pt, rep_keys, hd)
     return ops.tensor_acc(a, v_rot, acc)
+
+
+def sum_steps(hd):
+    """Steps of a two-level sum over hd = a * b consecutive slots: (1 .. a-1) and (a, 2a, .. (b-1)a)."""
+    bits = hd.bit_length() - 1
+    a = 1 << (bits - bits // 2)
+    return list(range(1, a)), [a * j for j in range(1, hd // a)]
+
+
+def score_diagonal_hoisted(ops, logN, q_ct, k_rot, relin, inner_keys, outer_keys, hd):
+    """The QK^T unit with the rotate-and-sum over the hd slots of a token done as two hoisted sums (the ciphertext
+    plus its rotations by 1..a-1, then that plus its rotations by a, 2a, ..): two decompositions and two ModDowns
+    instead of log2(hd) key switches. Same slot sums as score_diagonal, other rounding."""
+    d = ops.hmult(q_ct, k_rot, relin)
+    inner, outer = sum_steps(hd)
+    d = ops.hrot_sum(d, [galois_element(k, logN) for k in inner], inner_keys)
+    return ops.hrot_sum(d, [galois_element(k, logN) for k in outer], outer_keys)

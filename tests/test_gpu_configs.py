@@ -111,6 +111,17 @@ def test_attention_unit_full_ring(gpu):
         s = acc + tmp                      # residues < 2^50: no int64 overflow; test-side modular add
         acc = torch.where(s >= mods, s - mods, s)
     assert_same(to_host(acc), want, "attention unit")
+    # the unit with the sum over a token's 64 slots as two hoisted sums (flows.score_diagonal_hoisted)
+    from flows import GpuOps, RefOps, score_diagonal_hoisted, sum_steps
+    inner, outer = sum_steps(64)
+    ik = [uniform_residues(120 + i, p.moduli, (p.dnum, 2), p.N) for i in range(len(inner))]
+    ok = [uniform_residues(140 + i, p.moduli, (p.dnum, 2), p.N) for i in range(len(outer))]
+    ref.set_threads(4)
+    want_h = score_diagonal_hoisted(RefOps(rc), p.logN, qa, kb, relin, ik, ok, 64)
+    ref.set_threads(1)
+    got_h = score_diagonal_hoisted(GpuOps(gpu, gc, B, nl), p.logN, to_dev(qa), to_dev(kb), to_dev(relin),
+                                   [to_dev(k) for k in ik], [to_dev(k) for k in ok], 64)
+    assert_same(to_host(got_h), want_h, "attention unit, hoisted sums")
 
 
 SWEEP = [

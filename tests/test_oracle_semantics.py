@@ -336,6 +336,14 @@ def test_attention_unit_scores():
     z = keys.decrypt_slots(acc[0], 2.0**60).real
     want = np.sum(Q * Kmat, axis=1)
     assert np.max(np.abs(z[::hd] - want)) < 2.0**-14
+    # the same unit with the sum over the token's slots as two hoisted sums (7 + 7 rotations, two ModDowns)
+    from flows import RefOps, score_diagonal_hoisted, sum_steps
+    inner, outer = sum_steps(hd)
+    assert inner == list(range(1, 8)) and outer == [8 * j for j in range(1, 8)]
+    rk = lambda k: keys.rotation_key(galois_element(k, p.logN))
+    hs = score_diagonal_hoisted(RefOps(c), p.logN, cq, ck, keys.relin_key(), [rk(k) for k in inner], [rk(k) for k in outer], hd)
+    zh = keys.decrypt_slots(hs[0], 2.0**60).real
+    assert np.max(np.abs(zh[::hd] - want)) < 2.0**-14
 
 
 def test_pmult_then_rescale_keeps_the_scale():
