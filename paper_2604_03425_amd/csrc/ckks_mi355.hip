@@ -806,21 +806,12 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   return ks16_finish(c, lt, io, B, nlimbs, ws, st, joined ? nullptr : c->ev_join);
 }
 
-// Hoisted rotations, N = 2^16: out[r] = HRot_{g_r}(ct_in) for r < R. The Galois map commutes exactly with the
-// centred base conversion (it permutes coefficients up to sign, and the conversion is odd), so INTT, ModUp and the
-// forward transform of c1 are done once on the un-rotated polynomial; each rotation then reads the transformed
-// digits through its own index map in the streaming inner product and finishes as usual.
-// acc_base != null: rotation r stops before ModDown and leaves its accumulators, with P * sigma(c0) added to the
-// first one, at acc_base + r * acc_stride (rotations kept in the extended basis), or adds them to what is there
-// (acc_add); out_base is not used then. scratch != null (ordinary rotations): room for the accumulators
-// ([B][2][next][N] each) of scratch_rots rotations, which are then computed that many at a time in one pass over the
-// digits before each is finished.
-int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in, u32 B, u32 nlimbs, const u32* galois,
-                   const u64* const* evks, u32 R, char* ws, hipStream_t st, u64* acc_base = nullptr, u64 acc_stride = 0,
-                   bool acc_add = false, u64* scratch = nullptr, u32 scratch_rots = 0) {
-  const LevelTables* lt;
-  int rc = get_level(c, nlimbs, &lt);
-  if (rc) return rc;
+// Shared front of the hoisted rotations at N = 2^16: inverse transform, ModUp and forward transform of c1 of ct_in
+// ([B][2][nlimbs][N]) into the workspace, and the arguments of the streaming inner-product kernels that read them
+// (accumulators default to the workspace's own).
+static int hoist_front16(ckks_ctx* c, const LevelTables* lt, const u64* ct_in, u32 B, u32 nlimbs, char* ws, hipStream_t st,
+                         FwdInnerArgs& ia) {
+  int rc;
   const u32 N = c->N, next = lt->next, beta = lt->beta;
   const u64 polyN = (u64)nlimbs * N;
   KsLayout L = ks_layout(c, B, nlimbs);
@@ -842,7 +833,6 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
   of.raw_out = true;  // reduced doubles on double-precision moduli, canonical residues elsewhere
   if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, of)))
     return rc;
-  FwdInnerArgs ia;
   ia.ext = ext;
   ia.d = c1;
   ia.d_poly_stride = 2 * polyN;
@@ -857,6 +847,30 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
   ia.beta = beta;
   ia.next = next;
   ia.map_mode = map_mode_inner(c, true);
+  return CKKS_OK;
+}
+
+// Hoisted rotations, N = 2^16: out[r] = HRot_{g_r}(ct_in) for r < R. The Galois map commutes exactly with the
+// centred base conversion (it permutes coefficients up to sign, and the conversion is odd), so INTT, ModUp and the
+// forward transform of c1 are done once on the un-rotated polynomial; each rotation then reads the transformed
+// digits through its own index map in the streaming inner product and finishes as usual.
+// acc_base != null: rotation r stops before ModDown and leaves its accumulators, with P * sigma(c0) added to the
+// first one, at acc_base + r * acc_stride (rotations kept in the extended basis), or adds them to what is there
+// (acc_add); out_base is not used then. scratch != null (ordinary rotations): room for the accumulators
+// ([B][2][next][N] each) of scratch_rots rotations, which are then computed that many at a time in one pass over the
+// digits before each is finished.
+int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in, u32 B, u32 nlimbs, const u32* galois,
+                   const u64* const* evks, u32 R, char* ws, hipStream_t st, u64* acc_base = nullptr, u64 acc_stride = 0,
+                   bool acc_add = false, u64* scratch = nullptr, u32 scratch_rots = 0) {
+  const LevelTables* lt;
+  int rc = get_level(c, nlimbs, &lt);
+  if (rc) return rc;
+  const u32 N = c->N, next = lt->next, beta = lt->beta;
+  const u64 polyN = (u64)nlimbs * N;
+  const LimbMap emap = ext_map(c, nlimbs);
+  const u64* c1 = ct_in + polyN;
+  FwdInnerArgs ia;
+  if ((rc = hoist_front16(c, lt, ct_in, B, nlimbs, ws, st, ia))) return rc;
   if (acc_base) {
     ia.c0 = ct_in;
     ia.c0_poly_stride = 2 * polyN;
@@ -1540,16 +1554,33 @@ int ckks_hrot_sum(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t
   const u32 next = nlimbs + c->np;
   char* hws = (char*)ws;
   u64* total = (u64*)(hws + ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0));
-  LiftArgs la{(const u64*)ct_in, total, c->d_mods, c->logN, nlimbs, next, {}};
-  for (u32 i = 0; i < nlimbs; i++) la.fp[i] = host_class(c, c->mod[i]) == 0 ? 1 : 0;
-  {
-    ProfScope ps(c, PK_ADD, st);
-    hipLaunchKernelGGL(lift_qp_kernel, dim3(N / 512, next, 2 * B), dim3(256), 0, st, la);
+  FwdInnerArgs ia;
+  if ((rc = hoist_front16(c, lt, (const u64*)ct_in, B, nlimbs, hws, st, ia))) return rc;
+  ia.acc = total;
+  ia.c0 = (const u64*)ct_in;
+  ia.c0_poly_stride = 2 * (u64)nlimbs * N;
+  const LimbMap emap = ext_map(c, nlimbs);
+  // up to KS_MULTI_MAX rotations per launch; the first launch starts from P * ct, later ones add to the sum
+  for (u32 r0 = 0; r0 == 0 || r0 < R; r0 += KS_MULTI_MAX) {
+    const u32 nr = std::min<u32>(KS_MULTI_MAX, R - r0);
+    ia.nrot = nr;
+    ia.accumulate = r0 ? 1u : 0u;
+    for (u32 r = 0; r < nr; r++) {
+      ia.galois_pc[r] = galois_elts[r0 + r];
+      ia.evk_pc[r] = (const u64*)evks[r0 + r];
+    }
+    for (int fp = 1; fp >= 0; fp--) {
+      FwdInnerArgs a = ia;
+      u32 cnt = 0;
+      for (u32 s_ = 0; s_ < next; s_++)
+        if ((host_class(c, c->mod[emap.id[s_]]) == 0) == (fp == 1)) a.slots[cnt++] = (unsigned char)s_;
+      if (!cnt) continue;
+      ProfScope ps(c, fp ? PK_INNER16 : PK_INNER16_INT, st);
+      if (fp) hipLaunchKernelGGL(inner16_sum_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
+      else hipLaunchKernelGGL(inner16_sum_int_kernel, dim3(B, 128, cnt), dim3(256), 0, st, a);
+    }
+    HIP_TRY(hipGetLastError());
   }
-  HIP_TRY(hipGetLastError());
-  if (R && (rc = hrot_hoisted16(c, nullptr, 0, (const u64*)ct_in, B, nlimbs, galois_elts, (const u64* const*)evks, R, hws,
-                                st, total, 0, /*acc_add=*/true)))
-    return rc;
   KsIo io{nullptr, 0, 0, (u64*)ct_out, {0, 0}, nullptr, 0};
   return ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, total);
 }

@@ -1016,3 +1016,132 @@ __global__ void __launch_bounds__(256) inner16_rot_int_kernel(FwdInnerArgs a, u3
     }
   }
 }
+
+// ---- a ciphertext plus many of its rotations, summed before ModDown (hoisted rotate-and-sum) ----
+// acc[b][c][t][n] = P * ct[b][c][t][n] (main primes; or what acc holds, if accumulate)
+//                   + sum_r ( sum_j D_j[pi_r(n)] * evk_r[j][c][id(t)][n]  + [c = 0] P * c0[b][t][pi_r(n)] ),
+// output-stationary: a lane owns two adjacent positions, walks over the rotations with its sums in registers (digits,
+// c1 and c0 read through rotation r's index map, key words read in place) and stores once. galois_pc[r] is the
+// Galois element of rotation r, evk_pc[r] its key; d = c1 and c0 are the two components of the input ciphertext.
+// Same grid and mapping as inner16_fp_kernel.
+__global__ void __launch_bounds__(256) inner16_sum_fp_kernel(FwdInnerArgs a) {
+  const size_t N = 65536;
+  u32 b, blk, zi;
+  ntt16_map(a.map_mode, b, blk, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const double q = mi.qd, qinv = mi.qinv;
+  const u32 n = (blk * 256 + threadIdx.x) * 2;
+  const bool main_prime = t < a.nlimbs;
+  const double pm = u2d(mi.pmod);
+  const u64* c0 = a.c0 + (size_t)b * a.c0_poly_stride + (size_t)t * N;
+  const u64* c1 = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
+  u64* o1 = o0 + (size_t)a.next * N;
+  double s0[2] = {0.0, 0.0}, s1[2] = {0.0, 0.0};
+  if (a.accumulate) {
+    const ulonglong2 p0 = *(const ulonglong2*)o0, p1 = *(const ulonglong2*)o1;
+    s0[0] = u2d(p0.x), s0[1] = u2d(p0.y), s1[0] = u2d(p1.x), s1[1] = u2d(p1.y);
+  } else if (main_prime) {
+    const ulonglong2 v0 = *(const ulonglong2*)(c0 + n), v1 = *(const ulonglong2*)(c1 + n);
+    s0[0] = fp_mulmod_var(u2d(v0.x), pm, qinv, q), s0[1] = fp_mulmod_var(u2d(v0.y), pm, qinv, q);
+    s1[0] = fp_mulmod_var(u2d(v1.x), pm, qinv, q), s1[1] = fp_mulmod_var(u2d(v1.y), pm, qinv, q);
+  }
+  for (u32 r = 0; r < a.nrot; r++) {
+    const u32 g = a.galois_pc[r];
+    const u64* evk = uniform_ptr(a.evk_pc[r]) + (size_t)id * N + n;
+    const u32 m[2] = {galois_src_index16(n, g), galois_src_index16(n + 1, g)};
+    // the running sums enter a rotation below 1.5 q in magnitude; three products (0.75 q each) are added between folds
+    u32 pending = 0;
+    for (u32 j = 0; j < a.beta; j++) {
+      double x[2];
+      if (fwd_inner_owns(a, t, j)) {
+        x[0] = u2d(c1[m[0]]);
+        x[1] = u2d(c1[m[1]]);
+      } else {
+        const u64* e = a.ext + (((size_t)b * a.beta + j) * a.next + t) * N;
+        x[0] = __longlong_as_double((long long)e[m[0]]);
+        x[1] = __longlong_as_double((long long)e[m[1]]);
+      }
+      const ulonglong2 eb = *(const ulonglong2*)(evk + ((size_t)j * 2 + 0) * a.nm * N);
+      const ulonglong2 ea = *(const ulonglong2*)(evk + ((size_t)j * 2 + 1) * a.nm * N);
+      s0[0] += fp_mulmod_var(x[0], u2d(eb.x), qinv, q);
+      s0[1] += fp_mulmod_var(x[1], u2d(eb.y), qinv, q);
+      s1[0] += fp_mulmod_var(x[0], u2d(ea.x), qinv, q);
+      s1[1] += fp_mulmod_var(x[1], u2d(ea.y), qinv, q);
+      if (++pending == 3) {
+        pending = 0;
+#pragma unroll
+        for (int e2 = 0; e2 < 2; e2++) {
+          s0[e2] = fp_reduce(s0[e2], qinv, q);
+          s1[e2] = fp_reduce(s1[e2], qinv, q);
+        }
+      }
+    }
+    if (main_prime) {
+      s0[0] += fp_mulmod_var(u2d(c0[m[0]]), pm, qinv, q);
+      s0[1] += fp_mulmod_var(u2d(c0[m[1]]), pm, qinv, q);
+    }
+#pragma unroll
+    for (int e2 = 0; e2 < 2; e2++) {   // back to |.| <= q/2 before the next rotation
+      s0[e2] = fp_reduce(s0[e2], qinv, q);
+      s1[e2] = fp_reduce(s1[e2], qinv, q);
+    }
+  }
+  *(ulonglong2*)o0 = ulonglong2{d2u_canon(fp_reduce(s0[0], qinv, q), q), d2u_canon(fp_reduce(s0[1], qinv, q), q)};
+  *(ulonglong2*)o1 = ulonglong2{d2u_canon(fp_reduce(s1[0], qinv, q), q), d2u_canon(fp_reduce(s1[1], qinv, q), q)};
+}
+
+// The same for integer-class moduli (every term with the factor 2^-64, as in inner16_int_kernel).
+__global__ void __launch_bounds__(256) inner16_sum_int_kernel(FwdInnerArgs a) {
+  const size_t N = 65536;
+  u32 b, blk, zi;
+  ntt16_map(a.map_mode, b, blk, zi);
+  const u32 t = a.slots[zi];
+  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
+  const ModInfo mi = a.mods[id];
+  const u64 q = mi.m, q2 = 2 * mi.m;
+  const u32 n = (blk * 256 + threadIdx.x) * 2;
+  const bool main_prime = t < a.nlimbs;
+  const u64* c0 = a.c0 + (size_t)b * a.c0_poly_stride + (size_t)t * N;
+  const u64* c1 = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + n;
+  u64* o1 = o0 + (size_t)a.next * N;
+  auto times_p = [&](u64 v) {   // v * P * 2^-64, below 2q
+    Acc128 p = {v * mi.pmod, mul_hi64(v, mi.pmod)};
+    return redc(p, q, mi.minv);
+  };
+  u64 s0[2] = {0, 0}, s1[2] = {0, 0};   // kept below 2q
+  if (a.accumulate) {
+    const ulonglong2 p0 = *(const ulonglong2*)o0, p1 = *(const ulonglong2*)o1;
+    s0[0] = p0.x, s0[1] = p0.y, s1[0] = p1.x, s1[1] = p1.y;
+  } else if (main_prime) {
+    const ulonglong2 v0 = *(const ulonglong2*)(c0 + n), v1 = *(const ulonglong2*)(c1 + n);
+    s0[0] = times_p(v0.x), s0[1] = times_p(v0.y), s1[0] = times_p(v1.x), s1[1] = times_p(v1.y);
+  }
+  for (u32 r = 0; r < a.nrot; r++) {
+    const u32 g = a.galois_pc[r];
+    const u64* evk = uniform_ptr(a.evk_pc[r]) + (size_t)id * N + n;
+    const u32 m[2] = {galois_src_index16(n, g), galois_src_index16(n + 1, g)};
+    for (u32 j = 0; j < a.beta; j++) {
+      const u64* src = fwd_inner_owns(a, t, j) ? c1 : a.ext + (((size_t)b * a.beta + j) * a.next + t) * N;
+      const u64 x[2] = {src[m[0]], src[m[1]]};
+      const ulonglong2 eb = *(const ulonglong2*)(evk + ((size_t)j * 2 + 0) * a.nm * N);
+      const ulonglong2 ea = *(const ulonglong2*)(evk + ((size_t)j * 2 + 1) * a.nm * N);
+      const u64 e0[2] = {eb.x, eb.y}, e1[2] = {ea.x, ea.y};
+#pragma unroll
+      for (int e = 0; e < 2; e++) {
+        Acc128 p0 = {x[e] * e0[e], mul_hi64(x[e], e0[e])}, p1 = {x[e] * e1[e], mul_hi64(x[e], e1[e])};
+        s0[e] = csub(s0[e] + redc(p0, q, mi.minv), q2);
+        s1[e] = csub(s1[e] + redc(p1, q, mi.minv), q2);
+      }
+    }
+    if (main_prime) {
+      s0[0] = csub(s0[0] + times_p(c0[m[0]]), q2);
+      s0[1] = csub(s0[1] + times_p(c0[m[1]]), q2);
+    }
+  }
+  *(ulonglong2*)o0 = ulonglong2{csub(s0[0], q), csub(s0[1], q)};
+  *(ulonglong2*)o1 = ulonglong2{csub(s1[0], q), csub(s1[1], q)};
+}

@@ -550,6 +550,7 @@ def test_pcmm_schedules_under_knobs(gpu):
     ((16, 4, 60, 2, 60, 2), 3, 3, (5,)),           # integer-class everywhere, one rotation
     ((16, 4, 45, 2, 50, 2), 4, 1, ()),             # no rotation: the input comes back
     ((16, 6, 50, 2, 60, 3), 4, 2, (8, 16, 24, 32, 40, 48, 56)),   # lower level, seven rotations (the outer sum of 64)
+    ((16, 2, 50, 1, 60, 2), 2, 1, tuple(range(1, 66))),           # 65 rotations: two launches, the second adds on
 ])
 def test_hrot_sum(gpu, shape, nl, B, steps):
     """ct + sum of rotations with one ModDown, bit-exact against the oracle; one rotation also equals the library's
@@ -560,11 +561,14 @@ def test_hrot_sum(gpu, shape, nl, B, steps):
     rc, gc = ref.RefContext(p), gpu.Context(p)
     ct = uniform_residues(900, p.q[:nl], (B, 2), p.N)
     gs = [galois_element(k, p.logN) for k in steps]
-    evks = [uniform_residues(910 + i, p.moduli, (p.dnum, 2), p.N) for i in range(len(steps))]
+    nkeys = min(len(steps), 7)                 # keys repeat beyond seven rotations
+    kpool = [uniform_residues(910 + i, p.moduli, (p.dnum, 2), p.N) for i in range(nkeys)]
+    evks = [kpool[i % nkeys] for i in range(len(steps))]
     ref.set_threads(4)
     want = rc.hrot_sum(ct, gs, evks)
     ref.set_threads(1)
-    d_ct, d_evks = to_dev(ct), [to_dev(k) for k in evks]
+    d_pool = [to_dev(k) for k in kpool]
+    d_ct, d_evks = to_dev(ct), [d_pool[i % nkeys] for i in range(len(steps))]
     out = torch.empty_like(d_ct)
     ws = gc.workspace(gpu.OP_HROT_SUM, B, nl)
     gpu.ckks_hrot_sum(gc, out, d_ct, B, nl, gs, d_evks, ws)
