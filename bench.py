@@ -243,7 +243,9 @@ def other_workloads(args):
                           "units_per_s_hoisted_sums": round(B / dth, 1),
                           "key_switches_per_s": round(7 * B / dt, 1),
                           "note": "unit = HMult+relin + 6 rotate-and-sum HRot at 20 limbs, dnum=4, K=5; "
-                                  "1536 units per (head, block pair) x 3 heads scale linearly"}))
+                                  "1536 units per (head, block pair) x 3 heads scale linearly; hoisted_sums: the "
+                                  "sum over a token's 64 slots as two ckks_hrot_sum calls (7 rotations and one "
+                                  "ModDown each) instead of 6 key switches"}))
     elif args.workload == "attention_av":
         # second attention workload: score diagonal (as above), mask-and-pack (Rescale, PMult by the slot mask,
         # Rescale, 6 replicating right rotations) and the product with V two limbs lower; 14 key switches per unit
@@ -289,12 +291,39 @@ def other_workloads(args):
                 units()
             ck.ckks_relin(ctx, out, acc3, B, nl - 2, relin, ws)
         dt_late = _time(torch, block, 1) / 64
+        # every slot sum as two hoisted sums (rotations by +-1..7, then +-8..56), late relinearisation as above
+        rot28 = rot + [_uniform(torch, gen, dev, (p.dnum, 2), p.moduli, N) for _ in range(16)]
+        ws_sum = ctx.workspace(ck.OP_HROT_SUM, B, nl)
+        gin = [galois_element(k, p.logN) for k in range(1, 8)]
+        gout = [galois_element(8 * j, p.logN) for j in range(1, 8)]
+        gin_r = [galois_element(-k, p.logN) for k in range(1, 8)]
+        gout_r = [galois_element(-8 * j, p.logN) for j in range(1, 8)]
+
+        def units_hoisted():
+            ck.ckks_hmult_relin(ctx, d, qa, kb, B, nl, relin, ws)
+            ck.ckks_hrot_sum(ctx, tmp, d, B, nl, gin, rot28[:7], ws_sum)
+            ck.ckks_hrot_sum(ctx, d, tmp, B, nl, gout, rot28[7:14], ws_sum)
+            ck.ckks_rescale(ctx, d1, d, B, nl, ws)
+            ck.ckks_pmult(ctx, m1, d1, mask, B, nl - 1)
+            ck.ckks_rescale(ctx, m, m1, B, nl - 1, ws)
+            ck.ckks_hrot_sum(ctx, tmp2, m, B, nl - 2, gin_r, rot28[14:21], ws_sum)
+            ck.ckks_hrot_sum(ctx, m, tmp2, B, nl - 2, gout_r, rot28[21:28], ws_sum)
+            ck.ckks_tensor_acc(ctx, acc3, m, vb, acc3, B, nl - 2)
+
+        def block_hoisted():
+            for _ in range(64):
+                units_hoisted()
+            ck.ckks_relin(ctx, out, acc3, B, nl - 2, relin, ws)
+        dt_h = _time(torch, block_hoisted, 1) / 64
         print(json.dumps({"workload": "attention_av_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
                           "key_switches_per_s": round(14 * B / dt, 1),
                           "units_per_s_late_relin": round(B / dt_late, 1),
+                          "units_per_s_hoisted_sums": round(B / dt_h, 1),
                           "note": "unit = score diagonal (HMult+relin + 6 HRot) + mask-and-pack (2 Rescale, PMult, "
                                   "6 HRot) + HMult+relin with V, 20 -> 18 limbs, dnum=4, K=5; late_relin: the "
-                                  "product with V accumulated in three components, one key switch per 64 units"}))
+                                  "product with V accumulated in three components, one key switch per 64 units; "
+                                  "hoisted_sums: also every sum over a token's 64 slots as two ckks_hrot_sum calls "
+                                  "(7 rotations each, one ModDown each)"}))
     elif args.workload == "sweep":
         B = 32
         for limbs in (4, 8, 12, 16, 20, 24, 28, 32, 36):

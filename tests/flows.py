@@ -164,3 +164,16 @@ def score_diagonal_hoisted(ops, logN, q_ct, k_rot, relin, inner_keys, outer_keys
     inner, outer = sum_steps(hd)
     d = ops.hrot_sum(d, [galois_element(k, logN) for k in inner], inner_keys)
     return ops.hrot_sum(d, [galois_element(k, logN) for k in outer], outer_keys)
+
+
+def av_unit_hoisted(ops, logN, q_ct, k_rot, v_rot, relin, keys, mask_pt, hd, acc):
+    """av_unit_late with every slot sum done as two hoisted sums: the score diagonal through score_diagonal_hoisted,
+    the replication over a token's slots as the same two sums with right rotations. keys = (inner, outer, inner_right,
+    outer_right) lists of rotation keys for sum_steps(hd) and their negatives. Four decompositions and four ModDowns
+    replace 2 log2(hd) key switches; the product with V stays in three components (acc, None for the first unit)."""
+    inner, outer = sum_steps(hd)
+    d = score_diagonal_hoisted(ops, logN, q_ct, k_rot, relin, keys[0], keys[1], hd)
+    m = ops.rescale(ops.pmult(ops.rescale(d), mask_pt))
+    m = ops.hrot_sum(m, [galois_element(-k, logN) for k in inner], keys[2])
+    m = ops.hrot_sum(m, [galois_element(-k, logN) for k in outer], keys[3])
+    return ops.tensor_acc(m, v_rot, acc)

@@ -267,6 +267,19 @@ def test_attention_av_unit(gpu, name, nl, B, hd):
     ref.set_threads(1)
     assert_same(to_host(g), w, "A x V units in three components")
     assert_same(to_host(gops.relin(g, dev[3])), want_late, "A x V block relinearised late")
+    if p.logN == 16:
+        # every slot sum as two hoisted sums (ckks_hrot_sum), products kept in three components
+        from flows import av_unit_hoisted, sum_steps
+        inner, outer = sum_steps(hd)
+        key = lambda i: uniform_residues(700 + i, p.moduli, (p.dnum, 2), p.N)
+        hk = ([key(i) for i in range(len(inner))], [key(10 + i) for i in range(len(outer))],
+              [key(20 + i) for i in range(len(inner))], [key(30 + i) for i in range(len(outer))])
+        dhk = tuple([to_dev(k) for k in ks] for ks in hk)
+        ref.set_threads(4)
+        wh = av_unit_hoisted(rops, p.logN, q_ct, k_ct, v_ct, relin, hk, mask, hd, None)
+        ref.set_threads(1)
+        gh = av_unit_hoisted(gops, p.logN, dev[0], dev[1], dev[2], dev[3], dhk, dev[5], hd, None)
+        assert_same(to_host(gh), wh, "A x V unit with hoisted sums")
 
 
 @pytest.mark.parametrize("name,nl,B", [("tiny_hrot", 4, 8), ("keyswitch_micro", 24, 3),

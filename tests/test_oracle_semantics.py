@@ -366,7 +366,7 @@ def test_attention_av_block():
     aggregation with V is local): summing the units over all cyclic diagonals r gives (Q K^T) V. hd = 8 slots per
     token, 64 tokens per ciphertext, Delta = 2^40 with 40-bit primes so that each Rescale keeps the scale near
     Delta; max |err| < 2^-20."""
-    from flows import RefOps, av_unit, av_unit_late
+    from flows import RefOps, av_unit, av_unit_late, av_unit_hoisted, sum_steps
     p = make_params(10, 5, 40, 3, 50, 2)
     c = ref.RefContext(p)
     keys = Keys(p, c, 71)
@@ -387,7 +387,9 @@ def test_attention_av_block():
     rep_keys = [rk(-(1 << i)) for i in range(3)]
     g_tok, tok_key = galois_element(hd, p.logN), rk(hd)
     ops = RefOps(c)
-    out = late = None
+    inner, outer = sum_steps(hd)
+    hkeys = ([rk(k) for k in inner], [rk(k) for k in outer], [rk(-k) for k in inner], [rk(-k) for k in outer])
+    out = late = hoist = None
     for r in range(T):
         if r:
             ck = c.hrot(ck, g_tok, tok_key)
@@ -395,6 +397,7 @@ def test_attention_av_block():
         u = av_unit(ops, p.logN, cq, ck, cv, relin, sum_keys, mask_pt, rep_keys, hd)
         out = u if out is None else ops.add(out, u)
         late = av_unit_late(ops, p.logN, cq, ck, cv, relin, sum_keys, mask_pt, rep_keys, hd, late)
+        hoist = av_unit_hoisted(ops, p.logN, cq, ck, cv, relin, hkeys, mask_pt, hd, hoist)
     assert out.shape == (1, 2, 3, p.N)
     scale = D**4 / (p.q[4] * p.q[3])
     got = keys.decrypt_slots(out[0], scale).real.reshape(T, hd)
@@ -405,3 +408,7 @@ def test_attention_av_block():
     got_late = keys.decrypt_slots(ops.relin(late, relin)[0], scale).real.reshape(T, hd)
     err_late = np.max(np.abs(got_late - want))
     assert err_late < 2.0**-20, err_late
+    # every slot sum as two hoisted sums (one ModDown each), products with V relinearised late
+    got_h = keys.decrypt_slots(ops.relin(hoist, relin)[0], scale).real.reshape(T, hd)
+    err_h = np.max(np.abs(got_h - want))
+    assert err_h < 2.0**-20, err_h
