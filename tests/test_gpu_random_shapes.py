@@ -65,6 +65,13 @@ def test_random_parameter_sets(seed):
         same(d3, want3, "tensor_acc")
         gpu.ckks_relin(gc, out, d3, B, nl, d_evk2, ws)
         same(out, rc.relin(want3, evk2), "relin")
+        if p.logN == 16:
+            R = rng.randint(0, 4)
+            sg = [galois_element(rng.randrange(1, p.N // 2), p.logN) for _ in range(R)]
+            sk = [evk if r % 2 == 0 else evk2 for r in range(R)]
+            gpu.ckks_hrot_sum(gc, out, d_ct, B, nl, sg, [d_evk if r % 2 == 0 else d_evk2 for r in range(R)],
+                              gc.workspace(gpu.OP_HROT_SUM, B, nl))
+            same(out, rc.hrot_sum(ct, sg, sk), "hrot_sum R=%d" % R)
         if nl >= 2:
             rs = torch.empty((B, 2, nl - 1, p.N), dtype=torch.int64, device="cuda")
             gpu.ckks_rescale(gc, rs, d_ct, B, nl, gc.workspace(gpu.OP_RESCALE, B, nl))
