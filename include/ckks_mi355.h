@@ -84,8 +84,9 @@ int ckks_ctx_destroy(ckks_ctx* ctx);
 
 /*
  * Bytes of device workspace that `op` (CKKS_OP_*) needs for a batch of `batch`
- * ciphertexts at `nlimbs` limbs; n1 is the baby-step count for CKKS_OP_PCMM_BSGS and is
- * ignored otherwise. Returns 0 on a bad argument. Workspace must be 256-byte aligned.
+ * ciphertexts at `nlimbs` limbs; n1 is the baby-step count for CKKS_OP_PCMM_BSGS and
+ * CKKS_OP_PCMM_BSGS_DH and is ignored otherwise. Returns 0 on a bad argument. Workspace must be
+ * 256-byte aligned.
  */
 size_t ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch, uint32_t nlimbs, uint32_t n1);
 
