@@ -5,8 +5,6 @@
 
 #include <algorithm>
 #include <cstring>
-#include <map>
-#include <mutex>
 #include <string>
 #include <vector>
 
@@ -167,8 +165,10 @@ struct ckks_ctx {
   hipStream_t side = nullptr;       // second stream for the fork/join inside a key switch (default priority)
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   std::vector<Pass> passes;  // forward order
-  std::mutex mu;
-  std::map<u32, LevelTables> levels;
+  // Base-conversion constants of every limb count 1..nq, built when the context is created (and again when knob 1
+  // or 5 changes): levels[nlimbs] points into one device allocation, d_levels.
+  std::vector<LevelTables> levels;
+  char* d_levels = nullptr;
 };
 
 namespace {
@@ -222,16 +222,23 @@ struct ProfScope {
   }
 };
 
-int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
-  std::lock_guard<std::mutex> lock(c->mu);
-  const bool fp_on = c->tune[1] == 0;
-  const u32 key = nlimbs * 4 + (fp_on ? 1 : 0) + (c->tune[5] ? 2 : 0);
-  auto is_fp = [&](u64 m) { return fp_on && (m >> 50) == 0; };
-  auto it = c->levels.find(key);
-  if (it != c->levels.end()) {
-    *out = &it->second;
-    return CKKS_OK;
+// Host image of the device allocation that holds the level tables: every table starts on a 256-byte boundary; the
+// LevelTables pointers hold offsets until the image has been uploaded.
+struct LevelArena {
+  std::vector<char> host;
+  template <class T>
+  T* add(const std::vector<T>& v) {
+    const size_t off = (host.size() + 255) & ~(size_t)255;
+    host.resize(off + std::max<size_t>(1, v.size()) * sizeof(T));
+    if (!v.empty()) memcpy(host.data() + off, v.data(), v.size() * sizeof(T));
+    return (T*)off;
   }
+};
+
+// Constants for ciphertexts at `nlimbs` limbs, appended to the arena (pointers are offsets into it).
+LevelTables build_level(const ckks_ctx* c, u32 nlimbs, LevelArena& arena) {
+  const bool fp_on = c->tune[1] == 0;
+  auto is_fp = [&](u64 m) { return fp_on && (m >> 50) == 0; };
   LevelTables t;
   t.nlimbs = nlimbs;
   t.beta = (nlimbs + c->alpha - 1) / c->alpha;
@@ -348,20 +355,58 @@ int get_level(ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
       rs_qinv16[i] = is_fp(m) ? as_fp(inv, m) : rs_qinv[i];
     }
   }
+  t.rs_one = arena.add(rs_one);
+  t.rs_mat = arena.add(rs_mat);
+  t.rs_qinv = arena.add(rs_qinv);
+  t.rs_qinv16 = arena.add(rs_qinv16);
+  t.up_scale = arena.add(up_scale);
+  t.dn_scale = arena.add(dn_scale);
+  t.dn_mat_plain = arena.add(dn_mat_plain);
+  t.pinv2 = arena.add(pinv2);
+  t.up_inv = arena.add(up_inv);
+  t.up_mat = arena.add(up_mat);
+  t.dn_inv = arena.add(dn_inv);
+  t.dn_mat = arena.add(dn_mat);
+  t.pinv = arena.add(pinv);
+  return t;
+}
+
+// (Re)build the tables of all limb counts under the current knobs 1 and 5: one allocation, one copy. Called from
+// ckks_ctx_create and from ckks_tune_set, never from a call that enqueues work.
+int build_levels(ckks_ctx* c) {
+  LevelArena arena;
+  std::vector<LevelTables> lv(c->nq + 1);
+  for (u32 nl = 1; nl <= c->nq; nl++) lv[nl] = build_level(c, nl, arena);
   DeviceGuard guard(c->device);
   if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
-  int rc;
-  if ((rc = upload(&t.rs_one, rs_one)) || (rc = upload(&t.rs_mat, rs_mat)) || (rc = upload(&t.rs_qinv, rs_qinv)) ||
-      (rc = upload(&t.rs_qinv16, rs_qinv16)))
-    return rc;
-  if ((rc = upload(&t.up_scale, up_scale)) || (rc = upload(&t.dn_scale, dn_scale)) ||
-      (rc = upload(&t.dn_mat_plain, dn_mat_plain)) || (rc = upload(&t.pinv2, pinv2)))
-    return rc;
-  if ((rc = upload(&t.up_inv, up_inv)) || (rc = upload(&t.up_mat, up_mat)) || (rc = upload(&t.dn_inv, dn_inv)) ||
-      (rc = upload(&t.dn_mat, dn_mat)) || (rc = upload(&t.pinv, pinv)))
-    return rc;
-  auto res = c->levels.emplace(key, t);
-  *out = &res.first->second;
+  char* dev = nullptr;
+  HIP_TRY(hipMalloc((void**)&dev, arena.host.size()));
+  hipError_t e = hipMemcpy(dev, arena.host.data(), arena.host.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(dev);
+    return fail(CKKS_EHIP, std::string("uploading the level tables: ") + hipGetErrorString(e));
+  }
+  auto rebase = [&](auto*& ptr) { ptr = (std::remove_reference_t<decltype(ptr)>)(dev + (size_t)ptr); };
+  for (u32 nl = 1; nl <= c->nq; nl++) {
+    LevelTables& t = lv[nl];
+    rebase(t.up_inv); rebase(t.up_mat); rebase(t.dn_inv); rebase(t.dn_mat); rebase(t.pinv);
+    rebase(t.up_scale); rebase(t.dn_scale); rebase(t.dn_mat_plain); rebase(t.pinv2);
+    rebase(t.rs_one); rebase(t.rs_mat); rebase(t.rs_qinv); rebase(t.rs_qinv16);
+  }
+  if (c->d_levels) {
+    // a knob changed: nothing may still be reading the old tables
+    HIP_TRY(hipDeviceSynchronize());
+    (void)hipFree(c->d_levels);
+  }
+  c->d_levels = dev;
+  c->levels.swap(lv);
+  return CKKS_OK;
+}
+
+// Table look-up only: no allocation, no copy, no synchronisation.
+int get_level(const ckks_ctx* c, u32 nlimbs, const LevelTables** out) {
+  if (nlimbs == 0 || nlimbs >= c->levels.size()) return fail(CKKS_ESHAPE, "nlimbs must be in [1, L+1]");
+  *out = &c->levels[nlimbs];
   return CKKS_OK;
 }
 
@@ -703,11 +748,6 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   const bool fork = unfused_fp && any_fp && any_int && c->tune[4] == 0;
   hipStream_t sb = st;  // stream of the double-precision chain
   if (fork) {
-    if (!c->side) {
-      HIP_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-      HIP_TRY(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
-      HIP_TRY(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
-    }
     sb = c->side;
     HIP_TRY(hipEventRecord(c->ev_fork, st));
     HIP_TRY(hipStreamWaitEvent(sb, c->ev_fork, 0));
@@ -1142,6 +1182,12 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
   if (!rc) rc = upload(&c->d_tw_inv, inv);
   if (!rc) rc = upload(&c->d_twfp_fwd, fwdfp);
   if (!rc) rc = upload(&c->d_twfp_inv, invfp);
+  if (!rc) rc = build_levels(c);
+  // the second stream and the events of the fork/join inside a key switch (knob 4) exist from the start, so that
+  // no call that enqueues work has to create them
+  if (!rc && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) rc = fail(CKKS_EHIP, "hipStreamCreate");
+  if (!rc && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess) rc = fail(CKKS_EHIP, "hipEventCreate");
+  if (!rc && hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) rc = fail(CKKS_EHIP, "hipEventCreate");
   if (rc) {
     ckks_ctx_destroy(c);
     return rc;
@@ -1166,28 +1212,17 @@ int ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipEventDestroy(r.stop);
   }
   for (auto& e : c->prof_pool) (void)hipEventDestroy(e);
-  for (auto& kv : c->levels) {
-    (void)hipFree(kv.second.up_inv);
-    (void)hipFree(kv.second.up_mat);
-    (void)hipFree(kv.second.dn_inv);
-    (void)hipFree(kv.second.dn_mat);
-    (void)hipFree(kv.second.pinv);
-    (void)hipFree(kv.second.up_scale);
-    (void)hipFree(kv.second.dn_scale);
-    (void)hipFree(kv.second.dn_mat_plain);
-    (void)hipFree(kv.second.pinv2);
-    (void)hipFree(kv.second.rs_one);
-    (void)hipFree(kv.second.rs_mat);
-    (void)hipFree(kv.second.rs_qinv);
-    (void)hipFree(kv.second.rs_qinv16);
-  }
+  (void)hipFree(c->d_levels);
   delete c;
   return CKKS_OK;
 }
 
 int ckks_tune_set(ckks_ctx* c, int knob, int value) {
   if (!c || knob < 0 || knob >= 8) return fail(CKKS_EINVAL, "bad knob");
+  const int old = c->tune[knob];
   c->tune[knob] = value;
+  // knobs 1 and 5 select the arithmetic the level tables are scaled for: rebuild them (waits for the device)
+  if ((knob == 1 || knob == 5) && (old != 0) != (value != 0)) return build_levels(c);
   return CKKS_OK;
 }
 int ckks_prof_enable(ckks_ctx* c, int on) {
