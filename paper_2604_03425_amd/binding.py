@@ -89,10 +89,20 @@ def _check(rc):
         raise CkksError(rc, _lib.ckks_last_error().decode())
 
 
-def _ptr(t, name):
+def _ptr(t, name, ctx=None, elems=None):
+    """Device address of `t`. With ctx/elems: also refuse a tensor on another GPU than the context's or with fewer
+    than `elems` elements, so that a wrong shape raises here instead of becoming an out-of-bounds device access."""
     if not isinstance(t, torch.Tensor) or not t.is_cuda or t.element_size() != 8 or not t.is_contiguous():
         raise TypeError("%s must be a contiguous CUDA tensor with 8-byte elements" % name)
+    if ctx is not None and t.device.index != ctx.device:
+        raise ValueError("%s is on cuda:%d, the context on cuda:%d" % (name, t.device.index, ctx.device))
+    if elems is not None and t.numel() < elems:
+        raise ValueError("%s has %d elements, the call reads or writes %d" % (name, t.numel(), elems))
     return C.c_void_p(t.data_ptr())
+
+
+def _key_elems(ctx):
+    return ctx.params.dnum * 2 * (ctx.nq + ctx.np_) * ctx.N
 
 
 def _stream():
@@ -166,43 +176,52 @@ def ckks_workspace_bytes(ctx, op, batch, nlimbs, n1=0):
 
 def ckks_ntt(ctx, data, npoly, limb_ids):
     ids, n = _ids(limb_ids)
-    _check(_lib.ckks_ntt(ctx.handle, _ptr(data, "data"), npoly, ids, n, _stream()))
+    _check(_lib.ckks_ntt(ctx.handle, _ptr(data, "data", ctx, npoly * len(limb_ids) * ctx.N), npoly, ids, n, _stream()))
 
 
 def ckks_intt(ctx, data, npoly, limb_ids):
     ids, n = _ids(limb_ids)
-    _check(_lib.ckks_intt(ctx.handle, _ptr(data, "data"), npoly, ids, n, _stream()))
+    _check(_lib.ckks_intt(ctx.handle, _ptr(data, "data", ctx, npoly * len(limb_ids) * ctx.N), npoly, ids, n, _stream()))
 
 
 def ckks_automorph(ctx, out, inp, npoly, limb_ids, galois_elt, eval_domain):
     ids, n = _ids(limb_ids)
-    _check(_lib.ckks_automorph(ctx.handle, _ptr(out, "out"), _ptr(inp, "in"), npoly, ids, n, galois_elt,
+    e = npoly * len(limb_ids) * ctx.N
+    _check(_lib.ckks_automorph(ctx.handle, _ptr(out, "out", ctx, e), _ptr(inp, "in", ctx, e), npoly, ids, n, galois_elt,
                                1 if eval_domain else 0, _stream()))
 
 
 def ckks_keyswitch(ctx, ks_out, d, B, nlimbs, evk, galois_elt, dnum, ws):
-    _check(_lib.ckks_keyswitch(ctx.handle, _ptr(ks_out, "ks_out"), _ptr(d, "d"), B, nlimbs, _ptr(evk, "evk"),
-                               galois_elt, dnum, _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    e = B * nlimbs * ctx.N
+    _check(_lib.ckks_keyswitch(ctx.handle, _ptr(ks_out, "ks_out", ctx, 2 * e), _ptr(d, "d", ctx, e), B, nlimbs,
+                               _ptr(evk, "evk", ctx, _key_elems(ctx)), galois_elt, dnum, _ptr(ws, "ws", ctx),
+                               ws.numel() * 8, _stream()))
 
 
 def ckks_hrot(ctx, ct_out, ct_in, B, nlimbs, galois_elt, evk_rot, ws):
-    _check(_lib.ckks_hrot(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, galois_elt,
-                          _ptr(evk_rot, "evk_rot"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_hrot(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e), B, nlimbs, galois_elt,
+                          _ptr(evk_rot, "evk_rot", ctx, _key_elems(ctx)), _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
 
 
 def ckks_hmult_relin(ctx, ct_out, ct_a, ct_b, B, nlimbs, evk_mult, ws):
-    _check(_lib.ckks_hmult_relin(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_a, "ct_a"), _ptr(ct_b, "ct_b"), B, nlimbs,
-                                 _ptr(evk_mult, "evk_mult"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_hmult_relin(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_a, "ct_a", ctx, e),
+                                 _ptr(ct_b, "ct_b", ctx, e), B, nlimbs, _ptr(evk_mult, "evk_mult", ctx, _key_elems(ctx)),
+                                 _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
 
 
 def ckks_tensor_acc(ctx, d_out, ct_a, ct_b, d_acc, B, nlimbs):
-    _check(_lib.ckks_tensor_acc(ctx.handle, _ptr(d_out, "d_out"), _ptr(ct_a, "ct_a"), _ptr(ct_b, "ct_b"),
-                                None if d_acc is None else _ptr(d_acc, "d_acc"), B, nlimbs, _stream()))
+    e = B * nlimbs * ctx.N
+    _check(_lib.ckks_tensor_acc(ctx.handle, _ptr(d_out, "d_out", ctx, 3 * e), _ptr(ct_a, "ct_a", ctx, 2 * e),
+                                _ptr(ct_b, "ct_b", ctx, 2 * e),
+                                None if d_acc is None else _ptr(d_acc, "d_acc", ctx, 3 * e), B, nlimbs, _stream()))
 
 
 def ckks_relin(ctx, ct_out, d_in, B, nlimbs, evk_mult, ws):
-    _check(_lib.ckks_relin(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(d_in, "d_in"), B, nlimbs, _ptr(evk_mult, "evk_mult"),
-                           _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    e = B * nlimbs * ctx.N
+    _check(_lib.ckks_relin(ctx.handle, _ptr(ct_out, "ct_out", ctx, 2 * e), _ptr(d_in, "d_in", ctx, 3 * e), B, nlimbs,
+                           _ptr(evk_mult, "evk_mult", ctx, _key_elems(ctx)), _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
 
 
 def ckks_hrot_hoisted(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
@@ -210,9 +229,10 @@ def ckks_hrot_hoisted(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
     if len(evks) != R:
         raise ValueError("need one key per Galois element")
     gs, _ = _ids(galois_elts)
-    keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk").value for k in evks])
-    _check(_lib.ckks_hrot_hoisted(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys, R,
-                                  _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk", ctx, _key_elems(ctx)).value for k in evks])
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_hrot_hoisted(ctx.handle, _ptr(ct_out, "ct_out", ctx, R * e), _ptr(ct_in, "ct_in", ctx, e), B, nlimbs,
+                                  gs, keys, R, _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
 
 
 def ckks_hrot_sum(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
@@ -220,47 +240,58 @@ def ckks_hrot_sum(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
     if len(evks) != R:
         raise ValueError("need one key per Galois element")
     gs, _ = _ids(galois_elts)
-    keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk").value for k in evks])
-    _check(_lib.ckks_hrot_sum(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys, R,
-                              _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    keys = (C.c_void_p * max(1, R))(*[_ptr(k, "evk", ctx, _key_elems(ctx)).value for k in evks])
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_hrot_sum(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e), B, nlimbs, gs, keys,
+                              R, _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
 
 
 def ckks_hrot_add(ctx, ct_out, ct_in, ct_add, B, nlimbs, galois_elt, evk_rot, ws):
-    _check(_lib.ckks_hrot_add(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), _ptr(ct_add, "ct_add"), B, nlimbs,
-                              galois_elt, _ptr(evk_rot, "evk_rot"), _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_hrot_add(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e),
+                              _ptr(ct_add, "ct_add", ctx, e), B, nlimbs, galois_elt,
+                              _ptr(evk_rot, "evk_rot", ctx, _key_elems(ctx)), _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
 
 
 def ckks_hrot_multi(ctx, ct_out, ct_in, B, nlimbs, galois_elts, evks, ws):
     if len(galois_elts) != B or len(evks) != B:
         raise ValueError("need one Galois element and one key per ciphertext")
     gs, _ = _ids(galois_elts)
-    keys = (C.c_void_p * max(1, B))(*[_ptr(k, "evk").value for k in evks])
-    _check(_lib.ckks_hrot_multi(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, gs, keys,
-                                _ptr(ws, "ws"), ws.numel() * 8, _stream()))
+    keys = (C.c_void_p * max(1, B))(*[_ptr(k, "evk", ctx, _key_elems(ctx)).value for k in evks])
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_hrot_multi(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e), B, nlimbs, gs, keys,
+                                _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
 
 
 def ckks_pcmm_bsgs(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws, hoisted=False):
-    baby = (C.c_void_p * max(1, n1 - 1))(*[_ptr(k, "evk_baby").value for k in evk_baby])
-    giant = (C.c_void_p * max(1, n2 - 1))(*[_ptr(k, "evk_giant").value for k in evk_giant])
+    baby = (C.c_void_p * max(1, n1 - 1))(*[_ptr(k, "evk_baby", ctx, _key_elems(ctx)).value for k in evk_baby])
+    giant = (C.c_void_p * max(1, n2 - 1))(*[_ptr(k, "evk_giant", ctx, _key_elems(ctx)).value for k in evk_giant])
     if len(evk_baby) != n1 - 1 or len(evk_giant) != n2 - 1:
         raise ValueError("need n1-1 baby-step keys and n2-1 giant-step keys")
     fn = {False: _lib.ckks_pcmm_bsgs, True: _lib.ckks_pcmm_bsgs_hoisted, "double": _lib.ckks_pcmm_bsgs_double_hoisted}[hoisted]
-    _check(fn(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs,
-                               _ptr(pt_diag, "pt_diag"), n1, n2, stride, baby, giant, _ptr(ws, "ws"), ws.numel() * 8,
-                               _stream()))
+    e = B * 2 * nlimbs * ctx.N
+    pt_limbs = nlimbs + ctx.np_ if hoisted == "double" else nlimbs   # the extended-basis schedule takes extended plaintexts
+    _check(fn(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e), B, nlimbs,
+              _ptr(pt_diag, "pt_diag", ctx, n1 * n2 * pt_limbs * ctx.N), n1, n2, stride, baby, giant, _ptr(ws, "ws", ctx),
+              ws.numel() * 8, _stream()))
 
 
 def ckks_rescale(ctx, ct_out, ct_in, B, nlimbs, ws):
-    _check(_lib.ckks_rescale(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), B, nlimbs, _ptr(ws, "ws"),
+    _check(_lib.ckks_rescale(ctx.handle, _ptr(ct_out, "ct_out", ctx, B * 2 * (nlimbs - 1) * ctx.N),
+                             _ptr(ct_in, "ct_in", ctx, B * 2 * nlimbs * ctx.N), B, nlimbs, _ptr(ws, "ws", ctx),
                              ws.numel() * 8, _stream()))
 
 
 def ckks_pmult(ctx, ct_out, ct_in, pt, B, nlimbs):
-    _check(_lib.ckks_pmult(ctx.handle, _ptr(ct_out, "ct_out"), _ptr(ct_in, "ct_in"), _ptr(pt, "pt"), B, nlimbs, _stream()))
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_pmult(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e),
+                           _ptr(pt, "pt", ctx, nlimbs * ctx.N), B, nlimbs, _stream()))
 
 
 def ckks_add(ctx, out, a, b, npoly, nlimbs):
-    _check(_lib.ckks_add(ctx.handle, _ptr(out, "out"), _ptr(a, "a"), _ptr(b, "b"), npoly, nlimbs, _stream()))
+    e = npoly * nlimbs * ctx.N
+    _check(_lib.ckks_add(ctx.handle, _ptr(out, "out", ctx, e), _ptr(a, "a", ctx, e), _ptr(b, "b", ctx, e), npoly, nlimbs,
+                         _stream()))
 
 
 def ckks_pcmm_bsgs_hoisted(ctx, ct_out, ct_in, B, nlimbs, pt_diag, n1, n2, stride, evk_baby, evk_giant, ws):

@@ -8,8 +8,8 @@
 #include <string>
 #include <vector>
 
-#include "kernels.cuh"
-#include "ntt16_kernels.cuh"
+#include "kernels.hip.h"
+#include "ntt16_kernels.hip.h"
 
 typedef unsigned __int128 u128;
 

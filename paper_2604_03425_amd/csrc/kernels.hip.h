@@ -1,6 +1,6 @@
 // Device kernels of the RNS-CKKS hot path (gfx950, wave64).
 #pragma once
-#include "modarith.cuh"
+#include "modarith.hip.h"
 
 #define CKKS_MAX_SLOTS 128   // limb slots addressable by one launch (L+1+K <= 128)
 #define NTT_THREADS 256

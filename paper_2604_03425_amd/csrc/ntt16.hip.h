@@ -9,7 +9,7 @@
 // butterflies let sums double for the 8 stages of a pass (inputs < 2q -> < 512q). BIG primes (q < 2^61)
 // use Harvey's butterflies with values kept in [0,4q) (forward) / [0,2q) (inverse).
 #pragma once
-#include "modarith.cuh"
+#include "modarith.hip.h"
 
 #define NTT16_THREADS 256
 #define NTT16_LDS_BYTES (16 * 272 * 8)

@@ -4,8 +4,8 @@
 // format of the data between the two passes of a transform (reduced doubles / lazy integers) and of the
 // constants passed in 16-byte slots (double2 / Shoup pair).
 #pragma once
-#include "ntt16.cuh"
-#include "ntt16fp.cuh"
+#include "ntt16.hip.h"
+#include "ntt16fp.hip.h"
 
 // ---- standalone passes: grid = (polynomials, 16 tiles, limb slots) ----
 // A batched rotation may give every ciphertext its own Galois element and key: the kernels then take both from

@@ -1,4 +1,4 @@
-// Double-precision variants of the N = 2^16 pass bodies of ntt16.cuh, for primes q < 2^50.
+// Double-precision variants of the N = 2^16 pass bodies of ntt16.hip.h, for primes q < 2^50.
 // On gfx950 the vector FP64 units run at full rate, and a modular multiply by a constant is 6 FP64
 // instructions (against ~23 integer instructions for the 64-bit Shoup form), exact because every value is an
 // integer below 2^53. Same tiles, lane layouts and LDS transposes as the integer bodies.
@@ -9,7 +9,7 @@
 // sums, so they are brought back after every two stages. Between the two passes of a transform the data lives in
 // global memory as reduced doubles.
 #pragma once
-#include "ntt16.cuh"
+#include "ntt16.hip.h"
 
 template <class TW>
 __device__ __forceinline__ void radix16_fwd_fp(double (&x)[16], double q, double qinv, TW tw) {
