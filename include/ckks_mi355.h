@@ -134,6 +134,22 @@ int ckks_hrot(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B
               uint32_t galois_elt, const uint64_t* evk_rot, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * HRot for callers that cannot allocate device memory: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. Same operation, arguments, overlap rules and result as ckks_hrot, but without a
+ * workspace argument: the kernels use a fixed array of ckks_noalloc_scratch_bytes() bytes (128 MiB) that lives in
+ * the library's device image, one copy per GPU, held until the process ends. The call makes no hipMalloc/hipFree
+ * and calls no allocating library routine. A batch whose CKKS_OP_HROT workspace would exceed the array is rejected
+ * with CKKS_EWORKSPACE (at N = 2^16, 24 limbs, K = 8, dnum = 3 exactly one ciphertext fits); so is a call while
+ * per-kernel timing is enabled (CKKS_EINVAL), because timing creates events. All calls on one GPU share that GPU's
+ * array, from every context and every stream: calls that may overlap in time on one GPU race on it, so keep them on
+ * one stream or order them with events. Nothing in the array has to be cleared between calls (each region is written
+ * before it is read within a call); its contents after a call are unspecified.
+ */
+size_t ckks_noalloc_scratch_bytes(void);
+int ckks_hrot_noalloc(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
+                      uint32_t galois_elt, const uint64_t* evk_rot, void* stream);
+
+/*
  * Rotate-and-add (the step of the rotate-and-sum reductions and of the rotate-multiply-accumulate loops of the
  * attention and linear layers, paper Sec. 4.2-4.3): ct_out = ct_add + HRot_{galois_elt}(ct_in), with the addition
  * done where the rotation's result is assembled instead of in a pass of its own. ct_add is a device ciphertext

@@ -18,7 +18,8 @@ _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_work
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
             "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
             "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi", "ckks_hrot_add", "ckks_tensor_acc",
-            "ckks_relin", "ckks_pcmm_bsgs_double_hoisted", "ckks_hrot_sum"]
+            "ckks_relin", "ckks_pcmm_bsgs_double_hoisted", "ckks_hrot_sum", "ckks_hrot_noalloc",
+            "ckks_noalloc_scratch_bytes"]
 
 
 class CkksError(RuntimeError):
@@ -53,6 +54,9 @@ def _load():
     lib.ckks_keyswitch.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, C.c_uint32, C.c_uint32, vp,
                                    C.c_size_t, vp]
     lib.ckks_hrot.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
+    lib.ckks_hrot_noalloc.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, C.c_uint32, u64p, vp]
+    lib.ckks_noalloc_scratch_bytes.restype = C.c_size_t
+    lib.ckks_noalloc_scratch_bytes.argtypes = []
     lib.ckks_hmult_relin.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
     lib.ckks_tensor_acc.argtypes = [vp, u64p, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
     lib.ckks_relin.argtypes = [vp, u64p, u64p, C.c_uint32, C.c_uint32, u64p, vp, C.c_size_t, vp]
@@ -202,6 +206,16 @@ def ckks_hrot(ctx, ct_out, ct_in, B, nlimbs, galois_elt, evk_rot, ws):
     e = B * 2 * nlimbs * ctx.N
     _check(_lib.ckks_hrot(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e), B, nlimbs, galois_elt,
                           _ptr(evk_rot, "evk_rot", ctx, _key_elems(ctx)), _ptr(ws, "ws", ctx), ws.numel() * 8, _stream()))
+
+
+def ckks_noalloc_scratch_bytes():
+    return int(_lib.ckks_noalloc_scratch_bytes())
+
+
+def ckks_hrot_noalloc(ctx, ct_out, ct_in, B, nlimbs, galois_elt, evk_rot):
+    e = B * 2 * nlimbs * ctx.N
+    _check(_lib.ckks_hrot_noalloc(ctx.handle, _ptr(ct_out, "ct_out", ctx, e), _ptr(ct_in, "ct_in", ctx, e), B, nlimbs,
+                                  galois_elt, _ptr(evk_rot, "evk_rot", ctx, _key_elems(ctx)), _stream()))
 
 
 def ckks_hmult_relin(ctx, ct_out, ct_a, ct_b, B, nlimbs, evk_mult, ws):

@@ -13,6 +13,12 @@
 
 typedef unsigned __int128 u128;
 
+// Workspace of ckks_hrot_noalloc, the entry point for callers that cannot allocate: a fixed array in the library's
+// own device image (one copy per GPU, held until the process ends). Host code never passes the array's name to a
+// kernel or a copy: it uses the per-device address that hipGetSymbolAddress returns (ckks_ctx::scratch_ptr).
+#define CKKS_NOALLOC_SCRATCH_BYTES (128ull << 20)
+static __device__ __align__(256) unsigned char scratch[CKKS_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_err;
@@ -169,6 +175,7 @@ struct ckks_ctx {
   // or 5 changes): levels[nlimbs] points into one device allocation, d_levels.
   std::vector<LevelTables> levels;
   char* d_levels = nullptr;
+  void* scratch_ptr = nullptr;  // this device's address of `scratch` (hipGetSymbolAddress at context creation)
 };
 
 namespace {
@@ -1183,6 +1190,12 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
   if (!rc) rc = upload(&c->d_twfp_fwd, fwdfp);
   if (!rc) rc = upload(&c->d_twfp_inv, invfp);
   if (!rc) rc = build_levels(c);
+  if (!rc) {
+    // device current = the context's: every GPU holds its own copy of the array at its own address
+    hipError_t e = hipGetSymbolAddress(&c->scratch_ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !c->scratch_ptr)
+      rc = fail(CKKS_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+  }
   // the second stream and the events of the fork/join inside a key switch (knob 4) exist from the start, so that
   // no call that enqueues work has to create them
   if (!rc && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) rc = fail(CKKS_EHIP, "hipStreamCreate");
@@ -1397,6 +1410,24 @@ static int hrot_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
     HIP_TRY(hipGetLastError());
   }
   return CKKS_OK;
+}
+
+size_t ckks_noalloc_scratch_bytes(void) { return (size_t)CKKS_NOALLOC_SCRATCH_BYTES; }
+
+// ckks_hrot with the library's fixed scratch array as its workspace: no hipMalloc/hipFree here or below (the level
+// tables, the second stream and its events exist since ckks_ctx_create). Every region of the workspace is written
+// by a kernel of the call before a later kernel reads it, so nothing has to be cleared between calls.
+int ckks_hrot_noalloc(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs, uint32_t g,
+                      const uint64_t* evk, void* stream) {
+  int rc = check_common(c, B, nlimbs);
+  if (rc) return rc;
+  if (c->prof_on) return fail(CKKS_EINVAL, "ckks_hrot_noalloc: per-kernel timing creates events; disable it first");
+  const size_t need = ckks_workspace_bytes(c, CKKS_OP_HROT, B, nlimbs, 0);
+  if (need == 0 || need > (size_t)CKKS_NOALLOC_SCRATCH_BYTES)
+    return fail(CKKS_EWORKSPACE, "ckks_hrot_noalloc: this batch needs " + std::to_string(need) +
+                                     " bytes of workspace, the fixed scratch array holds " +
+                                     std::to_string((size_t)CKKS_NOALLOC_SCRATCH_BYTES));
+  return hrot_impl(c, ct_out, ct_in, B, nlimbs, g, evk, c->scratch_ptr, (size_t)CKKS_NOALLOC_SCRATCH_BYTES, stream, nullptr);
 }
 
 int ckks_hrot_add(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, const uint64_t* ct_add, uint32_t B, uint32_t nlimbs,
