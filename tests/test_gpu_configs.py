@@ -82,6 +82,48 @@ def test_pcmm_full_ring_small_bsgs(gpu):
     assert_same(to_host(out), want, "pcmm N=2^16")
 
 
+@pytest.mark.timeout(600)
+def test_pcmm_ffn_share_real_shape_against_oracle_digests(gpu):
+    """The FFN-layer workload at its real shape: N=2^16, 24 limbs, dnum=3, 32 baby x 24 giant steps, a batch of 8.
+    SHA-256 of every output ciphertext equals the digest the oracle wrote (tests/golden/pcmm_ffn_digests.txt, made
+    by make_pcmm_ffn_digests.py from the same seeded inputs), for the one-rotation-at-a-time schedule and for the
+    hoisted one, which is bit-identical by definition. This is the shape at which the N=2^16 schedule runs whole
+    tiles of 24 giant steps (6-giant-step launches of the double-precision inner sums, 3-giant-step integer ones),
+    accumulates the giant steps in place, and packs the hoisted baby steps' accumulators into the inner-sum region."""
+    import hashlib
+    import importlib.util
+    import os
+    import torch
+    from gpu_util import to_dev, to_host
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("_pcmm_ffn_inputs", os.path.join(here, "golden", "make_pcmm_ffn_digests.py"))
+    mk = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mk)
+    want = {}
+    with open(os.path.join(here, "golden", "pcmm_ffn_digests.txt")) as f:
+        for line in f:
+            if line.startswith("pcmm "):
+                _, b, h = line.split()
+                want[int(b)] = h
+    B, n1, n2, nl = mk.B, mk.N1, mk.N2, 24
+    assert sorted(want) == list(range(B))
+    p = config_params("keyswitch_micro")
+    gc = gpu.Context(p)
+    ct, pt, baby, giant = mk.inputs(p)
+    d_ct, d_pt = to_dev(ct), to_dev(pt)
+    del pt
+    d_baby, d_giant = [to_dev(k) for k in baby], [to_dev(k) for k in giant]
+    del baby, giant
+    ws = gc.workspace(gpu.OP_PCMM_BSGS, B, nl, n1)
+    for name, fn in (("plain", gpu.ckks_pcmm_bsgs), ("hoisted", gpu.ckks_pcmm_bsgs_hoisted)):
+        out = torch.zeros((B, 2, nl, p.N), dtype=torch.int64, device="cuda")
+        fn(gc, out, d_ct, B, nl, d_pt, n1, n2, 1, d_baby, d_giant, ws)
+        got = to_host(out)
+        bad = [b for b in range(B) if hashlib.sha256(np.ascontiguousarray(got[b]).tobytes()).hexdigest() != want[b]]
+        assert not bad, "%s schedule: ciphertexts %s differ from the oracle's digests" % (name, bad)
+    gc.close()
+
+
 def test_attention_unit_full_ring(gpu):
     """N=2^16, 20 limbs, dnum=4, 5 special primes: one QK^T unit = HMult+relin, then rotate-and-sum by
     1,2,4,...,32 (six HRot + add steps)."""
