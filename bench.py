@@ -51,7 +51,7 @@ MEASURED_TRAFFIC = {
 }
 
 
-def keyswitch_model(p, B, nl, hrot, hmult, fp_inner=2, int_inner=2):
+def keyswitch_model(p, B, nl, hrot, hmult, fp_inner=2, bconv_fused=False):
     """Algorithmic bytes and lane-ops per kernel kind for ONE key-switch call on a batch of B (N = 2^16 path:
     double-precision bodies on primes < 2^50, with their inner product as a separate streaming kernel)."""
     N, K, alpha = p.N, len(p.p), p.alpha
@@ -81,29 +81,46 @@ def keyswitch_model(p, B, nl, hrot, hmult, fp_inner=2, int_inner=2):
     put("ntt16_inv_blocks_kernel", 2, inv_int * 2 * limb, inv_int * bf_pass)
     put("ntt16_inv_rows_kernel", 0, inv_fp * 2 * limb, inv_fp * (bf_pass_fp + N * OPS_SHOUP_FP))
     put("ntt16_inv_rows_kernel", 2, inv_int * 2 * limb, inv_int * (bf_pass + N * OPS_SHOUP))
-    # base conversion, as executed: 4 multiply-adds per term on 30-bit halves + a 27-instruction reduction per output
-    put("modup_kernel", None, B * (nl + new_limbs) * limb,
-        B * N * sum((nxt - len(dg)) * ((len(dg) + 1) * OPS_DOT30 + OPS_REDUCE90) for dg in digits))
-    rows_fp, rows_int = B * (new_fp + 2 * own_fp), B * (new_int + 2 * own_int)
-    put("ntt16_fwd_rows_kernel", 0, rows_fp * 2 * limb, rows_fp * bf_pass_fp)
-    put("ntt16_fwd_rows_kernel", 2, rows_int * 2 * limb, rows_int * bf_pass)
-    if fp_inner == 2:
-        # default on double-precision moduli: block pass fused with one key component per workgroup; every converted
-        # tile is transformed by both workgroups of its ciphertext (twice in ops, once in bytes: the second read is
-        # served by L2)
-        put("ntt16_fwd_blocks_inner_c_kernel", None, (B * (new_fp + own_fp + 2 * n_fp) + 2 * beta * n_fp) * limb,
-            B * (2 * new_fp * bf_pass_fp + N * n_fp * beta * 2 * OPS_MULRED_FP))
+    fp_main = [t for t in range(nl) if fp[t]]
+    fp_t, int_t = [t for t in range(nxt) if fp[t]], [t for t in range(nxt) if not fp[t]]
+    dn_fp, dn_int = 2 * own_fp, 2 * own_int     # ModDown targets per ciphertext
+    if not bconv_fused:
+        # base conversion, as executed: 4 multiply-adds per term on 30-bit halves + a 27-instruction reduction per output
+        put("modup_kernel", None, B * (nl + new_limbs) * limb,
+            B * N * sum((nxt - len(dg)) * ((len(dg) + 1) * OPS_DOT30 + OPS_REDUCE90) for dg in digits))
+        put("moddown_kernel", None, 2 * B * (K + nl) * limb, 2 * B * N * nl * ((K + 1) * OPS_DOT30 + OPS_REDUCE90))
+        rows_fp, rows_int = B * (new_fp + dn_fp), B * (new_int + dn_int)
+        put("ntt16_fwd_rows_kernel", 0, rows_fp * 2 * limb, rows_fp * bf_pass_fp)
+        put("ntt16_fwd_rows_kernel", 2, rows_int * 2 * limb, rows_int * bf_pass)
     else:
-        # plain block pass followed by the streaming product
+        # Knob 2 = 1: base conversion inside the first forward pass: 4 multiply-adds per term and a 27-instruction
+        # reduction per output, then 8 butterfly stages. HBM bytes if every source tile is fetched once per
+        # (polynomial, tile) group and the other targets of the group find it in L2.
+        up_ops = lambda targets: sum(sum(1 for t in targets if t not in dg) * (len(dg) * OPS_DOT30 + OPS_REDUCE90) for dg in digits)
+        dn_term = K * OPS_DOT30 + OPS_REDUCE90
+        put("ntt16_bconv_rows_kernel", 0, B * ((nl if new_fp else 0) + new_fp + (2 * K if dn_fp else 0) + dn_fp) * limb,
+            B * (N * (up_ops(fp_t) + dn_fp * dn_term) + (new_fp + dn_fp) * bf_pass_fp))
+        put("ntt16_bconv_rows_kernel", 2, B * ((nl if new_int else 0) + new_int + (2 * K if dn_int else 0) + dn_int) * limb,
+            B * (N * (up_ops(int_t) + dn_int * dn_term) + (new_int + dn_int) * bf_pass))
+    addend = 1 if hrot else 2 if hmult else 0
+    if fp_inner != 1:
+        # default on double-precision main limbs: block pass of the digits fused with one key component per workgroup
+        # (every converted tile is transformed by both workgroups of its ciphertext: twice in ops, once in bytes, the
+        # second read being served by L2), then the block pass of the ModDown correction, the division by P and the
+        # addends in the same kernel. Special limbs below 2^50 (none in the benchmark) keep the store of the sums.
+        put("ntt16_fwd_blocks_inner_c_kernel", None,
+            (B * (new_fp + own_fp + 2 * kfp + (2 + addend + 2) * own_fp) + 2 * beta * n_fp) * limb,
+            B * (2 * new_fp * bf_pass_fp + N * n_fp * beta * 2 * OPS_MULRED_FP) +
+            2 * B * own_fp * (bf_pass_fp + N * (OPS_SHOUP_FP + 2)))
+    else:
+        # plain block pass, streaming product and a separate assembly kernel
         put("ntt16_fwd_blocks_kernel", 0, B * new_fp * 2 * limb, B * new_fp * bf_pass_fp)
         put("inner16_fp_kernel", None, (B * (new_fp + own_fp + 2 * n_fp) + 2 * beta * n_fp) * limb,
             B * N * n_fp * beta * 2 * OPS_MULRED_FP)
-    put("ntt16_fwd_blocks_inner8_kernel" if int_inner == 2 else "ntt16_fwd_blocks_inner_kernel", 2, (B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
+        put("ntt16_fwd_blocks_final_kernel", 0, B * own_fp * (6 + addend) * limb,
+            2 * B * own_fp * (bf_pass_fp + N * (OPS_SHOUP_FP + 2)))
+    put("ntt16_fwd_blocks_inner8_kernel", 2, (B * (new_int + own_int + 2 * n_int) + 2 * beta * n_int) * limb,
         B * (new_int * bf_pass + N * n_int * beta * 2 * mul_redc))
-    put("moddown_kernel", None, 2 * B * (K + nl) * limb, 2 * B * N * nl * ((K + 1) * OPS_DOT30 + OPS_REDUCE90))
-    addend = 1 if hrot else 2 if hmult else 0
-    put("ntt16_fwd_blocks_final_kernel", 0, B * own_fp * (6 + addend) * limb,
-        2 * B * own_fp * (bf_pass_fp + N * (OPS_SHOUP_FP + 2)))
     put("ntt16_fwd_blocks_final_kernel", 2, B * own_int * (6 + addend) * limb,
         2 * B * own_int * (bf_pass + N * (OPS_SHOUP + 2 * OPS_ADD)))
     if hmult:
@@ -367,6 +384,8 @@ def main():
     ap.add_argument("--int-only", action="store_true", help="experiment: integer bodies for every modulus")
     ap.add_argument("--tune", type=str, default="", help="experiment: comma-separated knob=value pairs")
     ap.add_argument("--streams", type=int, default=1, help="HIP streams the independent calls of a step are spread over")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="experiment: time the steps without the per-kernel HIP events (no phases, no roofline)")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate NTT / HRot / HMult timings (profiling runs)")
     ap.add_argument("--workload", default="keyswitch_micro", choices=["keyswitch_micro", "pcmm", "attention", "attention_av", "sweep"])
     ap.add_argument("--pcmm-batch", type=int, default=32)
@@ -401,14 +420,14 @@ def main():
         ck.ckks_tune_set(ctx, 0, args.map_mode)
     if args.int_only:
         ck.ckks_tune_set(ctx, 1, 1)
-    fp_inner, int_inner = 2, 2   # library defaults of knobs 3 and 2
+    fp_inner, bconv_fused = 2, False   # library defaults of knobs 3 and 2
     for kv in filter(None, args.tune.split(",")):
         k, v = kv.split("=")
         ck.ckks_tune_set(ctx, int(k), int(v))
         if int(k) == 3:
             fp_inner = int(v)
         if int(k) == 2:
-            int_inner = int(v)
+            bconv_fused = int(v) == 1
     gen = torch.Generator(device=dev).manual_seed(0xC0FFEE)
 
     def uniform(prefix, moduli):
@@ -457,7 +476,7 @@ def main():
         step()
     torch.cuda.synchronize()
     ck.ckks_prof_reset(ctx)
-    ck.ckks_prof_enable(ctx, True)
+    ck.ckks_prof_enable(ctx, not args.no_kernel_events)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -473,7 +492,7 @@ def main():
     # --- per-kind roofline figures from the event durations of the timed region ---
     model = {}
     for (b, hrot, hmult, calls) in ((Bg, True, False, G), (B // 2, False, True, 1)):
-        for kind, v in keyswitch_model(p, b, nl, hrot, hmult, fp_inner, int_inner).items():
+        for kind, v in keyswitch_model(p, b, nl, hrot, hmult, fp_inner, bconv_fused).items():
             acc = model.setdefault(kind, dict(bytes=0.0, ops=0.0))
             acc["bytes"] += v["bytes"] * calls
             acc["ops"] += v["ops"] * calls
@@ -487,11 +506,13 @@ def main():
                             Tops=round(mdl["ops"] / per_step_ms / 1e9, 2) if per_step_ms else None)
     # the counter runs were made in the default configuration only
     default_cfg = (G == 64 and multi and not args.tune and not args.int_only and args.map_mode is None and nstreams == 1)
-    dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
-    d = phases[dom]
+    dom = max(prof.items(), key=lambda kv: kv[1][0])[0] if prof else None
+    d = phases[dom] if dom else dict(GBps=None, Tops=None, avg_launch_us=None)
     hbm_frac = (d["GBps"] or 0) / PEAK_HBM_GBS
     alu_frac = (d["Tops"] or 0) / PEAK_ALU_TOPS
-    if alu_frac >= hbm_frac:
+    if dom is None:
+        roofline = None
+    elif alu_frac >= hbm_frac:
         roofline = dict(bound="alu", kernel=dom, achieved=d["Tops"], peak=round(PEAK_ALU_TOPS, 1), unit="Tlane-op/s",
                         frac=round(alu_frac, 4), traffic=MEASURED_TRAFFIC.get(dom) if default_cfg else None, avg_launch_us=d["avg_launch_us"])
     else:

@@ -113,6 +113,9 @@ struct LevelTables {
   ulonglong2* up_scale = nullptr;  // [nlimbs]  (Q_j/q_i)^-1 / N mod q_i
   ulonglong2* dn_scale = nullptr;  // [K]       2^64 (P/p_k)^-1 / N mod p_k
   u64* dn_mat_plain = nullptr;     // dn_mat without the Montgomery factor
+  u64* up_off = nullptr;           // [beta][next] -sum_i ((q_i-1)/2) (Q_j/q_i) mod m_t, scaled like up_mat
+  u64* dn_off = nullptr;           // [nlimbs]     -sum_k ((p_k-1)/2) (P/p_k) mod q_i, scaled like dn_mat_plain
+  u32 up_pitch = 0, dn_pitch = 0;  // constants per target in up_mat / dn_mat_plain
   ulonglong2* pinv2 = nullptr;     // [nlimbs]  2^64 / P mod q_i
   // rescale from this limb count: drop q_{nlimbs-1}
   ulonglong2* rs_one = nullptr;    // [1]          Shoup pair of 1 (the single source needs no pre-scaling)
@@ -128,7 +131,7 @@ enum ProfKind {
   // N = 2^16 kernels: three consecutive kinds each, one per modulus class (the kernel's template argument)
   PK_FWD_ROWS, PK_FWD_BLOCKS = PK_FWD_ROWS + 3, PK_INV_BLOCKS = PK_FWD_BLOCKS + 3, PK_INV_ROWS = PK_INV_BLOCKS + 3,
   PK_FWD_INNER = PK_INV_ROWS + 3, PK_FWD_FINAL = PK_FWD_INNER + 3,
-  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_INNER2, PK_INNER8, PK_INNER8_BIG, PK_MODDOWN, PK_FINAL, PK_TENSOR, PK_PMACC, PK_PMACC_FP, PK_ADD,
+  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_INNER2, PK_INNER8, PK_INNER8_BIG, PK_BCONV_ROWS, PK_MODDOWN = PK_BCONV_ROWS + 3, PK_FINAL, PK_TENSOR, PK_PMACC, PK_PMACC_FP, PK_ADD,
   PK_COPY, PK_COUNT
 };
 static const char* const kProfNames[PK_COUNT] = {
@@ -139,7 +142,8 @@ static const char* const kProfNames[PK_COUNT] = {
     "ntt16_inv_rows_kernel<0>", "ntt16_inv_rows_kernel<1>", "ntt16_inv_rows_kernel<2>",
     "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
     "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
-    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "ntt16_fwd_blocks_inner2_kernel", "ntt16_fwd_blocks_inner8_kernel<1>", "ntt16_fwd_blocks_inner8_kernel<2>", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
+    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "ntt16_fwd_blocks_inner2_kernel", "ntt16_fwd_blocks_inner8_kernel<1>", "ntt16_fwd_blocks_inner8_kernel<2>",
+    "ntt16_bconv_rows_kernel<0>", "ntt16_bconv_rows_kernel<1>", "ntt16_bconv_rows_kernel<2>", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
     "pmacc_int_kernel", "pmacc_fp_kernel", "addto_kernel", "copy"};
 struct ProfRec {
   int kind;
@@ -266,7 +270,9 @@ LevelTables build_level(const ckks_ctx* c, u32 nlimbs, LevelArena& arena) {
   auto mont_dn = [&](u64 v, u64 m) { return t.narrow_dn ? h_mont90(v, m) : h_mont(v, m); };
   auto mont_rs = [&](u64 v, u64 m) { return t.narrow_rs ? h_mont90(v, m) : h_mont(v, m); };
   std::vector<ulonglong2> up_inv((size_t)t.beta * alpha, ulonglong2{0, 0});
-  std::vector<u64> up_mat((size_t)t.beta * next * (R + 1), 0);
+  std::vector<u64> up_mat((size_t)t.beta * next * (R + 1), 0), up_off((size_t)t.beta * next, 0);
+  t.up_pitch = R + 1;
+  t.dn_pitch = RK + 1;
   for (u32 j = 0; j < t.beta; j++) {
     u32 lo = j * alpha, hi = std::min(lo + alpha, nlimbs);
     for (u32 i = lo; i < hi; i++) {
@@ -286,6 +292,15 @@ LevelTables build_level(const ckks_ctx* c, u32 nlimbs, LevelArena& arena) {
       u64 m = ext_mod(s), v = 1;
       for (u32 k = lo; k < hi; k++) v = h_mul(v, c->mod[k] % m, m);
       up_mat[((size_t)j * next + s) * (R + 1) + R] = mont_up(v ? m - v : 0, m);
+      // offset of the shifted-residue form: -sum_i h_i (Q_j/q_i), h_i = (q_i - 1) / 2
+      u64 sum = 0;
+      for (u32 i = lo; i < hi; i++) {
+        u64 w = 1;
+        for (u32 k = lo; k < hi; k++)
+          if (k != i) w = h_mul(w, c->mod[k] % m, m);
+        sum = (u64)(((u128)sum + h_mul(w, ((c->mod[i] - 1) / 2) % m, m)) % m);
+      }
+      up_off[(size_t)j * next + s] = mont_up(sum ? m - sum : 0, m);
     }
   }
   std::vector<ulonglong2> dn_inv(K), pinv(nlimbs);
@@ -314,7 +329,7 @@ LevelTables build_level(const ckks_ctx* c, u32 nlimbs, LevelArena& arena) {
   // (c, c/q) (double-precision class). Integer-class accumulators carry a factor 2^-64 (Montgomery products), which
   // dn_scale and pinv2 undo; double-precision accumulators are plain.
   std::vector<ulonglong2> up_scale(nlimbs), dn_scale(K), pinv2(nlimbs);
-  std::vector<u64> dn_mat_plain(dn_mat.size(), 0);
+  std::vector<u64> dn_mat_plain(dn_mat.size(), 0), dn_off(nlimbs, 0);
   auto as_fp = [](u64 v, u64 m) {
     double2 d{(double)v, (double)v / (double)m};
     ulonglong2 r;
@@ -325,6 +340,17 @@ LevelTables build_level(const ckks_ctx* c, u32 nlimbs, LevelArena& arena) {
     u64 m = c->mod[i], ninv = h_inv(c->N % m, m);
     u64 v = h_mul(up_inv[(size_t)(i / alpha) * alpha + (i % alpha)].x, ninv, m);
     u64 r64_inv = h_inv(h_mont(1, m), m);
+    {
+      u64 sum = 0;   // -sum_k h_k (P/p_k) mod m, then scaled like the row of constants below
+      for (u32 k = 0; k < K; k++) {
+        u64 w = 1;
+        for (u32 r = 0; r < K; r++)
+          if (r != k) w = h_mul(w, c->mod[c->nq + r] % m, m);
+        sum = (u64)(((u128)sum + h_mul(w, ((c->mod[c->nq + k] - 1) / 2) % m, m)) % m);
+      }
+      const u64 neg = mont_dn(sum ? m - sum : 0, m);
+      dn_off[i] = is_fp(m) ? neg : h_mul(neg, r64_inv, m);
+    }
     if (is_fp(m)) {
       up_scale[i] = as_fp(v, m);
       pinv2[i] = as_fp(pinv[i].x, m);
@@ -369,6 +395,8 @@ LevelTables build_level(const ckks_ctx* c, u32 nlimbs, LevelArena& arena) {
   t.up_scale = arena.add(up_scale);
   t.dn_scale = arena.add(dn_scale);
   t.dn_mat_plain = arena.add(dn_mat_plain);
+  t.up_off = arena.add(up_off);
+  t.dn_off = arena.add(dn_off);
   t.pinv2 = arena.add(pinv2);
   t.up_inv = arena.add(up_inv);
   t.up_mat = arena.add(up_mat);
@@ -398,6 +426,7 @@ int build_levels(ckks_ctx* c) {
     LevelTables& t = lv[nl];
     rebase(t.up_inv); rebase(t.up_mat); rebase(t.dn_inv); rebase(t.dn_mat); rebase(t.pinv);
     rebase(t.up_scale); rebase(t.dn_scale); rebase(t.dn_mat_plain); rebase(t.pinv2);
+    rebase(t.up_off); rebase(t.dn_off);
     rebase(t.rs_one); rebase(t.rs_mat); rebase(t.rs_qinv); rebase(t.rs_qinv16);
   }
   if (c->d_levels) {
@@ -463,6 +492,7 @@ struct NttOpts {
   u32 galois = 0;                     // N = 2^16 inverse only: read src through the eval-domain Galois map
   const u32* galois_pc = nullptr;     // same, one element per polynomial (host array, npoly <= KS_MULTI_MAX entries)
   const ulonglong2* scale = nullptr;  // N = 2^16 inverse only: per-slot constants (from slot0) replacing N^-1
+  bool split_out = false;             // N = 2^16 inverse only: write the shifted, split form the fused base conversion reads
   bool rows_only = false;             // N = 2^16 forward only: stop after the row pass (a fused kernel does the rest)
   bool blocks_only = false;           // N = 2^16 forward only: only the block pass, in place on dst
   bool raw_out = false;               // with blocks_only: leave reduced doubles on double-precision moduli
@@ -496,6 +526,7 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     }
     a.scale = opt.scale;
     a.raw_out = opt.raw_out ? 1 : 0;
+    a.split_out = opt.split_out ? 1 : 0;
     Ntt16Args b = a;  // second pass: in place on dst
     b.src = a.dst;
     b.src_poly_stride = dst_stride;
@@ -652,70 +683,136 @@ struct KsIo {
   bool add2_three = false;     // add2 is [B][3][nlimbs][N]; its first two components are the addends
 };
 
-// Second half of a key switch on the N = 2^16 path: from the accumulators (acc, all slots) to the assembled output.
-// wait_before_assembly: event the stream must wait for before the last kernel reads the main-prime accumulators.
-int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, char* ws, hipStream_t st,
-                hipEvent_t wait_before_assembly, u64* acc_in = nullptr) {
-  int rc;
-  const u32 N = c->N, next = lt->next, K = c->np;
-  KsLayout L = ks_layout(c, B, nlimbs);
-  // acc_in: accumulators held outside the workspace ([B][2][next][N]; their special-prime slots are overwritten)
-  u64* acc = acc_in ? acc_in : (u64*)(ws + L.acc);
-  u64* tq = (u64*)(ws + L.tq);
-  const LimbMap qmap = identity_map(nlimbs);
-  NttOpts o2;
-  o2.rows_only = true;
-  {
-    LimbMap pmap;
-    for (u32 k = 0; k < CKKS_MAX_SLOTS; k++) pmap.id[k] = (unsigned char)(k < K ? c->nq + k : 0);
-    NttOpts o3;
-    o3.scale = lt->dn_scale;
-    if ((rc = launch_ntt(c, true, acc, (u64)next * N, acc, (u64)next * N, B * 2, nlimbs, K, pmap, 0, 0, st, o3))) return rc;
+// Base conversion fused with the first forward pass (ntt16_bconv_rows_kernel): one launch per modulus class among
+// the `ntarget` target slots. class_of_slot(slot) < 0 leaves a slot out.
+template <class ClassOf>
+int launch_bconv_rows(const ckks_ctx* c, BconvRowsArgs a, u32 npoly, bool narrow, ClassOf class_of_slot, hipStream_t st) {
+  if (npoly > 65535) return fail(CKKS_ESHAPE, "batch too large for one launch");
+  a.tw = c->d_tw_fwd;
+  a.twfp = c->d_twfp_fwd;
+  a.mods = c->d_mods;
+  // every target of a (polynomial, tile) group on one XCD, whose L2 then serves the shared source tiles
+  a.map_mode = c->tune[0] >= 0 ? (u32)c->tune[0] : 4u;
+  for (int cls = 0; cls < 3; cls++) {
+    u32 cnt = 0;
+    for (u32 s = 0; s < a.ntarget; s++)
+      if (class_of_slot(s) == cls) a.slots[cnt++] = (unsigned char)s;
+    if (!cnt) continue;
+    const dim3 grid(cnt, 16, npoly), block(NTT16_THREADS);
+    ProfScope ps(c, PK_BCONV_ROWS + cls, st);
+#define LAUNCH_BCONV(CLS)                                                                              \
+  if (narrow) hipLaunchKernelGGL((ntt16_bconv_rows_kernel<CLS, true>), grid, block, 0, st, a);         \
+  else hipLaunchKernelGGL((ntt16_bconv_rows_kernel<CLS, false>), grid, block, 0, st, a)
+    if (cls == 0) { LAUNCH_BCONV(0); }
+    else if (cls == 1) { LAUNCH_BCONV(1); }
+    else { LAUNCH_BCONV(2); }
+#undef LAUNCH_BCONV
   }
-  {
-    ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
-    ProfScope ps(c, PK_MODDOWN, st);
-    launch_moddown<true>(c, a, B * 2, lt->narrow_dn, st);
-    HIP_TRY(hipGetLastError());
-  }
-  if ((rc = launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, qmap, 0, 0, st, o2))) return rc;
-  if (wait_before_assembly) HIP_TRY(hipStreamWaitEvent(st, wait_before_assembly, 0));
-  {
-    FwdFinalArgs a;
-    a.tq = tq;
-    a.acc = acc;
-    a.out = io.out;
-    a.add_src = io.add_src;
-    a.add2 = io.add2 ? io.add2 : io.out;
-    a.add2_three = io.add2 && io.add2_three ? 1u : 0u;
-    a.tw = c->d_tw_fwd;
-    a.twfp = c->d_twfp_fwd;
-    a.mods = c->d_mods;
-    a.pinv = lt->pinv2;
-    a.nlimbs = nlimbs;
-    a.next = next;
-    a.mode0 = io.mode[0];
-    a.mode1 = io.mode[1];
-    a.galois = io.add_galois;
-    if (io.galois_pc) {
-      a.multi = 1;
-      for (u32 i = 0; i < B; i++) a.galois_pc[i] = io.galois_pc[i];
-    }
-    a.map_mode = map_mode_pass(c);
-    auto cls_of = [&](u32 s) { return host_class(c, c->mod[s]); };
-    LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
-    HIP_TRY(hipGetLastError());
-  }
+  HIP_TRY(hipGetLastError());
   return CKKS_OK;
 }
 
+// ModDown's conversion and the first forward pass of its result on the N = 2^16 path: the special limbs of both
+// accumulators back to coefficient form (scaled by (P/p_k)^-1 / N), P -> Q_l, stages 0..7; tq receives the converted
+// limbs in row-pass form. Knob 2 = 1 does the conversion inside the row pass (ntt16_bconv_rows_kernel).
+int ks16_moddown_rows(ckks_ctx* c, const LevelTables* lt, u32 B, u32 nlimbs, u64* acc, u64* tq, hipStream_t st) {
+  int rc;
+  const u32 N = c->N, next = lt->next, K = c->np;
+  const bool fused = c->tune[2] == 1;
+  LimbMap pmap;
+  for (u32 k = 0; k < CKKS_MAX_SLOTS; k++) pmap.id[k] = (unsigned char)(k < K ? c->nq + k : 0);
+  NttOpts o3;
+  o3.scale = lt->dn_scale;
+  o3.split_out = fused;
+  if ((rc = launch_ntt(c, true, acc, (u64)next * N, acc, (u64)next * N, B * 2, nlimbs, K, pmap, 0, 0, st, o3))) return rc;
+  if (!fused) {
+    {
+      ModDownArgs a{acc, tq, c->d_mods, lt->dn_inv, lt->dn_mat_plain, c->logN, nlimbs, c->nq, K, next, nlimbs, c->nq};
+      ProfScope ps(c, PK_MODDOWN, st);
+      launch_moddown<true>(c, a, B * 2, lt->narrow_dn, st);
+      HIP_TRY(hipGetLastError());
+    }
+    NttOpts o2;
+    o2.rows_only = true;
+    return launch_ntt(c, false, tq, (u64)nlimbs * N, tq, (u64)nlimbs * N, B * 2, 0, nlimbs, identity_map(nlimbs), 0, 0, st, o2);
+  }
+  BconvRowsArgs a;
+  a.src = acc;
+  a.dst = tq;
+  a.mat = lt->dn_mat_plain;
+  a.off = lt->dn_off;
+  a.src_poly_stride = (u64)next * N;
+  a.dst_poly_stride = (u64)nlimbs * N;
+  a.src_slot0 = nlimbs;
+  a.src_nlimbs = K;
+  a.alpha = K;
+  a.beta = 1;
+  a.skip_own = 0;
+  a.ntarget = nlimbs;
+  a.pitch = lt->dn_pitch;
+  for (u32 i = 0; i < 128; i++) a.id[i] = (unsigned char)(i < nlimbs ? i : 0);
+  return launch_bconv_rows(c, a, B * 2, lt->narrow_dn, [&](u32 s) { return host_class(c, c->mod[s]); }, st);
+}
+
+// Last kernel of a key switch on the N = 2^16 path: block pass of tq fused with (acc - tq) / P and the addends.
+// exclude_class >= 0 leaves the limbs of that modulus class to another kernel.
+int ks16_assemble(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, const u64* acc, const u64* tq,
+                  hipStream_t st, int exclude_class = -1) {
+  FwdFinalArgs a;
+  a.tq = tq;
+  a.acc = acc;
+  a.out = io.out;
+  a.add_src = io.add_src;
+  a.add2 = io.add2 ? io.add2 : io.out;
+  a.add2_three = io.add2 && io.add2_three ? 1u : 0u;
+  a.tw = c->d_tw_fwd;
+  a.twfp = c->d_twfp_fwd;
+  a.mods = c->d_mods;
+  a.pinv = lt->pinv2;
+  a.nlimbs = nlimbs;
+  a.next = lt->next;
+  a.mode0 = io.mode[0];
+  a.mode1 = io.mode[1];
+  a.galois = io.add_galois;
+  if (io.galois_pc) {
+    a.multi = 1;
+    for (u32 i = 0; i < B; i++) a.galois_pc[i] = io.galois_pc[i];
+  }
+  a.map_mode = map_mode_pass(c);
+  auto cls_of = [&](u32 s) {
+    const int k = host_class(c, c->mod[s]);
+    return k == exclude_class ? -1 : k;
+  };
+  LAUNCH_BY_CLASS(c, PK_FWD_FINAL, ntt16_fwd_blocks_final_kernel, a, B * 2, nlimbs, cls_of, st)
+  HIP_TRY(hipGetLastError());
+  return CKKS_OK;
+}
+
+// Second half of a key switch on the N = 2^16 path: from the accumulators (all slots) to the assembled output.
+// acc_in: accumulators held outside the workspace ([B][2][next][N]; their special-prime slots are overwritten).
+int ks16_finish(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, char* ws, hipStream_t st,
+                u64* acc_in = nullptr) {
+  int rc;
+  KsLayout L = ks_layout(c, B, nlimbs);
+  u64* acc = acc_in ? acc_in : (u64*)(ws + L.acc);
+  u64* tq = (u64*)(ws + L.tq);
+  if ((rc = ks16_moddown_rows(c, lt, B, nlimbs, acc, tq, st))) return rc;
+  return ks16_assemble(c, lt, io, B, nlimbs, acc, tq, st);
+}
 
 // N = 2^16: transforms fused with their neighbours.
-//   INTT(d) with (Q_j/q_i)^-1/N folded in -> ModUp -> row pass -> [block pass + evk inner product] (x 2^-64)
-//   -> INTT of the special limbs with 2^64 (P/p_k)^-1/N folded in -> ModDown (x 2^-64) -> row pass
-//   -> [block pass + (acc - t) * 2^64/P + addend].
-// acc_add != null (knobs 2 and 3 at their defaults only): the sequence stops before ModDown and ADDS the two
-// accumulators, plus P * sigma(io.add_src component 0) on the main primes of the first, to acc_add ([B][2][next][N]).
+//   1. INTT(d) with (Q_j/q_i)^-1 / N folded in, written in the split form
+//   2. ModUp conversion and row pass of every slot a digit does not own (two kernels; knob 2 = 1: one fused kernel)
+//   3. integer-class slots (the special primes): [block pass + evk inner product] (x 2^-64 from the Montgomery products)
+//   4. INTT of the special limbs with 2^64 (P/p_k)^-1 / N folded in; ModDown conversion and row pass (as step 2)
+//   5. double-precision main limbs: [block pass of the digits + evk inner product + block pass of the ModDown
+//      correction + (sum - correction) / P + addends] in one kernel, so their accumulators never reach memory;
+//      integer-class main limbs take the assembly kernel on the accumulators of step 3.
+// With knob 3 = 1 the double-precision slots take a plain block pass, a streaming product and the assembly kernel
+// instead of step 5's fusion. With knob 4 = 0 the double-precision part of step 2 runs on the context's second stream
+// beside steps 3 and 4, which do not depend on it, and is joined before step 5.
+// acc_add != null (knob 3 at its default only): the sequence stops before ModDown and ADDS the two accumulators, plus
+// P * sigma(io.add_src component 0) on the main primes of the first, to acc_add ([B][2][next][N]).
 int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B, u32 nlimbs, const u64* evk, char* ws,
                       hipStream_t st, u64* acc_add = nullptr) {
   int rc;
@@ -724,41 +821,81 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
   u64* dcoef = (u64*)(ws + L.dcoef);
   u64* ext = (u64*)(ws + L.ext);
   u64* acc = (u64*)(ws + L.acc);
+  u64* tq = (u64*)(ws + L.tq);
   const LimbMap qmap = identity_map(nlimbs), emap = ext_map(c, nlimbs);
   if (io.galois_pc && B > KS_MULTI_MAX) return fail(CKKS_ESHAPE, "internal: per-ciphertext keys for too many ciphertexts");
+  const bool fused_fp = c->tune[3] != 1;
+  if (acc_add && !fused_fp) return fail(CKKS_EINVAL, "internal: accumulation needs the default inner kernels");
+  auto ext_class = [&](u32 s) { return host_class(c, c->mod[emap.id[s]]); };
+  bool any_fp = false, any_int = false, special_fp = false;
+  for (u32 s_ = 0; s_ < next; s_++) {
+    const bool fp = ext_class(s_) == 0;
+    any_fp |= fp;
+    any_int |= !fp;
+    if (s_ >= nlimbs) special_fp |= fp;
+  }
+  const bool fused_up = c->tune[2] == 1;
+  // 1.
   NttOpts o1;
   o1.galois = io.d_galois;
   o1.galois_pc = io.galois_pc;
   o1.scale = lt->up_scale;
+  o1.split_out = fused_up;
   if ((rc = launch_ntt(c, true, io.d, io.d_stride, dcoef, (u64)nlimbs * N, B, 0, nlimbs, qmap, 0, 0, st, o1))) return rc;
-  {
+  // 2. The double-precision part of the row pass (memory-bound) may run on the second stream beside the
+  // integer-class chain of steps 2-4 (arithmetic-bound), which does not depend on it.
+  const bool fork = any_fp && any_int && !special_fp && !acc_add && c->tune[4] == 0;
+  hipStream_t sb = st;
+  if (!fused_up) {
     ModUpArgs a{dcoef, ext, c->d_mods, lt->up_inv, lt->up_mat, c->logN, nlimbs, c->nq, c->alpha, beta, next};
     ProfScope ps(c, PK_MODUP, st);
     launch_modup<true>(c, a, beta, B, lt->narrow_up, st);
     HIP_TRY(hipGetLastError());
   }
-  NttOpts o2;
-  o2.rows_only = true;
-  // Double-precision slots take their own kernels for the block pass and the inner product (knob 3: fused with one
-  // key component per workgroup, or a plain block pass + streaming product; memory-bound either way); integer-class
-  // slots (the special primes) take the block pass fused with both key components and then feed ModDown
-  // (ALU-bound). The two chains touch disjoint slots, so with knob 4 == 0 they run side by side on two streams and
-  // join before the result is assembled.
-  const bool unfused_fp = c->tune[3] != 0;   // class-0 slots are not handled by the two-accumulator fused kernel
-  bool any_fp = false, any_int = false, special_fp = false;
-  for (u32 s_ = 0; s_ < next; s_++) {
-    const bool fp = host_class(c, c->mod[emap.id[s_]]) == 0;
-    any_fp |= fp;
-    any_int |= !fp;
-    if (s_ >= nlimbs) special_fp |= fp;
-  }
-  const bool fork = unfused_fp && any_fp && any_int && c->tune[4] == 0;
-  hipStream_t sb = st;  // stream of the double-precision chain
   if (fork) {
     sb = c->side;
     HIP_TRY(hipEventRecord(c->ev_fork, st));
     HIP_TRY(hipStreamWaitEvent(sb, c->ev_fork, 0));
   }
+  if (!fused_up) {
+    NttOpts o2;
+    o2.rows_only = true;
+    if (any_fp) {
+      NttOpts o = o2;
+      o.only_class = 0;
+      if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
+        return rc;
+    }
+    if (any_int) {
+      NttOpts o = o2;
+      o.exclude_class = 0;
+      if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, o)))
+        return rc;
+    }
+  } else {
+    BconvRowsArgs up;
+    up.src = dcoef;
+    up.dst = ext;
+    up.mat = lt->up_mat;
+    up.off = lt->up_off;
+    up.src_poly_stride = (u64)nlimbs * N;
+    up.dst_poly_stride = (u64)next * N;
+    up.src_slot0 = 0;
+    up.src_nlimbs = nlimbs;
+    up.alpha = c->alpha;
+    up.beta = beta;
+    up.skip_own = 1;
+    up.ntarget = next;
+    up.pitch = lt->up_pitch;
+    for (u32 i = 0; i < 128; i++) up.id[i] = emap.id[i];
+    if (any_fp &&
+        (rc = launch_bconv_rows(c, up, B * beta, lt->narrow_up, [&](u32 s) { return ext_class(s) == 0 ? 0 : -1; }, sb)))
+      return rc;
+    if (any_int &&
+        (rc = launch_bconv_rows(c, up, B * beta, lt->narrow_up, [&](u32 s) { return ext_class(s) == 0 ? -1 : ext_class(s); }, st)))
+      return rc;
+  }
+  if (fork) HIP_TRY(hipEventRecord(c->ev_join, sb));
   FwdInnerArgs ia;
   ia.ext = ext;
   ia.d = io.d;
@@ -782,75 +919,77 @@ int keyswitch_fused16(ckks_ctx* c, const LevelTables* lt, const KsIo& io, u32 B,
     for (u32 i = 0; i < B; i++) ia.galois_pc[i] = io.galois_pc[i], ia.evk_pc[i] = io.evk_pc[i];
   }
   if (acc_add) {
-    if (c->tune[3] != 2 || c->tune[2] != 2) return fail(CKKS_EINVAL, "internal: accumulation needs the default inner kernels");
     ia.acc = acc_add;
     ia.accumulate = 1;
     ia.c0 = io.add_src;
     ia.c0_poly_stride = 2 * (u64)nlimbs * N;
   }
-  if (unfused_fp && any_fp) {
-    NttOpts o = o2;
-    o.only_class = 0;
-    if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
-      return rc;
+  // 3. integer-class slots, 8 values per lane (grid.y = 32 tiles of 8 blocks)
+  for (int cls = 1; cls <= 2; cls++) {
     FwdInnerArgs a = ia;
     u32 cnt = 0;
     for (u32 s_ = 0; s_ < next; s_++)
-      if (host_class(c, c->mod[emap.id[s_]]) == 0) a.slots[cnt++] = (unsigned char)s_;
-    if (c->tune[3] == 3) {
-      // block pass fused with the product on both key components, 8 values per lane
-      ProfScope ps(c, PK_INNER2, sb);
-      hipLaunchKernelGGL(ntt16_fwd_blocks_inner2_kernel, dim3(B, 32, cnt), dim3(256), 0, sb, a);
-    } else if (c->tune[3] == 2) {
-      // block pass fused with the product, one key component per workgroup
-      ProfScope ps(c, PK_INNER_C, sb);
-      hipLaunchKernelGGL(ntt16_fwd_blocks_inner_c_kernel, dim3(B * 2, 16, cnt), dim3(NTT16_THREADS), 0, sb, a);
+      if (ext_class(s_) == cls) a.slots[cnt++] = (unsigned char)s_;
+    if (!cnt) continue;
+    ProfScope ps(c, PK_INNER8 + cls - 1, st);
+    if (cls == 1) hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<1>, dim3(B, 32, cnt), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<2>, dim3(B, 32, cnt), dim3(256), 0, st, a);
+  }
+  HIP_TRY(hipGetLastError());
+  // double-precision slots whose accumulators are needed in memory: the special ones always (ModDown reads them),
+  // the main ones when the result is accumulated or when the fusion of step 5 is switched off
+  auto launch_inner_fp = [&](bool special, bool main_slots, hipStream_t s) -> int {
+    FwdInnerArgs a = ia;
+    u32 cnt = 0;
+    for (u32 s_ = 0; s_ < next; s_++)
+      if (ext_class(s_) == 0 && (s_ >= nlimbs ? special : main_slots)) a.slots[cnt++] = (unsigned char)s_;
+    if (!cnt) return CKKS_OK;
+    if (fused_fp) {
+      ProfScope ps(c, PK_INNER_C, s);
+      hipLaunchKernelGGL(ntt16_fwd_blocks_inner_c_kernel, dim3(B * 2, 16, cnt), dim3(NTT16_THREADS), 0, s, a);
     } else {
-      o = NttOpts();
+      // plain block pass of every converted double-precision slot (own limbs are skipped), then a streaming product
+      NttOpts o;
       o.blocks_only = true;
       o.raw_out = true;
       o.only_class = 0;
-      if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, sb, o)))
-        return rc;
-      ProfScope ps(c, PK_INNER16, sb);
-      hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, sb, a);
+      int r2 = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, s, o);
+      if (r2) return r2;
+      ProfScope ps(c, PK_INNER16, s);
+      hipLaunchKernelGGL(inner16_fp_kernel, dim3(B, 128, cnt), dim3(256), 0, s, a);
     }
     HIP_TRY(hipGetLastError());
-    if (fork) HIP_TRY(hipEventRecord(c->ev_join, sb));
-  }
-  bool joined = !fork;
-  {
-    NttOpts o = o2;
-    if (unfused_fp) o.exclude_class = 0;
-    if ((rc = launch_ntt(c, false, ext, (u64)next * N, ext, (u64)next * N, B * beta, 0, next, emap, beta, nlimbs, st, o)))
-      return rc;
-    FwdInnerArgs a = ia;
-    auto cls_of = [&](u32 s) {
-      int k = host_class(c, c->mod[emap.id[s]]);
-      return (unfused_fp && k == 0) ? -1 : k;
-    };
-    if (c->tune[2] == 2 && unfused_fp) {
-      // integer classes with 8 values per lane (grid.y = 32 tiles of 8 blocks)
-      for (int cls = 1; cls <= 2; cls++) {
-        u32 cnt = 0;
-        for (u32 s_ = 0; s_ < next; s_++)
-          if (cls_of(s_) == cls) a.slots[cnt++] = (unsigned char)s_;
-        if (!cnt) continue;
-        ProfScope ps(c, PK_INNER8 + cls - 1, st);
-        if (cls == 1) hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<1>, dim3(B, 32, cnt), dim3(256), 0, st, a);
-        else hipLaunchKernelGGL(ntt16_fwd_blocks_inner8_kernel<2>, dim3(B, 32, cnt), dim3(256), 0, st, a);
-      }
-    } else {
-      LAUNCH_BY_CLASS(c, PK_FWD_INNER, ntt16_fwd_blocks_inner_kernel, a, B, next, cls_of, st)
-    }
-    HIP_TRY(hipGetLastError());
-  }
-  if (!joined && (special_fp || acc_add)) {  // a special prime's accumulator came from the other chain
-    HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
-    joined = true;
+    return CKKS_OK;
+  };
+  if (special_fp || acc_add || !fused_fp) {
+    if ((rc = launch_inner_fp(true, acc_add || !fused_fp, st))) return rc;
   }
   if (acc_add) return CKKS_OK;
-  return ks16_finish(c, lt, io, B, nlimbs, ws, st, joined ? nullptr : c->ev_join);
+  // 4.
+  if ((rc = ks16_moddown_rows(c, lt, B, nlimbs, acc, tq, st))) return rc;
+  if (fork) HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
+  // 5.
+  if (fused_fp && any_fp) {
+    FwdInnerArgs a = ia;
+    u32 cnt = 0;
+    for (u32 s_ = 0; s_ < nlimbs; s_++)
+      if (ext_class(s_) == 0) a.slots[cnt++] = (unsigned char)s_;
+    if (cnt) {
+      a.fin_tq = tq;
+      a.fin_out = io.out;
+      a.fin_add_src = io.add_src;
+      a.fin_add2 = io.add2 ? io.add2 : io.out;
+      a.fin_add2_three = io.add2 && io.add2_three ? 1u : 0u;
+      a.fin_pinv = lt->pinv2;
+      a.fin_mode0 = io.mode[0];
+      a.fin_mode1 = io.mode[1];
+      a.fin_galois = io.add_galois;
+      ProfScope ps(c, PK_INNER_C, st);
+      hipLaunchKernelGGL(ntt16_fwd_blocks_inner_c_kernel, dim3(B * 2, 16, cnt), dim3(NTT16_THREADS), 0, st, a);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+  return ks16_assemble(c, lt, io, B, nlimbs, acc, tq, st, fused_fp ? 0 : -1);
 }
 
 // Shared front of the hoisted rotations at N = 2^16: inverse transform, ModUp and forward transform of c1 of ct_in
@@ -969,7 +1108,7 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
       for (u32 k = 0; k < nr; k++) {
         const u32 r = r0 + k;
         KsIo io{c1, 2 * polyN, galois[r], out_base + (size_t)r * out_stride, {2, 0}, ct_in, galois[r]};
-        if ((rc = ks16_finish(c, lt, io, B, nlimbs, ws, st, nullptr, scratch + (size_t)k * one))) return rc;
+        if ((rc = ks16_finish(c, lt, io, B, nlimbs, ws, st, scratch + (size_t)k * one))) return rc;
       }
     }
     return CKKS_OK;
@@ -992,7 +1131,7 @@ int hrot_hoisted16(ckks_ctx* c, u64* out_base, u64 out_stride, const u64* ct_in,
     HIP_TRY(hipGetLastError());
     if (acc_base) continue;
     KsIo io{c1, 2 * polyN, galois[r], out_base + (size_t)r * out_stride, {2, 0}, ct_in, galois[r]};
-    if ((rc = ks16_finish(c, lt, io, B, nlimbs, ws, st, nullptr))) return rc;
+    if ((rc = ks16_finish(c, lt, io, B, nlimbs, ws, st))) return rc;
   }
   return CKKS_OK;
 }
@@ -1648,7 +1787,7 @@ int ckks_hrot_sum(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t
     HIP_TRY(hipGetLastError());
   }
   KsIo io{nullptr, 0, 0, (u64*)ct_out, {0, 0}, nullptr, 0};
-  return ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, total);
+  return ks16_finish(c, lt, io, B, nlimbs, hws, st, total);
 }
 
 static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint32_t B, uint32_t nlimbs,
@@ -1819,10 +1958,10 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
         // (one hoisted rotation that stops before ModDown) added to `total`
         if (g == 0) continue;
         KsIo io{nullptr, 0, 0, rot, {0, 0}, nullptr, 0};
-        if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, inner + (size_t)k * sum_elems))) return rc;
+        if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, inner + (size_t)k * sum_elems))) return rc;
         const u32 gg = galois((u64)g * n1 * stride);
         const u64* key = (const u64*)evk_giant[g - 1];
-        if (c->tune[3] == 2 && c->tune[2] == 2) {
+        if (c->tune[3] != 1) {
           // the usual fused sequence of a rotation (c1 read through the Galois map), stopped before ModDown
           KsIo gio{rot + polyN, 2 * (u64)polyN, gg, nullptr, {0, 0}, rot, gg};
           rc = keyswitch_fused16(c, lt, gio, B, nlimbs, key, hws, st, total);
@@ -1852,7 +1991,7 @@ static int pcmm_impl(ckks_ctx* c, uint64_t* ct_out, const uint64_t* ct_in, uint3
   }
   if (dh) {   // one ModDown of the sum over giant steps
     KsIo io{nullptr, 0, 0, (u64*)ct_out, {0, 0}, nullptr, 0};
-    if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, nullptr, total))) return rc;
+    if ((rc = ks16_finish(c, lt, io, B, nlimbs, hws, st, total))) return rc;
   }
   return CKKS_OK;
 }

@@ -69,14 +69,12 @@ __device__ __forceinline__ u64 barrett_lazy(u64 v, u64 mu, u64 q) { return v - m
 // ---- pass bodies. `base` points at one limb-vector of 65536 words, `tw` at that modulus' table. ----
 
 // Forward, stages 0..7. In: canonical (or < 2q). Out: SMALL < 17q (+in), BIG < 4q.
+// `x` holds, for lane (r0 = t>>4, col = t&15), the rows i*16 + r0 (i = 0..15) of column col0 + col.
 template <bool BIG>
-__device__ __forceinline__ void ntt16_fwd_rows(const u64* __restrict__ src, u64* __restrict__ dst, const ulonglong2* __restrict__ tw,
-                                               u64 q, u32 tile, u64* sm) {
+__device__ __forceinline__ void ntt16_fwd_rows_loaded(u64 (&x)[16], u64* __restrict__ dst, const ulonglong2* __restrict__ tw,
+                                                      u64 q, u32 tile, u64* sm) {
   const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
   const u64 q2 = 2 * q;
-  u64 x[16];
-#pragma unroll
-  for (int i = 0; i < 16; i++) x[i] = src[(size_t)(i * 16 + r0) * 256 + col0 + col];
   radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(1 << s) + g]; });
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[i * 256 + t] = x[i];
@@ -87,6 +85,15 @@ __device__ __forceinline__ void ntt16_fwd_rows(const u64* __restrict__ src, u64*
   radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(16 << s) + (i0 << s) + g]; });
 #pragma unroll
   for (int j = 0; j < 16; j++) dst[(size_t)(i0 * 16 + j) * 256 + col0 + col] = x[j];
+}
+template <bool BIG>
+__device__ __forceinline__ void ntt16_fwd_rows(const u64* __restrict__ src, u64* __restrict__ dst, const ulonglong2* __restrict__ tw,
+                                               u64 q, u32 tile, u64* sm) {
+  const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
+  u64 x[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = src[(size_t)(i * 16 + r0) * 256 + col0 + col];
+  ntt16_fwd_rows_loaded<BIG>(x, dst, tw, q, tile, sm);
 }
 
 // Forward, stages 8..15, then canonical (CANON) or < 2q. `x` is left holding, for lane (hb = t>>4, j0 = t&15), the 16 values at

@@ -22,6 +22,8 @@ struct Ntt16Args {
   u32 skip_beta, skip_alpha, skip_nq;    // digit p % skip_beta leaves its own limbs alone (ModUp'ed digits)
   u32 map_mode;                          // workgroup -> (poly, tile, slot) mapping, see ntt16_map
   u32 raw_out;                           // forward last pass, double-precision class only: != 0 leaves reduced doubles
+  u32 split_out = 0;                     // inverse second pass only: != 0 writes (y + (q-1)/2) mod q as two 30-bit halves
+                                         // (bits 0..29, 32..62), the source form of ntt16_bconv_rows_kernel
   u32 galois;                            // inverse first pass only: != 0 reads src through the eval-domain Galois map
   u32 multi = 0;                         // != 0: polynomial p is read through galois_pc[p] instead (p < KS_MULTI_MAX)
   u32 galois_pc[KS_MULTI_MAX];
@@ -132,9 +134,164 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_inv_rows_kernel(Ntt16Args
     if (cls == 2) ntt16_inv_rows<true>(x, src, tw, mi.m, sc, scs, tile, sm);
     else ntt16_inv_rows<false>(x, src, tw, mi.m, sc, scs, tile, sm);
   }
+  if (a.split_out) {   // wave-uniform
+    const u64 hq = mi.m >> 1;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      const u64 y = csub(x[i] + hq, mi.m);
+      x[i] = (y & 0x3FFFFFFFull) | ((y >> 30) << 32);
+    }
+  }
   const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
 #pragma unroll
   for (int i = 0; i < 16; i++) dst[(size_t)(i * 16 + r0) * 256 + col0 + col] = x[i];
+}
+
+// ---- fused: base conversion + first forward pass (ModUp and ModDown) ----
+// The coefficient-domain sources arrive in the form the inverse row pass writes when Ntt16Args::split_out is set:
+// for a source modulus c with h = (c - 1) / 2, the word holds yt = (y + h) mod c, y = [x (C/c)^-1]_c, as two 30-bit
+// halves (bits 0..29 and bits 32..62). Since yt - h is the centred representative of y,
+//   sum_k (y_k centred) (C/c_k)  =  sum_k yt_k (C/c_k)  -  sum_k h_k (C/c_k),
+// the conversion is one dot product plus a per-target constant (`off`), with no sign handling per coefficient, and
+// the halves enter the 32-bit multiply-adds as they are loaded. A workgroup builds the 256 x 16 tile of one target
+// limb from the `len` source tiles of its digit and takes it straight through stages 0..7; the converted limb is
+// never written in coefficient form. All targets of one (polynomial, tile) run next to each other on one XCD
+// (ntt16_map mode 4 with the target index as the fastest dimension), so its L2 serves the source tiles to all of
+// them after the first has fetched them.
+struct BconvRowsArgs {
+  const u64* src;           // source limbs, split form (see above)
+  u64* dst;                 // target limbs after the row pass (reduced doubles / lazy integers, by class)
+  const u64* mat;           // [beta][ntarget][pitch] constants (C/c_k) mod m_t in Montgomery form (2^90 or 2^64)
+  const u64* off;           // [beta][ntarget] the constant -sum_k h_k (C/c_k) mod m_t in the same form
+  const ulonglong2* tw;
+  const double* twfp;
+  const ModInfo* mods;
+  u64 src_poly_stride;      // elements between the source rows of consecutive (p / beta)
+  u64 dst_poly_stride;      // elements between consecutive destination polynomials p
+  u32 src_slot0;            // limb index, inside a source row, of the first source of digit 0
+  u32 src_nlimbs, alpha, beta;  // digit j = p % beta owns sources j*alpha .. j*alpha + len - 1, len = min(alpha, src_nlimbs - j*alpha)
+  u32 skip_own;             // != 0: target slots j*alpha .. j*alpha + len - 1 are the digit's own limbs: left alone
+  u32 ntarget, pitch;
+  u32 map_mode;
+  unsigned char id[128];    // target slot -> modulus id
+  unsigned char slots[128]; // grid.x index -> target slot (one modulus class per launch)
+};
+
+#define BCONV_M30 0x3FFFFFFFu
+// Converted values for 8 of the lane's 16 tile positions (those at voff[0..7], offsets inside a limb).
+template <bool NARROW>
+__device__ __forceinline__ void bconv_rows_eight(u64 (&r)[8], const u64* __restrict__ src, const u32 (&voff)[8], u32 len,
+                                                 const u64* __restrict__ crow, u64 offc, const ModInfo& mi) {
+  const u64 m = mi.m;
+  u64 w[8], wn[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++) w[i] = src[voff[i]];
+  if (NARROW) {
+    Dot30N dd[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      dd[i].a = (u32)offc & BCONV_M30;
+      dd[i].b = offc >> 30;
+      dd[i].c = 0;
+      r[i] = 0;
+    }
+    for (u32 k = 0, pending = 0; k < len; k++) {
+      const u64* nxt = src + (size_t)(k + 1 < len ? k + 1 : k) * 65536;
+#pragma unroll
+      for (int i = 0; i < 8; i++) wn[i] = nxt[voff[i]];
+      const u64 c = crow[k];
+      const u32 c0 = (u32)c & BCONV_M30, c1 = (u32)(c >> 30);
+#pragma unroll
+      for (int i = 0; i < 8; i++) dot30n_mac(dd[i], (u32)w[i], (u32)(w[i] >> 32), c0, c1);
+      if (++pending == 15 && k + 1 < len) {   // wave-uniform: chunks of 15 terms are reduced separately
+        pending = 0;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          r[i] += dot30n_redc90(dd[i], m, mi.minv);
+          dot30n_init(dd[i]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; i++) w[i] = wn[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) r[i] += dot30n_redc90(dd[i], m, mi.minv);   // each part < m + 2^34
+  } else {
+    Dot30 dd[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      dot30_init(dd[i]);
+      dd[i].s00 = (u32)offc & BCONV_M30;
+      dd[i].s01 = offc >> 30;
+      r[i] = 0;
+    }
+    for (u32 k = 0, pending = 0; k < len; k++) {
+      const u64* nxt = src + (size_t)(k + 1 < len ? k + 1 : k) * 65536;
+#pragma unroll
+      for (int i = 0; i < 8; i++) wn[i] = nxt[voff[i]];
+      const u64 c = crow[k];
+      const u32 c0 = (u32)c & BCONV_M30, c1 = (u32)(c >> 30);
+#pragma unroll
+      for (int i = 0; i < 8; i++) dot30_mac(dd[i], (u32)w[i], (u32)(w[i] >> 32), c0, c1);
+      if (++pending == 15 && k + 1 < len) {
+        pending = 0;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          r[i] += redc(dot30_value(dd[i]), m, mi.minv);
+          dot30_init(dd[i]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; i++) w[i] = wn[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) r[i] += redc(dot30_value(dd[i]), m, mi.minv);   // each part < 2m
+  }
+  // at most three chunks (45 sources): the sum of the parts is below 6m
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    u64 v = r[i];
+    if (len > 15 || !NARROW) v = csub(csub(v, 4 * m), 2 * m);
+    r[i] = csub(v, m);
+  }
+}
+
+template <int CLS, bool NARROW>
+__global__ void __launch_bounds__(NTT16_THREADS) ntt16_bconv_rows_kernel(BconvRowsArgs a) {
+  __shared__ u64 sm[NTT16_LDS_BYTES / 8];
+  u32 zi, tile, poly;
+  ntt16_map(a.map_mode, zi, tile, poly);
+  const u32 slot = a.slots[zi];
+  const u32 j = poly % a.beta, lo = j * a.alpha, len = min(a.alpha, a.src_nlimbs - lo);
+  if (a.skip_own && slot >= lo && slot < lo + len) return;
+  const u32 id = a.id[slot];
+  const ModInfo mi = a.mods[id];
+  const u64* src = a.src + (size_t)(poly / a.beta) * a.src_poly_stride + (size_t)(a.src_slot0 + lo) * 65536;
+  const u64* crow = a.mat + ((size_t)j * a.ntarget + slot) * a.pitch;
+  const u64 offc = a.off[(size_t)j * a.ntarget + slot];
+  u64* dst = a.dst + (size_t)poly * a.dst_poly_stride + (size_t)slot * 65536;
+  const u32 t = threadIdx.x, pos0 = (t >> 4) * 256 + tile * 16 + (t & 15);   // row r0, column col0 + col
+  u64 x[16];
+#pragma unroll
+  for (int half = 0; half < 2; half++) {
+    u32 voff[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) voff[i] = pos0 + (half * 8 + i) * 4096;   // rows i*16 + r0
+    u64 r[8];
+    bconv_rows_eight<NARROW>(r, src, voff, len, crow, offc, mi);
+#pragma unroll
+    for (int i = 0; i < 8; i++) x[half * 8 + i] = r[i];
+  }
+  if (CLS == 0) {
+    double xd[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) xd[i] = u2d(x[i]);
+    ntt16_fwd_rows_fp_loaded(xd, (double*)dst, a.twfp + (size_t)id * 65536, mi.qd, mi.qinv, tile, (double*)sm);
+  } else if (CLS == 2) {
+    ntt16_fwd_rows_loaded<true>(x, dst, a.tw + (size_t)id * 65536, mi.m, tile, sm);
+  } else {
+    ntt16_fwd_rows_loaded<false>(x, dst, a.tw + (size_t)id * 65536, mi.m, tile, sm);
+  }
 }
 
 // ---- fused: last forward pass of the ModUp'ed digits + inner product with the evaluation key ----
@@ -168,6 +325,15 @@ struct FwdInnerArgs {
   // acc + r * acc_rot_stride, and galois_pc[r] holds the INVERSE of its Galois element modulo 2N
   u32 nrot = 0;
   u64 acc_rot_stride = 0;
+  // ntt16_fwd_blocks_inner_c_kernel on main-prime slots only: fin_tq != null finishes the key switch in the same
+  // kernel instead of storing the accumulator: out = (sum - NTT(tq)) / P (+ addends), with the arguments of
+  // FwdFinalArgs (tq after the row pass, [B*2][nlimbs][N]; pinv [nlimbs] as (1/P, (1/P)/q); addend modes per component)
+  const u64* fin_tq = nullptr;
+  u64* fin_out = nullptr;
+  const u64* fin_add2 = nullptr;
+  const u64* fin_add_src = nullptr;
+  const ulonglong2* fin_pinv = nullptr;
+  u32 fin_mode0 = 0, fin_mode1 = 0, fin_galois = 0, fin_add2_three = 0;
 };
 // b is the same for the whole workgroup; saying so keeps the table look-ups on the scalar unit and their results
 // in scalar registers.
@@ -180,131 +346,9 @@ __device__ __forceinline__ const u64* fwd_inner_evk(const FwdInnerArgs& a, u32 b
   return (const u64*)(((u64)hi << 32) | lo);
 }
 
-// Raw 64-bit words of the tile that digit j contributes to slot t: the digit's own limb read from d (through the
-// Galois map if asked), else the row-pass output in ext. Lane (hb, j0) gets positions i*16 + j0 of block h.
-__device__ __forceinline__ void fwd_inner_load(u64 (&raw)[16], const FwdInnerArgs& a, u32 b, u32 t, u32 j, bool own, u32 h,
-                                               u32 j0, u32 g) {
-  const size_t N = 65536;
-  if (own) {
-    const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
-    if (g) {
-#pragma unroll
-      for (int i = 0; i < 16; i++) raw[i] = src[galois_src_index16(h * 256 + i * 16 + j0, g)];
-    } else {
-#pragma unroll
-      for (int i = 0; i < 16; i++) raw[i] = src[(size_t)h * 256 + i * 16 + j0];
-    }
-  } else {
-    const u64* src = a.ext + (((size_t)b * a.beta + j) * a.next + t) * N + (size_t)h * 256 + j0;
-#pragma unroll
-    for (int i = 0; i < 16; i++) raw[i] = src[i * 16];
-  }
-}
 __device__ __forceinline__ bool fwd_inner_owns(const FwdInnerArgs& a, u32 t, u32 j) {
   const u32 lo = j * a.alpha, hi = min(lo + a.alpha, a.nlimbs);
   return t >= lo && t < hi;
-}
-
-// Software pipeline per digit: the next digit's tile is requested together with this digit's key words, before
-// the multiply-accumulate, so it arrives while the ALUs work (the LDS barriers inside the transform do not wait
-// for global loads).
-template <bool BIG>
-__device__ __forceinline__ void fwd_inner_body(const FwdInnerArgs& a, u32 b, u32 tile, u32 t, u32 id, const ModInfo& mi,
-                                               u64* sm) {
-  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
-  const size_t N = 65536;
-  const u64 q = mi.m, q2 = 2 * mi.m;
-  const ulonglong2* tw = a.tw + (size_t)id * N;
-  u64 acc0[16], acc1[16], x[16], xn[16];
-#pragma unroll
-  for (int i = 0; i < 16; i++) acc0[i] = acc1[i] = 0;
-  const u64* evk = fwd_inner_evk(a, b);
-  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
-  bool own = fwd_inner_owns(a, t, 0);
-  fwd_inner_load(xn, a, b, t, 0, own, h, j0, g);
-  for (u32 j = 0; j < a.beta; j++) {
-#pragma unroll
-    for (int i = 0; i < 16; i++) x[i] = xn[i];
-    const u64* kb = evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
-    const u64* ka = kb + (size_t)a.nm * N;
-    if (!own) {
-      if (j) wave_lds_sync();  // the previous digit's transposes (inside 16-lane groups) are done with the LDS tile
-      ntt16_fwd_blocks_loaded<BIG, false>(x, tw, q, mi.mu64, tile, sm);
-    }
-    const bool own_next = j + 1 < a.beta && fwd_inner_owns(a, t, j + 1);
-    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0, g);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < 16; i++) {
-      const u64 eb = kb[i * 16], ea = ka[i * 16];
-      Acc128 p0, p1;
-      p0.lo = x[i] * eb;
-      p0.hi = mul_hi64(x[i], eb);
-      p1.lo = x[i] * ea;
-      p1.hi = mul_hi64(x[i], ea);
-      acc0[i] = csub(acc0[i] + redc(p0, q, mi.minv), q2);
-      acc1[i] = csub(acc1[i] + redc(p1, q, mi.minv), q2);
-    }
-    own = own_next;
-  }
-  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + (size_t)h * 256 + j0;
-  u64* o1 = o0 + (size_t)a.next * N;
-#pragma unroll
-  for (int i = 0; i < 16; i++) {
-    o0[i * 16] = csub(acc0[i], q);
-    o1[i * 16] = csub(acc1[i], q);
-  }
-}
-
-__device__ __forceinline__ void fwd_inner_body_fp(const FwdInnerArgs& a, u32 b, u32 tile, u32 t, u32 id, const ModInfo& mi,
-                                                  double* sm) {
-  const u32 tid = threadIdx.x, j0 = tid & 15, h = tile * 16 + (tid >> 4);
-  const size_t N = 65536;
-  const double q = mi.qd, qinv = mi.qinv;
-  const double* tw = a.twfp + (size_t)id * N;
-  double acc0[16], acc1[16], x[16];
-  u64 xn[16];
-#pragma unroll
-  for (int i = 0; i < 16; i++) acc0[i] = acc1[i] = 0.0;
-  const u64* evk = fwd_inner_evk(a, b);
-  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
-  bool own = fwd_inner_owns(a, t, 0);
-  fwd_inner_load(xn, a, b, t, 0, own, h, j0, g);
-  for (u32 j = 0; j < a.beta; j++) {
-    // own limbs arrive as canonical residues, converted digits as the reduced doubles the row pass left
-#pragma unroll
-    for (int i = 0; i < 16; i++) x[i] = own ? u2d(xn[i]) : __longlong_as_double((long long)xn[i]);
-    const u64* kb = evk + (((size_t)j * 2 + 0) * a.nm + id) * N + (size_t)h * 256 + j0;
-    const u64* ka = kb + (size_t)a.nm * N;
-    if (!own) {
-      if (j) wave_lds_sync();
-      ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm);
-    }
-    const bool own_next = j + 1 < a.beta && fwd_inner_owns(a, t, j + 1);
-    if (j + 1 < a.beta) fwd_inner_load(xn, a, b, t, j + 1, own_next, h, j0, g);
-    __builtin_amdgcn_sched_barrier(0);
-    // each product is below 0.9 q in magnitude; bring the sums back before they can reach 2^53
-#pragma unroll
-    for (int i = 0; i < 16; i++) {
-      acc0[i] += fp_mulmod_var(x[i], u2d(kb[i * 16]), qinv, q);
-      acc1[i] += fp_mulmod_var(x[i], u2d(ka[i * 16]), qinv, q);
-    }
-    if ((j & 3) == 3) {
-#pragma unroll
-      for (int i = 0; i < 16; i++) {
-        acc0[i] = fp_reduce(acc0[i], qinv, q);
-        acc1[i] = fp_reduce(acc1[i], qinv, q);
-      }
-    }
-    own = own_next;
-  }
-  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + (size_t)h * 256 + j0;
-  u64* o1 = o0 + (size_t)a.next * N;
-#pragma unroll
-  for (int i = 0; i < 16; i++) {
-    o0[i * 16] = d2u_canon(fp_reduce(acc0[i], qinv, q), q);
-    o1[i * 16] = d2u_canon(fp_reduce(acc1[i], qinv, q), q);
-  }
 }
 
 // Double-precision moduli, one key component per workgroup: grid.x = 2B, polynomial index bc = 2b + c. Each of the
@@ -371,6 +415,47 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
       for (int i = 0; i < 16; i++) acc[i] = fp_reduce(acc[i], qinv, q);
     }
   }
+  if (a.fin_tq) {
+    // The rest of the key switch for this tile (t is a main-prime slot): block pass of the ModDown correction, then
+    // out = (sum - correction) / P + addends. Addend modes per component: 0 none; 1 the plain addend fin_add2;
+    // 2 fin_add_src read through the Galois map (HRot's sigma(c0)); 3 both.
+    const u32 mode = c ? a.fin_mode1 : a.fin_mode0;
+    const u32 gf = a.multi ? g : a.fin_galois;
+    const size_t a2poly = a.fin_add2_three ? (size_t)b * 3 + c : (size_t)bc;
+    const u64* a2 = a.fin_add2 + (a2poly * a.nlimbs + t) * N;
+    const u64* as = a.fin_add_src + ((size_t)bc * a.nlimbs + t) * N;
+    {
+      const double* src = (const double*)(a.fin_tq + ((size_t)bc * a.nlimbs + t) * N) + lane_pos();
+#pragma unroll
+      for (int i = 0; i < 16; i++) x[i] = src[i * 16];
+    }
+    wave_lds_sync();
+    // the first addend is requested between the two rounds of the transform (e[] is free by now)
+    ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm, [&] {
+      const u32 pos = lane_pos();
+      if (mode & 1) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) e[i] = a2[pos + i * 16];
+      } else if (mode == 2) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) e[i] = as[galois_src_index16(pos + i * 16, gf)];
+      }
+    });
+    const double2 pv = ((const double2*)a.fin_pinv)[t];
+    u64* o = a.fin_out + ((size_t)bc * a.nlimbs + t) * N + lane_pos();
+    const u32 pos = lane_pos();
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      double r = fp_mulmod_const(fp_reduce(acc[i], qinv, q) - x[i], pv.x, pv.y, q);   // |r| <= 0.75 q
+      if (mode) r += u2d(e[i]);
+      if (mode == 3) {   // two addends: the gathered one is fetched here; bring the sum back below 2q first
+        r += u2d(as[galois_src_index16(pos + i * 16, gf)]);
+        r = r >= q ? r - q : r;
+      }
+      o[i * 16] = d2u_canon(r, q);
+    }
+    return;
+  }
   u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + lane_pos();
   if (a.accumulate) {   // a rotation kept in the extended basis, added to what acc holds (wave-uniform branch)
 #pragma unroll
@@ -397,96 +482,11 @@ ntt16_fwd_blocks_inner_c_kernel(FwdInnerArgs a) {
   fwd_inner_c_body_fp(a, bc, tile, t, id, mi, (double*)sm);
 }
 
-// Double-precision moduli, both key components in one workgroup, 8 values per lane: a workgroup of 256 lanes takes
+// Integer-class moduli (the special primes): both key components per workgroup, 8 values per lane: a workgroup takes
 // 8 of the 256-element blocks of a (ciphertext, slot) (grid.y = 32 tiles), each block transformed by 32 lanes
-// (ntt256_fwd_blocks_fp8). With half as many values per lane the two accumulator tiles, both key tiles of a digit
-// (requested between the first two rounds of the transform) and the transform itself fit in 3 waves per SIMD, so
-// every digit tile is read and transformed once. After the transform a lane holds 8 consecutive coefficients:
-// key words, own-digit words and the accumulators move as 16-byte accesses. Measured equal to the kernel above
-// (2.6 against 2.5 ms per step): kept as an alternative (tuning knob 3 = 3).
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
-ntt16_fwd_blocks_inner2_kernel(FwdInnerArgs a) {
-  __shared__ double sm[8 * NTT8_BLOCK_LDS];
-  u32 b, tile, zi;
-  ntt16_map(a.map_mode, b, tile, zi);
-  const u32 t = a.slots[zi];
-  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
-  const ModInfo mi = a.mods[id];
-  const size_t N = 65536;
-  const double q = mi.qd, qinv = mi.qinv;
-  const double* tw = a.twfp + (size_t)id * N;
-  const u32 tid = threadIdx.x, l = tid & 31, hb = tid >> 5, h = tile * 8 + hb;
-  double* smb = sm + hb * NTT8_BLOCK_LDS;
-  const u64* evk = fwd_inner_evk(a, b) + (size_t)id * N;
-  const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
-  const u32 posA = h * 256 + l;                              // element 0 of the lane before the transform
-  const u32 posC = h * 256 + (l >> 2) * 32 + (l & 3) * 8;    // first of its 8 consecutive elements after it
-  double acc0[8], acc1[8], x[8];
-  ulonglong2 e0[4], e1[4];
-#pragma unroll
-  for (int c = 0; c < 8; c++) acc0[c] = acc1[c] = 0.0;
-#pragma nounroll
-  for (u32 j = 0; j < a.beta; j++) {
-    const u64* kb = evk + (size_t)j * 2 * a.nm * N + posC;
-    const u64* ka = kb + (size_t)a.nm * N;
-    auto request_key = [&]() {
-#pragma unroll
-      for (int v = 0; v < 4; v++) {
-        e0[v] = *(const ulonglong2*)(kb + 2 * v);
-        e1[v] = *(const ulonglong2*)(ka + 2 * v);
-      }
-    };
-    if (fwd_inner_owns(a, t, j)) {
-      const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
-      request_key();
-      if (g) {
-#pragma unroll
-        for (int c = 0; c < 8; c++) x[c] = u2d(src[galois_src_index16(posC + c, g)]);
-      } else {
-#pragma unroll
-        for (int v = 0; v < 4; v++) {
-          const ulonglong2 w = *(const ulonglong2*)(src + posC + 2 * v);
-          x[2 * v] = u2d(w.x);
-          x[2 * v + 1] = u2d(w.y);
-        }
-      }
-    } else {
-      const double* src = (const double*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N) + posA;
-#pragma unroll
-      for (int i = 0; i < 8; i++) x[i] = src[i * 32];
-      wave_lds_sync();  // the previous digit's exchanges are done with the block's LDS rows
-      ntt256_fwd_blocks_fp8(x, tw, q, qinv, h, l, smb, request_key);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int v = 0; v < 4; v++) {
-      acc0[2 * v] += fp_mulmod_var(x[2 * v], u2d(e0[v].x), qinv, q);
-      acc0[2 * v + 1] += fp_mulmod_var(x[2 * v + 1], u2d(e0[v].y), qinv, q);
-      acc1[2 * v] += fp_mulmod_var(x[2 * v], u2d(e1[v].x), qinv, q);
-      acc1[2 * v + 1] += fp_mulmod_var(x[2 * v + 1], u2d(e1[v].y), qinv, q);
-    }
-    if ((j & 3) == 3) {   // each product is below 0.75 q: fold before the sums can reach 2^53
-#pragma unroll
-      for (int c = 0; c < 8; c++) {
-        acc0[c] = fp_reduce(acc0[c], qinv, q);
-        acc1[c] = fp_reduce(acc1[c], qinv, q);
-      }
-    }
-  }
-  u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + posC;
-  u64* o1 = o0 + (size_t)a.next * N;
-#pragma unroll
-  for (int v = 0; v < 4; v++) {
-    *(ulonglong2*)(o0 + 2 * v) = ulonglong2{d2u_canon(fp_reduce(acc0[2 * v], qinv, q), q),
-                                           d2u_canon(fp_reduce(acc0[2 * v + 1], qinv, q), q)};
-    *(ulonglong2*)(o1 + 2 * v) = ulonglong2{d2u_canon(fp_reduce(acc1[2 * v], qinv, q), q),
-                                           d2u_canon(fp_reduce(acc1[2 * v + 1], qinv, q), q)};
-  }
-}
-
-// The same for integer-class moduli (the special primes): both key components per workgroup, 8 values per lane, so
-// that the kernel runs at 3-4 waves per SIMD instead of the 2 the 16-values-per-lane form is held to. Products go
-// through a Montgomery reduction (acc carries the factor 2^-64), as in fwd_inner_body.
+// (ntt256_fwd_blocks_int8), which keeps the kernel at 3 waves per SIMD. After the transform a lane holds 8 consecutive
+// coefficients, so key words and accumulators move as 16-byte accesses. Products go through a Montgomery reduction:
+// acc carries the factor 2^-64, which the later stages absorb into their constants.
 template <int CLS>
 __global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerArgs a) {
   constexpr bool BIG = CLS == 2;
@@ -584,21 +584,6 @@ __global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerAr
     *(ulonglong2*)(o0 + 2 * v) = ulonglong2{csub(acc0[2 * v], q), csub(acc0[2 * v + 1], q)};
     *(ulonglong2*)(o1 + 2 * v) = ulonglong2{csub(acc1[2 * v], q), csub(acc1[2 * v + 1], q)};
   }
-}
-
-// The 16-values-per-lane form of the kernels above (both key components, 240-248 registers, 2 waves per SIMD):
-// the first version of this fusion, kept selectable (tuning knobs 2 = 0 / 3 = 0).
-template <int CLS>
-__global__ void __launch_bounds__(NTT16_THREADS) ntt16_fwd_blocks_inner_kernel(FwdInnerArgs a) {
-  __shared__ u64 sm[NTT16_LDS_BYTES / 8];
-  u32 b, tile, zi;
-  ntt16_map(a.map_mode, b, tile, zi);
-  const u32 t = a.slots[zi];
-  const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
-  const ModInfo mi = a.mods[id];
-  if (CLS == 0) fwd_inner_body_fp(a, b, tile, t, id, mi, (double*)sm);
-  else if (CLS == 2) fwd_inner_body<true>(a, b, tile, t, id, mi, sm);
-  else fwd_inner_body<false>(a, b, tile, t, id, mi, sm);
 }
 
 // ---- fused: last forward pass of the ModDown correction + final assembly ----

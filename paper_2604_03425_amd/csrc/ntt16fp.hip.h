@@ -56,13 +56,12 @@ __device__ __forceinline__ void radix16_inv_fp(double (&x)[16], double q, double
   }
 }
 
-// Forward, stages 0..7. src holds canonical residues (uint64); dst receives reduced doubles.
-__device__ __forceinline__ void ntt16_fwd_rows_fp(const u64* __restrict__ src, double* __restrict__ dst,
-                                                  const double* __restrict__ tw, double q, double qinv, u32 tile, double* sm) {
+// Forward, stages 0..7. `x` holds integers of magnitude at most q (residues as doubles) in the row layout of
+// ntt16_fwd_rows_loaded; dst receives reduced doubles.
+__device__ __forceinline__ void ntt16_fwd_rows_fp_loaded(double (&x)[16], double* __restrict__ dst,
+                                                         const double* __restrict__ tw, double q, double qinv, u32 tile,
+                                                         double* sm) {
   const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
-  double x[16];
-#pragma unroll
-  for (int i = 0; i < 16; i++) x[i] = u2d(src[(size_t)(i * 16 + r0) * 256 + col0 + col]);
   const u32 i0 = r0;
   double twb[15];  // second-round twiddles, requested before the first round
 #pragma unroll
@@ -78,6 +77,15 @@ __device__ __forceinline__ void ntt16_fwd_rows_fp(const u64* __restrict__ src, d
   radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return twb[(1 << s) - 1 + g]; });
 #pragma unroll
   for (int j = 0; j < 16; j++) dst[(size_t)(i0 * 16 + j) * 256 + col0 + col] = x[j];
+}
+// The same from canonical residues (uint64) in memory.
+__device__ __forceinline__ void ntt16_fwd_rows_fp(const u64* __restrict__ src, double* __restrict__ dst,
+                                                  const double* __restrict__ tw, double q, double qinv, u32 tile, double* sm) {
+  const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
+  double x[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) x[i] = u2d(src[(size_t)(i * 16 + r0) * 256 + col0 + col]);
+  ntt16_fwd_rows_fp_loaded(x, dst, tw, q, qinv, tile, sm);
 }
 
 // Forward, stages 8..15 on reduced doubles. Leaves x (|x| <= q/2) in the i-layout of ntt16_fwd_blocks.

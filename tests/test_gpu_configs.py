@@ -389,9 +389,10 @@ def test_extreme_residues(gpu, shape):
 
 
 def test_tuning_knobs_do_not_change_results(gpu):
-    """Every alternative code path selectable with ckks_tune_set gives the oracle's bits: workgroup mappings,
-    the three forms of the inner product on double-precision moduli, the 3-wave build of the fused kernel, and the
-    two-stream fork/join of a key switch."""
+    """Every alternative code path selectable with ckks_tune_set gives the oracle's bits: workgroup mappings, the
+    unfused form of the inner product on double-precision moduli (plain block pass, streaming product, separate
+    assembly kernel), the base conversions done inside the row passes, integer-only arithmetic, the general
+    base-conversion reduction, and the two-stream fork/join of a key switch."""
     import torch
     from gpu_util import to_dev, to_host, assert_same
     p = make_params(16, 5, 50, 3, 60, 2)
@@ -406,8 +407,8 @@ def test_tuning_knobs_do_not_change_results(gpu):
     ref.set_threads(1)
     d_ct, d_evk = to_dev(ct), to_dev(evk)
     d_rev = d_ct.flip(0).contiguous()
-    for knobs in ({0: 0}, {0: 1}, {0: 2}, {0: 3}, {3: 0}, {3: 0, 2: 0}, {2: 0}, {3: 1}, {3: 1, 4: 0}, {3: 2}, {3: 2, 4: 0}, {3: 3},
-                  {3: 3, 4: 0}, {1: 1, 3: 0}, {1: 1, 3: 1}, {1: 1, 2: 0, 3: 1}):
+    for knobs in ({0: 0}, {0: 1}, {0: 2}, {0: 3}, {0: 4}, {3: 1}, {3: 1, 4: 0}, {4: 0}, {1: 1}, {1: 1, 3: 1}, {5: 1},
+                  {5: 1, 4: 0}, {2: 1}, {2: 1, 4: 0}, {2: 1, 5: 1}, {2: 1, 1: 1}, {2: 1, 3: 1}):
         gc = gpu.Context(p)
         for k, v in knobs.items():
             gpu.ckks_tune_set(gc, k, v)
@@ -586,7 +587,7 @@ def test_pcmm_schedules_under_knobs(gpu):
     ref.set_threads(1)
     d_ct, d_pte, d_pt = to_dev(ct), to_dev(pte), to_dev(pt)
     dbk, dgk = [to_dev(k) for k in bk], [to_dev(k) for k in gk]
-    for knobs in [{1: 1}, {5: 1}, {6: 1}, {0: 0}, {0: 2}, {3: 0}, {3: 3}, {2: 0}, {4: 0}, {1: 1, 5: 1, 6: 1}]:
+    for knobs in [{1: 1}, {5: 1}, {6: 1}, {0: 0}, {0: 2}, {3: 1}, {4: 0}, {2: 1}, {1: 1, 5: 1, 6: 1}]:
         gc = gpu.Context(p)
         for k, v in knobs.items():
             gpu.ckks_tune_set(gc, k, v)

@@ -314,9 +314,14 @@ def test_argument_errors(gpu):
     with pytest.raises(gpu.CkksError) as e:
         gpu.ckks_hrot(gc, out, x, 1, 4, 4, evk, ws)            # even Galois element
     assert e.value.code == -1
+    x5 = torch.zeros((1, 2, 5, p.N), dtype=torch.int64, device="cuda")
     with pytest.raises(gpu.CkksError) as e:
-        gpu.ckks_hrot(gc, out, x, 1, 5, 5, evk, ws)            # more limbs than the context has
+        gpu.ckks_hrot(gc, torch.empty_like(x5), x5, 1, 5, 5, evk, ws)   # more limbs than the context has
     assert e.value.code == -2
+    with pytest.raises(ValueError):
+        gpu.ckks_hrot(gc, out, x, 2, 4, 5, evk, ws)            # the binding refuses tensors smaller than the call's shape
+    with pytest.raises(ValueError):
+        gpu.ckks_hrot(gc, out, x, 1, 4, 5, evk[:1], ws)        # ... and a key with too few digits
     with pytest.raises(gpu.CkksError) as e:
         gpu.ckks_hrot(gc, out, x, 1, 4, 5, evk, ws[:1024])     # workspace too small
     assert e.value.code == -3
