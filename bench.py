@@ -38,17 +38,23 @@ OPS_BUTTERFLY_FP, OPS_MULRED_FP, OPS_SHOUP_FP = 9.5, 7, 6
 OPS_DOT30, OPS_REDUCE90 = 4, 27
 
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload in its default
-# configuration (bytes, average over the two launches of a step: 64 rotations, 32 products; fetch scaled by the
-# copy-kernel calibration); the counter summary is kept under profiles/.
-MEASURED_TRAFFIC = {
-    "moddown_kernel": 1610744934, "modup_kernel": 2416124006,
-    "ntt16_fwd_blocks_final_kernel<0>": 4565991014, "ntt16_fwd_blocks_inner8_kernel<2>": 1834122445,
-    "ntt16_fwd_blocks_inner_c_kernel": 5507694387, "ntt16_fwd_rows_kernel<0>": 2416117350,
-    "ntt16_fwd_rows_kernel<2>": 1208248115, "ntt16_inv_blocks_kernel<0>": 1222694707,
-    "ntt16_inv_blocks_kernel<2>": 815880192, "ntt16_inv_rows_kernel<0>": 1208182374,
-    "ntt16_inv_rows_kernel<2>": 805633434, "tensor_kernel": 2818658918,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "keyswitch_micro_traffic.json")
+
+
+def measured_traffic():
+    """HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs on this workload in its default
+    configuration, as written by paper_2604_03425_amd/profile_summary.py into profiles/ together with the digest of
+    the sources they were taken on. Returns {} when that digest is not the one of the sources in this tree (the
+    counters then describe other kernels and the line reports traffic: null)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return {}
+    from paper_2604_03425_amd.srcdigest import source_digest
+    if rec.get("source_sha256") != source_digest():
+        return {}
+    return {k: int(v) for k, v in rec.get("hbm_bytes_per_launch", {}).items()}
 
 
 def keyswitch_model(p, B, nl, hrot, hmult, fp_inner=2, bconv_fused=False):
@@ -145,6 +151,59 @@ def _time(torch, fn, iters):
     return (time.perf_counter() - t) / iters
 
 
+def _time_events(torch, fn, iters, warmup=3):
+    """Median of `iters` HIP-event timings of fn (seconds) on torch's current stream, which is the stream the library
+    is handed, after `warmup` untimed calls."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        e1.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e-3)
+    ts.sort()
+    return ts[len(ts) // 2]
+
+
+def _host(t):
+    import numpy as np
+    return t.cpu().numpy().view(np.uint64)
+
+
+def _fail_parity(what):
+    print("bench.py: GPU output differs from the oracle on the sample (%s)" % what, file=sys.stderr)
+    sys.exit(3)
+
+
+def _oracle_pcmm_one(rc, ct1, pt, n1, n2, stride, baby, giant, logN, threads):
+    """The BSGS definition (one rotation at a time) for ONE ciphertext [1][2][nl][N] through the oracle's HRot and
+    pointwise calls, the independent rotations and inner sums spread over host threads."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from ckks_inputs import galois_element
+    nl = ct1.shape[2]
+    ids = list(range(nl))
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        rots = [ct1] + list(ex.map(lambda b: rc.hrot(ct1, galois_element(b * stride, logN), baby[b - 1]), range(1, n1)))
+
+        def inner(g):
+            acc = None
+            for b in range(n1):
+                t = rc.pointwise(rots[b][0], pt[g, b][None], ids, "mul")
+                acc = t if acc is None else rc.pointwise(acc, t, ids, "add")
+            acc = acc[None]
+            return acc if g == 0 else rc.hrot(acc, galois_element(g * n1 * stride, logN), giant[g - 1])
+        parts = list(ex.map(inner, range(n2)))
+    out = parts[0]
+    for part in parts[1:]:
+        out = rc.pointwise(out[0], part[0], ids, "add")[None]
+    return out
+
+
 def other_workloads(args):
     """Secondary workloads (not the headline metric): `pcmm` = the FFN layer share, `attention` = QK^T units,
     `sweep` = level/dnum sweep. Each prints its own JSON line(s)."""
@@ -153,7 +212,58 @@ def other_workloads(args):
     from ckks_inputs import config_params, galois_element, make_params
     dev = "cuda:0"
     gen = torch.Generator(device=dev).manual_seed(0xFEED)
-    if args.workload == "pcmm":
+    if args.workload == "calibrate":
+        # the copy kernel of known size the HBM byte counters are calibrated on: 1 GiB read + 1 GiB written per launch
+        p = config_params("tiny_hrot")
+        ctx = ck.Context(p, 0)
+        src = torch.ones(1 << 27, dtype=torch.int64, device=dev)
+        dst = torch.zeros_like(src)
+        dt = _time_events(torch, lambda: ck.ckks_prof_copy(ctx, dst, src), 3, warmup=0)
+        assert torch.equal(dst, src)
+        print(json.dumps({"workload": "calibrate", "kernel": "ckks_prof_copy_kernel", "launches": 3,
+                          "bytes_read_per_launch": src.numel() * 8, "bytes_written_per_launch": src.numel() * 8,
+                          "copy_GBps": round(2 * src.numel() * 8 / dt / 1e9, 1)}))
+    elif args.workload == "ntt":
+        # the transforms alone on the batch of the key-switch micro-benchmark: [64 * 2][24] limb-vectors of 2^16
+        # residues (50-bit primes), forward then inverse, `--steps` times; --int-only forces the integer bodies
+        # (64-bit Shoup butterflies from 32-bit multiplies) that the double-precision bodies replace by default
+        p = config_params("keyswitch_micro")
+        N, nl, B = p.N, len(p.q), 64
+        ctx = ck.Context(p, 0)
+        if args.int_only:
+            ck.ckks_tune_set(ctx, 1, 1)
+        x = _uniform(torch, gen, dev, (B * 2,), p.q, N)
+        x0 = x[:2].clone()
+        ids = list(range(nl))
+        for _ in range(max(1, args.warmup)):
+            ck.ckks_ntt(ctx, x, B * 2, ids)
+            ck.ckks_intt(ctx, x, B * 2, ids)
+        torch.cuda.synchronize()
+        ck.ckks_prof_reset(ctx)
+        ck.ckks_prof_enable(ctx, True)
+        for _ in range(args.steps):
+            ck.ckks_ntt(ctx, x, B * 2, ids)
+            ck.ckks_intt(ctx, x, B * 2, ids)
+        torch.cuda.synchronize()
+        ck.ckks_prof_enable(ctx, False)
+        prof = ck.ckks_prof_collect(ctx)
+        assert torch.equal(x[:2], x0), "INTT(NTT(x)) != x"
+        limbs = B * 2 * nl
+        ops_bf = OPS_BUTTERFLY if args.int_only else OPS_BUTTERFLY_FP
+        kinds = {}
+        for k, (ms, n) in prof.items():
+            t = ms * 1e-3 / n                    # one pass (8 of the 16 stages) over every limb
+            kinds[k] = dict(avg_launch_us=round(t * 1e6, 2), GBps=round(limbs * 2 * 8 * N / t / 1e9, 1),
+                            modelled_Tops=round(limbs * (N / 2) * 8 * ops_bf / t / 1e12, 2))
+        fwd = sum(ms for k, (ms, n) in prof.items() if "fwd" in k) * 1e-3 / args.steps
+        inv = sum(ms for k, (ms, n) in prof.items() if "inv" in k) * 1e-3 / args.steps
+        print(json.dumps({"workload": "ntt", "arithmetic": "int32 (Shoup, 24 instructions per butterfly)" if args.int_only
+                          else "fp64 (9.5 instructions per butterfly)", "limb_vectors": limbs,
+                          "ntt_limbs_per_s": round(limbs / fwd), "intt_limbs_per_s": round(limbs / inv),
+                          "ntt_hbm_frac": round(limbs * 4 * 8 * N / fwd / 1e9 / PEAK_HBM_GBS, 4),
+                          "ntt_alu_frac_modelled_ops": round(limbs * (N / 2) * 16 * ops_bf / fwd / 1e12 / PEAK_ALU_TOPS, 4),
+                          "kernels": kinds}))
+    elif args.workload == "pcmm":
         # 2048 tokens x 768 hidden in 128 ciphertexts (16 tokens each), 768x768 weight slice as 32 x 24 diagonals,
         # processed in calls of `--pcmm-batch` ciphertexts; 31 baby + 23 giant rotation keys shared by all
         p = config_params("keyswitch_micro")
@@ -199,6 +309,26 @@ def other_workloads(args):
         dh_call()
         ck.ckks_prof_enable(ctx, False)
         prof_d = {k: round(v[0], 2) for k, v in ck.ckks_prof_collect(ctx).items()}
+        # parity of what was timed: ciphertext `Bc - 1` of the plain and of the hoisted call against the oracle
+        checked = None
+        if not args.no_cpu_baseline:
+            from oracle import ref
+            threads = min(16, os.cpu_count() or 1)
+            rc = ref.RefContext(p)
+            ref.set_threads(1)
+            b1 = Bc - 1
+            t_or = time.perf_counter()
+            want = _oracle_pcmm_one(rc, _host(ct[b1:b1 + 1]), _host(pt), n1, n2, 1, [_host(k) for k in baby[:n1 - 1]],
+                                    [_host(k) for k in giant[:n2 - 1]], p.logN, threads)
+            t_or = time.perf_counter() - t_or
+            for name, fn in (("ckks_pcmm_bsgs", ck.ckks_pcmm_bsgs), ("ckks_pcmm_bsgs_hoisted", ck.ckks_pcmm_bsgs_hoisted)):
+                wsc = ctx.workspace(ck.OP_PCMM_BSGS, Bc, nl, n1)
+                fn(ctx, out, ct, Bc, nl, pt, n1, n2, 1, baby[:n1 - 1], giant[:n2 - 1], wsc)
+                torch.cuda.synchronize()
+                if not (_host(out[b1:b1 + 1]) == want).all():
+                    _fail_parity(name)
+                del wsc
+            checked = "ciphertext %d of the plain and the hoisted call equals the oracle's BSGS (%.0f s on %d threads)" % (b1, t_or, threads)
         rots = Bc * (n1 - 1 + n2 - 1)
         # inner sums on the double-precision limbs: 7 FP64 instructions per multiply-add (exact product in two
         # parts, quotient, remainder, accumulate), against the chip's FP64 vector issue rate
@@ -210,7 +340,7 @@ def other_workloads(args):
             tops = macs * OPS_MULRED_FP / (pm_ms * 1e-3) / 1e12
             pm_roof = {"bound": "alu", "kernel": "pmacc_fp_kernel", "achieved": round(tops, 2), "peak": round(PEAK_ALU_TOPS, 1),
                        "unit": "T lane-instructions/s", "frac": round(tops / PEAK_ALU_TOPS, 3)}
-        print(json.dumps({"workload": "pcmm_ffn_share", "inner_sum_roofline": pm_roof, "ciphertexts_per_call": Bc, "seconds_per_call": round(dt, 4),
+        print(json.dumps({"workload": "pcmm_ffn_share", "gpu_matches_oracle_on_sample": checked, "inner_sum_roofline": pm_roof, "ciphertexts_per_call": Bc, "seconds_per_call": round(dt, 4),
                           "seconds_for_128_ciphertexts": round(dt * total / Bc, 3), "hrot_per_s": round(rots / dt, 1),
                           "hoisted_seconds_per_call": round(dth, 4),
                           "hoisted_seconds_for_128_ciphertexts": round(dth * total / Bc, 3),
@@ -243,6 +373,7 @@ def other_workloads(args):
             for i in range(6):   # rotate-and-sum: next = cur + HRot(cur)
                 ck.ckks_hrot_add(ctx, nxt, cur, cur, B, nl, galois_element(1 << i, p.logN), rot[i], ws)
                 cur, nxt = nxt, cur
+            return cur
         dt = _time(torch, units, 2)
         # the same slot sums as two hoisted sums (rotations by 1..7, then by 8, 16, .., 56): 2 decompositions and 2
         # ModDowns instead of 6 key switches, 14 rotation keys instead of 6
@@ -255,8 +386,35 @@ def other_workloads(args):
             ck.ckks_hmult_relin(ctx, acc, qa, kb, B, nl, relin, ws)
             ck.ckks_hrot_sum(ctx, tmp, acc, B, nl, g_in, rot14[:7], ws_sum)
             ck.ckks_hrot_sum(ctx, acc, tmp, B, nl, g_out, rot14[7:], ws_sum)
+            return acc
         dth = _time(torch, units_hoisted, 2)
-        print(json.dumps({"workload": "attention_qk_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
+        # parity of what was timed: the first two units of both forms against the same sequences on the oracle
+        checked = None
+        if not args.no_cpu_baseline:
+            from oracle import ref
+            ns = min(2, B)
+            rc = ref.RefContext(p)
+            ref.set_threads(ns)
+            ids = list(range(nl))
+            t_or = time.perf_counter()
+            w = rc.hmult_relin(_host(qa[:ns]), _host(kb[:ns]), _host(relin))
+            prod = w
+            for i in range(6):
+                w = rc.pointwise(w, rc.hrot(w, galois_element(1 << i, p.logN), _host(rot[i])), ids, "add")
+            wh = rc.hrot_sum(prod, g_in, [_host(k) for k in rot14[:7]])
+            wh = rc.hrot_sum(wh, g_out, [_host(k) for k in rot14[7:]])
+            t_or = time.perf_counter() - t_or
+            got = units()
+            torch.cuda.synchronize()
+            if not (_host(got[:ns]) == w).all():
+                _fail_parity("attention unit")
+            got = units_hoisted()
+            torch.cuda.synchronize()
+            if not (_host(got[:ns]) == wh).all():
+                _fail_parity("attention unit, hoisted sums")
+            checked = "units 0..%d of both forms equal the oracle's (%.0f s on %d threads)" % (ns - 1, t_or, ns)
+        print(json.dumps({"workload": "attention_qk_units", "gpu_matches_oracle_on_sample": checked,
+                          "units_per_call": B, "units_per_s": round(B / dt, 1),
                           "units_per_s_hoisted_sums": round(B / dth, 1),
                           "key_switches_per_s": round(7 * B / dt, 1),
                           "note": "unit = HMult+relin + 6 rotate-and-sum HRot at 20 limbs, dnum=4, K=5; "
@@ -299,6 +457,27 @@ def other_workloads(args):
         late = [False]
         acc3 = torch.zeros((B, 3, nl - 2, N), dtype=torch.int64, device=dev)
         dt = _time(torch, units, 2)
+        # parity of what was timed: the first two units against the same sequence of calls on the oracle
+        checked = None
+        if not args.no_cpu_baseline:
+            from oracle import ref
+            ns = min(2, B)
+            rc = ref.RefContext(p)
+            ref.set_threads(ns)
+            t_or = time.perf_counter()
+            w = rc.hmult_relin(_host(qa[:ns]), _host(kb[:ns]), _host(relin))
+            for i in range(6):
+                w = rc.pointwise(w, rc.hrot(w, galois_element(1 << i, p.logN), _host(rot[i])), list(range(nl)), "add")
+            w = rc.rescale(rc.pmult(rc.rescale(w), _host(mask)))
+            for i in range(6):
+                w = rc.pointwise(w, rc.hrot(w, galois_element(-(1 << i), p.logN), _host(rot[6 + i])), list(range(nl - 2)), "add")
+            w = rc.hmult_relin(w, _host(vb[:ns]), _host(relin))
+            t_or = time.perf_counter() - t_or
+            units()
+            torch.cuda.synchronize()
+            if not (_host(out[:ns]) == w).all():
+                _fail_parity("attention A x V unit")
+            checked = "units 0..%d equal the oracle's (%.0f s on %d threads)" % (ns - 1, t_or, ns)
         # late relinearisation (Sec. 5.2): the products with V of a block's 64 diagonals stay in three components
         # and share one key switch, timed here as 64 calls of the unit followed by one ckks_relin
         late[0] = True
@@ -332,7 +511,8 @@ def other_workloads(args):
                 units_hoisted()
             ck.ckks_relin(ctx, out, acc3, B, nl - 2, relin, ws)
         dt_h = _time(torch, block_hoisted, 1) / 64
-        print(json.dumps({"workload": "attention_av_units", "units_per_call": B, "units_per_s": round(B / dt, 1),
+        print(json.dumps({"workload": "attention_av_units", "gpu_matches_oracle_on_sample": checked,
+                          "units_per_call": B, "units_per_s": round(B / dt, 1),
                           "key_switches_per_s": round(14 * B / dt, 1),
                           "units_per_s_late_relin": round(B / dt_late, 1),
                           "units_per_s_hoisted_sums": round(B / dt_h, 1),
@@ -354,14 +534,23 @@ def other_workloads(args):
                 evk = _uniform(torch, gen, dev, (p.dnum, 2), p.moduli, p.N)
                 out = torch.empty((B, 2, limbs, p.N), dtype=torch.int64, device=dev)
                 ws = ctx.workspace(ck.OP_KEYSWITCH, B, limbs)
-                dt = _time(torch, lambda: ck.ckks_keyswitch(ctx, out, d, B, limbs, evk, 0, dnum, ws), 2)
+                dt = _time_events(torch, lambda: ck.ckks_keyswitch(ctx, out, d, B, limbs, evk, 0, dnum, ws), 20)
                 x = _uniform(torch, gen, dev, (B * 2,), p.q, p.N)
                 ids = list(range(limbs))
-                dn = _time(torch, lambda: ck.ckks_ntt(ctx, x, B * 2, ids), 2)
+                dn = _time_events(torch, lambda: ck.ckks_ntt(ctx, x, B * 2, ids), 20)
+                if not args.no_cpu_baseline:   # parity of what was timed: ciphertext 0 of the key switch
+                    from oracle import ref
+                    rc = ref.RefContext(p)
+                    ref.set_threads(1)
+                    torch.cuda.synchronize()
+                    if not (_host(out[:1]) == rc.keyswitch(_host(d[:1]), _host(evk))).all():
+                        _fail_parity("sweep point %d limbs, dnum %d" % (limbs, dnum))
                 model = keyswitch_model(p, B, limbs, False, False)
                 nbytes = sum(v["bytes"] for v in model.values())
                 nops = sum(v["ops"] for v in model.values())
                 print(json.dumps({"workload": "sweep", "limbs": limbs, "dnum": dnum, "K": K, "batch": B,
+                                  "timing": "median of 20 HIP-event iterations after 3 warm-ups",
+                                  "gpu_matches_oracle_on_sample": not args.no_cpu_baseline,
                                   "key_switches_per_s": round(B / dt, 1), "ntt_limbs_per_s": round(B * 2 * limbs / dn),
                                   "hbm_frac_modelled_bytes": round(nbytes / dt / 1e9 / PEAK_HBM_GBS, 3),
                                   "alu_frac_modelled_ops": round(nops / dt / 1e12 / PEAK_ALU_TOPS, 3),
@@ -387,7 +576,7 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="experiment: time the steps without the per-kernel HIP events (no phases, no roofline)")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate NTT / HRot / HMult timings (profiling runs)")
-    ap.add_argument("--workload", default="keyswitch_micro", choices=["keyswitch_micro", "pcmm", "attention", "attention_av", "sweep"])
+    ap.add_argument("--workload", default="keyswitch_micro", choices=["keyswitch_micro", "pcmm", "attention", "attention_av", "sweep", "ntt", "calibrate"])
     ap.add_argument("--pcmm-batch", type=int, default=32)
     ap.add_argument("--pcmm-n1", type=int, default=32, help="baby steps (32 x 24 = the FFN share; 8 x 8 = a 64-slot block)")
     ap.add_argument("--pcmm-n2", type=int, default=24, help="giant steps")
@@ -506,6 +695,7 @@ def main():
                             Tops=round(mdl["ops"] / per_step_ms / 1e9, 2) if per_step_ms else None)
     # the counter runs were made in the default configuration only
     default_cfg = (G == 64 and multi and not args.tune and not args.int_only and args.map_mode is None and nstreams == 1)
+    traffic_tab = measured_traffic() if default_cfg else {}
     dom = max(prof.items(), key=lambda kv: kv[1][0])[0] if prof else None
     d = phases[dom] if dom else dict(GBps=None, Tops=None, avg_launch_us=None)
     hbm_frac = (d["GBps"] or 0) / PEAK_HBM_GBS
@@ -514,10 +704,10 @@ def main():
         roofline = None
     elif alu_frac >= hbm_frac:
         roofline = dict(bound="alu", kernel=dom, achieved=d["Tops"], peak=round(PEAK_ALU_TOPS, 1), unit="Tlane-op/s",
-                        frac=round(alu_frac, 4), traffic=MEASURED_TRAFFIC.get(dom) if default_cfg else None, avg_launch_us=d["avg_launch_us"])
+                        frac=round(alu_frac, 4), traffic=traffic_tab.get(dom) if default_cfg else None, avg_launch_us=d["avg_launch_us"])
     else:
         roofline = dict(bound="hbm", kernel=dom, achieved=d["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(hbm_frac, 4), traffic=MEASURED_TRAFFIC.get(dom) if default_cfg else None, avg_launch_us=d["avg_launch_us"])
+                        frac=round(hbm_frac, 4), traffic=traffic_tab.get(dom) if default_cfg else None, avg_launch_us=d["avg_launch_us"])
     total_bytes = sum(v["bytes"] for v in model.values())
     total_ops = sum(v["ops"] for v in model.values())
     # compulsory traffic of a step: read every input ciphertext and key once, write every output once
@@ -539,6 +729,10 @@ def main():
       scratch = ct.clone()
       t_ntt = timed(lambda: ck.ckks_ntt(ctx, scratch, B * 2, ids), 5)
       t_intt = timed(lambda: ck.ckks_intt(ctx, scratch, B * 2, ids), 5)
+      ctx_int = ck.Context(p, 0)
+      ck.ckks_tune_set(ctx_int, 1, 1)
+      t_ntt_int = timed(lambda: ck.ckks_ntt(ctx_int, scratch, B * 2, ids), 5)
+      ctx_int.close()
       t_rot = timed(lambda: [ck.ckks_hrot(ctx, out_rot[g * Bg:(g + 1) * Bg], ct[g * Bg:(g + 1) * Bg], Bg, nl, gal[g], evks[g], ws)
                              for g in range(G)], 3)
       t_rot1 = timed(lambda: ck.ckks_hrot(ctx, out_rot, ct, B, nl, gal[0], evks[0],
@@ -571,7 +765,12 @@ def main():
                  automorph_coeff_GBps=round(B * 2 * nl * 2 * 8 * N / t_auc / 1e9, 1),
                  pmult_hbm_frac=round(B * 2 * nl * 2 * 8 * N / t_pm / 1e9 / PEAK_HBM_GBS, 4),
                  add_hbm_frac=round(B * 2 * nl * 3 * 8 * N / t_ad / 1e9 / PEAK_HBM_GBS, 4),
-                   ntt_int32_equiv_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
+                   # executed arithmetic of the standalone NTT against the 39.3 T lane-ops/s vector issue rate: the
+                   # default path runs 9.5 FP64 instructions per butterfly on these 50-bit limbs; the integer bodies
+                   # (knob 1, timed on a context of their own) 24 32-bit integer instructions per butterfly
+                   ntt_fp64_issue_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY_FP / t_ntt / 1e12 / PEAK_ALU_TOPS, 4),
+                   ntt_int_limbs_per_s=round(B * 2 * nl / t_ntt_int),
+                   ntt_int32_alu_frac=round(B * 2 * nl * (N / 2) * p.logN * OPS_BUTTERFLY / t_ntt_int / 1e12 / PEAK_ALU_TOPS, 4),
                  ntt_hbm_frac=round(B * 2 * nl * 4 * 8 * N / t_ntt / 1e9 / PEAK_HBM_GBS, 4),
                    hbm_frac_compulsory_bytes=round(compulsory * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),
                    hbm_frac_modelled_bytes=round(total_bytes * args.steps / sec / 1e9 / PEAK_HBM_GBS, 4),
@@ -593,8 +792,15 @@ def main():
         r1 = rctx.hrot(h_ct, gal[0], h_evk)
         r2 = rctx.hmult_relin(h_ct[0::2], h_ct[1::2], h_mul)
         cpu_sec = time.perf_counter() - t
+        ref.set_threads(1)
+        t = time.perf_counter()
+        r1_one = rctx.hrot(h_ct[:1], gal[0], h_evk)
+        one_sec = time.perf_counter() - t
+        assert (r1_one == r1[:1]).all()
         cpu = dict(value=round((ns + ns // 2) / cpu_sec, 3), unit="key-switches/s", cores=threads, kind="oracle",
-                   sample="%d HRot + %d HMult+relin of the same workload (N=2^16, 24 limbs, dnum=3), %.1f s" % (ns, ns // 2, cpu_sec))
+                   sample="%d HRot + %d HMult+relin of the same workload (N=2^16, 24 limbs, dnum=3), %.1f s on %d threads; "
+                          "single thread: 1 HRot in %.1f s" % (ns, ns // 2, cpu_sec, threads, one_sec),
+                   single_thread_value=round(1.0 / one_sec, 3), host_cpus=os.cpu_count())
         # the sample doubles as an end-of-run parity check of the timed configuration
         chk = torch.empty_like(ct[:ns])
         ck.ckks_hrot(ctx, chk, ct[:ns].contiguous(), ns, nl, gal[0], evks[0], ctx.workspace(ck.OP_HROT, ns, nl))

@@ -30,10 +30,10 @@
  * library owns only the context and its constant tables.
  *
  * Streams: every call enqueues its kernels on `stream` (a hipStream_t passed as void*;
- * NULL = the default stream) and returns without synchronising. With tuning knob 4 set to 0 a
- * key switch runs part of its kernels on a second stream owned by the context, forked from and
- * joined back into `stream` with events, so everything is ordered as if it ran on `stream`
- * alone. Calls on one context must not be issued from several host threads at once. Workspace passed to a
+ * NULL = the default stream) and returns without synchronising or allocating: every table a
+ * call needs is built by ckks_ctx_create. With tuning knob 4 set to 0 a key switch runs part of its
+ * kernels on a second stream owned by the context, forked from and joined back into `stream` with
+ * events, so everything is ordered as if it ran on `stream` alone. Calls on one context must not be issued from several host threads at once. Workspace passed to a
  * call must stay untouched until that stream has drained the call.
  *
  * Errors: calls return CKKS_OK or a negative code; they never throw or abort. After a
@@ -72,8 +72,8 @@ const char* ckks_last_error(void);
 /*
  * Create a context on GPU `device` for ring degree 2^logN (10 <= logN <= 17), main primes
  * q[0..nq) (the top level, L+1 = nq), special primes p[0..np), and digit count dnum
- * (digit width alpha = ceil(nq/dnum) limbs; paper Sec. 2.1: special primes "used for digit
- * decomposition"). psi[i] is a primitive 2N-th root of unity modulo the i-th modulus
+ * (digit width alpha = ceil(nq/dnum) limbs; paper Sec. 2.1, last paragraph: the special primes serve the digit
+ * decomposition of key switching). psi[i] is a primitive 2N-th root of unity modulo the i-th modulus
  * (q first, then p). All three arrays are host pointers. Every modulus must be a distinct
  * prime < 2^60 congruent to 1 mod 2N, and psi[i]^N must be -1; otherwise CKKS_EINVAL.
  * Builds twiddle tables and base-conversion constants in device memory owned by the context.
@@ -273,7 +273,7 @@ int ckks_hrot_sum(ckks_ctx* ctx, uint64_t* ct_out, const uint64_t* ct_in, uint32
                   void* stream);
 
 /*
- * Rescale (paper Sec. 2.1: "divides by the last modulus q_L to reduce scale and remove one prime"): for
+ * Rescale (paper Sec. 2.1: division by the last modulus of the chain, which lowers the scale and drops that prime): for
  * ct_in [B][2][nlimbs][N] (device, evaluation domain, nlimbs >= 2) writes ct_out [B][2][nlimbs-1][N] with
  * every coefficient c replaced by round(c / q_{nlimbs-1}) (centred representatives, exact). ct_out must not
  * overlap ct_in.
@@ -300,20 +300,25 @@ int ckks_add(ckks_ctx* ctx, uint64_t* out, const uint64_t* a, const uint64_t* b,
  * Not thread-safe: use one thread per context while profiling.
  */
 int ckks_prof_enable(ckks_ctx* ctx, int on);
-/* Tuning knobs for experiments: knob 0 = workgroup-to-tile mapping of the N = 2^16 kernels (0..4 forces one
- * mapping everywhere; default -1 chooses per kernel);
- * knob 1 != 0 turns the double-precision bodies for primes < 2^50 off (integer bodies everywhere);
- * knob 2 picks the fused inner product on integer-class moduli: 2 (default) = 8 values per lane, 0 = 16; knob 3 picks the inner product
- * on double-precision moduli: 0 = block pass fused with both key components (two accumulator tiles), 1 = plain
- * block pass followed by a streaming product, 2 (default) = block pass fused with one key component per workgroup,
- * 3 = block pass with 8 values per lane fused with both key components; knob 4 == 0 lets a key switch fork its two independent kernel
- * chains (double-precision slots / special-prime slots) onto a second internal stream and join them before the
- * result is assembled (default 1: everything on the caller's stream); knob 5 != 0 makes every base conversion
- * use the general four-sum accumulation with a 128-bit Montgomery reduction, also where the bit sizes of the
- * bases would allow the shorter three-sum form (set before the first call at a given limb count); knob 6 != 0
- * computes the inner sums of ckks_pcmm_bsgs with the integer kernel on every limb (default: double precision on
- * primes < 2^50), knob 7 > 0 caps the number of giant steps whose inner sums one pass over the baby-step
- * ciphertexts computes (default and maximum 24). */
+/* Calibration of hardware byte counters: a plain copy kernel (ckks_prof_copy_kernel) that reads `bytes` from src and
+ * writes them to dst (device pointers, multiples of 16 bytes, not overlapping) and nothing else. */
+int ckks_prof_copy(ckks_ctx* ctx, void* dst, const void* src, size_t bytes, void* stream);
+/* Tuning knobs for experiments (defaults in brackets):
+ * knob 0 [-1] workgroup-to-tile mapping of the N = 2^16 kernels: 0..4 forces one mapping everywhere, -1 chooses per kernel;
+ * knob 1 [0]  != 0 turns the double-precision bodies for primes < 2^50 off (integer bodies everywhere);
+ * knob 2 [0]  1 = the base conversions of ModUp and ModDown run inside the following row pass (one kernel each)
+ *             instead of a conversion kernel followed by a row pass; measured slower, kept for the measurement;
+ * knob 3 [2]  inner product on double-precision main limbs: 2 = block pass of the digits, product with one key
+ *             component, block pass of the ModDown correction and final assembly in one kernel; 1 = plain block
+ *             pass, streaming product and a separate assembly kernel;
+ * knob 4 [1]  0 lets a key switch run the double-precision row pass of the converted digits on a second stream
+ *             owned by the context, beside the special-prime chain, joined before the result is assembled;
+ * knob 5 [0]  != 0 makes every base conversion use the general four-sum accumulation with a 128-bit Montgomery
+ *             reduction, also where the bit sizes of the bases allow the shorter three-sum form;
+ * knob 6 [0]  != 0 computes the inner sums of ckks_pcmm_bsgs with the integer kernel on every limb;
+ * knob 7 [0]  > 0 caps the number of giant steps whose inner sums one pass over the baby-step ciphertexts
+ *             computes (default and maximum 24).
+ * Knobs 1 and 5 rebuild the context's constant tables: the call waits for the device and reallocates them. */
 int ckks_tune_set(ckks_ctx* ctx, int knob, int value);
 int ckks_prof_num_kinds(void);
 const char* ckks_prof_kind_name(int kind);

@@ -16,7 +16,7 @@ OP_KEYSWITCH, OP_HROT, OP_HMULT_RELIN, OP_PCMM_BSGS, OP_RESCALE, OP_PCMM_BSGS_DH
 _SYMBOLS = ["ckks_last_error", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_workspace_bytes", "ckks_ntt", "ckks_intt",
             "ckks_automorph", "ckks_keyswitch", "ckks_hrot", "ckks_hmult_relin", "ckks_pcmm_bsgs",
             "ckks_prof_enable", "ckks_prof_num_kinds", "ckks_prof_kind_name", "ckks_prof_collect", "ckks_prof_read",
-            "ckks_prof_reset", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
+            "ckks_prof_reset", "ckks_prof_copy", "ckks_tune_set", "ckks_rescale", "ckks_pmult", "ckks_add",
             "ckks_hrot_hoisted", "ckks_pcmm_bsgs_hoisted", "ckks_hrot_multi", "ckks_hrot_add", "ckks_tensor_acc",
             "ckks_relin", "ckks_pcmm_bsgs_double_hoisted", "ckks_hrot_sum", "ckks_hrot_noalloc",
             "ckks_noalloc_scratch_bytes"]
@@ -74,6 +74,7 @@ def _load():
     lib.ckks_pmult.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
     lib.ckks_add.argtypes = [vp, u64p, u64p, u64p, C.c_uint32, C.c_uint32, vp]
     lib.ckks_prof_enable.argtypes = [vp, C.c_int]
+    lib.ckks_prof_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
     lib.ckks_tune_set.argtypes = [vp, C.c_int, C.c_int]
     lib.ckks_prof_kind_name.restype = C.c_char_p
     lib.ckks_prof_kind_name.argtypes = [C.c_int]
@@ -156,6 +157,12 @@ def ckks_tune_set(ctx, knob, value):
 
 def ckks_prof_enable(ctx, on):
     _check(_lib.ckks_prof_enable(ctx.handle, 1 if on else 0))
+
+
+def ckks_prof_copy(ctx, dst, src):
+    """Plain copy of src into dst (same size), the calibration kernel for the HBM byte counters."""
+    n = src.numel() * 8
+    _check(_lib.ckks_prof_copy(ctx.handle, _ptr(dst, "dst", ctx, src.numel()), _ptr(src, "src", ctx), n, _stream()))
 
 
 def ckks_prof_reset(ctx):

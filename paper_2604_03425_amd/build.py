@@ -20,12 +20,6 @@ def build(verbose=False):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    # measurement support: copy kernel of known size for calibrating the HBM byte counters
-    probe = [hipcc, "--offload-arch=gfx950", "-O3", "-o", os.path.join(HERE, "hbm_copy_probe"),
-             os.path.join(CSRC, "hbm_copy_probe.hip")]
-    res = subprocess.run(probe, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed on hbm_copy_probe:\n" + res.stdout)
     return LIB
 
 

@@ -1382,6 +1382,20 @@ int ckks_prof_enable(ckks_ctx* c, int on) {
   c->prof_on = on != 0;
   return CKKS_OK;
 }
+int ckks_prof_copy(ckks_ctx* c, void* dst, const void* src, size_t bytes, void* stream) {
+  if (!c || !dst || !src) return fail(CKKS_EINVAL, "null argument");
+  if (bytes == 0 || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15) || bytes / 16 / 256 >= (1ull << 31))
+    return fail(CKKS_ESHAPE, "ckks_prof_copy: size and addresses must be multiples of 16 bytes");
+  if (overlap(dst, bytes, src, bytes)) return fail(CKKS_EINVAL, "dst overlaps src");
+  DeviceGuard guard(c->device);
+  if (!guard.ok) return fail(CKKS_EHIP, "cannot select the context's device");
+  const size_t n = bytes / 16;
+  ProfScope ps(c, PK_COPY, (hipStream_t)stream);
+  hipLaunchKernelGGL(ckks_prof_copy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                     (const ulonglong2*)src, (ulonglong2*)dst, n);
+  HIP_TRY(hipGetLastError());
+  return CKKS_OK;
+}
 int ckks_prof_num_kinds(void) { return PK_COUNT; }
 const char* ckks_prof_kind_name(int kind) { return kind >= 0 && kind < PK_COUNT ? kProfNames[kind] : ""; }
 int ckks_prof_collect(ckks_ctx* c) {

@@ -682,3 +682,10 @@ __global__ void __launch_bounds__(256) add_kernel(PointwiseArgs a) {
   const ulonglong2 y = *(const ulonglong2*)(a.b + o);
   *(ulonglong2*)(a.out + o) = ulonglong2{addmod(x.x, y.x, m), addmod(x.y, y.y, m)};
 }
+
+// Plain copy of known size (16 bytes per lane): the calibration kernel for the HBM byte counters.
+__global__ void __launch_bounds__(256) ckks_prof_copy_kernel(const ulonglong2* __restrict__ in, ulonglong2* __restrict__ out,
+                                                              size_t n) {
+  const size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
+  if (i < n) out[i] = in[i];
+}

@@ -36,7 +36,10 @@ TRANSFORM_SHAPES = [
     (11, 2, 50, 1, 60, 1),
     (12, 4, 40, 1, 50, 2),
     (13, 2, 50, 2, 60, 1),
+    (14, 2, 50, 1, 60, 1),
+    (15, 2, 40, 1, 60, 1),
     (16, 3, 50, 2, 60, 1),
+    (17, 2, 50, 1, 60, 1),
 ]
 
 
