@@ -193,6 +193,27 @@ def test_sweep_point_keyswitch(gpu, limbs, dnum):
     gc.close()
 
 
+def test_paper_parameter_shape_keyswitch(gpu):
+    """The paper's own parameter set as an extra point (Sec. 5.1, Encryption Parameters: N = 2^16, 35 primes in Q and
+    4 special primes, 1661 bits in all): here 35 x 42-bit + 4 x 48-bit primes (1662 bits), 9 digits of 4 limbs with the
+    last one short (3 limbs). Key switch and HRot at the top level and at 14 limbs (the level left after bootstrapping
+    in the paper's schedule), bit-exact."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(16, 35, 42, 4, 48, 9)
+    assert p.alpha == 4
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    evk = uniform_residues(902, p.moduli, (p.dnum, 2), p.N)
+    d_evk = to_dev(evk)
+    for nl in (35, 14):
+        ct = uniform_residues(900 + nl, p.q[:nl], (1, 2), p.N)
+        g = galois_element(321, p.logN)
+        out = torch.empty((1, 2, nl, p.N), dtype=torch.int64, device="cuda")
+        gpu.ckks_hrot(gc, out, to_dev(ct), 1, nl, g, d_evk, gc.workspace(gpu.OP_HROT, 1, nl))
+        assert_same(to_host(out), rc.hrot(ct, g, evk), "paper-shape HRot at %d limbs" % nl)
+    gc.close()
+
+
 @pytest.mark.parametrize("shape,nlimbs,B", [((12, 4, 40, 1, 50, 2), 4, 3), ((12, 5, 50, 2, 60, 2), 3, 2),
                                             ((16, 6, 50, 2, 60, 2), 6, 2), ((16, 3, 60, 1, 60, 1), 3, 1)])
 def test_rescale_pmult_add(gpu, shape, nlimbs, B):

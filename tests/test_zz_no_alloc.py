@@ -65,3 +65,35 @@ def test_hrot_noalloc_small_ring():
         ck.ckks_hrot_noalloc(ctx, got, ct, B, nl, g, evk)
         assert_same(to_host(got), to_host(want), "ckks_hrot_noalloc tiny B=%d" % B)
     ctx.close()
+
+
+def test_hrot_noalloc_replayed_from_a_hip_graph():
+    """What the entry point is for: captured once into a HIP graph (capture forbids allocation), then replayed with
+    new inputs in the same buffers. Every replay is checked against an eager ckks_hrot, with eager work and
+    synchronisations between the replays."""
+    import torch
+    import paper_2604_03425_amd as ck
+    from gpu_util import to_dev, to_host, assert_same
+    p = config_params("keyswitch_micro")
+    ctx = ck.Context(p, 0)
+    nl, B = 24, 1
+    evk = to_dev(uniform_residues(31, p.moduli, (p.dnum, 2), p.N))
+    g = galois_element(4242, p.logN)
+    static_in = to_dev(uniform_residues(300, p.q, (B, 2), p.N))
+    static_out = torch.zeros_like(static_in)
+    ws = ctx.workspace(ck.OP_HROT, B, nl)
+    ck.ckks_hrot_noalloc(ctx, static_out, static_in, B, nl, g, evk)      # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ck.ckks_hrot_noalloc(ctx, static_out, static_in, B, nl, g, evk)
+    for trial in range(3):
+        fresh = to_dev(uniform_residues(310 + trial, p.q, (B, 2), p.N))
+        want = torch.empty_like(fresh)
+        ck.ckks_hrot(ctx, want, fresh, B, nl, g, evk, ws)               # eager work between the replays
+        torch.cuda.synchronize()
+        static_in.copy_(fresh)
+        static_out.zero_()
+        graph.replay()
+        assert_same(to_host(static_out), to_host(want), "graph replay %d" % trial)
+    ctx.close()
