@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "kernels.hip.h"
+#include "ntt12.hip.h"
 #include "ntt16_kernels.hip.h"
 
 typedef unsigned __int128 u128;
@@ -546,6 +547,34 @@ int launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, u64 src_stride, 
     } else {
       LAUNCH_BY_CLASS(c, PK_INV_BLOCKS, ntt16_inv_blocks_kernel, a, npoly, nslots, cls_of, st)
       LAUNCH_BY_CLASS(c, PK_INV_ROWS, ntt16_inv_rows_kernel, b, npoly, nslots, cls_of, st)
+    }
+    HIP_TRY(hipGetLastError());
+    return CKKS_OK;
+  }
+  if (c->logN == 12) {
+    // the whole limb in one workgroup: all 12 stages in one pass over memory, in or out of place
+    Ntt12Args a;
+    a.src = src + (size_t)slot0 * c->N;
+    a.dst = dst + (size_t)slot0 * c->N;
+    a.tw = inverse ? c->d_tw_inv : c->d_tw_fwd;
+    a.twfp = inverse ? c->d_twfp_inv : c->d_twfp_fwd;
+    a.mods = c->d_mods;
+    a.src_poly_stride = src_stride;
+    a.dst_poly_stride = dst_stride;
+    a.skip_beta = skip_beta;
+    a.skip_alpha = c->alpha;
+    a.skip_nq = skip_nq;
+    a.fp_on = c->tune[1] == 0 ? 1u : 0u;
+    for (u32 i = 0; i < 128; i++) a.id[i] = ids_from_slot0.id[i];
+    const u32 chunk = 65535 - (skip_beta ? 65535 % skip_beta : 0);   // grid.x carries the polynomial index; whole digit groups
+    for (u32 p0 = 0; p0 < npoly; p0 += chunk) {
+      const u32 np_ = std::min<u32>(chunk, npoly - p0);
+      Ntt12Args b = a;
+      b.src += (size_t)p0 * src_stride;
+      b.dst += (size_t)p0 * dst_stride;
+      ProfScope ps(c, kind, st);
+      if (inverse) hipLaunchKernelGGL(ntt12_kernel<true>, dim3(np_, nslots), dim3(256), 0, st, b);
+      else hipLaunchKernelGGL(ntt12_kernel<false>, dim3(np_, nslots), dim3(256), 0, st, b);
     }
     HIP_TRY(hipGetLastError());
     return CKKS_OK;
@@ -1278,7 +1307,7 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
   std::vector<ModInfo> mods(c->nm);
   std::vector<ulonglong2> fwd((size_t)c->nm * N), inv((size_t)c->nm * N);
   std::vector<double> fwdfp, invfp;
-  if (logN == 16) {
+  if (logN == 16 || logN == 12) {
     fwdfp.assign((size_t)c->nm * N, 0.0);
     invfp.assign((size_t)c->nm * N, 0.0);
   }
@@ -1315,7 +1344,7 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, const uint64_t* q, uint32_t n
       u32 e = h_brev(k, logN);
       u64 wi = e == 0 ? 1 : m - pw[N - e];
       inv[(size_t)i * N + k] = ulonglong2{wi, h_shoup(wi, m)};
-      if (logN == 16 && (m >> 50) == 0) {
+      if ((logN == 16 || logN == 12) && (m >> 50) == 0) {
         fwdfp[(size_t)i * N + k] = (double)w;
         invfp[(size_t)i * N + k] = (double)wi;
       }
