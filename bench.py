@@ -227,8 +227,8 @@ def other_workloads(args):
         # the transforms alone on the batch of the key-switch micro-benchmark: [64 * 2][24] limb-vectors of 2^16
         # residues (50-bit primes), forward then inverse, `--steps` times; --int-only forces the integer bodies
         # (64-bit Shoup butterflies from 32-bit multiplies) that the double-precision bodies replace by default
-        p = config_params("keyswitch_micro")
-        N, nl, B = p.N, len(p.q), 64
+        p = config_params("keyswitch_micro" if args.ntt_logn == 16 else "tiny_hrot_k2")
+        N, nl, B = p.N, len(p.q), 64 if args.ntt_logn == 16 else 4096
         ctx = ck.Context(p, 0)
         if args.int_only:
             ck.ckks_tune_set(ctx, 1, 1)
@@ -251,17 +251,19 @@ def other_workloads(args):
         limbs = B * 2 * nl
         ops_bf = OPS_BUTTERFLY if args.int_only else OPS_BUTTERFLY_FP
         kinds = {}
+        npass = 2 if args.ntt_logn == 16 else 1   # passes over memory per transform
         for k, (ms, n) in prof.items():
-            t = ms * 1e-3 / n                    # one pass (8 of the 16 stages) over every limb
+            t = ms * 1e-3 / n                    # one pass over every limb
             kinds[k] = dict(avg_launch_us=round(t * 1e6, 2), GBps=round(limbs * 2 * 8 * N / t / 1e9, 1),
-                            modelled_Tops=round(limbs * (N / 2) * 8 * ops_bf / t / 1e12, 2))
+                            modelled_Tops=round(limbs * (N / 2) * (p.logN / npass) * ops_bf / t / 1e12, 2))
         fwd = sum(ms for k, (ms, n) in prof.items() if "fwd" in k) * 1e-3 / args.steps
         inv = sum(ms for k, (ms, n) in prof.items() if "inv" in k) * 1e-3 / args.steps
         print(json.dumps({"workload": "ntt", "arithmetic": "int32 (Shoup, 24 instructions per butterfly)" if args.int_only
                           else "fp64 (9.5 instructions per butterfly)", "limb_vectors": limbs,
                           "ntt_limbs_per_s": round(limbs / fwd), "intt_limbs_per_s": round(limbs / inv),
-                          "ntt_hbm_frac": round(limbs * 4 * 8 * N / fwd / 1e9 / PEAK_HBM_GBS, 4),
-                          "ntt_alu_frac_modelled_ops": round(limbs * (N / 2) * 16 * ops_bf / fwd / 1e12 / PEAK_ALU_TOPS, 4),
+                          "ring": "N = 2^%d" % p.logN,
+                          "ntt_hbm_frac": round(limbs * 2 * npass * 8 * N / fwd / 1e9 / PEAK_HBM_GBS, 4),
+                          "ntt_alu_frac_modelled_ops": round(limbs * (N / 2) * p.logN * ops_bf / fwd / 1e12 / PEAK_ALU_TOPS, 4),
                           "kernels": kinds}))
     elif args.workload == "pcmm":
         # 2048 tokens x 768 hidden in 128 ciphertexts (16 tokens each), 768x768 weight slice as 32 x 24 diagonals,
@@ -583,6 +585,8 @@ def main():
     ap.add_argument("--pcmm-dh-n1", type=int, default=64, help="baby steps of the double-hoisted schedule (same product n1*n2, else the plain split is used)")
     ap.add_argument("--pcmm-dh-n2", type=int, default=12)
     ap.add_argument("--att-batch", type=int, default=32)
+    ap.add_argument("--ntt-logn", type=int, default=16, choices=[12, 16],
+                    help="ring degree of the `ntt` workload (12: the tiny configuration's primes, 4096 x 2 polynomials)")
     ap.add_argument("--cpu-sample", type=int, default=32, help="ciphertexts the CPU oracle rotates (half as many HMult pairs)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -7,7 +7,8 @@
 // Layouts. Round 1 (stages 0..3): lane t holds elements i*256 + t. Round 2 (stages 4..7): lane (i0 = t>>4, col = t&15)
 // holds elements (i0*16 + j)*16 + col: a workgroup-wide exchange. Round 3 (stages 8..11): lane (i0, l) holds the 16
 // consecutive elements of row R = i0*16 + l: an exchange inside groups of 16 adjacent lanes (no workgroup barrier for
-// the data, one to recycle the LDS tile).
+// the data, one to recycle the LDS tile). Memory is always touched one column per lane (16 adjacent lanes on one
+// 128-byte line); the row layout exists only between two exchanges.
 #pragma once
 #include "ntt16fp.hip.h"
 
@@ -42,9 +43,13 @@ __device__ __forceinline__ void ntt12_fwd_int(const u64* __restrict__ src, u64* 
     v = BIG ? csub(v, q2) : barrett_lazy(v, mu, q);
     x[c] = csub(v, q);
   }
-  ulonglong2* o = (ulonglong2*)(dst + R * 16);
+  // back to one column per lane, so that 16 adjacent lanes store one 128-byte line
+  wave_lds_sync();
 #pragma unroll
-  for (int c = 0; c < 8; c++) o[c] = ulonglong2{x[2 * c], x[2 * c + 1]};
+  for (int c = 0; c < 16; c++) sm[i0 * 272 + l * 17 + c] = x[c];
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) dst[(i0 * 16 + j) * 16 + l] = sm[i0 * 272 + j * 17 + l];
 }
 
 // Inverse, with the multiplication by the constant (sc, scs) (N^-1) at the end; canonical in, canonical out.
@@ -54,14 +59,14 @@ __device__ __forceinline__ void ntt12_inv_int(const u64* __restrict__ src, u64* 
   const u32 t = threadIdx.x, l = t & 15, i0 = t >> 4, R = i0 * 16 + l;
   const u64 q2 = 2 * q;
   u64 x[16];
-  const ulonglong2* in = (const ulonglong2*)(src + R * 16);
+  // 16 adjacent lanes load one 128-byte line; an exchange inside the group gives every lane its row
 #pragma unroll
-  for (int c = 0; c < 8; c++) {
-    const ulonglong2 v = in[c];
-    x[2 * c] = v.x;
-    x[2 * c + 1] = v.y;
-  }
+  for (int j = 0; j < 16; j++) sm[i0 * 272 + j * 17 + l] = src[(i0 * 16 + j) * 16 + l];
+  wave_lds_sync();
+#pragma unroll
+  for (int c = 0; c < 16; c++) x[c] = sm[i0 * 272 + l * 17 + c];
   radix16_inv<BIG>(x, q, q2, [&](int s, int g) { return twi[(256 << s) + (R << s) + g]; });
+  wave_lds_sync();
 #pragma unroll
   for (int c = 0; c < 16; c++) sm[i0 * 272 + l * 17 + c] = x[c];
   wave_lds_sync();
@@ -104,23 +109,25 @@ __device__ __forceinline__ void ntt12_fwd_fp(const u64* __restrict__ src, u64* _
 #pragma unroll
   for (int c = 0; c < 16; c++) x[c] = sm[i0 * 272 + l * 17 + c];
   radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return tw[(256 << s) + (R << s) + g]; });
-  ulonglong2* o = (ulonglong2*)(dst + R * 16);
+  wave_lds_sync();
 #pragma unroll
-  for (int c = 0; c < 8; c++) o[c] = ulonglong2{d2u_canon(x[2 * c], q), d2u_canon(x[2 * c + 1], q)};
+  for (int c = 0; c < 16; c++) sm[i0 * 272 + l * 17 + c] = x[c];
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) dst[(i0 * 16 + j) * 16 + l] = d2u_canon(sm[i0 * 272 + j * 17 + l], q);
 }
 
 __device__ __forceinline__ void ntt12_inv_fp(const u64* __restrict__ src, u64* __restrict__ dst, const double* __restrict__ twi,
                                              double q, double qinv, double sc, double scq, double* sm) {
   const u32 t = threadIdx.x, l = t & 15, i0 = t >> 4, R = i0 * 16 + l;
   double x[16];
-  const ulonglong2* in = (const ulonglong2*)(src + R * 16);
 #pragma unroll
-  for (int c = 0; c < 8; c++) {
-    const ulonglong2 v = in[c];
-    x[2 * c] = u2d(v.x);
-    x[2 * c + 1] = u2d(v.y);
-  }
+  for (int j = 0; j < 16; j++) sm[i0 * 272 + j * 17 + l] = u2d(src[(i0 * 16 + j) * 16 + l]);
+  wave_lds_sync();
+#pragma unroll
+  for (int c = 0; c < 16; c++) x[c] = sm[i0 * 272 + l * 17 + c];
   radix16_inv_fp(x, q, qinv, [&](int s, int g) { return twi[(256 << s) + (R << s) + g]; });
+  wave_lds_sync();
 #pragma unroll
   for (int c = 0; c < 16; c++) sm[i0 * 272 + l * 17 + c] = x[c];
   wave_lds_sync();

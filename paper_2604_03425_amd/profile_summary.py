@@ -3,10 +3,11 @@
 
     python3 paper_2604_03425_amd/profile_summary.py kernels DIR        # --kernel-trace --stats run: top kernels
     python3 paper_2604_03425_amd/profile_summary.py counters DIR...    # --pmc runs: per-kernel counter averages
-    python3 paper_2604_03425_amd/profile_summary.py traffic CAL_FETCH CAL_WRITE FETCH WRITE
+    python3 paper_2604_03425_amd/profile_summary.py traffic CAL_FETCH CAL_WRITE FETCH WRITE [OUT.json]
         # four --pmc runs (FETCH_SIZE / WRITE_SIZE on `bench.py --workload calibrate`, then on the default
         # bench.py): prints the calibration and the HBM bytes per launch of every kernel and writes them, with the
-        # digest of the sources they were measured on, to profiles/keyswitch_micro_traffic.json
+        # digest of the sources they were measured on, to OUT.json (default profiles/keyswitch_micro_traffic.json,
+        # the file bench.py reads)
 
 Runs anywhere (no GPU, no torch): it only reads the csv files.
 """
@@ -75,7 +76,7 @@ def cmd_counters(dirs):
                 print("   %-26s %16.0f" % (c, agg[k][c][1]))
 
 
-def cmd_traffic(cal_fetch, cal_write, fetch, write):
+def cmd_traffic(cal_fetch, cal_write, fetch, write, out=None):
     cf, cw = read_counters(cal_fetch), read_counters(cal_write)
     nf, sf = cf[(COPY_KERNEL, "FETCH_SIZE")]
     nw, sw = cw[(COPY_KERNEL, "WRITE_SIZE")]
@@ -98,11 +99,11 @@ def cmd_traffic(cal_fetch, cal_write, fetch, write):
     rec = {"source_sha256": source_digest(), "fetch_factor_to_KiB": round(f_fetch, 4), "write_factor_to_KiB": round(f_write, 4),
            "note": "HBM bytes per launch, average over the launches of a step (one on 64 ciphertexts, one on 32)",
            "hbm_bytes_per_launch": table}
-    out = os.path.join(os.path.dirname(HERE), "profiles", "keyswitch_micro_traffic.json")
+    out = out or os.path.join(os.path.dirname(HERE), "profiles", "keyswitch_micro_traffic.json")
     with open(out, "w") as f:
         json.dump(rec, f, indent=1, sort_keys=True)
         f.write("\n")
-    print("\nwrote %s (sources %s)" % (os.path.relpath(out, os.path.dirname(HERE)), rec["source_sha256"][:16]))
+    print("\nwrote %s (sources %s)" % (out, rec["source_sha256"][:16]))
 
 
 if __name__ == "__main__":
@@ -110,7 +111,7 @@ if __name__ == "__main__":
         cmd_kernels(sys.argv[2])
     elif len(sys.argv) >= 3 and sys.argv[1] == "counters":
         cmd_counters(sys.argv[2:])
-    elif len(sys.argv) == 6 and sys.argv[1] == "traffic":
+    elif len(sys.argv) in (6, 7) and sys.argv[1] == "traffic":
         cmd_traffic(*sys.argv[2:])
     else:
         print(__doc__)
