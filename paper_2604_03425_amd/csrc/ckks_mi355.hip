@@ -131,8 +131,8 @@ enum ProfKind {
   PK_NTT_FWD = 0, PK_NTT_INV,
   // N = 2^16 kernels: three consecutive kinds each, one per modulus class (the kernel's template argument)
   PK_FWD_ROWS, PK_FWD_BLOCKS = PK_FWD_ROWS + 3, PK_INV_BLOCKS = PK_FWD_BLOCKS + 3, PK_INV_ROWS = PK_INV_BLOCKS + 3,
-  PK_FWD_INNER = PK_INV_ROWS + 3, PK_FWD_FINAL = PK_FWD_INNER + 3,
-  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_INNER2, PK_INNER8, PK_INNER8_BIG, PK_BCONV_ROWS, PK_MODDOWN = PK_BCONV_ROWS + 3, PK_FINAL, PK_TENSOR, PK_PMACC, PK_PMACC_FP, PK_ADD,
+  PK_FWD_FINAL = PK_INV_ROWS + 3,
+  PK_AUTOMORPH = PK_FWD_FINAL + 3, PK_MODUP, PK_INNER, PK_INNER16, PK_INNER16_INT, PK_INNER_C, PK_INNER8, PK_INNER8_BIG, PK_BCONV_ROWS, PK_MODDOWN = PK_BCONV_ROWS + 3, PK_FINAL, PK_TENSOR, PK_PMACC, PK_PMACC_FP, PK_ADD,
   PK_COPY, PK_COUNT
 };
 static const char* const kProfNames[PK_COUNT] = {
@@ -141,9 +141,8 @@ static const char* const kProfNames[PK_COUNT] = {
     "ntt16_fwd_blocks_kernel<0>", "ntt16_fwd_blocks_kernel<1>", "ntt16_fwd_blocks_kernel<2>",
     "ntt16_inv_blocks_kernel<0>", "ntt16_inv_blocks_kernel<1>", "ntt16_inv_blocks_kernel<2>",
     "ntt16_inv_rows_kernel<0>", "ntt16_inv_rows_kernel<1>", "ntt16_inv_rows_kernel<2>",
-    "ntt16_fwd_blocks_inner_kernel<0>", "ntt16_fwd_blocks_inner_kernel<1>", "ntt16_fwd_blocks_inner_kernel<2>",
     "ntt16_fwd_blocks_final_kernel<0>", "ntt16_fwd_blocks_final_kernel<1>", "ntt16_fwd_blocks_final_kernel<2>",
-    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "ntt16_fwd_blocks_inner2_kernel", "ntt16_fwd_blocks_inner8_kernel<1>", "ntt16_fwd_blocks_inner8_kernel<2>",
+    "automorph_kernel", "modup_kernel", "inner_kernel", "inner16_fp_kernel", "inner16_int_kernel", "ntt16_fwd_blocks_inner_c_kernel", "ntt16_fwd_blocks_inner8_kernel<1>", "ntt16_fwd_blocks_inner8_kernel<2>",
     "ntt16_bconv_rows_kernel<0>", "ntt16_bconv_rows_kernel<1>", "ntt16_bconv_rows_kernel<2>", "moddown_kernel", "ks_final_kernel", "tensor_kernel",
     "pmacc_int_kernel", "pmacc_fp_kernel", "addto_kernel", "copy"};
 struct ProfRec {
@@ -152,14 +151,11 @@ struct ProfRec {
 };
 
 struct ckks_ctx {
-  int tune[8] = {-1, 0, 2, 2, 1, 0, 0, 0};  // 0: workgroup mapping of the 2^16 kernels (-1: per kernel); 2: fused inner product
-                                         // on integer-class moduli (2: 8 values per lane, 0: 16); 3: inner product on
-                                         // double-precision moduli (0 fused, two accumulators; 1 plain block pass +
-                                         // streaming product; 2 fused, one key component per workgroup);
-                                         // 4: 1 = one stream only (0 forks the two chains of a key switch);
-                                         // 5: 1 = base conversions always take the general (128-bit) reduction;
-                                         // 6: 1 = PCMM inner sums with the integer kernel on every limb;
-                                         // 7: > 0 caps the giant steps per pass of the PCMM inner sums
+  // Tuning knobs (ckks_tune_set; meanings in the public header). 0: workgroup mapping of the N = 2^16 kernels (-1: per
+  // kernel); 1: integer bodies everywhere; 2: 1 = base conversions inside the row passes; 3: 2 = inner product fused
+  // with the final assembly on double-precision main limbs, 1 = separate kernels; 4: 0 = fork part of a key switch onto
+  // the second stream; 5: general base-conversion reduction; 6: integer PCMM inner sums; 7: cap on giant steps per pass.
+  int tune[8] = {-1, 0, 0, 2, 1, 0, 0, 0};
   bool prof_on = false;
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
