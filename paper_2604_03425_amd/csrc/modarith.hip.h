@@ -67,6 +67,31 @@ __device__ __forceinline__ u64 submod(u64 a, u64 b, u64 m) { return a >= b ? a -
 // Result in [0, 2m).
 __device__ __forceinline__ u64 shoup_lazy(u64 x, u64 w, u64 ws, u64 m) { return x * w - mul_hi64(x, ws) * m; }
 __device__ __forceinline__ u64 shoup(u64 x, u64 w, u64 ws, u64 m) { return csub(shoup_lazy(x, w, ws, m), m); }
+// Same product with a cheaper quotient estimate: of the four 32 x 32 partial products of x * ws only the top one
+// and the high words of the two middle ones are summed (2 multiply-highs, 1 multiply-add and a 64-bit add instead of
+// the carry chain of an exact high word). The estimate never exceeds floor(x * ws / 2^64) and falls short of it by
+// at most 2, so the result lies in [0, 4m). Any x < 2^64; m < 2^62. The subtraction of estimate * m is done by
+// adding estimate * (2^64 - m): both low-word products then share one multiply-add chain and no borrow is needed.
+// neg_opaque() hides that the value is a negation, which the compiler would otherwise turn back into a subtraction.
+__device__ __forceinline__ u64 neg_opaque(u64 m) {
+  u64 nm = 0 - m;
+  asm("" : "+s"(nm));
+  return nm;
+}
+__device__ __forceinline__ u64 shoup_lazy4(u64 x, u64 w, u64 ws, u64 m) {
+  const u64 nm = neg_opaque(m);
+  const u32 x0 = (u32)x, x1 = (u32)(x >> 32), p0 = (u32)ws, p1 = (u32)(ws >> 32);
+  const u64 qt = (u64)x1 * p1 + __umulhi(x1, p0) + __umulhi(x0, p1);
+  const u32 q0 = (u32)qt, q1 = (u32)(qt >> 32), w0 = (u32)w, w1 = (u32)(w >> 32), n0 = (u32)nm, n1 = (u32)(nm >> 32);
+  const u64 t = (u64)x0 * w0 + (u64)q0 * n0;   // modulo 2^64
+  const u32 hi = (u32)(t >> 32) + x0 * w1 + x1 * w0 + q0 * n1 + q1 * n0;
+  return ((u64)hi << 32) | (u32)t;
+}
+// x - m if x >= m, computed as x + (2^64 - m): one 64-bit add, no borrow chain.
+__device__ __forceinline__ u64 csub_neg(u64 x, u64 m) {
+  const u64 d = x + neg_opaque(m);
+  return x >= m ? d : x;
+}
 
 // 128-bit lazy accumulator for sums of 64x64 products (up to 2^128 - 1 in total).
 struct Acc128 {

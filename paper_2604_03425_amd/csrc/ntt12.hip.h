@@ -19,7 +19,7 @@ template <bool BIG>
 __device__ __forceinline__ void ntt12_fwd_int(const u64* __restrict__ src, u64* __restrict__ dst,
                                               const ulonglong2* __restrict__ tw, u64 q, u64 mu, u64* sm) {
   const u32 t = threadIdx.x, l = t & 15, i0 = t >> 4, R = i0 * 16 + l;
-  const u64 q2 = 2 * q;
+  const u64 q2 = lazy_const<BIG>(q);
   u64 x[16];
 #pragma unroll
   for (int i = 0; i < 16; i++) x[i] = src[i * 256 + t];
@@ -40,7 +40,7 @@ __device__ __forceinline__ void ntt12_fwd_int(const u64* __restrict__ src, u64* 
 #pragma unroll
   for (int c = 0; c < 16; c++) {
     u64 v = x[c];
-    v = BIG ? csub(v, q2) : barrett_lazy(v, mu, q);
+    v = BIG ? csub(csub(v, q2), 2 * q) : barrett_lazy(v, mu, q);
     x[c] = csub(v, q);
   }
   // back to one column per lane, so that 16 adjacent lanes store one 128-byte line
@@ -57,7 +57,7 @@ template <bool BIG>
 __device__ __forceinline__ void ntt12_inv_int(const u64* __restrict__ src, u64* __restrict__ dst,
                                               const ulonglong2* __restrict__ twi, u64 q, u64 mu, u64 sc, u64 scs, u64* sm) {
   const u32 t = threadIdx.x, l = t & 15, i0 = t >> 4, R = i0 * 16 + l;
-  const u64 q2 = 2 * q;
+  const u64 q2 = lazy_const<BIG>(q);
   u64 x[16];
   // 16 adjacent lanes load one 128-byte line; an exchange inside the group gives every lane its row
 #pragma unroll

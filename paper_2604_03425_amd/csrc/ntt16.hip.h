@@ -6,8 +6,9 @@
 //
 // Lazy ranges. SMALL primes (q < 2^52): forward butterflies never correct, values grow by 2q per
 // stage (< 33q < 2^58 after 16 stages from canonical input) and are reduced once at the end; inverse
-// butterflies let sums double for the 8 stages of a pass (inputs < 2q -> < 512q). BIG primes (q < 2^61)
-// use Harvey's butterflies with values kept in [0,4q) (forward) / [0,2q) (inverse).
+// butterflies let sums double for the 8 stages of a pass (inputs < 2q -> < 512q). BIG primes (q < 2^60)
+// use Harvey's butterflies with the approximate twiddle product shoup_lazy4 (below 4q): values are kept in
+// [0,8q) (forward) / [0,4q) (inverse); the lazy constant `ql` those bodies pass around is 4q (2q for SMALL).
 #pragma once
 #include "modarith.hip.h"
 
@@ -16,21 +17,24 @@
 
 // ---- butterflies ----
 template <bool BIG>
+__device__ __forceinline__ u64 lazy_const(u64 q) { return BIG ? 4 * q : 2 * q; }
+// Forward (Cooley-Tukey). BIG: q2 = 4q, inputs and outputs in [0,8q). SMALL: q2 = 2q, values grow by 2q.
+template <bool BIG>
 __device__ __forceinline__ void bf_fwd(u64& X, u64& Y, ulonglong2 w, u64 q, u64 q2) {
-  if (BIG) X = csub(X, q2);
-  u64 T = shoup_lazy(Y, w.x, w.y, q);
+  if (BIG) X = csub_neg(X, q2);
+  u64 T = BIG ? shoup_lazy4(Y, w.x, w.y, q) : shoup_lazy(Y, w.x, w.y, q);
   Y = X + q2 - T;
   X = X + T;
 }
-// Inverse (Gentleman-Sande). BIG: inputs in [0,2q), outputs in [0,2q). SMALL: inputs < c (a multiple of q),
+// Inverse (Gentleman-Sande). BIG: c = 4q, inputs in [0,4q), outputs in [0,4q). SMALL: inputs < c (a multiple of q),
 // X' < 2c, Y' < 2q.
 template <bool BIG>
 __device__ __forceinline__ void bf_inv(u64& X, u64& Y, ulonglong2 w, u64 q, u64 c) {
   u64 S = X + Y;
   u64 D = X + c - Y;
-  if (BIG) S = csub(S, c);  // c == 2q
+  if (BIG) S = csub_neg(S, c);  // c == 4q
   X = S;
-  Y = shoup_lazy(D, w.x, w.y, q);
+  Y = BIG ? shoup_lazy4(D, w.x, w.y, q) : shoup_lazy(D, w.x, w.y, q);
 }
 
 // Four forward stages on 16 registers: stage s pairs (a, a + (8>>s)); tw(s, g) is the twiddle of group g.
@@ -47,7 +51,7 @@ __device__ __forceinline__ void radix16_fwd(u64 (&x)[16], u64 q, u64 q2, TW tw) 
     }
   }
 }
-// Four inverse stages, in the reverse order (s = 3..0). c0 = bound of the inputs (SMALL) or 2q (BIG).
+// Four inverse stages, in the reverse order (s = 3..0). c0 = bound of the inputs (SMALL) or 4q (BIG).
 template <bool BIG, class TW>
 __device__ __forceinline__ void radix16_inv(u64 (&x)[16], u64 q, u64 c0, TW tw) {
   u64 c = c0;
@@ -68,13 +72,13 @@ __device__ __forceinline__ u64 barrett_lazy(u64 v, u64 mu, u64 q) { return v - m
 
 // ---- pass bodies. `base` points at one limb-vector of 65536 words, `tw` at that modulus' table. ----
 
-// Forward, stages 0..7. In: canonical (or < 2q). Out: SMALL < 17q (+in), BIG < 4q.
+// Forward, stages 0..7. In: canonical (or < 2q). Out: SMALL < 17q (+in), BIG < 8q.
 // `x` holds, for lane (r0 = t>>4, col = t&15), the rows i*16 + r0 (i = 0..15) of column col0 + col.
 template <bool BIG>
 __device__ __forceinline__ void ntt16_fwd_rows_loaded(u64 (&x)[16], u64* __restrict__ dst, const ulonglong2* __restrict__ tw,
                                                       u64 q, u32 tile, u64* sm) {
   const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
-  const u64 q2 = 2 * q;
+  const u64 q2 = lazy_const<BIG>(q);
   radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(1 << s) + g]; });
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[i * 256 + t] = x[i];
@@ -102,7 +106,7 @@ template <bool BIG, bool CANON = true>
 __device__ __forceinline__ void ntt16_fwd_blocks_loaded(u64 (&x)[16], const ulonglong2* __restrict__ tw, u64 q, u64 mu,
                                                         u32 tile, u64* sm) {
   const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
-  const u64 q2 = 2 * q;
+  const u64 q2 = lazy_const<BIG>(q);
   radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[hb * 272 + i * 17 + j0] = x[i];
@@ -114,7 +118,7 @@ __device__ __forceinline__ void ntt16_fwd_blocks_loaded(u64 (&x)[16], const ulon
 #pragma unroll
   for (int j = 0; j < 16; j++) {
     u64 v = x[j];
-    if (BIG) v = csub(v, q2);
+    if (BIG) v = csub(csub(v, q2), 2 * q);
     else v = barrett_lazy(v, mu, q);
     x[j] = CANON ? csub(v, q) : v;
   }
@@ -138,7 +142,7 @@ __device__ __forceinline__ void ntt16_fwd_blocks(u64 (&x)[16], const u64* __rest
 
 // Forward, stages 8..15 of one 256-element block by 32 adjacent lanes with 8 values each (the layout of
 // ntt256_fwd_blocks_fp8: radix-8, exchange, radix-8, exchange, radix-4; LDS rows of pitch 35 words per 32 elements,
-// all exchanges inside the half-wave). In: x[i] = element i*32 + l, lazy (BIG: < 4q). Out: x[c] = element
+// all exchanges inside the half-wave). In: x[i] = element i*32 + l, lazy (BIG: < 8q). Out: x[c] = element
 // (l >> 2)*32 + (l & 3)*8 + c, below 2q. `between` runs after the first exchange has been written.
 #define NTT8_PITCH_I 35
 #define NTT8_BLOCK_LDS_I (8 * NTT8_PITCH_I)
@@ -159,7 +163,7 @@ template <bool BIG, class BETWEEN>
 __device__ __forceinline__ void ntt256_fwd_blocks_int8(u64 (&x)[8], const ulonglong2* __restrict__ tw, u64 q, u64 mu, u32 h,
                                                        u32 l, u64* smb, BETWEEN between) {
   const u32 a = l >> 2, b = l & 3;
-  const u64 q2 = 2 * q;
+  const u64 q2 = lazy_const<BIG>(q);
   radix8_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
 #pragma unroll
   for (int i = 0; i < 8; i++) smb[i * NTT8_PITCH_I + l] = x[i];
@@ -186,16 +190,16 @@ __device__ __forceinline__ void ntt256_fwd_blocks_int8(u64 (&x)[8], const ulongl
     bf_fwd<BIG>(x[2 * k], x[2 * k + 1], w, q, q2);
   }
 #pragma unroll
-  for (int c = 0; c < 8; c++) x[c] = BIG ? csub(x[c], q2) : barrett_lazy(x[c], mu, q);
+  for (int c = 0; c < 8; c++) x[c] = BIG ? csub(csub(x[c], q2), 2 * q) : barrett_lazy(x[c], mu, q);
 }
 
 // Inverse, stages 15..8 on contiguous blocks. In: x holds, for lane (hb, j0), the values at positions i*16 + j0
-// of block h (any value < 2q). Out: < 2q, same lane layout, ready for a coalesced store.
+// of block h (any value < 2q). Out: < 2q (BIG: < 4q), same lane layout, ready for a coalesced store.
 template <bool BIG>
 __device__ __forceinline__ void ntt16_inv_blocks(u64 (&x)[16], const ulonglong2* __restrict__ twi, u64 q, u64 mu, u32 tile,
                                                  u64* sm) {
   const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
-  const u64 q2 = 2 * q;
+  const u64 q2 = lazy_const<BIG>(q);
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[hb * 272 + i * 17 + j0] = x[i];
   wave_lds_sync();
@@ -217,13 +221,13 @@ __device__ __forceinline__ void ntt16_inv_blocks(u64 (&x)[16], const ulonglong2*
 }
 
 // Inverse, stages 7..0 on 256 rows x 16 columns, then multiplication by the constant (sc, scs) (N^-1, possibly
-// merged with another per-limb constant) and canonical output. In: < 2q. x holds for lane (r0 = t>>4, col = t&15)
+// merged with another per-limb constant) and canonical output. In: < 2q (BIG: < 4q). x holds for lane (r0 = t>>4, col = t&15)
 // the rows i*16 + r0 of column col0 + col.
 template <bool BIG>
 __device__ __forceinline__ void ntt16_inv_rows(u64 (&x)[16], const u64* __restrict__ src, const ulonglong2* __restrict__ twi,
                                                u64 q, u64 sc, u64 scs, u32 tile, u64* sm) {
   const u32 t = threadIdx.x, col = t & 15, i0 = t >> 4, col0 = tile * 16;
-  const u64 q2 = 2 * q;
+  const u64 q2 = lazy_const<BIG>(q);
 #pragma unroll
   for (int j = 0; j < 16; j++) x[j] = src[(size_t)(i0 * 16 + j) * 256 + col0 + col];
   radix16_inv<BIG>(x, q, q2, [&](int s, int g) { return twi[(16 << s) + (i0 << s) + g]; });
