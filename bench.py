@@ -532,6 +532,9 @@ def other_workloads(args):
                 K = -(-limbs // dnum)
                 p = make_params(16, limbs, 50, K, 60, dnum)
                 ctx = ck.Context(p, 0)
+                for kv in filter(None, args.tune.split(",")):
+                    k, v = kv.split("=")
+                    ck.ckks_tune_set(ctx, int(k), int(v))
                 d = _uniform(torch, gen, dev, (B,), p.q, p.N)
                 evk = _uniform(torch, gen, dev, (p.dnum, 2), p.moduli, p.N)
                 out = torch.empty((B, 2, limbs, p.N), dtype=torch.int64, device=dev)

@@ -716,14 +716,16 @@ int launch_bconv_rows(const ckks_ctx* c, BconvRowsArgs a, u32 npoly, bool narrow
   a.tw = c->d_tw_fwd;
   a.twfp = c->d_twfp_fwd;
   a.mods = c->d_mods;
-  // every target of a (polynomial, tile) group on one XCD, whose L2 then serves the shared source tiles
-  a.map_mode = c->tune[0] >= 0 ? (u32)c->tune[0] : 4u;
+  // the targets of a polynomial on one XCD, whose L2 then serves the shared source tiles, tiles fastest
+  a.map_mode = c->tune[0] >= 0 ? (u32)c->tune[0] : 5u;
+  a.npoly = npoly;
+  const u32 grid_poly = a.map_mode == 5 ? (npoly + 7) / 8 * 8 : npoly;
   for (int cls = 0; cls < 3; cls++) {
     u32 cnt = 0;
     for (u32 s = 0; s < a.ntarget; s++)
       if (class_of_slot(s) == cls) a.slots[cnt++] = (unsigned char)s;
     if (!cnt) continue;
-    const dim3 grid(cnt, 16, npoly), block(NTT16_THREADS);
+    const dim3 grid(cnt, 16, grid_poly), block(NTT16_THREADS);
     ProfScope ps(c, PK_BCONV_ROWS + cls, st);
 #define LAUNCH_BCONV(CLS)                                                                              \
   if (narrow) hipLaunchKernelGGL((ntt16_bconv_rows_kernel<CLS, true>), grid, block, 0, st, a);         \

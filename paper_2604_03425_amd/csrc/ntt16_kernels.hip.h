@@ -172,85 +172,110 @@ struct BconvRowsArgs {
   u32 src_nlimbs, alpha, beta;  // digit j = p % beta owns sources j*alpha .. j*alpha + len - 1, len = min(alpha, src_nlimbs - j*alpha)
   u32 skip_own;             // != 0: target slots j*alpha .. j*alpha + len - 1 are the digit's own limbs: left alone
   u32 ntarget, pitch;
-  u32 map_mode;
+  u32 map_mode;             // ntt16_map modes with the target index as the x dimension, or 5 (see the kernel)
+  u32 npoly;                // polynomials (map mode 5 pads the grid to a multiple of 8)
   unsigned char id[128];    // target slot -> modulus id
   unsigned char slots[128]; // grid.x index -> target slot (one modulus class per launch)
 };
 
+// A pointer that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ const u64* uniform_ptr(const u64* p) {
+  const u64 v = (u64)p;
+  const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
+  return (const u64*)(((u64)hi << 32) | lo);
+}
 #define BCONV_M30 0x3FFFFFFFu
-// Converted values for 8 of the lane's 16 tile positions (those at voff[0..7], offsets inside a limb).
+// Converted values for 8 of the lane's 16 tile positions (those at voff[0..7], offsets inside a limb). Two word
+// buffers alternate, so the loads of source k + 1 are in flight while source k is multiplied in.
 template <bool NARROW>
-__device__ __forceinline__ void bconv_rows_eight(u64 (&r)[8], const u64* __restrict__ src, const u32 (&voff)[8], u32 len,
+struct BconvAcc8 {
+  Dot30N n[8];
+  Dot30 g[8];
+  u64 r[8];
+  u32 pending;
+  __device__ __forceinline__ void init(u64 offc) {
+    pending = 0;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      r[i] = 0;
+      if (NARROW) {
+        n[i].a = (u32)offc & BCONV_M30;
+        n[i].b = offc >> 30;
+        n[i].c = 0;
+      } else {
+        dot30_init(g[i]);
+        g[i].s00 = (u32)offc & BCONV_M30;
+        g[i].s01 = offc >> 30;
+      }
+    }
+  }
+  __device__ __forceinline__ void fold(u64 m, u64 minv) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      if (NARROW) {
+        r[i] += dot30n_redc90(n[i], m, minv);   // each part < m + 2^34
+        dot30n_init(n[i]);
+      } else {
+        r[i] += redc(dot30_value(g[i]), m, minv);   // each part < 2m
+        dot30_init(g[i]);
+      }
+    }
+    pending = 0;
+  }
+  __device__ __forceinline__ void mac(const u64 (&w)[8], u64 c, bool more, u64 m, u64 minv) {
+    const u32 c0 = (u32)c & BCONV_M30, c1 = (u32)(c >> 30);
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      if (NARROW) dot30n_mac(n[i], (u32)w[i], (u32)(w[i] >> 32), c0, c1);
+      else dot30_mac(g[i], (u32)w[i], (u32)(w[i] >> 32), c0, c1);
+    }
+    if (++pending == 15 && more) fold(m, minv);   // wave-uniform: chunks of 15 terms are reduced separately
+  }
+};
+// boff: byte offsets of the 8 positions inside a limb. The source limbs of the digit are read through a buffer
+// resource (scalar base, bounds = the digit's len limbs; scalar offset = the limb, vector offset = the position), so
+// addressing costs no vector instructions. The loads are unconditional (a source index past the end is clamped and
+// meets the constant 0) and fenced against reordering: the younger buffer's loads stay in flight while the older
+// buffer is multiplied in.
+typedef u32 bconv_u32x2 __attribute__((ext_vector_type(2)));
+template <bool NARROW>
+__device__ __forceinline__ void bconv_rows_eight(u64 (&r)[8], const u64* __restrict__ src, const u32 (&boff)[8], u32 len,
                                                  const u64* __restrict__ crow, u64 offc, const ModInfo& mi) {
   const u64 m = mi.m;
-  u64 w[8], wn[8];
-#pragma unroll
-  for (int i = 0; i < 8; i++) w[i] = src[voff[i]];
-  if (NARROW) {
-    Dot30N dd[8];
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-      dd[i].a = (u32)offc & BCONV_M30;
-      dd[i].b = offc >> 30;
-      dd[i].c = 0;
-      r[i] = 0;
-    }
-    for (u32 k = 0, pending = 0; k < len; k++) {
-      const u64* nxt = src + (size_t)(k + 1 < len ? k + 1 : k) * 65536;
-#pragma unroll
-      for (int i = 0; i < 8; i++) wn[i] = nxt[voff[i]];
-      const u64 c = crow[k];
-      const u32 c0 = (u32)c & BCONV_M30, c1 = (u32)(c >> 30);
-#pragma unroll
-      for (int i = 0; i < 8; i++) dot30n_mac(dd[i], (u32)w[i], (u32)(w[i] >> 32), c0, c1);
-      if (++pending == 15 && k + 1 < len) {   // wave-uniform: chunks of 15 terms are reduced separately
-        pending = 0;
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-          r[i] += dot30n_redc90(dd[i], m, mi.minv);
-          dot30n_init(dd[i]);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 8; i++) w[i] = wn[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; i++) r[i] += dot30n_redc90(dd[i], m, mi.minv);   // each part < m + 2^34
-  } else {
-    Dot30 dd[8];
+  u64 wa[8], wb[8];
+  BconvAcc8<NARROW> acc;
+  acc.init(offc);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)src, 0, (int)(len * 524288u), 0x00020000);
+  auto load8 = [&](u64 (&w)[8], u32 k) {
+    const u32 soff = min(k, len - 1) * 524288u;   // wave-uniform
 #pragma unroll
     for (int i = 0; i < 8; i++) {
-      dot30_init(dd[i]);
-      dd[i].s00 = (u32)offc & BCONV_M30;
-      dd[i].s01 = offc >> 30;
-      r[i] = 0;
+      const bconv_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, boff[i], soff, 0);
+      w[i] = ((u64)v.y << 32) | v.x;
     }
-    for (u32 k = 0, pending = 0; k < len; k++) {
-      const u64* nxt = src + (size_t)(k + 1 < len ? k + 1 : k) * 65536;
-#pragma unroll
-      for (int i = 0; i < 8; i++) wn[i] = nxt[voff[i]];
-      const u64 c = crow[k];
-      const u32 c0 = (u32)c & BCONV_M30, c1 = (u32)(c >> 30);
-#pragma unroll
-      for (int i = 0; i < 8; i++) dot30_mac(dd[i], (u32)w[i], (u32)(w[i] >> 32), c0, c1);
-      if (++pending == 15 && k + 1 < len) {
-        pending = 0;
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-          r[i] += redc(dot30_value(dd[i]), m, mi.minv);
-          dot30_init(dd[i]);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 8; i++) w[i] = wn[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; i++) r[i] += redc(dot30_value(dd[i]), m, mi.minv);   // each part < 2m
+  };
+  // fence: neither the compiler's code motion (memory clobber) nor the instruction scheduler may move a buffer's
+  // loads next to their use
+#define BCONV_FENCE()                   \
+  asm volatile("" ::: "memory");        \
+  __builtin_amdgcn_sched_barrier(0)
+  load8(wa, 0);
+  for (u32 k = 0; k < len; k += 2) {
+    load8(wb, k + 1);
+    BCONV_FENCE();
+    acc.mac(wa, crow[k], k + 1 < len, m, mi.minv);
+    BCONV_FENCE();
+    load8(wa, k + 2);
+    BCONV_FENCE();
+    acc.mac(wb, k + 1 < len ? crow[k + 1] : 0, k + 2 < len, m, mi.minv);
+    BCONV_FENCE();
   }
+#undef BCONV_FENCE
+  acc.fold(m, mi.minv);
   // at most three chunks (45 sources): the sum of the parts is below 6m
 #pragma unroll
   for (int i = 0; i < 8; i++) {
-    u64 v = r[i];
+    u64 v = acc.r[i];
     if (len > 15 || !NARROW) v = csub(csub(v, 4 * m), 2 * m);
     r[i] = csub(v, m);
   }
@@ -260,7 +285,20 @@ template <int CLS, bool NARROW>
 __global__ void __launch_bounds__(NTT16_THREADS) ntt16_bconv_rows_kernel(BconvRowsArgs a) {
   __shared__ u64 sm[NTT16_LDS_BYTES / 8];
   u32 zi, tile, poly;
-  ntt16_map(a.map_mode, zi, tile, poly);
+  if (a.map_mode == 5) {
+    // Per XCD (workgroups are dealt to the 8 XCDs round-robin): tiles fastest, then targets, then polynomials, each
+    // XCD on polynomials of its own. The 16 tiles of a limb lie on 16 different L2 channels (rows are 2 KiB apart), so
+    // the workgroups in flight on an XCD spread their source reads over all channels instead of queueing on one,
+    // while the targets that share a polynomial's source tiles still follow each other on the same XCD.
+    const u32 lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const u32 r = lin >> 3;
+    tile = r & 15;
+    zi = (r >> 4) % gridDim.x;
+    poly = (lin & 7) + 8 * ((r >> 4) / gridDim.x);
+    if (poly >= a.npoly) return;
+  } else {
+    ntt16_map(a.map_mode, zi, tile, poly);
+  }
   const u32 slot = a.slots[zi];
   const u32 j = poly % a.beta, lo = j * a.alpha, len = min(a.alpha, a.src_nlimbs - lo);
   if (a.skip_own && slot >= lo && slot < lo + len) return;
@@ -274,11 +312,11 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_bconv_rows_kernel(BconvRo
   u64 x[16];
 #pragma unroll
   for (int half = 0; half < 2; half++) {
-    u32 voff[8];
+    u32 boff[8];
 #pragma unroll
-    for (int i = 0; i < 8; i++) voff[i] = pos0 + (half * 8 + i) * 4096;   // rows i*16 + r0
+    for (int i = 0; i < 8; i++) boff[i] = (pos0 + (half * 8 + i) * 4096) * 8;   // rows i*16 + r0, in bytes
     u64 r[8];
-    bconv_rows_eight<NARROW>(r, src, voff, len, crow, offc, mi);
+    bconv_rows_eight<NARROW>(r, src, boff, len, crow, offc, mi);
 #pragma unroll
     for (int i = 0; i < 8; i++) x[half * 8 + i] = r[i];
   }
@@ -354,84 +392,122 @@ __device__ __forceinline__ bool fwd_inner_owns(const FwdInnerArgs& a, u32 t, u32
 // Double-precision moduli, one key component per workgroup: grid.x = 2B, polynomial index bc = 2b + c. Each of the
 // two workgroups of a ciphertext transforms the digit tiles itself (the arithmetic is cheap next to the traffic and
 // the second reader finds the tile in its XCD's L2, the pair being adjacent in the launch order) and multiplies by
-// its own half of the key: one accumulator tile instead of two, so the kernel keeps 3 waves per SIMD and, unlike
-// the two-accumulator form above, stays memory-bound. The key tile of a digit is requested before the transform.
+// its own half of the key: one accumulator tile instead of two, so the kernel keeps 3 waves per SIMD.
+// Input tiles are prefetched: the converted digit tiles (and the ModDown correction tile of the fused tail) are
+// contiguous 32 KB pieces of memory, so each wave copies its quarter of the NEXT tile straight into LDS with
+// direct-to-LDS buffer loads (no registers) while it works on the current one, and starts a tile by reading its
+// values from LDS instead of waiting for memory. The own digit, which is read through the Galois map, goes first:
+// its loads are in flight together with the first prefetch. The key tile of a digit is requested between the two
+// rounds of its transform. LDS: the word tile of the split transposes (17 KB), the image (4 waves x 8 KB) and the
+// first-round twiddles (2 KB): 51 KB per workgroup, three workgroups per compute unit.
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* global_void_ptr;
+typedef const __attribute__((address_space(1))) u64* global_u64_ptr;
+#define INNER_C_EX_WORDS (16 * 272)
 __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 bc, u32 tile, u32 t, u32 id, const ModInfo& mi,
-                                                    double* sm) {
+                                                    u32* ex, double* img, double* twl) {
   const u32 b = bc >> 1, c = bc & 1;
   const size_t N = 65536;
   const double q = mi.qd, qinv = mi.qinv;
   const double* tw = a.twfp + (size_t)id * N;
   const u64* evk = fwd_inner_evk(a, b) + ((size_t)c * a.nm + id) * N;
   const u32 g = __builtin_amdgcn_readfirstlane(fwd_inner_galois(a, b));
-  // Every address below is rebuilt from the lane index where it is used (a few integer instructions) instead of
-  // being kept in registers across the digit loop: the kernel is held to 168 registers.
   auto lane_pos = [&]() {
     u32 tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     return (tile * 16 + (tid >> 4)) * 256 + (tid & 15);   // position of element 0 of this lane in the limb
   };
+  // a wave's quarter of a tile: blocks 4w .. 4w+3, 1024 consecutive words; lane L of request k moves words
+  // 128k + 2L and 128k + 2L + 1
+  auto request = [&](const u64* limb) {
+    u32 tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const u32 wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)uniform_ptr(limb + (size_t)tile * 4096 + wv * 1024), 0, 8192, 0x00020000);
+    const int vo = (int)((tid & 63) * 16);
+    double* li = img + wv * 1024;
+#pragma unroll
+    for (int k = 0; k < 8; k++)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(li + k * 128), 16, vo, k * 1024, 0, 0);
+  };
+  // the requested tile in the i-layout (lane (hb, j0) holds positions i*16 + j0 of block hb); afterwards the image is free
+  auto take = [&](double (&x)[16]) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    u32 tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const double* li = img + (tid >> 6) * 1024 + ((tid >> 4) & 3) * 256 + (tid & 15);
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = li[i * 16];
+    wave_lds_sync();
+  };
+  const u32 beta = a.beta;
+  const u32 jo = t < a.nlimbs ? t / a.alpha : 0xFFFFFFFFu;   // the digit that holds limb t itself (none for special slots)
+  auto ext_limb = [&](u32 j) { return a.ext + (((size_t)b * beta + j) * a.next + t) * N; };
+  const u64* tq_limb = a.fin_tq ? a.fin_tq + ((size_t)bc * a.nlimbs + t) * N : nullptr;
   double acc[16], x[16];
   u64 e[16];
 #pragma unroll
   for (int i = 0; i < 16; i++) acc[i] = 0.0;
-#pragma nounroll
-  for (u32 j = 0; j < a.beta; j++) {
-    const bool own = fwd_inner_owns(a, t, j);
-    // the gather indices do not depend on the digit, but holding 16 of them across the loop costs a wave of
-    // occupancy: hide the element so that they are recomputed where they are used
-    u32 gj = g;
-    asm volatile("" : "+s"(gj));
+  u32 jn = jo == 0 ? 1u : 0u;   // next converted digit
+  if (jn < beta) request(ext_limb(jn));
+  else if (tq_limb) request(tq_limb);
+  const double twv = ntt16_twl_fetch(tw, tile);
+  u32 cnt = 0;
+  if (jo != 0xFFFFFFFFu) {
     const u32 pos = lane_pos();
-    const u64* k = evk + (size_t)j * 2 * a.nm * N + pos;
-    if (own) {
-      const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+    const u64* k = evk + (size_t)jo * 2 * a.nm * N + pos;
+    const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
 #pragma unroll
-      for (int i = 0; i < 16; i++) e[i] = k[i * 16];
-      if (gj) {
+    for (int i = 0; i < 16; i++) e[i] = k[i * 16];
+    if (g) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) x[i] = u2d(src[galois_src_index16(pos + i * 16, gj)]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 16; i++) x[i] = u2d(src[pos + i * 16]);
-      }
+      for (int i = 0; i < 16; i++) x[i] = u2d(src[galois_src_index16(pos + i * 16, g)]);
     } else {
-      const double* src = (const double*)(a.ext + (((size_t)b * a.beta + j) * a.next + t) * N) + pos;
 #pragma unroll
-      for (int i = 0; i < 16; i++) x[i] = src[i * 16];
-      wave_lds_sync();  // the previous digit's transposes (inside 16-lane groups) are done with the LDS tile
-      // the key tile is requested between the two rounds of the transform, when the registers of the first
-      // round's twiddles are free again
-      ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm, [&] {
-#pragma unroll
-        for (int i = 0; i < 16; i++) e[i] = k[i * 16];
-      });
+      for (int i = 0; i < 16; i++) x[i] = u2d(src[pos + i * 16]);
     }
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc[i] += fp_mulmod_var(x[i], u2d(e[i]), qinv, q);
+    cnt = 1;
+  }
+  ntt16_twl_store(twv, twl);   // read by the wave's own lanes from the first transform on
+#pragma nounroll
+  while (jn < beta) {
+    take(x);
+    u32 jnext = jn + 1;
+    if (jnext == jo) jnext++;
+    // (a pointer rebuilt from scalar halves has lost its address space: say "global", or the loads become flat
+    // loads, which wait for the prefetch in case it lands where they read)
+    const global_u64_ptr k = (global_u64_ptr)(evk + (size_t)jn * 2 * a.nm * N + lane_pos());
+    ntt16_fwd_blocks_fp_words(
+        x, tw, q, qinv, tile, ex, twl,
+        [&] {
+          // always issued (the current tile again when nothing follows), so that the waits of the two rounds are
+          // the same static counts on every path
+          request(jnext < beta ? ext_limb(jnext) : tq_limb ? tq_limb : ext_limb(jn));
+        },
+        [&] {
+#pragma unroll
+          for (int i = 0; i < 16; i++) e[i] = k[i * 16];
+        });
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 16; i++) acc[i] += fp_mulmod_var(x[i], u2d(e[i]), qinv, q);
-    if ((j & 3) == 3) {   // each product is below 0.75 q: fold before the sum can reach 2^53 (own uniform branch)
+    if ((++cnt & 3) == 0) {   // each product is below 0.75 q: fold before the sum can reach 2^53
 #pragma unroll
       for (int i = 0; i < 16; i++) acc[i] = fp_reduce(acc[i], qinv, q);
     }
+    jn = jnext;
   }
   if (a.fin_tq) {
-    // The rest of the key switch for this tile (t is a main-prime slot): block pass of the ModDown correction, then
-    // out = (sum - correction) / P + addends. Addend modes per component: 0 none; 1 the plain addend fin_add2;
-    // 2 fin_add_src read through the Galois map (HRot's sigma(c0)); 3 both.
     const u32 mode = c ? a.fin_mode1 : a.fin_mode0;
     const u32 gf = a.multi ? g : a.fin_galois;
     const size_t a2poly = a.fin_add2_three ? (size_t)b * 3 + c : (size_t)bc;
     const u64* a2 = a.fin_add2 + (a2poly * a.nlimbs + t) * N;
     const u64* as = a.fin_add_src + ((size_t)bc * a.nlimbs + t) * N;
-    {
-      const double* src = (const double*)(a.fin_tq + ((size_t)bc * a.nlimbs + t) * N) + lane_pos();
-#pragma unroll
-      for (int i = 0; i < 16; i++) x[i] = src[i * 16];
-    }
-    wave_lds_sync();
-    // the first addend is requested between the two rounds of the transform (e[] is free by now)
-    ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm, [&] {
+    take(x);
+    ntt16_fwd_blocks_fp_words(x, tw, q, qinv, tile, ex, twl, [] {}, [&] {
       const u32 pos = lane_pos();
       if (mode & 1) {
 #pragma unroll
@@ -448,7 +524,7 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
     for (int i = 0; i < 16; i++) {
       double r = fp_mulmod_const(fp_reduce(acc[i], qinv, q) - x[i], pv.x, pv.y, q);   // |r| <= 0.75 q
       if (mode) r += u2d(e[i]);
-      if (mode == 3) {   // two addends: the gathered one is fetched here; bring the sum back below 2q first
+      if (mode == 3) {
         r += u2d(as[galois_src_index16(pos + i * 16, gf)]);
         r = r >= q ? r - q : r;
       }
@@ -457,10 +533,10 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
     return;
   }
   u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + lane_pos();
-  if (a.accumulate) {   // a rotation kept in the extended basis, added to what acc holds (wave-uniform branch)
+  if (a.accumulate) {
 #pragma unroll
     for (int i = 0; i < 16; i++) acc[i] = fp_reduce(acc[i], qinv, q) + u2d(o[i * 16]);
-    if (c == 0 && a.c0 && t < a.nlimbs) {   // + P * sigma_g(c0) on the main primes
+    if (c == 0 && a.c0 && t < a.nlimbs) {
       const u64* src = a.c0 + (size_t)b * a.c0_poly_stride + (size_t)t * N;
       const double pm = u2d(mi.pmod);
       const u32 pos = lane_pos();
@@ -473,13 +549,16 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
 }
 __global__ void __launch_bounds__(NTT16_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
 ntt16_fwd_blocks_inner_c_kernel(FwdInnerArgs a) {
-  __shared__ u64 sm[NTT16_LDS_BYTES / 8];
+  // two arrays, so that the compiler knows the transposes never touch the image a prefetch is landing in
+  __shared__ __attribute__((aligned(16))) double img[4096];
+  __shared__ u32 ex[INNER_C_EX_WORDS];
+  __shared__ double twl[16 * NTT16_TWL_PITCH];
   u32 bc, tile, zi;
   ntt16_map(a.map_mode, bc, tile, zi);
   const u32 t = a.slots[zi];
   const u32 id = t < a.nlimbs ? t : t - a.nlimbs + a.nq;
   const ModInfo mi = a.mods[id];
-  fwd_inner_c_body_fp(a, bc, tile, t, id, mi, (double*)sm);
+  fwd_inner_c_body_fp(a, bc, tile, t, id, mi, ex, img, twl);
 }
 
 // Integer-class moduli (the special primes): both key components per workgroup, 8 values per lane: a workgroup takes
@@ -837,11 +916,6 @@ __global__ void __launch_bounds__(256) inner16_int_kernel(FwdInnerArgs a) {
 #define INNER16_ROT_MAX_BETA 8
 #define INNER16_ROT_CB 4
 #define INNER16_ROT_CB_FP 8
-__device__ __forceinline__ const u64* uniform_ptr(const u64* p) {
-  const u64 v = (u64)p;
-  const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
-  return (const u64*)(((u64)hi << 32) | lo);
-}
 template <int MAXB, bool EXACT>   // EXACT: beta == MAXB (no per-digit tests), else beta <= MAXB
 __global__ void __launch_bounds__(256) inner16_rot_fp_kernel(FwdInnerArgs a, u32 B) {
   constexpr int CB = INNER16_ROT_CB_FP;

@@ -123,6 +123,74 @@ __device__ __forceinline__ void ntt16_fwd_blocks_fp_loaded(double (&x)[16], cons
   ntt16_fwd_blocks_fp_loaded(x, tw, q, qinv, tile, sm, [] {});
 }
 
+// The same block pass with its 16 x 16 transposes done in two halves, low words then high words, through a tile of
+// 4-byte words (16 groups x 272 words = 17 KB instead of 34 KB): a kernel that wants the rest of its LDS share for
+// something else (the prefetched input tiles of ntt16_fwd_blocks_inner_c_kernel) uses this one. `ex` is the
+// workgroup's word tile; exchanges stay inside 16-lane groups, so waiting for the wave's own LDS operations orders them.
+__device__ __forceinline__ void fp_transpose16_words(double (&x)[16], u32* row_major, u32 wr_stride, u32 wr_lane,
+                                                     u32 rd_stride, u32 rd_lane) {
+  u32 lo[16], hi[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) row_major[i * wr_stride + wr_lane] = (u32)__double2loint(x[i]);
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) lo[j] = row_major[j * rd_stride + rd_lane];
+  wave_lds_sync();
+#pragma unroll
+  for (int i = 0; i < 16; i++) row_major[i * wr_stride + wr_lane] = (u32)__double2hiint(x[i]);
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) hi[j] = row_major[j * rd_stride + rd_lane];
+  wave_lds_sync();
+#pragma unroll
+  for (int j = 0; j < 16; j++) x[j] = __hiloint2double((int)hi[j], (int)lo[j]);
+}
+// `loaded` runs once the loads of all 30 twiddles have been issued and before anything waits for them: memory
+// requests a caller starts there are younger than every load the two rounds wait for, so those waits leave them in
+// flight. `between` runs after the first round.
+// The first round's 15 twiddles are the same for the 16 lanes of a group and for every tile the workgroup transforms:
+// `twl` holds them in LDS (group hb at twl + hb * NTT16_TWL_PITCH, filled by ntt16_fwd_blocks_fp_words_twl), so a
+// transform starts on a short LDS read instead of a trip to the L2.
+#define NTT16_TWL_PITCH 18
+// Filling it is split in two so that a caller can put other work between the request and the use of the value:
+// wave w fills the rows of its own four groups, lane L < 60 moving twiddle L % 15 of group 4w + L / 15.
+__device__ __forceinline__ double ntt16_twl_fetch(const double* __restrict__ tw, u32 tile) {
+  const u32 t = threadIdx.x, L = min(t & 63, 59u);
+  const u32 hb = (t >> 6) * 4 + L / 15, k = L % 15, h = tile * 16 + hb;
+  const u32 s = k >= 7 ? 3 : k >= 3 ? 2 : k >= 1 ? 1 : 0, g = k + 1 - (1u << s);
+  return tw[(256 << s) + (h << s) + g];
+}
+__device__ __forceinline__ void ntt16_twl_store(double v, double* twl) {
+  const u32 t = threadIdx.x, L = t & 63;
+  if (L < 60) twl[((t >> 6) * 4 + L / 15) * NTT16_TWL_PITCH + L % 15] = v;
+}
+template <class LOADED, class BETWEEN>
+__device__ __forceinline__ void ntt16_fwd_blocks_fp_words(double (&x)[16], const double* __restrict__ tw, double q,
+                                                          double qinv, u32 tile, u32* ex, const double* twl, LOADED loaded,
+                                                          BETWEEN between) {
+  const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
+  const u32 i0 = j0;
+  u32* grp = ex + hb * 272;
+  double twa[15], twb[15];
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) twb[(1 << s) - 1 + g] = tw[(4096 << s) + (h << (4 + s)) + (i0 << s) + g];
+#pragma unroll
+  for (int k = 0; k < 15; k++) twa[k] = twl[hb * NTT16_TWL_PITCH + k];
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+  loaded();
+  __builtin_amdgcn_sched_barrier(0);
+  radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return twa[(1 << s) - 1 + g]; });
+  // element (i, j0) -> lane i0 = i holds (i0, j): written at i*17 + j0, read at i0*17 + j
+  fp_transpose16_words(x, grp, 17, j0, 1, i0 * 17);
+  between();
+  radix16_fwd_fp(x, q, qinv, [&](int s, int g) { return twb[(1 << s) - 1 + g]; });
+  // and back: written at i0*17 + j, read at i*17 + j0
+  fp_transpose16_words(x, grp, 1, i0 * 17, 17, j0);
+}
+
 // Inverse, stages 15..8. In: x = canonical residues as doubles, i-layout. Out: reduced doubles, i-layout.
 __device__ __forceinline__ void ntt16_inv_blocks_fp(double (&x)[16], const double* __restrict__ twi, double q, double qinv,
                                                     u32 tile, double* sm) {
