@@ -68,6 +68,29 @@ __device__ __forceinline__ void radix16_inv(u64 (&x)[16], u64 q, u64 c0, TW tw) 
   }
 }
 
+// The same rounds with a hook after every stage: a pass uses it to request the next round's twiddles as this round's
+// die, so that no twiddle is waited for right after it was requested (15 twiddle pairs are 60 registers: two rounds'
+// worth do not fit beside the data).
+template <bool BIG, class TW, class AFTER>
+__device__ __forceinline__ void radix16_inv_staged(u64 (&x)[16], u64 q, u64 c0, TW tw, AFTER after) {
+  u64 c = c0;
+#pragma unroll
+  for (int s = 3; s >= 0; s--) {
+    const int half = 8 >> s;
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      ulonglong2 w = tw(s, g);
+#pragma unroll
+      for (int p = 0; p < half; p++) bf_inv<BIG>(x[g * 2 * half + p], x[g * 2 * half + p + half], w, q, c);
+    }
+    if (!BIG) c <<= 1;
+    after(s);
+  }
+}
+// Twiddle pair k of a round (stage s, group g: k = 2^s - 1 + g), fetched into `w` with the loads kept where they are
+// written: nothing the scheduler may move crosses the end of the block.
+#define NTT16_TW_INDEX(s, g) ((1 << (s)) - 1 + (g))
+
 __device__ __forceinline__ u64 barrett_lazy(u64 v, u64 mu, u64 q) { return v - mul_hi64(v, mu) * q; }  // [0,2q)
 
 // ---- pass bodies. `base` points at one limb-vector of 65536 words, `tw` at that modulus' table. ----
@@ -79,14 +102,22 @@ __device__ __forceinline__ void ntt16_fwd_rows_loaded(u64 (&x)[16], u64* __restr
                                                       u64 q, u32 tile, u64* sm) {
   const u32 t = threadIdx.x, col = t & 15, r0 = t >> 4, col0 = tile * 16;
   const u64 q2 = lazy_const<BIG>(q);
+  const u32 i0 = r0;
+  // the second round's twiddles (one set per 16-lane group) are requested here, next to the data loads, and arrive
+  // during the first round, whose own twiddles are wave-uniform scalar loads
+  ulonglong2 twb[15];
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) twb[NTT16_TW_INDEX(s, g)] = tw[(16 << s) + (i0 << s) + g];
+  __builtin_amdgcn_sched_barrier(0);
   radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(1 << s) + g]; });
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[i * 256 + t] = x[i];
   lds_barrier();
-  const u32 i0 = r0;
 #pragma unroll
   for (int j = 0; j < 16; j++) x[j] = sm[(i0 * 16 + j) * 16 + col];
-  radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(16 << s) + (i0 << s) + g]; });
+  radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return twb[NTT16_TW_INDEX(s, g)]; });
 #pragma unroll
   for (int j = 0; j < 16; j++) dst[(size_t)(i0 * 16 + j) * 256 + col0 + col] = x[j];
 }
@@ -159,19 +190,63 @@ __device__ __forceinline__ void radix8_fwd(u64 (&x)[8], u64 q, u64 q2, TW tw) {
     }
   }
 }
+template <bool BIG, class TW, class AFTER>
+__device__ __forceinline__ void radix8_fwd_staged(u64 (&x)[8], u64 q, u64 q2, TW tw, AFTER after) {
+#pragma unroll
+  for (int s = 0; s < 3; s++) {
+    const int half = 4 >> s;
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      const ulonglong2 w = tw(s, g);
+#pragma unroll
+      for (int p = 0; p < half; p++) bf_fwd<BIG>(x[g * 2 * half + p], x[g * 2 * half + p + half], w, q, q2);
+    }
+    after(s);
+  }
+}
 template <bool BIG, class BETWEEN>
 __device__ __forceinline__ void ntt256_fwd_blocks_int8(u64 (&x)[8], const ulonglong2* __restrict__ tw, u64 q, u64 mu, u32 h,
                                                        u32 l, u64* smb, BETWEEN between) {
   const u32 a = l >> 2, b = l & 3;
   const u64 q2 = lazy_const<BIG>(q);
-  radix8_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
+  // The first two rounds' twiddles are requested before `between` runs: the first round's here, the second round's
+  // stage by stage as the first round's registers die. Whatever `between` requests is then younger than all of them,
+  // so the second round never waits for it. The last two stages' twiddles follow once the second round's registers
+  // are free; by then the caller needs what `between` requested anyway.
+  ulonglong2 t1[7], t2[7], t3[6];
+#pragma unroll
+  for (int s = 0; s < 3; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) t1[(1 << s) - 1 + g] = tw[(256 << s) + (h << s) + g];
+  __builtin_amdgcn_sched_barrier(0);
+  radix8_fwd_staged<BIG>(
+      x, q, q2, [&](int s, int g) { return t1[(1 << s) - 1 + g]; },
+      [&](int s) {
+        __builtin_amdgcn_sched_barrier(0);
+        const ulonglong2* ts = tw + (2048 << s) + (h << (3 + s)) + (a << s);
+        if (s == 0) {
+          t2[0] = ts[0];
+        } else if (s == 1) {
+          t2[1] = ts[0], t2[2] = ts[1];
+        } else {
+          t2[3] = ts[0], t2[4] = ts[1], t2[5] = ts[2], t2[6] = ts[3];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
 #pragma unroll
   for (int i = 0; i < 8; i++) smb[i * NTT8_PITCH_I + l] = x[i];
   between();
+  __builtin_amdgcn_sched_barrier(0);
   wave_lds_sync();
 #pragma unroll
   for (int r = 0; r < 8; r++) x[r] = smb[a * NTT8_PITCH_I + r * 4 + b];
-  radix8_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(2048 << s) + (h << (3 + s)) + (a << s) + g]; });
+  radix8_fwd<BIG>(x, q, q2, [&](int s, int g) { return t2[(1 << s) - 1 + g]; });
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int u = 0; u < 2; u++) t3[u] = tw[16384 + (h << 6) + (a << 3) + (b << 1) + u];
+#pragma unroll
+  for (int k = 0; k < 4; k++) t3[2 + k] = tw[32768 + (h << 7) + (a << 4) + (b << 2) + k];
+  __builtin_amdgcn_sched_barrier(0);
   wave_lds_sync();
 #pragma unroll
   for (int r = 0; r < 8; r++) smb[a * NTT8_PITCH_I + r * 4 + b] = x[r];
@@ -180,15 +255,11 @@ __device__ __forceinline__ void ntt256_fwd_blocks_int8(u64 (&x)[8], const ulongl
   for (int c = 0; c < 8; c++) x[c] = smb[a * NTT8_PITCH_I + b * 8 + c];
 #pragma unroll
   for (int u = 0; u < 2; u++) {   // stage 14: pairs (c, c + 2) inside each half
-    const ulonglong2 w = tw[16384 + (h << 6) + (a << 3) + (b << 1) + u];
 #pragma unroll
-    for (int p = 0; p < 2; p++) bf_fwd<BIG>(x[u * 4 + p], x[u * 4 + p + 2], w, q, q2);
+    for (int p = 0; p < 2; p++) bf_fwd<BIG>(x[u * 4 + p], x[u * 4 + p + 2], t3[u], q, q2);
   }
 #pragma unroll
-  for (int k = 0; k < 4; k++) {   // stage 15: pairs (2k, 2k + 1)
-    const ulonglong2 w = tw[32768 + (h << 7) + (a << 4) + (b << 2) + k];
-    bf_fwd<BIG>(x[2 * k], x[2 * k + 1], w, q, q2);
-  }
+  for (int k = 0; k < 4; k++) bf_fwd<BIG>(x[2 * k], x[2 * k + 1], t3[2 + k], q, q2);   // stage 15: pairs (2k, 2k + 1)
 #pragma unroll
   for (int c = 0; c < 8; c++) x[c] = BIG ? csub(csub(x[c], q2), 2 * q) : barrett_lazy(x[c], mu, q);
 }
@@ -200,20 +271,36 @@ __device__ __forceinline__ void ntt16_inv_blocks(u64 (&x)[16], const ulonglong2*
                                                  u64* sm) {
   const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
   const u64 q2 = lazy_const<BIG>(q);
+  const u32 i0 = j0;
+  // first round's twiddles (one set per lane): requested before the transpose; the second round's (one set per
+  // group) take their registers over stage by stage
+  ulonglong2 twa[15];
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) twa[NTT16_TW_INDEX(s, g)] = twi[(4096 << s) + (h << (4 + s)) + (i0 << s) + g];
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[hb * 272 + i * 17 + j0] = x[i];
   wave_lds_sync();
-  const u32 i0 = j0;
 #pragma unroll
   for (int j = 0; j < 16; j++) x[j] = sm[hb * 272 + i0 * 17 + j];
-  radix16_inv<BIG>(x, q, q2, [&](int s, int g) { return twi[(4096 << s) + (h << (4 + s)) + (i0 << s) + g]; });
+  ulonglong2 twb[15];
+  radix16_inv_staged<BIG>(
+      x, q, q2, [&](int s, int g) { return twa[NTT16_TW_INDEX(s, g)]; },
+      [&](int s) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < (1 << s); g++) twb[NTT16_TW_INDEX(s, g)] = twi[(256 << s) + (h << s) + g];
+        __builtin_amdgcn_sched_barrier(0);
+      });
   wave_lds_sync();
 #pragma unroll
   for (int j = 0; j < 16; j++) sm[hb * 272 + i0 * 17 + j] = x[j];
   wave_lds_sync();
 #pragma unroll
   for (int i = 0; i < 16; i++) x[i] = sm[hb * 272 + i * 17 + j0];
-  radix16_inv<BIG>(x, q, BIG ? q2 : (q2 << 4), [&](int s, int g) { return twi[(256 << s) + (h << s) + g]; });
+  radix16_inv<BIG>(x, q, BIG ? q2 : (q2 << 4), [&](int s, int g) { return twb[NTT16_TW_INDEX(s, g)]; });
   if (!BIG) {
 #pragma unroll
     for (int i = 0; i < 16; i++) x[i] = barrett_lazy(x[i], mu, q);
@@ -230,7 +317,14 @@ __device__ __forceinline__ void ntt16_inv_rows(u64 (&x)[16], const u64* __restri
   const u64 q2 = lazy_const<BIG>(q);
 #pragma unroll
   for (int j = 0; j < 16; j++) x[j] = src[(size_t)(i0 * 16 + j) * 256 + col0 + col];
-  radix16_inv<BIG>(x, q, q2, [&](int s, int g) { return twi[(16 << s) + (i0 << s) + g]; });
+  // first round's twiddles (one set per group) travel with the data; the second round's are scalar loads
+  ulonglong2 twa[15];
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) twa[NTT16_TW_INDEX(s, g)] = twi[(16 << s) + (i0 << s) + g];
+  __builtin_amdgcn_sched_barrier(0);
+  radix16_inv<BIG>(x, q, q2, [&](int s, int g) { return twa[NTT16_TW_INDEX(s, g)]; });
 #pragma unroll
   for (int j = 0; j < 16; j++) sm[(i0 * 16 + j) * 16 + col] = x[j];
   lds_barrier();

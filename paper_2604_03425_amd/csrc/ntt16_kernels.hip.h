@@ -403,6 +403,7 @@ __device__ __forceinline__ bool fwd_inner_owns(const FwdInnerArgs& a, u32 t, u32
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef __attribute__((address_space(1))) const void* global_void_ptr;
 typedef const __attribute__((address_space(1))) u64* global_u64_ptr;
+typedef u64 global_u64x2 __attribute__((ext_vector_type(2)));
 #define INNER_C_EX_WORDS (16 * 272)
 __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 bc, u32 tile, u32 t, u32 id, const ModInfo& mi,
                                                     u32* ex, double* img, double* twl) {
@@ -532,6 +533,7 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
     }
     return;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy into LDS may outlive the workgroup
   u64* o = a.acc + (((size_t)b * 2 + c) * a.next + t) * N + lane_pos();
   if (a.accumulate) {
 #pragma unroll
@@ -567,9 +569,11 @@ ntt16_fwd_blocks_inner_c_kernel(FwdInnerArgs a) {
 // coefficients, so key words and accumulators move as 16-byte accesses. Products go through a Montgomery reduction:
 // acc carries the factor 2^-64, which the later stages absorb into their constants.
 template <int CLS>
-__global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerArgs a) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+ntt16_fwd_blocks_inner8_kernel(FwdInnerArgs a) {
   constexpr bool BIG = CLS == 2;
   __shared__ u64 sm[8 * NTT8_BLOCK_LDS_I];
+  __shared__ __attribute__((aligned(16))) u64 img[2048];
   u32 b, tile, zi;
   ntt16_map(a.map_mode, b, tile, zi);
   const u32 t = a.slots[zi];
@@ -588,39 +592,30 @@ __global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerAr
   ulonglong2 e0[4], e1[4];
 #pragma unroll
   for (int c = 0; c < 8; c++) acc0[c] = acc1[c] = 0;
-#pragma nounroll
-  for (u32 j = 0; j < a.beta; j++) {
-    const u64* kb = evk + (size_t)j * 2 * a.nm * N + posC;
-    const u64* ka = kb + (size_t)a.nm * N;
-    auto request_key = [&]() {
+  // The converted digit tiles are prefetched: a wave copies its two blocks (4 KB) of the next tile straight into LDS
+  // while it multiplies the current one by the key, and starts a tile by reading its values from there.
+  auto request = [&](const u64* limb) {
+    u32 td = threadIdx.x;
+    asm volatile("" : "+v"(td));
+    const u32 wv = __builtin_amdgcn_readfirstlane(td >> 6);
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)uniform_ptr(limb + (size_t)tile * 2048 + wv * 512), 0, 4096, 0x00020000);
+    const int vo = (int)((td & 63) * 16);
+    u64* li = img + wv * 512;
 #pragma unroll
-      for (int v = 0; v < 4; v++) {
-        e0[v] = *(const ulonglong2*)(kb + 2 * v);
-        e1[v] = *(const ulonglong2*)(ka + 2 * v);
-      }
-    };
-    if (fwd_inner_owns(a, t, j)) {
-      const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
-      request_key();
-      if (g) {
+    for (int k = 0; k < 4; k++)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(li + k * 128), 16, vo, k * 1024, 0, 0);
+  };
+  auto take = [&]() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    u32 td = threadIdx.x;
+    asm volatile("" : "+v"(td));
+    const u64* li = img + (td >> 5) * 256 + (td & 31);
 #pragma unroll
-        for (int c = 0; c < 8; c++) x[c] = src[galois_src_index16(posC + c, g)];
-      } else {
-#pragma unroll
-        for (int v = 0; v < 4; v++) {
-          const ulonglong2 w = *(const ulonglong2*)(src + posC + 2 * v);
-          x[2 * v] = w.x;
-          x[2 * v + 1] = w.y;
-        }
-      }
-    } else {
-      const u64* src = a.ext + (((size_t)b * a.beta + j) * a.next + t) * N + posA;
-#pragma unroll
-      for (int i = 0; i < 8; i++) x[i] = src[i * 32];
-      wave_lds_sync();  // the previous digit's exchanges are done with the block's LDS rows
-      ntt256_fwd_blocks_int8<BIG>(x, tw, q, mi.mu64, h, l, smb, request_key);
-    }
-    __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < 8; i++) x[i] = li[i * 32];
+    wave_lds_sync();
+  };
+  auto multiply = [&]() {
 #pragma unroll
     for (int v = 0; v < 4; v++) {
       const u64 eb[2] = {e0[v].x, e0[v].y}, ea[2] = {e1[v].x, e1[v].y};
@@ -636,7 +631,55 @@ __global__ void __launch_bounds__(256) ntt16_fwd_blocks_inner8_kernel(FwdInnerAr
         acc1[2 * v + k] = csub(acc1[2 * v + k] + redc(p1, q, mi.minv), q2);
       }
     }
+  };
+  auto request_key = [&](u32 j) {
+    const global_u64_ptr kb = (global_u64_ptr)(evk + (size_t)j * 2 * a.nm * N + posC);
+    const global_u64_ptr ka = kb + (size_t)a.nm * N;
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+      const global_u64x2 vb = *(const __attribute__((address_space(1))) global_u64x2*)(kb + 2 * v);
+      const global_u64x2 va = *(const __attribute__((address_space(1))) global_u64x2*)(ka + 2 * v);
+      e0[v] = ulonglong2{vb.x, vb.y};
+      e1[v] = ulonglong2{va.x, va.y};
+    }
+  };
+  const u32 beta = a.beta;
+  const u32 jo = t < a.nlimbs ? t / a.alpha : 0xFFFFFFFFu;   // the digit that holds limb t itself (none for special slots)
+  auto ext_limb = [&](u32 j) { return a.ext + (((size_t)b * beta + j) * a.next + t) * N; };
+  u32 jn = jo == 0 ? 1u : 0u;   // next converted digit
+  if (jn < beta) request(ext_limb(jn));
+  if (jo != 0xFFFFFFFFu) {   // the own digit first: its loads are in flight together with the first prefetch
+    const u64* src = a.d + (size_t)b * a.d_poly_stride + (size_t)t * N;
+    request_key(jo);
+    if (g) {
+#pragma unroll
+      for (int c = 0; c < 8; c++) x[c] = src[galois_src_index16(posC + c, g)];
+    } else {
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        const ulonglong2 w = *(const ulonglong2*)(src + posC + 2 * v);
+        x[2 * v] = w.x;
+        x[2 * v + 1] = w.y;
+      }
+    }
+    multiply();
   }
+#pragma nounroll
+  while (jn < beta) {
+    take();
+    u32 jnext = jn + 1;
+    if (jnext == jo) jnext++;
+    const u32 jcur = jn;
+    ntt256_fwd_blocks_int8<BIG>(x, tw, q, mi.mu64, h, l, smb, [&] { request_key(jcur); });
+    __builtin_amdgcn_sched_barrier(0);
+    // younger than every load the products wait for, so it stays in flight across them (the current tile again when
+    // nothing follows: the same static wait counts on every path)
+    request(ext_limb(jnext < beta ? jnext : jcur));
+    __builtin_amdgcn_sched_barrier(0);
+    multiply();
+    jn = jnext;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy into LDS may outlive the workgroup
   u64* o0 = a.acc + (((size_t)b * 2 + 0) * a.next + t) * N + posC;
   u64* o1 = o0 + (size_t)a.next * N;
   if (a.accumulate) {   // a rotation kept in the extended basis, added to what acc holds (wave-uniform branch)
