@@ -4,11 +4,11 @@
 // limb (stride-256 butterflies, stages 0..7); pass "blk" works on 16 contiguous 256-element blocks
 // (stages 8..15). Global loads and stores always have 16 adjacent lanes on 128 contiguous bytes.
 //
-// Lazy ranges. SMALL primes (q < 2^52): forward butterflies never correct, values grow by 2q per
-// stage (< 33q < 2^58 after 16 stages from canonical input) and are reduced once at the end; inverse
-// butterflies let sums double for the 8 stages of a pass (inputs < 2q -> < 512q). BIG primes (q < 2^60)
-// use Harvey's butterflies with the approximate twiddle product shoup_lazy4 (below 4q): values are kept in
-// [0,8q) (forward) / [0,4q) (inverse); the lazy constant `ql` those bodies pass around is 4q (2q for SMALL).
+// Lazy ranges. Every twiddle product is the approximate shoup_lazy4 (below 4q), and the lazy constant the bodies
+// pass around is 4q. SMALL primes (q < 2^52): forward butterflies never correct, values grow by 4q per
+// stage (< 65q < 2^59 after 16 stages from canonical input) and are reduced once at the end; inverse
+// butterflies let sums double for the 8 stages of a pass (inputs < 4q -> < 1024q). BIG primes (q < 2^60)
+// use Harvey's butterflies: values are kept in [0,8q) (forward) / [0,4q) (inverse).
 #pragma once
 #include "modarith.hip.h"
 
@@ -17,24 +17,24 @@
 
 // ---- butterflies ----
 template <bool BIG>
-__device__ __forceinline__ u64 lazy_const(u64 q) { return BIG ? 4 * q : 2 * q; }
-// Forward (Cooley-Tukey). BIG: q2 = 4q, inputs and outputs in [0,8q). SMALL: q2 = 2q, values grow by 2q.
+__device__ __forceinline__ u64 lazy_const(u64 q) { return 4 * q; }
+// Forward (Cooley-Tukey), q2 = 4q. BIG: inputs and outputs in [0,8q). SMALL: values grow by 4q per stage.
 template <bool BIG>
 __device__ __forceinline__ void bf_fwd(u64& X, u64& Y, ulonglong2 w, u64 q, u64 q2) {
   if (BIG) X = csub_neg(X, q2);
-  u64 T = BIG ? shoup_lazy4(Y, w.x, w.y, q) : shoup_lazy(Y, w.x, w.y, q);
+  u64 T = shoup_lazy4(Y, w.x, w.y, q);
   Y = X + q2 - T;
   X = X + T;
 }
-// Inverse (Gentleman-Sande). BIG: c = 4q, inputs in [0,4q), outputs in [0,4q). SMALL: inputs < c (a multiple of q),
-// X' < 2c, Y' < 2q.
+// Inverse (Gentleman-Sande). BIG: c = 4q, inputs in [0,4q), outputs in [0,4q). SMALL: inputs < c (a multiple of q,
+// at least 4q), X' < 2c, Y' < 4q.
 template <bool BIG>
 __device__ __forceinline__ void bf_inv(u64& X, u64& Y, ulonglong2 w, u64 q, u64 c) {
   u64 S = X + Y;
   u64 D = X + c - Y;
   if (BIG) S = csub_neg(S, c);  // c == 4q
   X = S;
-  Y = BIG ? shoup_lazy4(D, w.x, w.y, q) : shoup_lazy(D, w.x, w.y, q);
+  Y = shoup_lazy4(D, w.x, w.y, q);
 }
 
 // Four forward stages on 16 registers: stage s pairs (a, a + (8>>s)); tw(s, g) is the twiddle of group g.
@@ -72,6 +72,20 @@ __device__ __forceinline__ void radix16_inv(u64 (&x)[16], u64 q, u64 c0, TW tw) 
 // die, so that no twiddle is waited for right after it was requested (15 twiddle pairs are 60 registers: two rounds'
 // worth do not fit beside the data).
 template <bool BIG, class TW, class AFTER>
+__device__ __forceinline__ void radix16_fwd_staged(u64 (&x)[16], u64 q, u64 q2, TW tw, AFTER after) {
+#pragma unroll
+  for (int s = 0; s < 4; s++) {
+    const int half = 8 >> s;
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) {
+      ulonglong2 w = tw(s, g);
+#pragma unroll
+      for (int p = 0; p < half; p++) bf_fwd<BIG>(x[g * 2 * half + p], x[g * 2 * half + p + half], w, q, q2);
+    }
+    after(s);
+  }
+}
+template <bool BIG, class TW, class AFTER>
 __device__ __forceinline__ void radix16_inv_staged(u64 (&x)[16], u64 q, u64 c0, TW tw, AFTER after) {
   u64 c = c0;
 #pragma unroll
@@ -87,15 +101,28 @@ __device__ __forceinline__ void radix16_inv_staged(u64 (&x)[16], u64 q, u64 c0, 
     after(s);
   }
 }
-// Twiddle pair k of a round (stage s, group g: k = 2^s - 1 + g), fetched into `w` with the loads kept where they are
-// written: nothing the scheduler may move crosses the end of the block.
+// Slot of the twiddle pair of stage s, group g in a round's table of 15.
 #define NTT16_TW_INDEX(s, g) ((1 << (s)) - 1 + (g))
+// The 2^s twiddle pairs of stage s, from `src`, into their slots of a round's table. Written out per stage so that
+// every index is a constant and the table stays in registers.
+__device__ __forceinline__ void ntt16_load_stage(ulonglong2 (&t)[15], const ulonglong2* __restrict__ src, int s) {
+  if (s == 0) {
+    t[0] = src[0];
+  } else if (s == 1) {
+    t[1] = src[0], t[2] = src[1];
+  } else if (s == 2) {
+    t[3] = src[0], t[4] = src[1], t[5] = src[2], t[6] = src[3];
+  } else {
+    t[7] = src[0], t[8] = src[1], t[9] = src[2], t[10] = src[3];
+    t[11] = src[4], t[12] = src[5], t[13] = src[6], t[14] = src[7];
+  }
+}
 
 __device__ __forceinline__ u64 barrett_lazy(u64 v, u64 mu, u64 q) { return v - mul_hi64(v, mu) * q; }  // [0,2q)
 
 // ---- pass bodies. `base` points at one limb-vector of 65536 words, `tw` at that modulus' table. ----
 
-// Forward, stages 0..7. In: canonical (or < 2q). Out: SMALL < 17q (+in), BIG < 8q.
+// Forward, stages 0..7. In: canonical (or < 2q). Out: SMALL < 33q (+in), BIG < 8q.
 // `x` holds, for lane (r0 = t>>4, col = t&15), the rows i*16 + r0 (i = 0..15) of column col0 + col.
 template <bool BIG>
 __device__ __forceinline__ void ntt16_fwd_rows_loaded(u64 (&x)[16], u64* __restrict__ dst, const ulonglong2* __restrict__ tw,
@@ -138,14 +165,28 @@ __device__ __forceinline__ void ntt16_fwd_blocks_loaded(u64 (&x)[16], const ulon
                                                         u32 tile, u64* sm) {
   const u32 t = threadIdx.x, j0 = t & 15, hb = t >> 4, h = tile * 16 + hb;
   const u64 q2 = lazy_const<BIG>(q);
-  radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(256 << s) + (h << s) + g]; });
+  const u32 i0 = j0;
+  // first round's twiddles (one set per group) requested here, next to the caller's data loads; the second round's
+  // (one set per lane) take their registers over stage by stage
+  ulonglong2 twa[15], twb[15];
+#pragma unroll
+  for (int s = 0; s < 4; s++)
+#pragma unroll
+    for (int g = 0; g < (1 << s); g++) twa[NTT16_TW_INDEX(s, g)] = tw[(256 << s) + (h << s) + g];
+  __builtin_amdgcn_sched_barrier(0);
+  radix16_fwd_staged<BIG>(
+      x, q, q2, [&](int s, int g) { return twa[NTT16_TW_INDEX(s, g)]; },
+      [&](int s) {
+        __builtin_amdgcn_sched_barrier(0);
+        ntt16_load_stage(twb, tw + (4096 << s) + (h << (4 + s)) + (i0 << s), s);
+        __builtin_amdgcn_sched_barrier(0);
+      });
 #pragma unroll
   for (int i = 0; i < 16; i++) sm[hb * 272 + i * 17 + j0] = x[i];
   wave_lds_sync();
-  const u32 i0 = j0;
 #pragma unroll
   for (int j = 0; j < 16; j++) x[j] = sm[hb * 272 + i0 * 17 + j];
-  radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return tw[(4096 << s) + (h << (4 + s)) + (i0 << s) + g]; });
+  radix16_fwd<BIG>(x, q, q2, [&](int s, int g) { return twb[NTT16_TW_INDEX(s, g)]; });
 #pragma unroll
   for (int j = 0; j < 16; j++) {
     u64 v = x[j];
@@ -290,8 +331,7 @@ __device__ __forceinline__ void ntt16_inv_blocks(u64 (&x)[16], const ulonglong2*
       x, q, q2, [&](int s, int g) { return twa[NTT16_TW_INDEX(s, g)]; },
       [&](int s) {
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int g = 0; g < (1 << s); g++) twb[NTT16_TW_INDEX(s, g)] = twi[(256 << s) + (h << s) + g];
+        ntt16_load_stage(twb, twi + (256 << s) + (h << s), s);
         __builtin_amdgcn_sched_barrier(0);
       });
   wave_lds_sync();
