@@ -26,7 +26,9 @@ PEAK_HBM_GBS = 8000.0
 PEAK_ALU_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
 
 # Algorithmic 32-bit lane-op counts: one 64-bit Shoup butterfly = 10 multiply-class
-# + 14 add/compare/select ops; one 64x64->128 multiply-accumulate = 4 multiplies + 4 adds; one 128->64
+# + 14 add/compare/select ops (the canonical form; the kernels' butterflies execute 21 instructions with their
+# approximate quotient, so fractions built on these counts read a little high against executed instructions, which
+# profiles/ reports from counters); one 64x64->128 multiply-accumulate = 4 multiplies + 4 adds; one 128->64
 # Montgomery reduction = 7 multiplies + 9 adds/selects; one Shoup constant multiply = 10 + 4.
 OPS_BUTTERFLY, OPS_MAC, OPS_REDUCE, OPS_SHOUP, OPS_ADD = 24, 8, 16, 14, 4
 # Double-precision bodies (primes < 2^50; FP64 instructions issue at the same one-per-lane-per-clock rate):
@@ -258,8 +260,8 @@ def other_workloads(args):
                             modelled_Tops=round(limbs * (N / 2) * (p.logN / npass) * ops_bf / t / 1e12, 2))
         fwd = sum(ms for k, (ms, n) in prof.items() if "fwd" in k) * 1e-3 / args.steps
         inv = sum(ms for k, (ms, n) in prof.items() if "inv" in k) * 1e-3 / args.steps
-        print(json.dumps({"workload": "ntt", "arithmetic": "int32 (Shoup, 24 instructions per butterfly)" if args.int_only
-                          else "fp64 (9.5 instructions per butterfly)", "limb_vectors": limbs,
+        print(json.dumps({"workload": "ntt", "arithmetic": "int32 (Shoup butterflies; utilisation counts the canonical 24 operations per butterfly)" if args.int_only
+                          else "fp64 (utilisation counts 9.5 operations per butterfly)", "limb_vectors": limbs,
                           "ntt_limbs_per_s": round(limbs / fwd), "intt_limbs_per_s": round(limbs / inv),
                           "ring": "N = 2^%d" % p.logN,
                           "ntt_hbm_frac": round(limbs * 2 * npass * 8 * N / fwd / 1e9 / PEAK_HBM_GBS, 4),
