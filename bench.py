@@ -762,7 +762,22 @@ def main():
           for b in range(B):
               ck.ckks_hrot_noalloc(ctx, out_rot[b:b + 1], ct[b:b + 1], 1, nl, gal64[b], evk64[b])
       t_rot_graph = timed(graph.replay, 3)
-      del graph, evk64
+      del graph
+      # the same 64 single-ciphertext rotations issued round-robin on four streams (a workspace each): what a caller
+      # that cannot batch gets by keeping several calls in flight (default-priority streams; one context serves them all)
+      side = [torch.cuda.Stream() for _ in range(4)]
+      ws4 = [ctx.workspace(ck.OP_HROT, 1, nl) for _ in range(4)]
+      def rot_streams():
+          cur = torch.cuda.current_stream()
+          for s_ in side:
+              s_.wait_stream(cur)
+          for b in range(B):
+              with torch.cuda.stream(side[b % 4]):
+                  ck.ckks_hrot(ctx, out_rot[b:b + 1], ct[b:b + 1], 1, nl, gal64[b], evk64[b], ws4[b % 4])
+          for s_ in side:
+              cur.wait_stream(s_)
+      t_rot_streams = timed(rot_streams, 3)
+      del evk64, ws4
       # the step after a product: Rescale (and the PMult / Add building blocks), same batch
       ws_rs = ctx.workspace(ck.OP_RESCALE, B, nl)
       out_rs = torch.empty((B, 2, nl - 1, N), dtype=torch.int64, device=dev)
@@ -778,6 +793,7 @@ def main():
                    hrot_per_s=round(B / t_rot, 1), hrot_per_s_one_group=round(B / t_rot1, 1),
                    hrot_per_s_own_key_each=round(B / t_rot64, 1),
                    hrot_per_s_one_by_one_hip_graph=round(B / t_rot_graph, 1),
+                   hrot_per_s_one_by_one_4_streams=round(B / t_rot_streams, 1),
                    hmult_relin_per_s=round(B / 2 / t_mul, 1),
                  rescale_per_s=round(B / t_rs, 1),
                  rescale_hbm_frac=round(B * 2 * (4 + 3 * (nl - 1) + 4 * (nl - 1)) * 8 * N / t_rs / 1e9 / PEAK_HBM_GBS, 4),
