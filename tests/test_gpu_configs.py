@@ -371,11 +371,13 @@ def test_hrot_multi_matches_single_rotations(gpu, name, nl, B):
     gc.close()
 
 
-@pytest.mark.parametrize("shape", [(16, 4, 50, 2, 60, 2), (12, 4, 40, 2, 50, 2), (16, 3, 60, 2, 60, 2)])
+@pytest.mark.parametrize("shape", [(16, 4, 50, 2, 60, 2), (12, 4, 40, 2, 50, 2), (16, 3, 60, 2, 60, 2),
+                                   (16, 4, 52, 2, 60, 2), (12, 4, 51, 2, 52, 2)])
 def test_extreme_residues(gpu, shape):
     """Inputs at the ends of the residue range (every residue q-1, and 0 / q-1 alternating), keys and plaintexts at
     m-1: the lazy ranges of the kernels (double-precision sums, 30-bit partial products, Harvey butterflies) are
-    argued from these maxima."""
+    argued from these maxima. The primes sit just below 2^bits, so the 52- and 51-bit shapes put the uncorrected
+    integer butterflies (primes in [2^50, 2^52)) at the top of their range, as the 60-bit ones do for the Harvey form."""
     import torch
     from gpu_util import to_dev, to_host, assert_same
     p = make_params(*shape)
