@@ -155,9 +155,10 @@ __global__ void __launch_bounds__(NTT16_THREADS) ntt16_inv_rows_kernel(Ntt16Args
 // the conversion is one dot product plus a per-target constant (`off`), with no sign handling per coefficient, and
 // the halves enter the 32-bit multiply-adds as they are loaded. A workgroup builds the 256 x 16 tile of one target
 // limb from the `len` source tiles of its digit and takes it straight through stages 0..7; the converted limb is
-// never written in coefficient form. All targets of one (polynomial, tile) run next to each other on one XCD
-// (ntt16_map mode 4 with the target index as the fastest dimension), so its L2 serves the source tiles to all of
-// them after the first has fetched them.
+// never written in coefficient form. The placement of the workgroups decides which cache serves the re-reads of the
+// source tiles: map mode 5 (the default, see the kernel) keeps a polynomial on one XCD with its tiles running side by
+// side, target after target; ntt16_map mode 4 with the target index as the fastest dimension puts all targets of one
+// (polynomial, tile) next to each other instead, which fetches every source tile once and measured slower.
 struct BconvRowsArgs {
   const u64* src;           // source limbs, split form (see above)
   u64* dst;                 // target limbs after the row pass (reduced doubles / lazy integers, by class)
@@ -551,7 +552,7 @@ __device__ __forceinline__ void fwd_inner_c_body_fp(const FwdInnerArgs& a, u32 b
 }
 __global__ void __launch_bounds__(NTT16_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
 ntt16_fwd_blocks_inner_c_kernel(FwdInnerArgs a) {
-  // two arrays, so that the compiler knows the transposes never touch the image a prefetch is landing in
+  // separate arrays, so that the compiler knows the transposes never touch the image a prefetch is landing in
   __shared__ __attribute__((aligned(16))) double img[4096];
   __shared__ u32 ex[INNER_C_EX_WORDS];
   __shared__ double twl[16 * NTT16_TWL_PITCH];
