@@ -33,8 +33,12 @@
  * NULL = the default stream) and returns without synchronising or allocating: every table a
  * call needs is built by ckks_ctx_create. With tuning knob 4 set to 0 a key switch runs part of its
  * kernels on a second stream owned by the context, forked from and joined back into `stream` with
- * events, so everything is ordered as if it ran on `stream` alone. Calls on one context must not be issued from several host threads at once. Workspace passed to a
- * call must stay untouched until that stream has drained the call.
+ * events, so everything is ordered as if it ran on `stream` alone. Calls on one context must not be
+ * issued from several host threads at once. Workspace passed to a call must stay untouched until that
+ * stream has drained the call. One host thread may keep calls of one context in flight on several
+ * streams, each with a workspace of its own (the context holds only constants once it is created),
+ * as long as knob 4 keeps its default, profiling is off and none of them is ckks_hrot_noalloc, whose
+ * calls share one scratch array per GPU.
  *
  * Errors: calls return CKKS_OK or a negative code; they never throw or abort. After a
  * failure ckks_last_error() returns a thread-local message. Nothing is enqueued when an

@@ -371,6 +371,45 @@ def test_hrot_multi_matches_single_rotations(gpu, name, nl, B):
     gc.close()
 
 
+def test_one_context_serves_calls_on_several_streams(gpu):
+    """Single-ciphertext rotations and products issued round-robin on four streams (a workspace each, one context)
+    while all of them are in flight: every result equals the oracle's. The context holds only constants once it is
+    created, so calls on different streams share nothing they write."""
+    import torch
+    from gpu_util import to_dev, to_host, assert_same
+    p = make_params(16, 6, 50, 2, 60, 3)
+    rc, gc = ref.RefContext(p), gpu.Context(p)
+    nl, B = 6, 8
+    ct = uniform_residues(900, p.q[:nl], (B, 2), p.N)
+    keys = [uniform_residues(910 + i, p.moduli, (p.dnum, 2), p.N) for i in range(2)]
+    gs = [galois_element(3 + 5 * b, p.logN) for b in range(B)]
+    ref.set_threads(4)
+    want_rot = np.concatenate([rc.hrot(ct[b:b + 1], gs[b], keys[b % 2]) for b in range(B)])
+    want_mul = np.concatenate([rc.hmult_relin(ct[b:b + 1], ct[(b + 1) % B:(b + 1) % B + 1], keys[b % 2]) for b in range(B)])
+    ref.set_threads(1)
+    d_ct, dkeys = to_dev(ct), [to_dev(k) for k in keys]
+    d_next = torch.roll(d_ct, -1, 0).contiguous()
+    out_rot, out_mul = torch.empty_like(d_ct), torch.empty_like(d_ct)
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    wss = [gc.workspace(gpu.OP_HROT, 1, nl) for _ in range(4)]
+    cur = torch.cuda.current_stream()
+    for rep in range(2):
+        for s_ in streams:
+            s_.wait_stream(cur)
+        for b in range(B):
+            with torch.cuda.stream(streams[b % 4]):
+                gpu.ckks_hrot(gc, out_rot[b:b + 1], d_ct[b:b + 1], 1, nl, gs[b], dkeys[b % 2], wss[b % 4])
+                gpu.ckks_hmult_relin(gc, out_mul[b:b + 1], d_ct[b:b + 1], d_next[b:b + 1], 1, nl, dkeys[b % 2], wss[b % 4])
+        for s_ in streams:
+            cur.wait_stream(s_)
+        torch.cuda.synchronize()
+        assert_same(to_host(out_rot), want_rot, "rotations on four streams, pass %d" % rep)
+        assert_same(to_host(out_mul), want_mul, "products on four streams, pass %d" % rep)
+        out_rot.zero_()
+        out_mul.zero_()
+    gc.close()
+
+
 @pytest.mark.parametrize("shape", [(16, 4, 50, 2, 60, 2), (12, 4, 40, 2, 50, 2), (16, 3, 60, 2, 60, 2),
                                    (16, 4, 52, 2, 60, 2), (12, 4, 51, 2, 52, 2)])
 def test_extreme_residues(gpu, shape):
